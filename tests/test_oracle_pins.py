@@ -1,0 +1,368 @@
+"""Pins for the CPU oracle: things the paper and the mathematics fix, none of which
+is the oracle's own formula typed again.
+
+* hand-worked cases (tests/golden/handworked.json), every intermediate value;
+* keep-all (T = D) decode == dense attention, Eq. (4) == torch's softmax attention;
+* brute force over all channel subsets: the kept set maximises Eq. (7), and among the
+  maximisers it is the one preferring lower channel indices;
+* exact-recovery construction: if every pruned entry already equals mu/a the method is
+  lossless for any T, so the output equals dense attention;
+* window-scale invariance, token-permutation invariance, convexity of the output,
+  probabilities summing to one, order relations between kept / pruned saliencies;
+* closed-form properties of the int8 storage variant.
+"""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+bf = wl.f32_to_bf16_bits
+fb = wl.bf16_bits_to_f32
+
+
+def _bits(x):
+    x = np.asarray(x, dtype=np.float32)
+    b = bf(x)
+    assert np.array_equal(fb(b), x), "fixture value not representable in bfloat16"
+    return b
+
+
+def _kept_channels(mask_row, D):
+    return [j for j in range(D) if (int(mask_row[j // 32]) >> (j % 32)) & 1]
+
+
+# ------------------------------------------------------------------ hand-worked cases
+
+with open(os.path.join(HERE, "golden", "handworked.json")) as fh:
+    _CASES = json.load(fh)["cases"]
+
+
+@pytest.mark.parametrize("case", _CASES, ids=[c["name"] for c in _CASES])
+def test_handworked(case):
+    B, Hq, Hkv, D, T, S = (case[x] for x in ("B", "Hq", "Hkv", "D", "T", "S"))
+    qwin, k, v, q = _bits(case["qwin"]), _bits(case["k"]), _bits(case["v"]), _bits(case["q"])
+    cu = np.array([0, S], np.int32)
+    exp = case["expect"]
+
+    qbar, a64, a32 = oracle.window_stat(qwin, Hkv)
+    assert np.array_equal(a64, np.asarray(exp["a"], np.float64))
+    assert np.array_equal(a32, np.asarray(exp["a"], np.float32))
+
+    pr = oracle.prune(k, "NHD", a32, cu, T, want_w=True)
+    assert np.array_equal(pr.w, np.asarray(exp["w"], np.float32))
+    for n in range(S):
+        for h in range(Hkv):
+            assert _kept_channels(pr.mask[n, h], D) == exp["kept_channels"][n][h]
+            want_vals = [case["k"][n][h][j] for j in exp["kept_channels"][n][h]]
+            assert np.array_equal(fb(pr.kept[n, h]), np.asarray(want_vals, np.float32))
+    assert np.array_equal(pr.mu64, np.asarray(exp["mu"], np.float64))
+    assert np.array_equal(pr.mu32, np.asarray(exp["mu"], np.float32))
+
+    out, probs = oracle.decode_literal(q, pr, v, "NHD", cu, want_probs=True)
+    s = np.asarray(exp["scores"], np.float64)[0]          # [Hq, S]
+    vv = np.asarray(case["v"], np.float64)                # [S, Hkv, D]
+    G = Hq // Hkv
+    for g in range(Hq):
+        p0 = 1.0 / (1.0 + math.exp(s[g, 1] - s[g, 0]))     # logistic closed form for S = 2
+        want_p = np.array([p0, 1.0 - p0])
+        assert np.allclose(probs[g], want_p, rtol=0, atol=1e-15)
+        want_o = want_p[0] * vv[0, g // G] + want_p[1] * vv[1, g // G]
+        assert np.allclose(out[0, g], want_o, rtol=0, atol=1e-15)
+    assert np.allclose(oracle.decode_fused(q, pr, v, "NHD", cu), out, rtol=0, atol=1e-14)
+
+
+# ------------------------------------------------------------------ dense attention pins
+
+def _random_small(seed, B=2, Hq=8, Hkv=2, D=128, W=8, seqlens=(37, 91), T=26, **kw):
+    w = wl.small(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=D, window=W, keep=T,
+                 seqlens=seqlens, seed=seed, **kw)
+    return w, wl.generate(w)
+
+
+def test_dense_attention_matches_library_softmax_attention():
+    w, t = _random_small(1)
+    out = oracle.dense_attn(t.q, t.k, t.v, t.layout, t.cu)
+    G = w.n_q_heads // w.n_kv_heads
+    kf = torch.from_numpy(fb(t.k).astype(np.float64))     # [Hkv, total, D]
+    vf = torch.from_numpy(fb(t.v).astype(np.float64))
+    qf = torch.from_numpy(fb(t.q).astype(np.float64))     # [B, Hq, D]
+    for b in range(w.batch):
+        s0, s1 = int(t.cu[b]), int(t.cu[b + 1])
+        kk = kf[:, s0:s1].repeat_interleave(G, dim=0)[None]           # [1, Hq, S, D]
+        vv = vf[:, s0:s1].repeat_interleave(G, dim=0)[None]
+        ref = torch.nn.functional.scaled_dot_product_attention(qf[b][None, :, None, :], kk, vv)
+        assert np.allclose(out[b], ref[0, :, 0].numpy(), rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("layout", ["HND", "NHD"])
+def test_keep_all_is_dense_attention(layout):
+    w, t = _random_small(2, T=128)
+    k, v = t.k, t.v
+    if layout == "NHD":
+        k = np.ascontiguousarray(k.transpose(1, 0, 2))
+        v = np.ascontiguousarray(v.transpose(1, 0, 2))
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(k, layout, a32, t.cu, 128)
+    assert np.all(pr.mask == 0xFFFFFFFF) and np.all(pr.mu32 == 0) and np.all(np.isinf(pr.gap))
+    kept_ref = k if layout == "NHD" else k.transpose(1, 0, 2)
+    assert np.array_equal(pr.kept, kept_ref)
+    dense = oracle.dense_attn(t.q, k, v, layout, t.cu)
+    assert np.allclose(oracle.decode_literal(t.q, pr, v, layout, t.cu), dense, rtol=0, atol=1e-14)
+    assert np.allclose(oracle.decode_fused(t.q, pr, v, layout, t.cu), dense, rtol=0, atol=1e-13)
+
+
+# ------------------------------------------------------------------ selection pins
+
+@pytest.mark.parametrize("D,T", [(6, 1), (7, 3), (8, 4), (9, 2), (10, 5), (10, 9)])
+def test_selection_is_the_brute_force_optimum(D, T):
+    rng = np.random.default_rng(100 + 10 * D + T)
+    S, Hkv = 40, 2
+    # few distinct magnitudes so ties (also across the cut) are common
+    k = rng.integers(-3, 4, size=(S, Hkv, D)).astype(np.float32) * 0.5
+    a32 = rng.integers(0, 3, size=(1, Hkv, D)).astype(np.float32) * 0.5   # zeros included
+    cu = np.array([0, S], np.int32)
+    pr = oracle.prune(bf(k), "NHD", a32, cu, T, want_w=True)
+    for n in range(S):
+        for h in range(Hkv):
+            wrow = (a32[0, h].astype(np.float64) * np.abs(k[n, h]).astype(np.float64))
+            assert np.array_equal(pr.w[n, h].astype(np.float64), wrow)    # products exact here
+            best, best_sets = -1.0, []
+            for sub in itertools.combinations(range(D), T):
+                tot = float(sum(wrow[j] for j in sub))
+                if tot > best + 1e-12:
+                    best, best_sets = tot, [sub]
+                elif abs(tot - best) <= 1e-12:
+                    best_sets.append(sub)
+            got = tuple(_kept_channels(pr.mask[n, h], D))
+            assert len(got) == T
+            assert got in best_sets                       # attains the maximum of Eq. (7)
+            assert got == min(best_sets)                  # ties resolved towards lower channels
+            pruned = [j for j in range(D) if j not in got]
+            assert pr.mu64[n, h] == pytest.approx(np.mean(wrow[pruned]), abs=1e-15)
+
+
+def test_selection_invariants_and_gqa_sharing():
+    w, t = _random_small(3, Hq=8, Hkv=2, T=26)
+    qbar, a64, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    # independent statement of the group weight: mean over the group's heads of |window mean|
+    qf = fb(t.qwin).astype(np.float64)                                   # [B,Hq,W,D]
+    G = w.n_q_heads // w.n_kv_heads
+    a_ref = np.abs(qf.mean(axis=2)).reshape(w.batch, w.n_kv_heads, G, w.head_dim).mean(axis=2)
+    assert np.allclose(a64, a_ref, rtol=0, atol=1e-15)
+    assert np.array_equal(a32, a_ref.astype(np.float32)) or np.allclose(a32, a_ref, rtol=1e-7)
+
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep, want_w=True)
+    D, T = w.head_dim, w.keep
+    bits = np.unpackbits(pr.mask.view(np.uint8), axis=-1, bitorder="little").astype(bool)   # [total,Hkv,D]
+    assert np.all(bits.sum(-1) == T)                                       # exactly T per (token, head)
+    wk = np.where(bits, pr.w, np.inf).min(-1)
+    wp = np.where(~bits, pr.w, -np.inf).max(-1)
+    assert np.all(wk >= wp)                                                # kept >= pruned
+    assert np.all(pr.mu64 <= wk + 1e-15) and np.all(pr.mu64 >= 0)
+    # on equality across the cut, every kept tied channel precedes every pruned tied channel
+    for n, h in zip(*np.nonzero(wk == wp)):
+        tied = np.nonzero(pr.w[n, h] == wk[n, h])[0]
+        kept_t = [j for j in tied if bits[n, h, j]]
+        prun_t = [j for j in tied if not bits[n, h, j]]
+        assert max(kept_t) < min(prun_t)
+    # K-hat holds the original bits of the kept channels, ascending
+    kk = t.k.transpose(1, 0, 2)
+    for n in (0, 5, w.total - 1):
+        for h in range(w.n_kv_heads):
+            assert np.array_equal(pr.kept[n, h], kk[n, h][bits[n, h]])
+    # recovery consistency: a_j * ktilde_tj == mu_t for pruned entries (checked through the
+    # literal decode in test_exact_recovery...); here: gap is the margin at the cut
+    srt = -np.sort(-pr.w.astype(np.float64), axis=-1)
+    assert np.allclose(pr.gap, (srt[..., T - 1] - srt[..., T]) / srt[..., T - 1], rtol=0, atol=1e-15)
+
+
+def test_ties_and_zero_rows_keep_lowest_channels():
+    D, T = 128, 26
+    k = np.zeros((3, 1, D), np.float32)
+    k[1] = 1.0                       # every saliency equal
+    k[2, 0, 100:] = 2.0              # 28 large equal values, 26 kept -> channels 100..125
+    a32 = np.ones((1, 1, D), np.float32)
+    pr = oracle.prune(bf(k), "NHD", a32, np.array([0, 3], np.int32), T)
+    assert _kept_channels(pr.mask[0, 0], D) == list(range(26))
+    assert _kept_channels(pr.mask[1, 0], D) == list(range(26))
+    assert _kept_channels(pr.mask[2, 0], D) == list(range(100, 126))
+    assert pr.near_ties() == 3
+
+
+# ------------------------------------------------------------------ recovery pins
+
+def test_exact_recovery_construction_equals_dense_attention():
+    """If every pruned entry already equals +mu/a, K-tilde == K and SparK is lossless."""
+    rng = np.random.default_rng(7)
+    B, Hq, Hkv, D, S = 2, 4, 2, 128, 50
+    G = Hq // Hkv
+    # window of one query whose entries are +-2^e  => a is a power of two per channel
+    e = rng.integers(-2, 3, size=(B, Hkv, D))
+    sign = rng.choice([-1.0, 1.0], size=(B, Hq, 1, D))
+    qwin = sign * np.exp2(np.repeat(e, G, axis=1))[:, :, None, :]
+    cu = np.array([0, S, 2 * S], np.int32)
+    for T in (1, 26, 64, 127):
+        k = np.empty((2 * S, Hkv, D), np.float32)
+        for n in range(2 * S):
+            b = n // S
+            for h in range(Hkv):
+                a = np.exp2(e[b, h])
+                m = np.exp2(rng.integers(-6, -2))                    # the row's pruned saliency
+                keep = rng.choice(D, size=T, replace=False)
+                row = m / a                                          # pruned entries: + mu / a
+                big = rng.choice([-1.0, 1.0], size=T) * rng.integers(2, 9, size=T) * m / a[keep]
+                row[keep] = big                                      # kept: saliency >= 2m
+                k[n, h] = row
+        kb, vb = _bits(k), bf(rng.standard_normal((2 * S, Hkv, D)).astype(np.float32))
+        qb = bf(rng.standard_normal((B, Hq, D)).astype(np.float32))
+        _, _, a32 = oracle.window_stat(_bits(qwin), Hkv)
+        assert np.array_equal(a32, np.exp2(e).astype(np.float32))
+        pr = oracle.prune(kb, "NHD", a32, cu, T)
+        dense = oracle.dense_attn(qb, kb, vb, "NHD", cu)
+        assert np.allclose(oracle.decode_literal(qb, pr, vb, "NHD", cu), dense, rtol=0, atol=1e-13)
+        assert np.allclose(oracle.decode_fused(qb, pr, vb, "NHD", cu), dense, rtol=0, atol=1e-11)
+
+
+def test_recovered_entries_are_nonnegative_mu_over_a():
+    """Lossy case: flipping the sign of a pruned key entry cannot change the output
+    (the method stores no sign), while flipping a kept entry must."""
+    w, t = _random_small(4, T=26)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    base = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
+    bits = np.unpackbits(pr.mask.view(np.uint8), axis=-1, bitorder="little").astype(bool)
+    k2 = t.k.copy()
+    flip = ~bits.transpose(1, 0, 2)                    # pruned entries, [Hkv,total,D]
+    k2[flip] ^= np.uint16(0x8000)
+    pr2 = oracle.prune(k2, t.layout, a32, t.cu, w.keep)
+    assert np.array_equal(pr2.mask, pr.mask)
+    assert np.array_equal(oracle.decode_literal(t.q, pr2, t.v, t.layout, t.cu), base)
+    k3 = t.k.copy()
+    k3[~flip] ^= np.uint16(0x8000)
+    pr3 = oracle.prune(k3, t.layout, a32, t.cu, w.keep)
+    assert np.array_equal(pr3.mask, pr.mask)
+    assert np.abs(oracle.decode_literal(t.q, pr3, t.v, t.layout, t.cu) - base).max() > 1e-3
+
+
+def test_zero_weight_channel_recovers_to_zero():
+    w, t = _random_small(5, Hq=2, Hkv=2, T=26)
+    qw = t.qwin.copy()
+    qw[:, :, :, 3] = 0            # channel 3: window mean 0 -> a = 0 -> saliency 0 -> always pruned
+    _, _, a32 = oracle.window_stat(qw, w.n_kv_heads)
+    assert np.all(a32[:, :, 3] == 0)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    assert not np.any(pr.mask[..., 0] & np.uint32(8))
+    out = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
+    assert np.all(np.isfinite(out))
+    q2 = t.q.copy()
+    q2[:, :, 3] = bf(np.float32(1000.0))      # the decode query's channel 3 meets a recovered 0
+    assert np.allclose(oracle.decode_literal(q2, pr, t.v, t.layout, t.cu), out, rtol=0, atol=1e-13)
+    assert np.allclose(oracle.decode_fused(t.q, pr, t.v, t.layout, t.cu), out, rtol=0, atol=1e-11)
+
+
+def test_window_scale_invariance():
+    w, t = _random_small(6, T=38)
+    _, _, a1 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    qw4 = bf(fb(t.qwin) * np.float32(4.0))
+    _, _, a4 = oracle.window_stat(qw4, w.n_kv_heads)
+    p1 = oracle.prune(t.k, t.layout, a1, t.cu, w.keep)
+    p4 = oracle.prune(t.k, t.layout, a4, t.cu, w.keep)
+    assert np.array_equal(p1.mask, p4.mask) and np.array_equal(p4.mu32, 4 * p1.mu32)
+    o1 = oracle.decode_literal(t.q, p1, t.v, t.layout, t.cu)
+    o4 = oracle.decode_literal(t.q, p4, t.v, t.layout, t.cu)
+    assert np.array_equal(o1, o4)
+
+
+# ------------------------------------------------------------------ softmax / PV pins
+
+def test_softmax_rows_and_convexity_and_permutation():
+    w, t = _random_small(8, B=1, seqlens=(120,), T=26)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    out, probs = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu, want_probs=True)
+    assert np.allclose(probs.sum(-1), 1.0, rtol=0, atol=1e-14) and np.all(probs >= 0)
+    vf = fb(t.v).astype(np.float64)
+    G = w.n_q_heads // w.n_kv_heads
+    for g in range(w.n_q_heads):
+        assert np.all(out[0, g] <= vf[g // G].max(0) + 1e-14)
+        assert np.all(out[0, g] >= vf[g // G].min(0) - 1e-14)
+    perm = np.random.default_rng(0).permutation(w.total)
+    k2, v2 = np.ascontiguousarray(t.k[:, perm]), np.ascontiguousarray(t.v[:, perm])
+    pr2 = oracle.prune(k2, t.layout, a32, t.cu, w.keep)
+    assert np.array_equal(pr2.mask, pr.mask[perm])
+    out2 = oracle.decode_literal(t.q, pr2, v2, t.layout, t.cu)
+    assert np.allclose(out2, out, rtol=0, atol=1e-13)
+
+
+def test_literal_and_fused_forms_agree_and_ragged_batches_are_independent():
+    w, t = _random_small(9, B=3, seqlens=(64, 1, 130), T=25)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    lit = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
+    fus = oracle.decode_fused(t.q, pr, t.v, t.layout, t.cu)
+    assert np.abs(lit - fus).max() < 1e-11
+    # a sequence of length 1 attends to its only token: output is that V row exactly
+    vf = fb(t.v).astype(np.float64)
+    G = w.n_q_heads // w.n_kv_heads
+    for g in range(w.n_q_heads):
+        assert np.array_equal(lit[1, g], vf[g // G, 64])
+    # running one sequence alone gives the same rows
+    sl = slice(65, 195)
+    _, _, a_b = oracle.window_stat(t.qwin[2:3], w.n_kv_heads)
+    pr_b = oracle.prune(np.ascontiguousarray(t.k[:, sl]), "HND", a_b, np.array([0, 130], np.int32), 25)
+    alone = oracle.decode_literal(t.q[2:3], pr_b, np.ascontiguousarray(t.v[:, sl]), "HND",
+                                  np.array([0, 130], np.int32))
+    assert np.array_equal(alone[0], lit[2])
+
+
+def test_empty_sequence_gives_zero_output():
+    w, t = _random_small(10, B=2, seqlens=(0, 33), T=26)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    out = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
+    assert np.all(out[0] == 0) and np.all(np.isfinite(out[1])) and np.any(out[1] != 0)
+
+
+# ------------------------------------------------------------------ int8 storage variant
+
+def test_int8_variant_closed_form_properties():
+    w, t = _random_small(12, T=26)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    pq = oracle.quant_int8(pr)
+    kf = fb(pr.kept).astype(np.float64)
+    amax = np.abs(kf).max(-1)
+    assert np.array_equal(pq.scale, (amax.astype(np.float32) / np.float32(127)).astype(np.float32))
+    imax = np.abs(kf).argmax(-1)
+    cmax = np.take_along_axis(pq.codes, imax[..., None], -1)[..., 0]
+    assert np.all(np.abs(cmax.astype(int)) == 127)
+    deq = pq.codes.astype(np.float64) * pq.scale.astype(np.float64)[..., None]
+    # half a step, plus the binary32 rounding of the quotient (|k/scale| <= 127, eps = 2^-24)
+    assert np.all(np.abs(deq - kf) <= pq.scale[..., None] * (0.5 + 127 * 2.0 ** -23))
+    assert np.all(np.sign(pq.codes) * np.sign(kf) >= 0)
+    # score perturbation bound: |ds| <= scale/2 * sum_kept |q_j| / sqrt(D); outputs stay close
+    # hence every probability moves by at most a factor exp(+-2 * max_t |ds|)
+    o_b, p_b = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu, want_probs=True)
+    o_q, p_q = oracle.decode_literal(t.q, pq, t.v, t.layout, t.cu, want_probs=True)
+    assert np.abs(o_b - o_q).max() > 0
+    G = w.n_q_heads // w.n_kv_heads
+    qabs = np.abs(fb(t.q).astype(np.float64)).sum(-1) / math.sqrt(w.head_dim)     # [B,Hq]
+    for b in range(w.batch):
+        sl = slice(int(t.cu[b]), int(t.cu[b + 1]))
+        for g in range(w.n_q_heads):
+            ds = (0.5 + 127 * 2.0 ** -23) * pq.scale[sl, g // G].astype(np.float64).max() * qabs[b, g]
+            ratio = p_q[g, sl] / p_b[g, sl]
+            assert np.all(ratio <= math.exp(2 * ds) * (1 + 1e-12))
+            assert np.all(ratio >= math.exp(-2 * ds) * (1 - 1e-12))
+    zero = oracle.Pruned(pr.mask[:1], np.zeros_like(pr.kept[:1]), pr.mu64[:1], pr.mu32[:1],
+                         pr.gap[:1], pr.a32, None, pr.T, pr.D)
+    zq = oracle.quant_int8(zero)
+    assert np.all(zq.scale == 0) and np.all(zq.codes == 0)
