@@ -1,0 +1,149 @@
+/*
+ * spark.h -- C ABI of the MI355X (gfx950) SparK hot path.
+ *
+ * SparK ("Query-Aware Unstructured Sparsity with Recoverable KV Cache Channel Pruning")
+ * prunes the key cache along the channel axis, per token and per head, at prefill, and
+ * restores the pruned entries from one cached statistic while the attention scores are
+ * computed at decode.  This library is that data path on one GPU:
+ *
+ *   spark_prune        prefill:  saliency -> per-token top-T channels -> packed key cache
+ *   spark_decode_attn  decode:   one attention step that reads only the packed keys and
+ *                                the dense values
+ *   spark_unpack       parity / debugging: canonical export of the opaque packed cache
+ *
+ * Conventions for every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller unless it is a `const
+ *     spark_desc *` (host) or documented otherwise.  The library never allocates, frees or
+ *     retains device memory; callers size buffers with the query functions below.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) and the call returns after the launches; the library never synchronises.
+ *   - Failure is a return code.  Arguments are checked on the host before anything is
+ *     launched; a launch error reported by the runtime becomes SPARK_ERR_HIP.  No
+ *     exceptions, no global state; calls on distinct streams and buffers are thread safe.
+ *   - bfloat16 tensors are raw 16-bit patterns.  Channel stride is 1 everywhere; token and
+ *     head strides are in ELEMENTS: K[n,h,j] = k[n*k_token_stride + h*k_head_stride + j]
+ *     for global token n in [0,total_tokens), likewise V.  Rows must be 16-byte aligned
+ *     (strides multiples of 8, base pointers 16-byte aligned).
+ *   - Sequences are ragged: cu_seqlens[b] .. cu_seqlens[b+1] are the global token indices
+ *     of batch element b (int32 [batch+1], cu_seqlens[0] = 0, cu_seqlens[batch] =
+ *     total_tokens).  Query head g reads KV head g / (n_q_heads / n_kv_heads).
+ */
+#ifndef SPARK_H
+#define SPARK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPARK_OK = 0,
+    SPARK_ERR_INVALID_ARG = 1,      /* NULL pointer, non-positive size, bad stride/alignment */
+    SPARK_ERR_UNSUPPORTED = 2,      /* head_dim != 128, group size not in {1,2,4,8,16}, ... */
+    SPARK_ERR_WORKSPACE_TOO_SMALL = 3,
+    SPARK_ERR_HIP = 4               /* the HIP runtime reported an error at launch */
+} spark_status;
+
+typedef enum { SPARK_PACK_BF16 = 0, SPARK_PACK_INT8 = 1 } spark_pack_dtype;
+typedef enum { SPARK_OUT_BF16 = 0, SPARK_OUT_F32 = 1 } spark_out_dtype;
+
+/* Problem description shared by all calls (plain data, host memory). */
+typedef struct spark_desc {
+    int32_t batch;            /* B >= 1 */
+    int32_t n_q_heads;        /* Hq, a multiple of n_kv_heads; Hq/Hkv in {1,2,4,8,16} */
+    int32_t n_kv_heads;       /* Hkv >= 1 */
+    int32_t head_dim;         /* D, must be 128 */
+    int32_t keep;             /* T in [1, D]: channels kept per (token, KV head).  An integer,
+                                 not a ratio: the paper's T = floor((1 - lambda) * D). */
+    int32_t window;           /* W >= 1: observation-window length (spark_prune only) */
+    int32_t pack_dtype;       /* spark_pack_dtype: storage of the kept key entries */
+    int32_t out_dtype;        /* spark_out_dtype: element type of spark_decode_attn's output */
+    int64_t total_tokens;     /* sum of sequence lengths, < 2^31 */
+    int64_t k_token_stride, k_head_stride;    /* dense K (spark_prune only) */
+    int64_t v_token_stride, v_head_stride;    /* dense V (spark_decode_attn only) */
+    float   softmax_scale;    /* 0 => 1/sqrt(head_dim) */
+    int32_t n_splits;         /* sequence splits per (batch, KV head) in decode; 0 => library picks.
+                                 Must be the same for the workspace query and the call. */
+} spark_desc;
+
+/* Size in bytes of the packed key cache for this description (depends on batch, n_kv_heads,
+ * keep, pack_dtype, total_tokens).  0 if the description is invalid. */
+size_t spark_packed_bytes(const spark_desc *desc);
+
+/* Scratch sizes in bytes (0 is possible; then NULL may be passed as the workspace). */
+size_t spark_prune_workspace(const spark_desc *desc);
+size_t spark_decode_workspace(const spark_desc *desc);
+
+/* Number of sequence splits spark_decode_attn will use for this description. */
+int32_t spark_decode_splits(const spark_desc *desc);
+
+/*
+ * Prefill-time channel pruning of the key cache.
+ * [Sec. "Problem Formulation and Analysis", Eq. (7) and the greedy Top_T solution;
+ *  Sec. "SparK", mean query over the observation window, "Saliency Measurement and
+ *  Unstructured Pruning"; App. "Caching Pruned Channel Statistics", mean over the pruned set]
+ *
+ *   qbar[b,g,:] = mean over the W window queries of head g
+ *   a[b,h,j]    = mean over the heads g of KV head h of |qbar[b,g,j]|   (float64, rounded to float32)
+ *   w[n,h,j]    = a[b,h,j] * |K[n,h,j]|                                 (one float32 multiply)
+ *   kept(n,h)   = the T channels of largest w; equal w: lower channel first
+ *   mu[n,h]     = mean of w over the D-T pruned channels (0 if T == D)
+ * and writes, per (token, KV head): the 128-bit channel mask, the kept entries (original
+ * bf16 bits, ascending channel; or int8 codes = round(k / scale), scale = max|k| / 127, for
+ * SPARK_PACK_INT8) and mu, plus a per (batch, KV head); all inside `packed_out`.
+ *
+ *   k_bf16     in   dense keys, bf16, addressed with k_*_stride
+ *   qwin_bf16  in   [batch, n_q_heads, window, 128] bf16, contiguous
+ *   cu_seqlens in   int32 [batch+1]
+ *   packed_out out  spark_packed_bytes(desc) bytes, 256-byte aligned; fully overwritten
+ *   workspace       spark_prune_workspace(desc) bytes (may be NULL when that is 0)
+ * Every token given is pruned, window tokens included.  V is not touched.
+ */
+spark_status spark_prune(const spark_desc *desc, const void *k_bf16, const void *qwin_bf16,
+                         const int32_t *cu_seqlens, void *packed_out, void *workspace,
+                         size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One decode step of attention over the packed key cache.
+ * [Sec. "SparK", "Channel Recovery" with the degenerate recovery function
+ *  ktilde[n,h,j] = mu[n,h] / a[b,h,j] for pruned entries; Sec. "Preliminaries", Eq. (4)]
+ *
+ *   s[g,n]  = scale * ( sum_{j kept} q[g,j] K[n,h,j] + sum_{j pruned} q[g,j] mu[n,h]/a[b,h,j] )
+ *   out[b,g,:] = sum_n softmax_n(s[g,:])[n] * V[n,h,:]       over the tokens n of sequence b
+ * (a[b,h,j] == 0 recovers 0).  The dense K-tilde is never written to memory.  A sequence of
+ * length 0 gives a zero output row.
+ *
+ *   q_bf16     in   [batch, n_q_heads, 128] bf16, contiguous
+ *   packed     in   written by spark_prune with the same batch / n_kv_heads / keep /
+ *                   pack_dtype / total_tokens and the same cu_seqlens
+ *   v_bf16     in   dense values, bf16, addressed with v_*_stride
+ *   out        out  [batch, n_q_heads, 128], bf16 or float32 per desc->out_dtype
+ *   workspace       spark_decode_workspace(desc) bytes, 16-byte aligned (split partials)
+ */
+spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const void *packed,
+                               const void *v_bf16, const int32_t *cu_seqlens, void *out,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Canonical export of a packed cache, for parity tests and debugging (not a hot path).
+ * Any output pointer may be NULL to skip it.
+ *   mask_out  uint32 [total_tokens, n_kv_heads, 4]   bit j%32 of word j/32 = channel j kept
+ *   vals_out  [total_tokens, n_kv_heads, keep]       kept entries, ascending channel:
+ *                                                    uint16 bf16 bits, or int8 codes
+ *   mu_out    float  [total_tokens, n_kv_heads]
+ *   scale_out float  [total_tokens, n_kv_heads]      int8 scales (SPARK_PACK_INT8 only)
+ *   a_out     float  [batch, n_kv_heads, 128]
+ */
+spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *mask_out,
+                          void *vals_out, float *mu_out, float *scale_out, float *a_out,
+                          void *hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *spark_status_string(spark_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARK_H */

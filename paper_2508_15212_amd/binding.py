@@ -1,0 +1,123 @@
+"""ctypes binding of the C ABI declared in ``include/spark.h``.
+
+Argument marshalling only: tensors are torch device tensors used as raw device memory
+(``data_ptr()``), the stream is torch's current HIP stream.  There is no fallback: if the
+shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libspark_hip.so")
+
+PACK_BF16, PACK_INT8 = 0, 1
+OUT_BF16, OUT_F32 = 0, 1
+
+EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspace", "spark_decode_splits",
+           "spark_prune", "spark_decode_attn", "spark_unpack", "spark_status_string"]
+
+
+class SparkError(RuntimeError):
+    pass
+
+
+class SparkDesc(ctypes.Structure):
+    """Mirror of ``struct spark_desc``."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("keep", ctypes.c_int32), ("window", ctypes.c_int32),
+        ("pack_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+        ("total_tokens", ctypes.c_int64),
+        ("k_token_stride", ctypes.c_int64), ("k_head_stride", ctypes.c_int64),
+        ("v_token_stride", ctypes.c_int64), ("v_head_stride", ctypes.c_int64),
+        ("softmax_scale", ctypes.c_float), ("n_splits", ctypes.c_int32),
+    ]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise SparkError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                         "(or paper_2508_15212_amd/build.py) first; there is no fallback path")
+    lib = ctypes.CDLL(_LIB_PATH)
+    dp = ctypes.POINTER(SparkDesc)
+    vp = ctypes.c_void_p
+    lib.spark_packed_bytes.restype = ctypes.c_size_t
+    lib.spark_packed_bytes.argtypes = [dp]
+    lib.spark_prune_workspace.restype = ctypes.c_size_t
+    lib.spark_prune_workspace.argtypes = [dp]
+    lib.spark_decode_workspace.restype = ctypes.c_size_t
+    lib.spark_decode_workspace.argtypes = [dp]
+    lib.spark_decode_splits.restype = ctypes.c_int32
+    lib.spark_decode_splits.argtypes = [dp]
+    lib.spark_prune.restype = ctypes.c_int
+    lib.spark_prune.argtypes = [dp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.spark_decode_attn.restype = ctypes.c_int
+    lib.spark_decode_attn.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.spark_unpack.restype = ctypes.c_int
+    lib.spark_unpack.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
+    lib.spark_status_string.restype = ctypes.c_char_p
+    lib.spark_status_string.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise SparkError(f"{what}: {load().spark_status_string(rc).decode()} (status {rc})")
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else int(t.data_ptr())
+
+
+def packed_bytes(desc: SparkDesc) -> int:
+    return int(load().spark_packed_bytes(ctypes.byref(desc)))
+
+
+def decode_workspace_bytes(desc: SparkDesc) -> int:
+    return int(load().spark_decode_workspace(ctypes.byref(desc)))
+
+
+def decode_splits(desc: SparkDesc) -> int:
+    return int(load().spark_decode_splits(ctypes.byref(desc)))
+
+
+def prune(desc: SparkDesc, k: torch.Tensor, qwin: torch.Tensor, cu: torch.Tensor,
+          packed: torch.Tensor) -> None:
+    """spark_prune: k, qwin bf16-bit tensors on the device; packed a uint8 buffer of packed_bytes()."""
+    ws_bytes = int(load().spark_prune_workspace(ctypes.byref(desc)))
+    assert ws_bytes == 0
+    rc = load().spark_prune(ctypes.byref(desc), _ptr(k), _ptr(qwin), _ptr(cu), _ptr(packed), None, 0, _stream())
+    _check(rc, "spark_prune")
+
+
+def decode_attn(desc: SparkDesc, q: torch.Tensor, packed: torch.Tensor, v: torch.Tensor, cu: torch.Tensor,
+                out: torch.Tensor, workspace: torch.Tensor) -> None:
+    rc = load().spark_decode_attn(ctypes.byref(desc), _ptr(q), _ptr(packed), _ptr(v), _ptr(cu), _ptr(out),
+                                  _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "spark_decode_attn")
+
+
+def unpack(desc: SparkDesc, packed: torch.Tensor, mask=None, vals=None, mu=None, scale=None, a=None) -> None:
+    rc = load().spark_unpack(ctypes.byref(desc), _ptr(packed), _ptr(mask), _ptr(vals), _ptr(mu), _ptr(scale),
+                             _ptr(a), _stream())
+    _check(rc, "spark_unpack")

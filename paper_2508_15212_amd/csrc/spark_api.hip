@@ -1,0 +1,162 @@
+// C ABI of the library (see include/spark.h): argument checks on the host, buffer sizing,
+// kernel launches on the caller's stream.  Nothing here allocates or synchronises.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/spark.h"
+#include "spark_kernels.h"
+#include "spark_layout.h"
+
+namespace {
+
+bool desc_ok(const spark_desc *d, spark_status *why)
+{
+    *why = SPARK_ERR_INVALID_ARG;
+    if (!d) return false;
+    if (d->batch < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1) return false;
+    if (d->total_tokens < 0 || d->total_tokens >= (int64_t)1 << 31) return false;
+    if (d->keep < 1 || d->keep > d->head_dim) return false;
+    if (d->n_q_heads % d->n_kv_heads) return false;
+    if (d->n_splits < 0 || d->n_splits > 4096) return false;
+    *why = SPARK_ERR_UNSUPPORTED;
+    if (d->head_dim != SPARK_D) return false;
+    const int G = d->n_q_heads / d->n_kv_heads;
+    if (!(G == 1 || G == 2 || G == 4 || G == 8 || G == 16)) return false;
+    if (d->pack_dtype != SPARK_PACK_BF16 && d->pack_dtype != SPARK_PACK_INT8) return false;
+    if (d->out_dtype != SPARK_OUT_BF16 && d->out_dtype != SPARK_OUT_F32) return false;
+    *why = SPARK_OK;
+    return true;
+}
+
+SparkLayout layout_of(const spark_desc *d)
+{
+    return spark_make_layout(d->keep, d->pack_dtype == SPARK_PACK_INT8, d->batch, d->n_kv_heads, d->total_tokens);
+}
+
+bool strides_ok(int64_t tok, int64_t head)
+{
+    return tok >= SPARK_D && head >= SPARK_D && tok % 8 == 0 && head % 8 == 0;
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Splits per (batch, KV head): enough blocks to cover the chip a few times over, but at least
+// four tiles (256 tokens) per wavefront of a block on an average-length sequence.
+int pick_splits(const spark_desc *d)
+{
+    if (d->n_splits > 0) return d->n_splits;
+    const int64_t pairs = (int64_t)d->batch * d->n_kv_heads;
+    const int64_t avg_tiles = (d->total_tokens / d->batch + SPARK_TILE_TOKENS - 1) / SPARK_TILE_TOKENS;
+    int64_t want = (2048 + pairs - 1) / pairs;
+    int64_t cap = avg_tiles / 16;
+    if (cap < 1) cap = 1;
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    if (want > 4096) want = 4096;
+    return (int)want;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *spark_status_string(spark_status s)
+{
+    switch (s) {
+        case SPARK_OK: return "ok";
+        case SPARK_ERR_INVALID_ARG: return "invalid argument";
+        case SPARK_ERR_UNSUPPORTED: return "unsupported configuration";
+        case SPARK_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case SPARK_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+size_t spark_packed_bytes(const spark_desc *desc)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return 0;
+    return (size_t)layout_of(desc).total_bytes;
+}
+
+size_t spark_prune_workspace(const spark_desc *desc)
+{
+    (void)desc;
+    return 0;
+}
+
+int32_t spark_decode_splits(const spark_desc *desc)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return 0;
+    return pick_splits(desc);
+}
+
+size_t spark_decode_workspace(const spark_desc *desc)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return 0;
+    const size_t slots = (size_t)desc->batch * desc->n_q_heads * pick_splits(desc);
+    return slots * (SPARK_D + 2) * sizeof(float);
+}
+
+spark_status spark_prune(const spark_desc *desc, const void *k_bf16, const void *qwin_bf16,
+                         const int32_t *cu_seqlens, void *packed_out, void *workspace, size_t workspace_bytes,
+                         void *hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!k_bf16 || !qwin_bf16 || !cu_seqlens || !packed_out) return SPARK_ERR_INVALID_ARG;
+    if (desc->window < 1) return SPARK_ERR_INVALID_ARG;
+    if (!strides_ok(desc->k_token_stride, desc->k_head_stride)) return SPARK_ERR_INVALID_ARG;
+    if (!aligned(k_bf16, 2) || !aligned(qwin_bf16, 2) || !aligned(packed_out, 256)) return SPARK_ERR_INVALID_ARG;
+    const SparkLayout L = layout_of(desc);
+    const hipError_t e = spark::launch_prune(static_cast<const uint16_t *>(k_bf16), desc->k_token_stride,
+                                             desc->k_head_stride, static_cast<const uint16_t *>(qwin_bf16),
+                                             cu_seqlens, static_cast<uint8_t *>(packed_out), L, desc->n_q_heads,
+                                             desc->window, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
+}
+
+spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const void *packed, const void *v_bf16,
+                               const int32_t *cu_seqlens, void *out, void *workspace, size_t workspace_bytes,
+                               void *hip_stream)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!q_bf16 || !packed || !v_bf16 || !cu_seqlens || !out || !workspace) return SPARK_ERR_INVALID_ARG;
+    if (!strides_ok(desc->v_token_stride, desc->v_head_stride)) return SPARK_ERR_INVALID_ARG;
+    if (!aligned(v_bf16, 16) || !aligned(packed, 256) || !aligned(workspace, 16) || !aligned(q_bf16, 2) ||
+        !aligned(out, 4))
+        return SPARK_ERR_INVALID_ARG;
+    if (workspace_bytes < spark_decode_workspace(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
+    const SparkLayout L = layout_of(desc);
+    const int nsplit = pick_splits(desc);
+    const size_t slots = (size_t)desc->batch * desc->n_q_heads * nsplit;
+    float *part_acc = static_cast<float *>(workspace);
+    float *part_ml = part_acc + slots * SPARK_D;
+    const float scale = desc->softmax_scale != 0.0f ? desc->softmax_scale : 1.0f / sqrtf((float)SPARK_D);
+    const hipError_t e = spark::launch_decode_attn(
+        static_cast<const uint16_t *>(q_bf16), static_cast<const uint8_t *>(packed),
+        static_cast<const uint16_t *>(v_bf16), desc->v_token_stride, desc->v_head_stride, cu_seqlens, part_acc,
+        part_ml, desc->n_q_heads, nsplit, scale, L, out, desc->out_dtype == SPARK_OUT_F32,
+        static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
+}
+
+spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *mask_out, void *vals_out,
+                          float *mu_out, float *scale_out, float *a_out, void *hip_stream)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!packed) return SPARK_ERR_INVALID_ARG;
+    const SparkLayout L = layout_of(desc);
+    const hipError_t e = spark::launch_unpack(static_cast<const uint8_t *>(packed), L, mask_out, vals_out, mu_out,
+                                              scale_out, a_out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
+}
+
+}  // extern "C"

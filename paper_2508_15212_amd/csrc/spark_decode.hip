@@ -1,0 +1,406 @@
+// Decode attention over the packed (channel-pruned) key cache for gfx950 (wave64).
+//
+// [Sec. "SparK", "Channel Recovery": pruned entry (n, j) is rebuilt as mu_n / a_j (the
+//  degenerate recovery function) and the scores are those of standard attention on the
+//  rebuilt keys; Sec. "Preliminaries", Eq. (4): softmax over the cached tokens, then P V.]
+//
+// The rebuilt key row is never formed.  With d_nj = k_nj - mu_n / a_j for kept channels,
+//     <q_g, ktilde_n> = sum_{j kept} q_gj d_nj + mu_n * R_g,   R_g = sum_j q_gj / a_j,
+// so a token costs T gathers from a 128-entry table {q_0j .. q_(G-1)j, 1/a_j} held in LDS.
+//
+// Work decomposition: one block of 4 wavefronts per (batch, KV head, sequence split); each
+// wavefront streams whole tiles of 64 tokens.  Per tile:
+//   1. lane = token: read the packed row (coalesced, see spark_layout.h), walk its mask
+//      bits, accumulate the G scores of the KV head's query group in float32;
+//   2. online softmax per query head (running maximum m, per-lane partial sums l);
+//   3. probabilities go through LDS into the A operand of the 16x16x32 bf16 MFMA (rows =
+//      query heads, K = tokens), split into a high and a low bf16 part so P keeps ~16
+//      significant bits; V rows are read 16 bytes per lane, transposed in registers with
+//      byte permutes into B operands (K = tokens, N = channels) and accumulated in float32.
+// Split partials (m, l, unnormalised output) are merged by spark_combine_kernel.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "spark_kernels.h"
+#include "spark_layout.h"
+
+namespace spark {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct DecodeParams {
+    const uint16_t *q;       // [B, Hq, 128] bf16
+    const uint8_t *packed;   // packed key cache
+    const uint16_t *v;       // dense values
+    int64_t v_tok_stride, v_head_stride;
+    const int32_t *cu;       // [B+1]
+    float *part_acc;         // [B*Hq*nsplit][128]
+    float *part_ml;          // [B*Hq*nsplit][2]  (m in log2 units, l)
+    int Hq, Hkv, nsplit;
+    float scale_log2;        // softmax scale * log2(e)
+    SparkLayout L;
+};
+
+constexpr int kDecodeWaves = 4;
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    // LDS operations of one wavefront execute in order; this only stops the compiler from
+    // moving accesses across the point where lanes exchange data through LDS.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+__device__ __forceinline__ uint32_t u4c(const uint4 &v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+template <int G, int TCT, int INT8>
+__global__ __launch_bounds__(kDecodeWaves * 64) void spark_decode_kernel(DecodeParams P)
+{
+    constexpr int GP = ((G + 1 + 3) / 4) * 4;   // floats per table entry: G queries, 1/a, pad
+    constexpr int VAL0 = INT8 ? 6 : 5;
+    constexpr int NV_CT = INT8 ? (TCT + 3) / 4 : (TCT + 1) / 2;
+    constexpr int NDW_CT = (VAL0 + NV_CT + 1) & ~1;
+    constexpr int NQ_CT = NDW_CT / 4;
+
+    __shared__ __align__(16) float qtab[SPARK_D * GP];
+    __shared__ float Rsh[16];
+    __shared__ __align__(16) uint16_t Pbuf[kDecodeWaves][2][G][64];
+    __shared__ __align__(16) float red_acc[kDecodeWaves][G][SPARK_D];
+    __shared__ float red_m[kDecodeWaves][G], red_l[kDecodeWaves][G];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const SparkLayout &L = P.L;
+    const int T = TCT ? TCT : L.T;
+    const int split = blockIdx.x % P.nsplit;
+    const int bh = blockIdx.x / P.nsplit;
+    const int h = bh % P.Hkv, b = bh / P.Hkv;
+    const int s0 = P.cu[b], s1 = P.cu[b + 1];
+
+    // ---- per-step query prep: table {q_g[j] * scale * log2e, 1/a[j]} and R_g
+    if (tid < SPARK_D) {
+        const int j = tid;
+        const float inva = reinterpret_cast<const float *>(P.packed + L.off_inva)[((int64_t)b * P.Hkv + h) * SPARK_D + j];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            qtab[j * GP + g] = bf16lo(P.q[((int64_t)b * P.Hq + h * G + g) * SPARK_D + j]) * P.scale_log2;
+        qtab[j * GP + G] = inva;
+#pragma unroll
+        for (int g = G + 1; g < GP; ++g) qtab[j * GP + g] = 0.0f;
+    }
+    __syncthreads();
+    for (int g = wave; g < G; g += kDecodeWaves) {
+        float r = qtab[lane * GP + g] * qtab[lane * GP + G] +
+                  qtab[(lane + 64) * GP + g] * qtab[(lane + 64) * GP + G];
+        r = wave_sum(r);
+        if (lane == 0) Rsh[g] = r;
+    }
+    __syncthreads();
+    float R[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) R[g] = Rsh[g];
+
+    // ---- tiles of this split
+    int t_begin = 0, t_end = 0;
+    if (s1 > s0) {
+        const int tf = s0 / SPARK_TILE_TOKENS, tl = (s1 - 1) / SPARK_TILE_TOKENS;
+        const int ntile = tl - tf + 1;
+        const int chunk = (ntile + P.nsplit - 1) / P.nsplit;
+        t_begin = tf + split * chunk;
+        t_end = t_begin + chunk;
+        if (t_end > tl + 1) t_end = tl + 1;
+    }
+
+    float m[G], l[G];
+    f32x4 acc[8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.0f; }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int tg = lane >> 4, cn = lane & 15;
+    const uint8_t *tiles = P.packed + L.off_tiles + (int64_t)h * L.n_tiles * L.tile_bytes;
+    const uint16_t *vbase = P.v + (int64_t)h * P.v_head_stride + cn * 8;
+
+    for (int tile = t_begin + wave; tile < t_end; tile += kDecodeWaves) {
+        const uint8_t *tp = tiles + (int64_t)tile * L.tile_bytes;
+        const int n_lane = tile * SPARK_TILE_TOKENS + lane;
+        const bool valid = (n_lane >= s0) && (n_lane < s1);
+
+        // ---- issue the loads: packed row of this lane's token, then 16 V row segments
+        uint32_t r[TCT ? NDW_CT : 6];
+        if (TCT) {
+#pragma unroll
+            for (int qd = 0; qd < NQ_CT; ++qd) {
+                const uint4 x = *reinterpret_cast<const uint4 *>(tp + qd * 1024 + lane * 16);
+                r[4 * qd + 0] = x.x; r[4 * qd + 1] = x.y; r[4 * qd + 2] = x.z; r[4 * qd + 3] = x.w;
+            }
+            if (NDW_CT % 4) {
+                const uint2 x = *reinterpret_cast<const uint2 *>(tp + NQ_CT * 1024 + lane * 8);
+                r[4 * NQ_CT + 0] = x.x; r[4 * NQ_CT + 1] = x.y;
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < 6; ++d)
+                r[d] = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, d));
+        }
+        uint4 vr[2][8];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int n = tile * SPARK_TILE_TOKENS + 32 * ks + 8 * tg + i;
+                n = (n < s0) ? s0 : n;
+                n = (n > s1 - 1) ? (s1 - 1) : n;     // rows outside the sequence get p = 0
+                vr[ks][i] = *reinterpret_cast<const uint4 *>(vbase + (int64_t)n * P.v_tok_stride);
+            }
+
+        // ---- scores, lane = token
+        const float mu = __uint_as_float(r[4]);
+        float s[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) s[g] = 0.0f;
+        {
+            uint64_t cur = ((uint64_t)r[1] << 32) | r[0];
+            const uint64_t upper = ((uint64_t)r[3] << 32) | r[2];
+            const int clo = __popc(r[0]) + __popc(r[1]);
+            int jb = 0;
+            float scale_row = 1.0f;
+            if (INT8) scale_row = __uint_as_float(r[5]);
+            uint32_t vw = 0;
+            auto entry = [&](int i, uint32_t word) {
+                const bool sw = (i == clo);          // first entry of channels 64..127
+                cur = sw ? upper : cur;
+                jb = sw ? 64 : jb;
+                const int j = (__ffsll((unsigned long long)cur) - 1 + jb) & (SPARK_D - 1);
+                cur &= cur - 1;
+                float kv;
+                if (INT8)
+                    kv = (float)(int)(int8_t)((word >> (8 * (i & 3))) & 0xFF) * scale_row;
+                else
+                    kv = (i & 1) ? bf16hi(word) : bf16lo(word);
+                const float *e = &qtab[j * GP];
+                const float d = fmaf(-mu, e[G], kv);
+#pragma unroll
+                for (int g = 0; g < G; ++g) s[g] = fmaf(e[g], d, s[g]);
+            };
+            if (TCT) {
+#pragma unroll
+                for (int i = 0; i < TCT; ++i) entry(i, r[VAL0 + (INT8 ? i / 4 : i / 2)]);
+            } else {
+                for (int i = 0; i < T; ++i) {
+                    const int per = INT8 ? 4 : 2;
+                    if (i % per == 0)
+                        vw = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, VAL0 + i / per));
+                    entry(i, vw);
+                }
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            s[g] = fmaf(mu, R[g], s[g]);
+            s[g] = valid ? s[g] : -INFINITY;
+        }
+
+        // ---- online softmax (log2 domain) and P -> LDS as bf16 high + low parts
+        bool rescale = false;
+        float alpha[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float tmax = wave_max(s[g]);
+            const float mnew = fmaxf(m[g], tmax);
+            const float msafe = (mnew == -INFINITY) ? 0.0f : mnew;
+            alpha[g] = fast_exp2(m[g] - msafe);            // m = -inf -> 0
+            rescale = rescale || (mnew != m[g]);
+            m[g] = mnew;
+            const float p = fast_exp2(s[g] - msafe);       // s = -inf -> 0
+            l[g] = fmaf(l[g], alpha[g], p);
+            const __bf16 ph = (__bf16)p;
+            const __bf16 pl = (__bf16)(p - (float)ph);
+            Pbuf[wave][0][g][lane] = __builtin_bit_cast(uint16_t, ph);
+            Pbuf[wave][1][g][lane] = __builtin_bit_cast(uint16_t, pl);
+        }
+        if (rescale) {   // wave-uniform: m is the same in every lane
+            float al[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) al[rr] = 1.0f;
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if ((g >> 2) == tg) al[g & 3] = alpha[g];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) acc[e][rr] *= al[rr];
+        }
+        wave_lds_sync();
+
+        // ---- P V on the matrix cores
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            uint4 ah = {0, 0, 0, 0}, alo = {0, 0, 0, 0};
+            if (cn < G) {
+                ah = *reinterpret_cast<const uint4 *>(&Pbuf[wave][0][cn][32 * ks + 8 * tg]);
+                alo = *reinterpret_cast<const uint4 *>(&Pbuf[wave][1][cn][32 * ks + 8 * tg]);
+            }
+            const bf16x8 A_hi = __builtin_bit_cast(bf16x8, ah);
+            const bf16x8 A_lo = __builtin_bit_cast(bf16x8, alo);
+#pragma unroll
+            for (int cp = 0; cp < 4; ++cp) {
+                u32x4 be, bo;   // channels 2cp and 2cp+1 of this lane's 8: tokens 0..7 along K
+#pragma unroll
+                for (int tp2 = 0; tp2 < 4; ++tp2) {
+                    const uint32_t x = u4c(vr[ks][2 * tp2], cp);
+                    const uint32_t y = u4c(vr[ks][2 * tp2 + 1], cp);
+                    be[tp2] = __builtin_amdgcn_perm(y, x, 0x05040100u);   // low halves  (x | y << 16)
+                    bo[tp2] = __builtin_amdgcn_perm(y, x, 0x07060302u);   // high halves
+                }
+                const bf16x8 B_e = __builtin_bit_cast(bf16x8, be);
+                const bf16x8 B_o = __builtin_bit_cast(bf16x8, bo);
+                acc[2 * cp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_hi, B_e, acc[2 * cp], 0, 0, 0);
+                acc[2 * cp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_lo, B_e, acc[2 * cp], 0, 0, 0);
+                acc[2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_hi, B_o, acc[2 * cp + 1], 0, 0, 0);
+                acc[2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_lo, B_o, acc[2 * cp + 1], 0, 0, 0);
+            }
+        }
+        wave_lds_sync();   // P buffer is rewritten by the next tile
+    }
+
+    // ---- merge the 4 wavefronts, write the split partial
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float lt = wave_sum(l[g]);
+        if (lane == 0) { red_m[wave][g] = m[g]; red_l[wave][g] = lt; }
+    }
+    // accumulator layout: lane (tg, cn), register rr of acc[e] = head 4*tg + rr, channel 8*cn + e
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int g = 4 * tg + rr;
+        if (g < G) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) red_acc[wave][g][8 * cn + e] = acc[e][rr];
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
+        const int g = idx / SPARK_D, ch = idx % SPARK_D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) M = fmaxf(M, red_m[w][g]);
+        const float Ms = (M == -INFINITY) ? 0.0f : M;
+        float Lsum = 0.0f, A = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) {
+            const float f = fast_exp2(red_m[w][g] - Ms);
+            Lsum = fmaf(red_l[w][g], f, Lsum);
+            A = fmaf(red_acc[w][g][ch], f, A);
+        }
+        const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nsplit + split;
+        P.part_acc[slot * SPARK_D + ch] = A;
+        if (ch == 0) { P.part_ml[slot * 2] = M; P.part_ml[slot * 2 + 1] = Lsum; }
+    }
+}
+
+// grid = B*Hq blocks, 128 threads (thread = channel): merge the split partials, normalise.
+__global__ __launch_bounds__(SPARK_D) void spark_combine_kernel(const float *__restrict__ part_acc,
+                                                                const float *__restrict__ part_ml,
+                                                                int nsplit, void *__restrict__ out,
+                                                                int out_f32)
+{
+    const int64_t bq = blockIdx.x;
+    const int ch = threadIdx.x;
+    float M = -INFINITY;
+    for (int i = 0; i < nsplit; ++i) M = fmaxf(M, part_ml[(bq * nsplit + i) * 2]);
+    const float Ms = (M == -INFINITY) ? 0.0f : M;
+    float Lsum = 0.0f, A = 0.0f;
+    for (int i = 0; i < nsplit; ++i) {
+        const float f = fast_exp2(part_ml[(bq * nsplit + i) * 2] - Ms);
+        Lsum = fmaf(part_ml[(bq * nsplit + i) * 2 + 1], f, Lsum);
+        A = fmaf(part_acc[(bq * nsplit + i) * SPARK_D + ch], f, A);
+    }
+    const float o = (Lsum > 0.0f) ? (A / Lsum) : 0.0f;
+    if (out_f32)
+        reinterpret_cast<float *>(out)[bq * SPARK_D + ch] = o;
+    else
+        reinterpret_cast<uint16_t *>(out)[bq * SPARK_D + ch] = __builtin_bit_cast(uint16_t, (__bf16)o);
+}
+
+
+// ---------------------------------------------------------------- host-side launch
+
+template <int G, int TCT, int INT8>
+static hipError_t launch_one(const DecodeParams &P, int nblocks, hipStream_t st)
+{
+    hipLaunchKernelGGL((spark_decode_kernel<G, TCT, INT8>), dim3(nblocks), dim3(kDecodeWaves * 64), 0, st, P);
+    return hipGetLastError();
+}
+
+template <int G>
+static hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
+{
+    const int T = P.L.T;
+    if (P.L.int8) {
+        if (T == 26) return launch_one<G, 26, 1>(P, nblocks, st);
+        return launch_one<G, 0, 1>(P, nblocks, st);
+    }
+    if (T == 26) return launch_one<G, 26, 0>(P, nblocks, st);
+    if (T == 64) return launch_one<G, 64, 0>(P, nblocks, st);
+    return launch_one<G, 0, 0>(P, nblocks, st);
+}
+
+hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const uint16_t *v, int64_t v_tok_stride,
+                              int64_t v_head_stride, const int32_t *cu, float *part_acc, float *part_ml, int Hq,
+                              int nsplit, float softmax_scale, const SparkLayout &L, void *out, int out_f32,
+                              hipStream_t st)
+{
+    DecodeParams P;
+    P.q = q;
+    P.packed = packed;
+    P.v = v;
+    P.v_tok_stride = v_tok_stride;
+    P.v_head_stride = v_head_stride;
+    P.cu = cu;
+    P.part_acc = part_acc;
+    P.part_ml = part_ml;
+    P.Hq = Hq;
+    P.Hkv = L.n_kv_heads;
+    P.nsplit = nsplit;
+    P.scale_log2 = softmax_scale * 1.44269504088896340736f;
+    P.L = L;
+    const int G = P.Hq / P.Hkv;
+    const int nblocks = L.batch * P.Hkv * P.nsplit;
+    hipError_t e;
+    switch (G) {
+        case 1: e = launch_g<1>(P, nblocks, st); break;
+        case 2: e = launch_g<2>(P, nblocks, st); break;
+        case 4: e = launch_g<4>(P, nblocks, st); break;
+        case 8: e = launch_g<8>(P, nblocks, st); break;
+        case 16: e = launch_g<16>(P, nblocks, st); break;
+        default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(spark_combine_kernel, dim3(L.batch * P.Hq), dim3(SPARK_D), 0, st, P.part_acc, P.part_ml,
+                       P.nsplit, out, out_f32);
+    return hipGetLastError();
+}
+
+}  // namespace spark

@@ -1,0 +1,24 @@
+// Internal: launch functions implemented next to their kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "spark_layout.h"
+
+namespace spark {
+
+struct DecodeParams;
+
+hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
+                        const int32_t *cu, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st);
+
+hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *mask_out, void *vals_out,
+                         float *mu_out, float *scale_out, float *a_out, hipStream_t st);
+
+// q [B,Hq,128] bf16; workspace split into part_acc / part_ml by the caller
+hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const uint16_t *v, int64_t v_tok_stride,
+                              int64_t v_head_stride, const int32_t *cu, float *part_acc, float *part_ml, int Hq,
+                              int nsplit, float softmax_scale, const SparkLayout &L, void *out, int out_f32,
+                              hipStream_t st);
+
+}  // namespace spark

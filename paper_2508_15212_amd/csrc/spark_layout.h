@@ -1,0 +1,87 @@
+// Packed key-cache layout shared by the prune, decode and unpack kernels.
+//
+// The cache is a header, the per-(batch, KV head) channel weights a and 1/a, and an
+// array of TILES.  A tile holds 64 consecutive global tokens of one KV head.  Every
+// token owns one ROW of `ndw` 32-bit words:
+//
+//   bf16 storage : [ m0 m1 m2 m3 | mu | v0 v1 ... v(nv-1) | pad ]   nv = ceil(T/2)
+//   int8 storage : [ m0 m1 m2 m3 | mu | scale | c0 ... c(nv-1) | pad ]   nv = ceil(T/4)
+//
+// m0..m3 is the 128-bit channel mask (bit j%32 of word j/32 = channel j kept), mu the
+// mean saliency of the pruned channels, v* the kept entries in ascending channel order
+// (two bf16 per word, the lower channel in the low half; or four int8 codes per word).
+// ndw is rounded up to an even number so a row is a whole number of 8-byte units.
+//
+// Inside a tile the rows are interleaved so that a wavefront whose lane l owns token l
+// reads the tile with fully coalesced 16-byte (then one 8-byte) accesses:
+//
+//   word d of token t lives at   (d/4)*1024 + t*16 + (d%4)*4          for d <  4*nq
+//                                nq*1024 + t*8 + (d - 4*nq)*4         for the 2-word tail
+//
+// with nq = ndw/4 full 16-byte sections.  Tiles are ordered [KV head][tile index]; the
+// tile index of global token n is n/64, so a tile may straddle two sequences.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#define SPARK_D 128
+#define SPARK_TILE_TOKENS 64
+#define SPARK_MAGIC 0x53504B31u /* "SPK1" */
+
+#if defined(__HIPCC__) || defined(__HIP__)
+#define SPARK_HD __host__ __device__
+#else
+#define SPARK_HD
+#endif
+
+struct SparkLayout {
+    int32_t T;            // kept channels per row
+    int32_t int8;         // 1 = int8 codes + scale
+    int32_t nv;           // value words per row
+    int32_t val0;         // index of the first value word in a row
+    int32_t ndw;          // words per row (even)
+    int32_t nq;           // full 16-byte sections per row
+    int32_t tail2;        // 1 if a 2-word tail section follows
+    int32_t tile_bytes;   // 64 * 4 * ndw
+    int32_t batch, n_kv_heads;
+    int64_t total_tokens;
+    int64_t n_tiles;      // ceil(total_tokens / 64)
+    int64_t off_a;        // float [batch][Hkv][128]
+    int64_t off_inva;     // float [batch][Hkv][128]   1/a, 0 where a == 0
+    int64_t off_tiles;    // tiles [Hkv][n_tiles]
+    int64_t total_bytes;
+};
+
+static inline SPARK_HD SparkLayout spark_make_layout(int T, int int8, int batch, int n_kv_heads,
+                                                     int64_t total_tokens)
+{
+    SparkLayout L;
+    L.T = T;
+    L.int8 = int8;
+    L.nv = int8 ? (T + 3) / 4 : (T + 1) / 2;
+    L.val0 = int8 ? 6 : 5;
+    int ndw = L.val0 + L.nv;
+    L.ndw = (ndw + 1) & ~1;
+    L.nq = L.ndw / 4;
+    L.tail2 = (L.ndw % 4) ? 1 : 0;
+    L.tile_bytes = SPARK_TILE_TOKENS * 4 * L.ndw;
+    L.batch = batch;
+    L.n_kv_heads = n_kv_heads;
+    L.total_tokens = total_tokens;
+    L.n_tiles = (total_tokens + SPARK_TILE_TOKENS - 1) / SPARK_TILE_TOKENS;
+    const int64_t abytes = (int64_t)batch * n_kv_heads * SPARK_D * 4;
+    const int64_t apad = (abytes + 255) & ~(int64_t)255;
+    L.off_a = 256;
+    L.off_inva = L.off_a + apad;
+    L.off_tiles = L.off_inva + apad;
+    L.total_bytes = L.off_tiles + (int64_t)n_kv_heads * L.n_tiles * L.tile_bytes;
+    return L;
+}
+
+// byte offset of word d of token t inside a tile
+static inline SPARK_HD int spark_tile_word_offset(const SparkLayout &L, int t, int d)
+{
+    const int q = d >> 2;
+    if (q < L.nq) return q * 1024 + t * 16 + (d & 3) * 4;
+    return L.nq * 1024 + t * 8 + (d - 4 * L.nq) * 4;
+}

@@ -1,0 +1,371 @@
+// Prefill-time channel pruning of the key cache for gfx950 (wave64).
+//
+// [Sec. "Problem Formulation and Analysis": saliency w = |q^j| * |k^j|, Eq. (7), Top_T;
+//  Sec. "SparK": mean query over the observation window, mask and pruned keys;
+//  App. "Caching Pruned Channel Statistics": mean saliency of the pruned set.]
+//
+// Kernels
+//   spark_window_stat_kernel  a[b,h,j] = mean_g | mean_t Q_win[b,g,t,j] |  in float64, stored
+//                             as float32 together with 1/a.
+//   spark_prune_kernel        one wavefront per tile (64 tokens of one KV head).  For each
+//                             token the 128 saliencies sit two per lane (channels l, l+64);
+//                             the T-th largest is found by a most-significant-bit-first
+//                             search on the float32 bit pattern where every probe is two
+//                             wave ballots and two scalar popcounts; the kept set is then a
+//                             pair of 64-bit ballots = the channel mask, and a prefix
+//                             popcount (mbcnt) gives each kept value its slot in the packed
+//                             row.  Rows are staged in LDS and the finished tile is written
+//                             with lane = token, coalesced.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "spark_kernels.h"
+#include "spark_layout.h"
+
+namespace spark {
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// ---------------------------------------------------------------- window statistic
+
+// grid = batch * Hkv blocks, 128 threads (thread = channel).  Sums run in the order
+// t ascending, then g ascending, all in float64; every sum of bf16 inputs this short is
+// exact, so the single rounding to float32 at the end decides a's bits.
+__global__ __launch_bounds__(128) void spark_window_stat_kernel(const uint16_t *__restrict__ qwin,
+                                                                int Hq, int Hkv, int W,
+                                                                uint8_t *__restrict__ packed,
+                                                                SparkLayout L)
+{
+    const int bh = blockIdx.x;
+    const int b = bh / Hkv, h = bh % Hkv;
+    const int j = threadIdx.x;
+    const int G = Hq / Hkv;
+    double s = 0.0;
+    for (int g = 0; g < G; ++g) {
+        const uint16_t *src = qwin + ((int64_t)(b * Hq + h * G + g) * W) * SPARK_D + j;
+        double qs = 0.0;
+        for (int t = 0; t < W; ++t) qs += (double)bf16_bits_to_float(src[(int64_t)t * SPARK_D]);
+        s += fabs(qs / (double)W);
+    }
+    const float a32 = (float)(s / (double)G);
+    float *a_out = reinterpret_cast<float *>(packed + L.off_a);
+    float *inva_out = reinterpret_cast<float *>(packed + L.off_inva);
+    a_out[(int64_t)bh * SPARK_D + j] = a32;
+    inva_out[(int64_t)bh * SPARK_D + j] = (a32 != 0.0f) ? (1.0f / a32) : 0.0f;
+    if (bh == 0 && j < 64) {
+        uint32_t *hdr = reinterpret_cast<uint32_t *>(packed);
+        uint32_t v = 0;
+        if (j == 0) v = SPARK_MAGIC;
+        if (j == 1) v = (uint32_t)L.T;
+        if (j == 2) v = (uint32_t)L.int8;
+        if (j == 3) v = (uint32_t)L.batch;
+        if (j == 4) v = (uint32_t)L.n_kv_heads;
+        if (j == 5) v = (uint32_t)L.total_tokens;
+        if (j == 6) v = (uint32_t)L.ndw;
+        hdr[j] = v;
+    }
+}
+
+// ---------------------------------------------------------------- top-T selection + pack
+
+constexpr int kPruneWaves = 4;      // wavefronts per block, one tile each
+constexpr int kPsumTokens = 16;     // tokens whose pruned-saliency partials are held before a flush
+constexpr int kPsumStride = 65;     // words per token in the partial-sum buffer (odd: no bank clash)
+
+// words per token in the LDS staging row: mask, mu, (scale), then T bf16 values
+__host__ __device__ inline int spark_stage_words(const SparkLayout &L)
+{
+    int w = L.val0 + (L.T + 1) / 2;
+    if (w < L.ndw) w = L.ndw;
+    return (w + 1) & ~1;
+}
+
+__host__ inline size_t spark_prune_lds_bytes(const SparkLayout &L)
+{
+    return (size_t)kPruneWaves *
+           ((size_t)SPARK_TILE_TOKENS * spark_stage_words(L) * 4 + (size_t)kPsumTokens * kPsumStride * 4);
+}
+
+template <int INT8>
+__global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
+    const uint16_t *__restrict__ k, int64_t k_tok_stride, int64_t k_head_stride,
+    const int32_t *__restrict__ cu, uint8_t *__restrict__ packed, SparkLayout L)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t wt = (int64_t)blockIdx.x * kPruneWaves + wave;
+    if (wt >= L.n_tiles * L.n_kv_heads) return;   // whole wavefront leaves; no block barrier is used
+    const int h = (int)(wt / L.n_tiles);
+    const int64_t tile = wt % L.n_tiles;
+    const int T = L.T;
+    const int B = L.batch;
+    const int sw = spark_stage_words(L);
+    uint32_t *stage = reinterpret_cast<uint32_t *>(smem) +
+                      (size_t)wave * (SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride);
+    float *psum = reinterpret_cast<float *>(stage + SPARK_TILE_TOKENS * sw);
+    uint16_t *stage16 = reinterpret_cast<uint16_t *>(stage);
+
+    const float *a_all = reinterpret_cast<const float *>(packed + L.off_a);
+    const int64_t n0 = tile * SPARK_TILE_TOKENS;
+    int nvalid = (int)((L.total_tokens - n0 < SPARK_TILE_TOKENS) ? (L.total_tokens - n0) : SPARK_TILE_TOKENS);
+
+    // sequence of the first token: largest b with cu[b] <= n0 (skips empty sequences)
+    int b = 0;
+    {
+        int lo = 0, hi = B;     // invariant: cu[lo] <= n0 < cu[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (cu[mid] <= n0) lo = mid; else hi = mid;
+        }
+        b = lo;
+    }
+    int64_t seq_end = cu[b + 1];
+    float a0 = a_all[((int64_t)b * L.n_kv_heads + h) * SPARK_D + lane];
+    float a1 = a_all[((int64_t)b * L.n_kv_heads + h) * SPARK_D + 64 + lane];
+
+    const uint16_t *krow = k + n0 * k_tok_stride + (int64_t)h * k_head_stride + lane;
+
+    uint32_t mreg0 = 0, mreg1 = 0, mreg2 = 0, mreg3 = 0;   // lane t: mask words of token t
+    float mureg = 0.0f;                                     // lane t: sum of pruned saliencies
+
+    constexpr int PF = 8;   // rows in flight
+    uint32_t xq0[PF], xq1[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+        const int tt = (u < nvalid) ? u : (nvalid - 1);
+        xq0[u] = krow[(int64_t)tt * k_tok_stride];
+        xq1[u] = krow[(int64_t)tt * k_tok_stride + 64];
+    }
+
+    for (int tb = 0; tb < SPARK_TILE_TOKENS; tb += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int t = tb + u;
+            const uint32_t x0 = xq0[u], x1 = xq1[u];
+            {   // refill this slot with the row PF tokens ahead
+                int tn = t + PF;
+                tn = (tn < nvalid) ? tn : (nvalid - 1);
+                xq0[u] = krow[(int64_t)tn * k_tok_stride];
+                xq1[u] = krow[(int64_t)tn * k_tok_stride + 64];
+            }
+            if (t < nvalid) {   // wave-uniform
+                const int64_t n = n0 + t;
+                while (n >= seq_end) {   // next non-empty sequence
+                    ++b;
+                    seq_end = cu[b + 1];
+                    a0 = a_all[((int64_t)b * L.n_kv_heads + h) * SPARK_D + lane];
+                    a1 = a_all[((int64_t)b * L.n_kv_heads + h) * SPARK_D + 64 + lane];
+                }
+                // saliency: one float32 multiply, never fused
+                const float w0 = __fmul_rn(a0, fabsf(bf16_bits_to_float(x0)));
+                const float w1 = __fmul_rn(a1, fabsf(bf16_bits_to_float(x1)));
+                const uint32_t key0 = __float_as_uint(w0), key1 = __float_as_uint(w1);
+
+                bool keep0, keep1;
+                if (T >= SPARK_D) {
+                    keep0 = keep1 = true;
+                } else {
+                    // T-th largest key: set bits from the top while at least T keys stay >= prefix
+                    uint32_t p = 0;
+                    bool exact = false;
+                    for (int bit = 30; bit >= 0; --bit) {
+                        const uint32_t cand = p | (1u << bit);
+                        const int c = __popcll(__ballot(key0 >= cand)) + __popcll(__ballot(key1 >= cand));
+                        if (c >= T) {
+                            p = cand;
+                            if (c == T) { exact = true; break; }
+                        }
+                    }
+                    if (exact) {          // exactly T keys are >= p: that is the kept set
+                        keep0 = key0 >= p;
+                        keep1 = key1 >= p;
+                    } else {              // p is the T-th largest value and it is tied
+                        const uint64_t e0 = __ballot(key0 == p), e1 = __ballot(key1 == p);
+                        const int need = T - __popcll(__ballot(key0 > p)) - __popcll(__ballot(key1 > p));
+                        const int r0 = __builtin_amdgcn_mbcnt_hi((uint32_t)(e0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)e0, 0));
+                        const int r1 = __popcll(e0) + __builtin_amdgcn_mbcnt_hi((uint32_t)(e1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)e1, 0));
+                        keep0 = (key0 > p) || (key0 == p && r0 < need);   // lower channel first
+                        keep1 = (key1 > p) || (key1 == p && r1 < need);
+                    }
+                }
+                const uint64_t kb0 = __ballot(keep0), kb1 = __ballot(keep1);
+                // slot of each kept value = number of kept channels below it
+                const int pos0 = __builtin_amdgcn_mbcnt_hi((uint32_t)(kb0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)kb0, 0));
+                const int pos1 = __popcll(kb0) + __builtin_amdgcn_mbcnt_hi((uint32_t)(kb1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)kb1, 0));
+                uint16_t *vrow = stage16 + (size_t)t * sw * 2 + L.val0 * 2;
+                if (keep0) vrow[pos0] = (uint16_t)x0;
+                if (keep1) vrow[pos1] = (uint16_t)x1;
+                const bool mine = (lane == t);   // lane t keeps the mask words of token t
+                mreg0 = mine ? (uint32_t)kb0 : mreg0;
+                mreg1 = mine ? (uint32_t)(kb0 >> 32) : mreg1;
+                mreg2 = mine ? (uint32_t)kb1 : mreg2;
+                mreg3 = mine ? (uint32_t)(kb1 >> 32) : mreg3;
+                psum[(t & (kPsumTokens - 1)) * kPsumStride + lane] = (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
+            }
+            if ((t & (kPsumTokens - 1)) == kPsumTokens - 1) {
+                // 16 tokens' partials are in LDS: lane (tt, qq) adds 16 of token tt's 64 partials,
+                // two butterfly steps finish the sum in every lane of column tt
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const int tt = lane & 15, qq = lane >> 4;
+                float s = 0.0f;
+#pragma unroll
+                for (int c = 0; c < 16; ++c) s += psum[tt * kPsumStride + qq * 16 + c];
+                s += __shfl_xor(s, 16);
+                s += __shfl_xor(s, 32);
+                if (qq == (t >> 4)) mureg = s;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+        }
+    }
+
+    // ---- row epilogue, lane = token
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const bool valid = lane < nvalid;
+    uint32_t *row = stage + (size_t)lane * sw;
+    const float mu = (valid && T < SPARK_D) ? (mureg / (float)(SPARK_D - T)) : 0.0f;
+    // rows past the last token carry a well-formed mask (channels 0..T-1) and zero values, so a
+    // reader that walks exactly T bits never runs off the mask
+    auto low_bits = [](int n) { return n <= 0 ? 0u : (n >= 32 ? 0xFFFFFFFFu : ((1u << n) - 1u)); };
+    row[0] = valid ? mreg0 : low_bits(T);
+    row[1] = valid ? mreg1 : low_bits(T - 32);
+    row[2] = valid ? mreg2 : low_bits(T - 64);
+    row[3] = valid ? mreg3 : low_bits(T - 96);
+    row[4] = __float_as_uint(mu);
+    if (!valid) {
+        for (int d = 5; d < sw; ++d) row[d] = 0u;
+    } else {
+        const int vend = L.val0 + (T + 1) / 2;               // one past the last staged bf16 word
+        if (T & 1) row[vend - 1] &= 0xFFFFu;                 // unused upper half of the last word
+        for (int d = vend; d < sw; ++d) row[d] = 0u;
+        if (INT8) {
+            // absmax scale and round-to-nearest-even codes, decided in float32
+            auto val = [&](int i) {
+                return bf16_bits_to_float((row[L.val0 + (i >> 1)] >> (16 * (i & 1))) & 0xFFFFu);
+            };
+            float amax = 0.0f;
+            for (int i = 0; i < T; ++i) amax = fmaxf(amax, fabsf(val(i)));
+            const float scale = __fdiv_rn(amax, 127.0f);
+            row[5] = __float_as_uint(scale);
+            for (int c = 0; c < L.nv; ++c) {
+                uint32_t word = 0;
+                for (int e = 0; e < 4; ++e) {
+                    const int i = 4 * c + e;
+                    int code = 0;
+                    if (i < T && scale != 0.0f) {
+                        float qf = rintf(__fdiv_rn(val(i), scale));
+                        qf = fminf(fmaxf(qf, -127.0f), 127.0f);
+                        code = (int)qf;
+                    }
+                    word |= ((uint32_t)code & 0xFFu) << (8 * e);
+                }
+                row[L.val0 + c] = word;   // never ahead of the bf16 words still to be read
+            }
+            for (int d = L.val0 + L.nv; d < L.ndw; ++d) row[d] = 0u;
+        }
+    }
+    // ---- coalesced tile write: section q holds words 4q..4q+3 of every token
+    uint8_t *tile_out = packed + L.off_tiles + ((int64_t)h * L.n_tiles + tile) * L.tile_bytes;
+    for (int q = 0; q < L.nq; ++q) {
+        uint4 v;
+        v.x = row[4 * q + 0];
+        v.y = row[4 * q + 1];
+        v.z = row[4 * q + 2];
+        v.w = row[4 * q + 3];
+        *reinterpret_cast<uint4 *>(tile_out + (size_t)q * 1024 + lane * 16) = v;
+    }
+    if (L.tail2) {
+        uint2 v;
+        v.x = row[4 * L.nq + 0];
+        v.y = row[4 * L.nq + 1];
+        *reinterpret_cast<uint2 *>(tile_out + (size_t)L.nq * 1024 + lane * 8) = v;
+    }
+}
+
+// ---------------------------------------------------------------- canonical export
+
+// one thread per (token, KV head) row
+__global__ void spark_unpack_kernel(const uint8_t *__restrict__ packed, SparkLayout L,
+                                    uint32_t *mask_out, void *vals_out, float *mu_out,
+                                    float *scale_out, float *a_out)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t rows = L.total_tokens * L.n_kv_heads;
+    if (a_out && idx < (int64_t)L.batch * L.n_kv_heads * SPARK_D)
+        a_out[idx] = reinterpret_cast<const float *>(packed + L.off_a)[idx];
+    if (idx >= rows) return;
+    const int64_t n = idx / L.n_kv_heads;
+    const int h = (int)(idx % L.n_kv_heads);
+    const uint8_t *tile = packed + L.off_tiles + ((int64_t)h * L.n_tiles + n / SPARK_TILE_TOKENS) * L.tile_bytes;
+    const int t = (int)(n % SPARK_TILE_TOKENS);
+    auto word = [&](int d) {
+        return *reinterpret_cast<const uint32_t *>(tile + spark_tile_word_offset(L, t, d));
+    };
+    if (mask_out)
+        for (int m = 0; m < 4; ++m) mask_out[idx * 4 + m] = word(m);
+    if (mu_out) mu_out[idx] = __uint_as_float(word(4));
+    if (L.int8) {
+        if (scale_out) scale_out[idx] = __uint_as_float(word(5));
+        if (vals_out) {
+            int8_t *o = reinterpret_cast<int8_t *>(vals_out) + idx * L.T;
+            for (int i = 0; i < L.T; ++i) o[i] = (int8_t)((word(L.val0 + i / 4) >> (8 * (i & 3))) & 0xFF);
+        }
+    } else if (vals_out) {
+        uint16_t *o = reinterpret_cast<uint16_t *>(vals_out) + idx * L.T;
+        for (int i = 0; i < L.T; ++i) o[i] = (uint16_t)((word(L.val0 + i / 2) >> (16 * (i & 1))) & 0xFFFF);
+    }
+}
+
+
+// ---------------------------------------------------------------- host-side launch
+
+hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
+                        const int32_t *cu, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st)
+{
+    hipLaunchKernelGGL(spark_window_stat_kernel, dim3(L.batch * L.n_kv_heads), dim3(SPARK_D), 0, st, qwin, Hq,
+                       L.n_kv_heads, W, packed, L);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t waves = L.n_tiles * L.n_kv_heads;
+    if (waves == 0) return hipSuccess;
+    const int nblocks = (int)((waves + kPruneWaves - 1) / kPruneWaves);
+    const size_t lds = spark_prune_lds_bytes(L);
+    if (L.int8) {
+        if (lds > 48 * 1024) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&spark_prune_kernel<1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(spark_prune_kernel<1>, dim3(nblocks), dim3(kPruneWaves * 64), lds, st, k, k_tok_stride,
+                           k_head_stride, cu, packed, L);
+    } else {
+        if (lds > 48 * 1024) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&spark_prune_kernel<0>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(spark_prune_kernel<0>, dim3(nblocks), dim3(kPruneWaves * 64), lds, st, k, k_tok_stride,
+                           k_head_stride, cu, packed, L);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *mask_out, void *vals_out,
+                         float *mu_out, float *scale_out, float *a_out, hipStream_t st)
+{
+    int64_t n = L.total_tokens * L.n_kv_heads;
+    const int64_t na = (int64_t)L.batch * L.n_kv_heads * SPARK_D;
+    if (a_out && na > n) n = na;
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(spark_unpack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed, L,
+                       mask_out, vals_out, mu_out, scale_out, a_out);
+    return hipGetLastError();
+}
+
+}  // namespace spark

@@ -1,0 +1,64 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol the header
+declares, answers the size queries, and rejects bad descriptions without touching a GPU."""
+import ctypes
+import os
+import re
+
+import paper_2508_15212_amd as spark
+from paper_2508_15212_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "spark.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spark_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = spark.load()
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def _desc(**kw):
+    d = spark.SparkDesc(batch=8, n_q_heads=32, n_kv_heads=8, head_dim=128, keep=26, window=32,
+                        total_tokens=8 * 32768, k_token_stride=128, k_head_stride=128 * 8 * 32768,
+                        v_token_stride=128, v_head_stride=128 * 8 * 32768)
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_size_queries_follow_the_layout():
+    d = _desc()
+    rows = 8 * 32768 * 8
+    # 72-byte rows at T = 26 (13 value words + 4 mask words + mu), plus header and a / 1/a
+    assert spark.packed_bytes(d) == 256 + 2 * 8 * 8 * 128 * 4 + rows * 72
+    assert spark.packed_bytes(_desc(keep=64)) == 256 + 2 * 8 * 8 * 128 * 4 + rows * 152
+    assert spark.packed_bytes(_desc(pack_dtype=spark.PACK_INT8)) == 256 + 2 * 8 * 8 * 128 * 4 + rows * 56
+    ns = spark.decode_splits(d)
+    assert ns >= 1
+    assert spark.decode_workspace_bytes(d) == 8 * 32 * ns * 130 * 4
+    assert spark.decode_splits(_desc(n_splits=7)) == 7
+    # partial last tile is padded to 64 tokens
+    assert spark.packed_bytes(_desc(batch=1, total_tokens=65)) == 256 + 2 * 8 * 128 * 4 + 2 * 64 * 8 * 72
+
+
+def test_bad_descriptions_are_rejected_on_the_host():
+    lib = spark.load()
+    assert spark.packed_bytes(_desc(head_dim=64)) == 0
+    assert spark.packed_bytes(_desc(keep=0)) == 0
+    assert spark.packed_bytes(_desc(keep=129)) == 0
+    assert spark.packed_bytes(_desc(n_q_heads=24, n_kv_heads=8)) == 0      # group of 3
+    assert spark.packed_bytes(_desc(n_q_heads=30)) == 0
+    # NULL pointers are caught before any launch (status 1 = invalid argument)
+    d = _desc()
+    assert lib.spark_prune(ctypes.byref(d), None, None, None, None, None, 0, None) == 1
+    assert lib.spark_decode_attn(ctypes.byref(d), None, None, None, None, None, None, 0, None) == 1
+    assert lib.spark_unpack(ctypes.byref(d), None, None, None, None, None, None, None) == 1
+    assert lib.spark_prune(ctypes.byref(_desc(head_dim=64)), None, None, None, None, None, 0, None) == 2
+    assert lib.spark_status_string(3) == b"workspace too small"

@@ -1,0 +1,154 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Index work (masks, kept entries, channel weights, int8 codes) must match
+bit for bit; floating point within the stated tolerance:
+
+    decode output (float32 out):  max |err| <= 1e-2, mean |err| <= 1e-3   (bf16 in, fp32 accumulate)
+    mu (float32 mean of <= 127 float32 saliencies, any summation order):  relative 1e-5
+
+Near-ties (relative saliency gap < 1e-6 at the cut) are counted and printed; they are
+expected to match as well because both sides compare the same float32 products.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_2508_15212_amd as spark
+from tests.gpu_util import run_gpu_case
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 1e-2, 1e-3
+
+
+def _oracle_all(w, t, int8=False):
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    if int8:
+        pr = oracle.quant_int8(pr)
+    ref = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
+    return a32, pr, ref
+
+
+def _check_prune(res, a32, pr, int8=False):
+    assert np.array_equal(res["a"], a32), "channel weights a differ"
+    assert np.array_equal(res["mask"], pr.mask), "kept-channel sets differ"
+    bits = np.unpackbits(res["mask"].view(np.uint8), axis=-1, bitorder="little")
+    assert np.all(bits.sum(-1) == pr.T)
+    if int8:
+        assert np.array_equal(res["scale"], pr.scale)
+        assert np.array_equal(res["vals"], pr.codes)
+    else:
+        assert np.array_equal(res["vals"], pr.kept), "kept entries differ"
+    assert np.allclose(res["mu"], pr.mu32, rtol=1e-5, atol=1e-30)
+
+
+def _check_out(res, ref, tag=""):
+    err = np.abs(res["out_f32"].astype(np.float64) - ref)
+    print(f"{tag} decode max|err|={err.max():.3e} mean|err|={err.mean():.3e}")
+    assert np.all(np.isfinite(res["out_f32"]))
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+    if "out_bf16" in res:
+        # the bf16 output is the float32 output rounded to nearest even
+        want = torch.from_numpy(res["out_f32"]).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(res["out_bf16"], want)
+
+
+def _run(w, t=None, int8=False, **kw):
+    t = wl.generate(w) if t is None else t
+    a32, pr, ref = _oracle_all(w, t, int8)
+    print(f"{w.name}: rows={w.total * w.n_kv_heads} near-ties(<1e-6)={pr.near_ties()}")
+    res = run_gpu_case(w, t, pack=spark.PACK_INT8 if int8 else spark.PACK_BF16, **kw)
+    _check_prune(res, a32, pr, int8)
+    _check_out(res, ref, w.name)
+    return res, pr, ref
+
+
+def test_small_ragged_keep26():
+    _run(wl.small())
+
+
+def test_config1_tiny_1k_keep64():
+    _run(wl.config(1))
+
+
+@pytest.mark.parametrize("T", [1, 2, 25, 26, 27, 38, 64, 65, 127, 128])
+def test_keep_values(T):
+    # several tiles and a ragged tail; odd T exercises the half-filled last value word,
+    # T = 128 is plain dense attention
+    _run(wl.small(name=f"keep{T}", keep=T, seqlens=(130, 321), seed=20 + T))
+
+
+@pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 2), (4, 3), (8, 2), (16, 1)])
+def test_group_sizes(G, Hkv):
+    _run(wl.small(name=f"gqa{G}", n_q_heads=G * Hkv, n_kv_heads=Hkv, keep=26, seqlens=(257, 64, 190), batch=3,
+                  seed=40 + G))
+
+
+@pytest.mark.parametrize("layout", ["HND", "NHD"])
+def test_layouts(layout):
+    _run(wl.small(name=f"layout{layout}", seqlens=(333, 129), seed=50), layout=layout)
+
+
+def test_ragged_with_empty_and_single_token_sequences():
+    w = wl.small(name="ragged_edges", batch=6, seqlens=(0, 1, 63, 64, 65, 0), keep=26, seed=60)
+    res, pr, ref = _run(w)
+    assert np.all(res["out_f32"][0] == 0) and np.all(res["out_f32"][5] == 0)
+    # one cached token: the output is that token's V row
+    vf = wl.bf16_bits_to_f32(wl.generate(w).v)
+    G = w.n_q_heads // w.n_kv_heads
+    for g in range(w.n_q_heads):
+        assert np.allclose(res["out_f32"][1, g], vf[g // G, 0], rtol=0, atol=1e-6)
+
+
+@pytest.mark.parametrize("ns", [1, 2, 3, 7, 33])
+def test_split_counts_agree(ns):
+    w = wl.small(name=f"splits{ns}", batch=2, seqlens=(1500, 700), keep=26, seed=70)
+    res, _, ref = _run(w, n_splits=ns)
+    res1 = run_gpu_case(w, wl.generate(w), n_splits=1, want_unpack=False, want_bf16=False)
+    assert np.abs(res["out_f32"] - res1["out_f32"]).max() < 1e-4
+
+
+def test_constructed_ties_and_zero_rows():
+    """Saliencies drawn from a handful of values: the cut falls inside a tie in most rows."""
+    w = wl.small(name="ties", batch=2, n_q_heads=4, n_kv_heads=2, keep=26, seqlens=(150, 90), seed=80)
+    t = wl.generate(w)
+    rng = np.random.default_rng(80)
+    kq = rng.integers(-2, 3, size=t.k.shape).astype(np.float32)
+    kq[:, 10:20, :] = 0.0                          # all-zero rows: channels 0..T-1 kept
+    kq[:, 30:40, :] = 1.0                          # all-equal rows
+    t.k = wl.f32_to_bf16_bits(kq)
+    t.qwin = wl.f32_to_bf16_bits(np.sign(wl.bf16_bits_to_f32(t.qwin)))   # |qbar| few distinct values
+    a32, pr, ref = _oracle_all(w, t)
+    assert pr.near_ties() > 0.5 * pr.gap.size
+    res = run_gpu_case(w, t)
+    _check_prune(res, a32, pr)
+    _check_out(res, ref, "ties")
+
+
+def test_int8_storage_variant():
+    _run(wl.small(name="int8", keep=26, seqlens=(300, 141), seed=90), int8=True)
+    _run(wl.small(name="int8_t25", keep=25, seqlens=(100, 70), seed=91), int8=True)
+
+
+def test_peaked_softmax_keeps_tolerance():
+    """A decode query aligned with one key makes the softmax nearly one-hot; outlier V channels are
+    large, so this is where a low-precision P would show."""
+    w = wl.small(name="peaked", batch=1, n_q_heads=4, n_kv_heads=1, keep=64, seqlens=(700,), seed=95,
+                 n_outlier=8, outlier_scale=10.0)
+    t = wl.generate(w)
+    kf = wl.bf16_bits_to_f32(t.k)
+    q = np.stack([kf[0, 100] * 0.5, kf[0, 300] * 0.35, -kf[0, 5] * 0.3, kf[0, 650] * 0.2])[None]
+    t.q = wl.f32_to_bf16_bits(q.astype(np.float32))
+    _run(w, t)
+
+
+def test_window_scale_invariance_on_gpu():
+    w = wl.small(name="scale_inv", keep=38, seqlens=(200, 100), seed=97)
+    t = wl.generate(w)
+    r1 = run_gpu_case(w, t)
+    t.qwin = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(t.qwin) * np.float32(4.0))
+    r4 = run_gpu_case(w, t)
+    assert np.array_equal(r1["mask"], r4["mask"])
+    assert np.abs(r1["out_f32"] - r4["out_f32"]).max() < 1e-5
