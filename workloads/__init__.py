@@ -148,6 +148,6 @@ def generate(w: Workload, chunk_tokens: int = 1 << 16) -> Tensors:
 
 def checksum(x: np.ndarray) -> int:
     """Order-dependent 64-bit checksum of a tensor's bytes (detects a generator change)."""
-    b = np.ascontiguousarray(x).view(np.uint8).astype(np.uint64)
+    b = np.ascontiguousarray(x).reshape(-1).view(np.uint8).astype(np.uint64)
     idx = (np.arange(b.size, dtype=np.uint64) % np.uint64(65521)) + np.uint64(1)
     return int(np.sum(b * idx, dtype=np.uint64))
