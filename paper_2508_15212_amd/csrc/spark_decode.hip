@@ -89,7 +89,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void spark_decode_kernel(DecodeP
     __shared__ float red_m[kDecodeWaves][G], red_l[kDecodeWaves][G];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep tile addressing scalar
     const SparkLayout &L = P.L;
     const int T = TCT ? TCT : L.T;
     const int split = blockIdx.x % P.nsplit;

@@ -8,7 +8,7 @@
 //   spark_window_stat_kernel  a[b,h,j] = mean_g | mean_t Q_win[b,g,t,j] |  in float64, stored
 //                             as float32 together with 1/a.
 //   spark_prune_kernel        one wavefront per tile (64 tokens of one KV head).  For each
-//                             token the 128 saliencies sit two per lane (channels l, l+64);
+//                             token the 128 saliencies sit two per lane (channels 2l, 2l+1);
 //                             the T-th largest is found by a most-significant-bit-first
 //                             search on the float32 bit pattern where every probe is two
 //                             wave ballots and two scalar popcounts; the kept set is then a
@@ -86,6 +86,22 @@ __host__ inline size_t spark_prune_lds_bytes(const SparkLayout &L)
            ((size_t)SPARK_TILE_TOKENS * spark_stage_words(L) * 4 + (size_t)kPsumTokens * kPsumStride * 4);
 }
 
+// bits 0..15 of x spread to the even bit positions of a 32-bit word
+__device__ __forceinline__ uint32_t spread16(uint32_t x)
+{
+    x &= 0xFFFFu;
+    x = (x | (x << 8)) & 0x00FF00FFu;
+    x = (x | (x << 4)) & 0x0F0F0F0Fu;
+    x = (x | (x << 2)) & 0x33333333u;
+    x = (x | (x << 1)) & 0x55555555u;
+    return x;
+}
+
+__device__ __forceinline__ int mbcnt64(uint64_t m)   // set bits of m below this lane
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+}
+
 template <int INT8>
 __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     const uint16_t *__restrict__ k, int64_t k_tok_stride, int64_t k_head_stride,
@@ -93,7 +109,9 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
 {
     extern __shared__ __align__(16) uint8_t smem[];
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    // the wavefront index is the same in all 64 lanes; saying so keeps everything derived from it
+    // (tile, token loop, search state) in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t wt = (int64_t)blockIdx.x * kPruneWaves + wave;
     if (wt >= L.n_tiles * L.n_kv_heads) return;   // whole wavefront leaves; no block barrier is used
     const int h = (int)(wt / L.n_tiles);
@@ -106,9 +124,9 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     float *psum = reinterpret_cast<float *>(stage + SPARK_TILE_TOKENS * sw);
     uint16_t *stage16 = reinterpret_cast<uint16_t *>(stage);
 
-    const float *a_all = reinterpret_cast<const float *>(packed + L.off_a);
+    const float2 *a_all = reinterpret_cast<const float2 *>(packed + L.off_a);
     const int64_t n0 = tile * SPARK_TILE_TOKENS;
-    int nvalid = (int)((L.total_tokens - n0 < SPARK_TILE_TOKENS) ? (L.total_tokens - n0) : SPARK_TILE_TOKENS);
+    const int nvalid = (int)((L.total_tokens - n0 < SPARK_TILE_TOKENS) ? (L.total_tokens - n0) : SPARK_TILE_TOKENS);
 
     // sequence of the first token: largest b with cu[b] <= n0 (skips empty sequences)
     int b = 0;
@@ -121,45 +139,52 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
         b = lo;
     }
     int64_t seq_end = cu[b + 1];
-    float a0 = a_all[((int64_t)b * L.n_kv_heads + h) * SPARK_D + lane];
-    float a1 = a_all[((int64_t)b * L.n_kv_heads + h) * SPARK_D + 64 + lane];
+    // lane l owns channels 2l (low half of its 32-bit load) and 2l+1 (high half)
+    float2 a01 = a_all[((int64_t)b * L.n_kv_heads + h) * (SPARK_D / 2) + lane];
 
-    const uint16_t *krow = k + n0 * k_tok_stride + (int64_t)h * k_head_stride + lane;
+    const uint32_t *krow = reinterpret_cast<const uint32_t *>(k + n0 * k_tok_stride + (int64_t)h * k_head_stride) + lane;
+    const int64_t row_stride = k_tok_stride / 2;   // in 32-bit words (the ABI requires even strides)
 
-    uint32_t mreg0 = 0, mreg1 = 0, mreg2 = 0, mreg3 = 0;   // lane t: mask words of token t
+    // lane t collects, for token t, the ballots of kept even channels (e) and kept odd channels (o)
+    uint32_t e_lo = 0, e_hi = 0, o_lo = 0, o_hi = 0;
     float mureg = 0.0f;                                     // lane t: sum of pruned saliencies
 
-    constexpr int PF = 8;   // rows in flight
-    uint32_t xq0[PF], xq1[PF];
+    // Rows are fetched a block ahead: while block tb is searched, block tb+PF is in flight.
+    constexpr int PF = 16;
+    uint32_t xc[PF];
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
         const int tt = (u < nvalid) ? u : (nvalid - 1);
-        xq0[u] = krow[(int64_t)tt * k_tok_stride];
-        xq1[u] = krow[(int64_t)tt * k_tok_stride + 64];
+        xc[u] = krow[(int64_t)tt * row_stride];
     }
 
     for (int tb = 0; tb < SPARK_TILE_TOKENS; tb += PF) {
+        uint32_t xn[PF];
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            int tn = tb + PF + u;
+            tn = (tn < nvalid) ? tn : (nvalid - 1);
+            xn[u] = krow[(int64_t)tn * row_stride];
+        }
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int t = tb + u;
-            const uint32_t x0 = xq0[u], x1 = xq1[u];
-            {   // refill this slot with the row PF tokens ahead
-                int tn = t + PF;
-                tn = (tn < nvalid) ? tn : (nvalid - 1);
-                xq0[u] = krow[(int64_t)tn * k_tok_stride];
-                xq1[u] = krow[(int64_t)tn * k_tok_stride + 64];
-            }
+            const uint32_t xx = xc[u];
             if (t < nvalid) {   // wave-uniform
                 const int64_t n = n0 + t;
-                while (n >= seq_end) {   // next non-empty sequence
-                    ++b;
-                    seq_end = cu[b + 1];
-                    a0 = a_all[((int64_t)b * L.n_kv_heads + h) * SPARK_D + lane];
-                    a1 = a_all[((int64_t)b * L.n_kv_heads + h) * SPARK_D + 64 + lane];
+                if (n >= seq_end) {      // rare: the tile crosses into the next non-empty sequence
+                    do {
+                        ++b;
+                        seq_end = cu[b + 1];
+                    } while (n >= seq_end);
+                    a01 = a_all[((int64_t)b * L.n_kv_heads + h) * (SPARK_D / 2) + lane];
+                    // finish this load here, inside the rare branch: otherwise the wait for it
+                    // lands after the join and drains the prefetched K rows on every token
+                    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
                 }
                 // saliency: one float32 multiply, never fused
-                const float w0 = __fmul_rn(a0, fabsf(bf16_bits_to_float(x0)));
-                const float w1 = __fmul_rn(a1, fabsf(bf16_bits_to_float(x1)));
+                const float w0 = __fmul_rn(a01.x, fabsf(__uint_as_float(xx << 16)));
+                const float w1 = __fmul_rn(a01.y, fabsf(__uint_as_float(xx & 0xFFFF0000u)));
                 const uint32_t key0 = __float_as_uint(w0), key1 = __float_as_uint(w1);
 
                 bool keep0, keep1;
@@ -181,26 +206,28 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                         keep0 = key0 >= p;
                         keep1 = key1 >= p;
                     } else {              // p is the T-th largest value and it is tied
-                        const uint64_t e0 = __ballot(key0 == p), e1 = __ballot(key1 == p);
+                        const bool eq0 = (key0 == p), eq1 = (key1 == p);
+                        const uint64_t q0 = __ballot(eq0), q1 = __ballot(eq1);
                         const int need = T - __popcll(__ballot(key0 > p)) - __popcll(__ballot(key1 > p));
-                        const int r0 = __builtin_amdgcn_mbcnt_hi((uint32_t)(e0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)e0, 0));
-                        const int r1 = __popcll(e0) + __builtin_amdgcn_mbcnt_hi((uint32_t)(e1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)e1, 0));
-                        keep0 = (key0 > p) || (key0 == p && r0 < need);   // lower channel first
-                        keep1 = (key1 > p) || (key1 == p && r1 < need);
+                        // tied channels below 2l: both halves of every lower lane; below 2l+1: plus own even
+                        const int r0 = mbcnt64(q0) + mbcnt64(q1);
+                        const int r1 = r0 + (eq0 ? 1 : 0);
+                        keep0 = (key0 > p) || (eq0 && r0 < need);   // lower channel first
+                        keep1 = (key1 > p) || (eq1 && r1 < need);
                     }
                 }
                 const uint64_t kb0 = __ballot(keep0), kb1 = __ballot(keep1);
                 // slot of each kept value = number of kept channels below it
-                const int pos0 = __builtin_amdgcn_mbcnt_hi((uint32_t)(kb0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)kb0, 0));
-                const int pos1 = __popcll(kb0) + __builtin_amdgcn_mbcnt_hi((uint32_t)(kb1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)kb1, 0));
+                const int pos0 = mbcnt64(kb0) + mbcnt64(kb1);
+                const int pos1 = pos0 + (keep0 ? 1 : 0);
                 uint16_t *vrow = stage16 + (size_t)t * sw * 2 + L.val0 * 2;
-                if (keep0) vrow[pos0] = (uint16_t)x0;
-                if (keep1) vrow[pos1] = (uint16_t)x1;
-                const bool mine = (lane == t);   // lane t keeps the mask words of token t
-                mreg0 = mine ? (uint32_t)kb0 : mreg0;
-                mreg1 = mine ? (uint32_t)(kb0 >> 32) : mreg1;
-                mreg2 = mine ? (uint32_t)kb1 : mreg2;
-                mreg3 = mine ? (uint32_t)(kb1 >> 32) : mreg3;
+                if (keep0) vrow[pos0] = (uint16_t)xx;
+                if (keep1) vrow[pos1] = (uint16_t)(xx >> 16);
+                const bool mine = (lane == t);
+                e_lo = mine ? (uint32_t)kb0 : e_lo;
+                e_hi = mine ? (uint32_t)(kb0 >> 32) : e_hi;
+                o_lo = mine ? (uint32_t)kb1 : o_lo;
+                o_hi = mine ? (uint32_t)(kb1 >> 32) : o_hi;
                 psum[(t & (kPsumTokens - 1)) * kPsumStride + lane] = (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
             }
             if ((t & (kPsumTokens - 1)) == kPsumTokens - 1) {
@@ -221,6 +248,8 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             }
         }
+#pragma unroll
+        for (int u = 0; u < PF; ++u) xc[u] = xn[u];
     }
 
     // ---- row epilogue, lane = token
@@ -230,13 +259,14 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     const bool valid = lane < nvalid;
     uint32_t *row = stage + (size_t)lane * sw;
     const float mu = (valid && T < SPARK_D) ? (mureg / (float)(SPARK_D - T)) : 0.0f;
-    // rows past the last token carry a well-formed mask (channels 0..T-1) and zero values, so a
-    // reader that walks exactly T bits never runs off the mask
+    // channel-ordered mask: bit 2l of the row = even ballot bit l, bit 2l+1 = odd ballot bit l.
+    // Rows past the last token carry a well-formed mask (channels 0..T-1) and zero values, so a
+    // reader that walks exactly T bits never runs off the mask.
     auto low_bits = [](int n) { return n <= 0 ? 0u : (n >= 32 ? 0xFFFFFFFFu : ((1u << n) - 1u)); };
-    row[0] = valid ? mreg0 : low_bits(T);
-    row[1] = valid ? mreg1 : low_bits(T - 32);
-    row[2] = valid ? mreg2 : low_bits(T - 64);
-    row[3] = valid ? mreg3 : low_bits(T - 96);
+    row[0] = valid ? (spread16(e_lo) | (spread16(o_lo) << 1)) : low_bits(T);
+    row[1] = valid ? (spread16(e_lo >> 16) | (spread16(o_lo >> 16) << 1)) : low_bits(T - 32);
+    row[2] = valid ? (spread16(e_hi) | (spread16(o_hi) << 1)) : low_bits(T - 64);
+    row[3] = valid ? (spread16(e_hi >> 16) | (spread16(o_hi >> 16) << 1)) : low_bits(T - 96);
     row[4] = __float_as_uint(mu);
     if (!valid) {
         for (int d = 5; d < sw; ++d) row[d] = 0u;
