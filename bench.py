@@ -87,7 +87,7 @@ def main() -> int:
     cu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
     pbytes = spark.packed_bytes(desc)
     packs = [torch.empty(pbytes, dtype=torch.uint8, device="cuda") for _ in range(ncopy)]
-    ws = torch.empty(max(16, spark.decode_workspace_bytes(desc)), dtype=torch.uint8, device="cuda")
+    ws = spark.new_decode_workspace(desc)
     out = torch.empty((w.batch, hq, D), dtype=torch.bfloat16, device="cuda")
     for c in range(ncopy):
         spark.prune(desc, ks[c], qwin, cu, packs[c])
@@ -157,7 +157,7 @@ def main() -> int:
                   "Mtokens_per_s": round(total / prune_us, 2) if prune_us > 0 else None},
         "roofline": {"bound": "hbm", "achieved": round(dec_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dec_gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "spark_decode_kernel (+ spark_combine_kernel), HIP events around spark_decode_attn"},
+                     "kernel": "spark_decode_kernel, HIP events around spark_decode_attn"},
         "packed_row_bytes": row_bytes,
         "input_generation_s": round(gen_s, 1),
     }

@@ -76,6 +76,16 @@ size_t spark_packed_bytes(const spark_desc *desc);
 size_t spark_prune_workspace(const spark_desc *desc);
 size_t spark_decode_workspace(const spark_desc *desc);
 
+/*
+ * Prepares a decode workspace: zeroes the per-(batch, KV head) arrival counters at its end.
+ * Call once after allocating (or overwriting) the workspace and whenever batch, n_q_heads,
+ * n_kv_heads or the split count change; spark_decode_attn leaves the counters zeroed, so one
+ * workspace serves any number of successive calls on one stream.  Two calls that overlap in
+ * time need two workspaces.
+ */
+spark_status spark_decode_workspace_init(const spark_desc *desc, void *workspace,
+                                         size_t workspace_bytes, void *hip_stream);
+
 /* Number of sequence splits spark_decode_attn will use for this description. */
 int32_t spark_decode_splits(const spark_desc *desc);
 
@@ -120,7 +130,10 @@ spark_status spark_prune(const spark_desc *desc, const void *k_bf16, const void 
  *                   pack_dtype / total_tokens and the same cu_seqlens
  *   v_bf16     in   dense values, bf16, addressed with v_*_stride
  *   out        out  [batch, n_q_heads, 128], bf16 or float32 per desc->out_dtype
- *   workspace       spark_decode_workspace(desc) bytes, 16-byte aligned (split partials)
+ *   workspace       spark_decode_workspace(desc) bytes, 16-byte aligned, prepared with
+ *                   spark_decode_workspace_init (split partials and arrival counters)
+ * One kernel launch: the sequence is split over blocks, and the block that finishes last for a
+ * (batch, KV head) pair merges the partial softmax states and writes the output.
  */
 spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const void *packed,
                                const void *v_bf16, const int32_t *cu_seqlens, void *out,
@@ -139,6 +152,14 @@ spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const
 spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *mask_out,
                           void *vals_out, float *mu_out, float *scale_out, float *a_out,
                           void *hip_stream);
+
+/*
+ * Measurement aid, not part of the method: reads `bytes` (a multiple of 16) from `src` once with
+ * 16-byte loads from n_blocks blocks of 256 threads and discards them.  Its time is the
+ * streaming-read ceiling the decode kernel is compared with.  `sink` is 4 writable bytes.
+ */
+spark_status spark_probe_read(const void *src, size_t bytes, void *sink, int32_t n_blocks,
+                              void *hip_stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char *spark_status_string(spark_status status);

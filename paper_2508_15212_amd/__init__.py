@@ -1,10 +1,12 @@
 """MI355X-native SparK hot path: channel pruning of the key cache at prefill and decode
 attention over the packed cache.  Thin ctypes binding over ``libspark_hip.so`` (C ABI in
 ``include/spark.h``); every step of the path runs in the library's HIP kernels."""
-from .binding import (SparkDesc, decode_attn, decode_splits, decode_workspace_bytes, lib_path,
-                      load, packed_bytes, prune, unpack, SparkError,
+from .binding import (SparkDesc, decode_attn, decode_splits, decode_workspace_bytes, decode_workspace_init,
+                      new_decode_workspace, lib_path,
+                      load, packed_bytes, probe_read, prune, unpack, SparkError,
                       PACK_BF16, PACK_INT8, OUT_BF16, OUT_F32)
 
-__all__ = ["SparkDesc", "decode_attn", "decode_splits", "decode_workspace_bytes", "lib_path", "load",
-           "packed_bytes", "prune", "unpack", "SparkError", "PACK_BF16", "PACK_INT8", "OUT_BF16",
+__all__ = ["SparkDesc", "decode_attn", "decode_splits", "decode_workspace_bytes", "decode_workspace_init",
+           "new_decode_workspace", "lib_path", "load",
+           "packed_bytes", "probe_read", "prune", "unpack", "SparkError", "PACK_BF16", "PACK_INT8", "OUT_BF16",
            "OUT_F32"]

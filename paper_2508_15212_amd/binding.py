@@ -17,8 +17,8 @@ _LIB_PATH = os.path.join(_HERE, "libspark_hip.so")
 PACK_BF16, PACK_INT8 = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
 
-EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspace", "spark_decode_splits",
-           "spark_prune", "spark_decode_attn", "spark_unpack", "spark_status_string"]
+EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspace", "spark_decode_workspace_init", "spark_decode_splits",
+           "spark_prune", "spark_decode_attn", "spark_unpack", "spark_probe_read", "spark_status_string"]
 
 
 class SparkError(RuntimeError):
@@ -62,6 +62,8 @@ def load() -> ctypes.CDLL:
     lib.spark_prune_workspace.argtypes = [dp]
     lib.spark_decode_workspace.restype = ctypes.c_size_t
     lib.spark_decode_workspace.argtypes = [dp]
+    lib.spark_decode_workspace_init.restype = ctypes.c_int
+    lib.spark_decode_workspace_init.argtypes = [dp, vp, ctypes.c_size_t, vp]
     lib.spark_decode_splits.restype = ctypes.c_int32
     lib.spark_decode_splits.argtypes = [dp]
     lib.spark_prune.restype = ctypes.c_int
@@ -70,6 +72,8 @@ def load() -> ctypes.CDLL:
     lib.spark_decode_attn.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.spark_unpack.restype = ctypes.c_int
     lib.spark_unpack.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
+    lib.spark_probe_read.restype = ctypes.c_int
+    lib.spark_probe_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, vp]
     lib.spark_status_string.restype = ctypes.c_char_p
     lib.spark_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -97,6 +101,19 @@ def decode_workspace_bytes(desc: SparkDesc) -> int:
     return int(load().spark_decode_workspace(ctypes.byref(desc)))
 
 
+def decode_workspace_init(desc: SparkDesc, workspace: torch.Tensor) -> None:
+    rc = load().spark_decode_workspace_init(ctypes.byref(desc), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "spark_decode_workspace_init")
+
+
+def new_decode_workspace(desc: SparkDesc) -> torch.Tensor:
+    """Allocate (through torch) and prepare a workspace for spark_decode_attn."""
+    ws = torch.empty(max(16, decode_workspace_bytes(desc)), dtype=torch.uint8, device="cuda")
+    decode_workspace_init(desc, ws)
+    return ws
+
+
 def decode_splits(desc: SparkDesc) -> int:
     return int(load().spark_decode_splits(ctypes.byref(desc)))
 
@@ -121,3 +138,9 @@ def unpack(desc: SparkDesc, packed: torch.Tensor, mask=None, vals=None, mu=None,
     rc = load().spark_unpack(ctypes.byref(desc), _ptr(packed), _ptr(mask), _ptr(vals), _ptr(mu), _ptr(scale),
                              _ptr(a), _stream())
     _check(rc, "spark_unpack")
+
+
+def probe_read(src: torch.Tensor, sink: torch.Tensor, n_blocks: int) -> None:
+    """spark_probe_read: stream `src` once (measurement aid)."""
+    rc = load().spark_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), n_blocks, _stream())
+    _check(rc, "spark_probe_read")

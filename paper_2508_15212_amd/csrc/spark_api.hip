@@ -41,15 +41,16 @@ bool strides_ok(int64_t tok, int64_t head)
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-// Splits per (batch, KV head): enough blocks to cover the chip a few times over, but at least
-// four tiles (256 tokens) per wavefront of a block on an average-length sequence.
+// Splits per (batch, KV head).  The decode kernel keeps two 4-wave blocks resident per compute
+// unit (256 CUs), so 512 blocks stream the cache in a single round with no tail; aim for that,
+// but keep at least two tiles (128 tokens) per wavefront on an average-length sequence.
 int pick_splits(const spark_desc *d)
 {
     if (d->n_splits > 0) return d->n_splits;
     const int64_t pairs = (int64_t)d->batch * d->n_kv_heads;
     const int64_t avg_tiles = (d->total_tokens / d->batch + SPARK_TILE_TOKENS - 1) / SPARK_TILE_TOKENS;
-    int64_t want = (2048 + pairs - 1) / pairs;
-    int64_t cap = avg_tiles / 16;
+    int64_t want = (512 + pairs / 2) / pairs;
+    int64_t cap = avg_tiles / 8;
     if (cap < 1) cap = 1;
     if (want > cap) want = cap;
     if (want < 1) want = 1;
@@ -57,9 +58,42 @@ int pick_splits(const spark_desc *d)
     return (int)want;
 }
 
+// Streaming-read yardstick: every lane pulls 16-byte words grid-stride and folds them into one
+// value that is stored only to keep the loads alive.
+__global__ __launch_bounds__(256) void spark_probe_read_kernel(const uint4 *__restrict__ src, size_t n16,
+                                                               uint32_t *__restrict__ sink)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    uint32_t acc = 0;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 a = src[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    if (acc == 0x9E3779B9u) sink[0] = acc;
+}
+
+size_t counter_bytes(const spark_desc *d)
+{
+    return (((size_t)d->batch * d->n_kv_heads * sizeof(uint32_t)) + 15) & ~(size_t)15;
+}
+
 }  // namespace
 
 extern "C" {
+
+spark_status spark_probe_read(const void *src, size_t bytes, void *sink, int32_t n_blocks, void *hip_stream)
+{
+    if (!src || !sink || bytes < 16 || n_blocks < 1 || !aligned(src, 16) || !aligned(sink, 4))
+        return SPARK_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(spark_probe_read_kernel, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const uint4 *>(src), bytes / 16, static_cast<uint32_t *>(sink));
+    return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
+}
 
 const char *spark_status_string(spark_status s)
 {
@@ -98,7 +132,21 @@ size_t spark_decode_workspace(const spark_desc *desc)
     spark_status why;
     if (!desc_ok(desc, &why)) return 0;
     const size_t slots = (size_t)desc->batch * desc->n_q_heads * pick_splits(desc);
-    return slots * (SPARK_D + 2) * sizeof(float);
+    return slots * (SPARK_D + 2) * sizeof(float) + counter_bytes(desc);
+}
+
+spark_status spark_decode_workspace_init(const spark_desc *desc, void *workspace, size_t workspace_bytes,
+                                         void *hip_stream)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!workspace || !aligned(workspace, 16)) return SPARK_ERR_INVALID_ARG;
+    if (workspace_bytes < spark_decode_workspace(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
+    const size_t slots = (size_t)desc->batch * desc->n_q_heads * pick_splits(desc);
+    uint32_t *counters = reinterpret_cast<uint32_t *>(static_cast<float *>(workspace) + slots * (SPARK_D + 2));
+    const hipError_t e = spark::launch_zero_counters(counters, desc->batch * desc->n_kv_heads,
+                                                     static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }
 
 spark_status spark_prune(const spark_desc *desc, const void *k_bf16, const void *qwin_bf16,
@@ -138,11 +186,12 @@ spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const
     const size_t slots = (size_t)desc->batch * desc->n_q_heads * nsplit;
     float *part_acc = static_cast<float *>(workspace);
     float *part_ml = part_acc + slots * SPARK_D;
+    uint32_t *counters = reinterpret_cast<uint32_t *>(part_ml + slots * 2);
     const float scale = desc->softmax_scale != 0.0f ? desc->softmax_scale : 1.0f / sqrtf((float)SPARK_D);
     const hipError_t e = spark::launch_decode_attn(
         static_cast<const uint16_t *>(q_bf16), static_cast<const uint8_t *>(packed),
         static_cast<const uint16_t *>(v_bf16), desc->v_token_stride, desc->v_head_stride, cu_seqlens, part_acc,
-        part_ml, desc->n_q_heads, nsplit, scale, L, out, desc->out_dtype == SPARK_OUT_F32,
+        part_ml, counters, desc->n_q_heads, nsplit, scale, L, out, desc->out_dtype == SPARK_OUT_F32,
         static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }

@@ -17,7 +17,8 @@
 //      query heads, K = tokens), split into a high and a low bf16 part so P keeps ~16
 //      significant bits; V rows are read 16 bytes per lane, transposed in registers with
 //      byte permutes into B operands (K = tokens, N = channels) and accumulated in float32.
-// Split partials (m, l, unnormalised output) are merged by spark_combine_kernel.
+// Split partials (m, l, unnormalised output) go to the workspace; the block that arrives last at
+// its (batch, KV head) counter merges them and writes the output, so one launch does the step.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -38,6 +39,9 @@ struct DecodeParams {
     const int32_t *cu;       // [B+1]
     float *part_acc;         // [B*Hq*nsplit][128]
     float *part_ml;          // [B*Hq*nsplit][2]  (m in log2 units, l)
+    uint32_t *counters;      // [B*Hkv] arrival counters, zero between calls
+    void *out;               // [B, Hq, 128] bf16 or float32
+    int out_f32;
     int Hq, Hkv, nsplit;
     float scale_log2;        // softmax scale * log2(e)
     SparkLayout L;
@@ -54,11 +58,26 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Maximum over the 64 lanes, returned wave-uniform.  Data-parallel-primitive moves: two quad
+// permutes and two row rotates leave each row of 16 lanes holding its row maximum, two row
+// broadcasts fold the four rows into lane 63.  Lanes a step does not address keep their value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_max_step(float x)
+{
+    const int xi = __float_as_int(x);
+    const float y = __int_as_float(__builtin_amdgcn_update_dpp(xi, xi, CTRL, ROW_MASK, 0xF, false));
+    return fmaxf(x, y);
+}
+
 __device__ __forceinline__ float wave_max(float x)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-    return x;
+    x = dpp_max_step<0xB1, 0xF>(x);    // quad_perm [1,0,3,2]
+    x = dpp_max_step<0x4E, 0xF>(x);    // quad_perm [2,3,0,1]
+    x = dpp_max_step<0x124, 0xF>(x);   // row_ror 4
+    x = dpp_max_step<0x128, 0xF>(x);   // row_ror 8
+    x = dpp_max_step<0x142, 0xA>(x);   // row_bcast 15 into rows 1 and 3
+    x = dpp_max_step<0x143, 0xC>(x);   // row_bcast 31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
 __device__ __forceinline__ float wave_sum(float x)
@@ -68,13 +87,16 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
+// device-scope (all XCDs) relaxed store / load of one float
+__device__ __forceinline__ void st_agent(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_agent(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ uint32_t u4c(const uint4 &v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
 template <int G, int TCT, int INT8>
-__global__ __launch_bounds__(kDecodeWaves * 64) void spark_decode_kernel(DecodeParams P)
+__global__ __launch_bounds__(kDecodeWaves * 64, 2) void spark_decode_kernel(DecodeParams P)
 {
     constexpr int GP = ((G + 1 + 3) / 4) * 4;   // floats per table entry: G queries, 1/a, pad
     constexpr int VAL0 = INT8 ? 6 : 5;
@@ -87,6 +109,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void spark_decode_kernel(DecodeP
     __shared__ __align__(16) uint16_t Pbuf[kDecodeWaves][2][G][64];
     __shared__ __align__(16) float red_acc[kDecodeWaves][G][SPARK_D];
     __shared__ float red_m[kDecodeWaves][G], red_l[kDecodeWaves][G];
+    __shared__ int last_flag;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -98,6 +121,81 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void spark_decode_kernel(DecodeP
     const int h = bh % P.Hkv, b = bh / P.Hkv;
     const int s0 = P.cu[b], s1 = P.cu[b + 1];
 
+    // ---- tiles of this split
+    int t_begin = 0, t_end = 0;
+    if (s1 > s0) {
+        const int tf = s0 / SPARK_TILE_TOKENS, tl = (s1 - 1) / SPARK_TILE_TOKENS;
+        const int ntile = tl - tf + 1;
+        const int chunk = (ntile + P.nsplit - 1) / P.nsplit;
+        t_begin = tf + split * chunk;
+        t_end = t_begin + chunk;
+        if (t_end > tl + 1) t_end = tl + 1;
+    }
+
+    float m[G], l[G], R[G];
+    f32x4 acc[8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.0f; }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int tg = lane >> 4, cn = lane & 15;
+    // slot of this lane's token in the P buffer: MFMA lane group tg' = token % 4 holds, as its K
+    // index i, token 32*ks + 4*i + tg' (the same order in which V rows are fetched)
+    const int ppos = (lane & 32) | ((lane & 3) << 3) | ((lane & 31) >> 2);
+    const uint8_t *tiles = P.packed + L.off_tiles + (int64_t)h * L.n_tiles * L.tile_bytes;
+    const uint16_t *vbase = P.v + (int64_t)h * P.v_head_stride + cn * 8;
+
+    constexpr int NR = TCT ? NDW_CT : 6;    // row words held in registers
+    auto load_row = [&](int tile, uint32_t (&r)[NR]) {
+        const uint8_t *tp = tiles + (int64_t)tile * L.tile_bytes;
+        if (TCT) {
+#pragma unroll
+            for (int qd = 0; qd < NQ_CT; ++qd) {
+                const uint4 x = *reinterpret_cast<const uint4 *>(tp + qd * 1024 + lane * 16);
+                r[4 * qd + 0] = x.x; r[4 * qd + 1] = x.y; r[4 * qd + 2] = x.z; r[4 * qd + 3] = x.w;
+            }
+            if (NDW_CT % 4) {
+                const uint2 x = *reinterpret_cast<const uint2 *>(tp + NQ_CT * 1024 + lane * 8);
+                r[4 * NQ_CT + 0] = x.x; r[4 * NQ_CT + 1] = x.y;
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < 6; ++d)
+                r[d] = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, d));
+        }
+    };
+    // half a tile of V: lane (tg, cn) takes 16 bytes (channels 8cn..8cn+7) of rows 4i + tg, so that
+    // one load instruction of the wavefront covers 4 consecutive rows (1 KB when rows are contiguous)
+    auto load_v = [&](int tile, int ks, uint4 (&vh)[8]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int n = tile * SPARK_TILE_TOKENS + 32 * ks + 4 * i + tg;
+            n = (n < s0) ? s0 : n;
+            n = (n > s1 - 1) ? (s1 - 1) : n;     // rows outside the sequence get p = 0
+            vh[i] = *reinterpret_cast<const uint4 *>(vbase + (int64_t)n * P.v_tok_stride);
+        }
+    };
+
+    // Software pipeline: the packed row of tile i+1 is requested before the scores of tile i are
+    // computed, and each half of V for tile i+1 is requested as soon as the registers of the same
+    // half of tile i have been turned into MFMA operands.
+    uint32_t rn[NR];
+    uint4 vr[2][8];
+    // Tiles are visited in rotated order, a different rotation per block.  The order does not
+    // matter to the running softmax, and it keeps the blocks (whose V chunks start at large
+    // power-of-two distances) from sweeping the memory channels in lockstep.
+    const int nts = t_end - t_begin;
+    const int rot = nts > 0 ? (int)((blockIdx.x * 37u) % (uint32_t)nts) : 0;
+    auto tile_of = [&](int k) { int li = k + rot; li = (li >= nts) ? li - nts : li; return t_begin + li; };
+    int kidx = wave;
+    int tile = tile_of(kidx);
+    if (kidx < nts) {
+        load_row(tile, rn);
+        load_v(tile, 0, vr[0]);
+        load_v(tile, 1, vr[1]);
+    }
+    // (the first tile's loads are already in flight while the table is built)
     // ---- per-step query prep: table {q_g[j] * scale * log2e, 1/a[j]} and R_g
     if (tid < SPARK_D) {
         const int j = tid;
@@ -117,64 +215,22 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void spark_decode_kernel(DecodeP
         if (lane == 0) Rsh[g] = r;
     }
     __syncthreads();
-    float R[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) R[g] = Rsh[g];
 
-    // ---- tiles of this split
-    int t_begin = 0, t_end = 0;
-    if (s1 > s0) {
-        const int tf = s0 / SPARK_TILE_TOKENS, tl = (s1 - 1) / SPARK_TILE_TOKENS;
-        const int ntile = tl - tf + 1;
-        const int chunk = (ntile + P.nsplit - 1) / P.nsplit;
-        t_begin = tf + split * chunk;
-        t_end = t_begin + chunk;
-        if (t_end > tl + 1) t_end = tl + 1;
-    }
 
-    float m[G], l[G];
-    f32x4 acc[8];
-#pragma unroll
-    for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.0f; }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    const int tg = lane >> 4, cn = lane & 15;
-    const uint8_t *tiles = P.packed + L.off_tiles + (int64_t)h * L.n_tiles * L.tile_bytes;
-    const uint16_t *vbase = P.v + (int64_t)h * P.v_head_stride + cn * 8;
-
-    for (int tile = t_begin + wave; tile < t_end; tile += kDecodeWaves) {
+    for (; kidx < nts; kidx += kDecodeWaves) {
+        tile = tile_of(kidx);
         const uint8_t *tp = tiles + (int64_t)tile * L.tile_bytes;
         const int n_lane = tile * SPARK_TILE_TOKENS + lane;
         const bool valid = (n_lane >= s0) && (n_lane < s1);
+        const bool more = kidx + kDecodeWaves < nts;            // wave-uniform
+        const int tnext = tile_of(more ? kidx + kDecodeWaves : kidx);
 
-        // ---- issue the loads: packed row of this lane's token, then 16 V row segments
-        uint32_t r[TCT ? NDW_CT : 6];
-        if (TCT) {
+        uint32_t r[NR];
 #pragma unroll
-            for (int qd = 0; qd < NQ_CT; ++qd) {
-                const uint4 x = *reinterpret_cast<const uint4 *>(tp + qd * 1024 + lane * 16);
-                r[4 * qd + 0] = x.x; r[4 * qd + 1] = x.y; r[4 * qd + 2] = x.z; r[4 * qd + 3] = x.w;
-            }
-            if (NDW_CT % 4) {
-                const uint2 x = *reinterpret_cast<const uint2 *>(tp + NQ_CT * 1024 + lane * 8);
-                r[4 * NQ_CT + 0] = x.x; r[4 * NQ_CT + 1] = x.y;
-            }
-        } else {
-#pragma unroll
-            for (int d = 0; d < 6; ++d)
-                r[d] = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, d));
-        }
-        uint4 vr[2][8];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                int n = tile * SPARK_TILE_TOKENS + 32 * ks + 8 * tg + i;
-                n = (n < s0) ? s0 : n;
-                n = (n > s1 - 1) ? (s1 - 1) : n;     // rows outside the sequence get p = 0
-                vr[ks][i] = *reinterpret_cast<const uint4 *>(vbase + (int64_t)n * P.v_tok_stride);
-            }
+        for (int d = 0; d < NR; ++d) r[d] = rn[d];
+        if (more) load_row(tnext, rn);
 
         // ---- scores, lane = token
         const float mu = __uint_as_float(r[4]);
@@ -205,6 +261,14 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void spark_decode_kernel(DecodeP
 #pragma unroll
                 for (int g = 0; g < G; ++g) s[g] = fmaf(e[g], d, s[g]);
             };
+#ifdef EXP_NO_QK
+            if (TCT) {
+                uint32_t xx = 0;
+#pragma unroll
+                for (int d = 0; d < NR; ++d) xx ^= r[d];
+                s[0] = __uint_as_float(xx & 0x3FFFFFFFu);
+            } else
+#endif
             if (TCT) {
 #pragma unroll
                 for (int i = 0; i < TCT; ++i) entry(i, r[VAL0 + (INT8 ? i / 4 : i / 2)]);
@@ -238,8 +302,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void spark_decode_kernel(DecodeP
             l[g] = fmaf(l[g], alpha[g], p);
             const __bf16 ph = (__bf16)p;
             const __bf16 pl = (__bf16)(p - (float)ph);
-            Pbuf[wave][0][g][lane] = __builtin_bit_cast(uint16_t, ph);
-            Pbuf[wave][1][g][lane] = __builtin_bit_cast(uint16_t, pl);
+            Pbuf[wave][0][g][ppos] = __builtin_bit_cast(uint16_t, ph);
+            Pbuf[wave][1][g][ppos] = __builtin_bit_cast(uint16_t, pl);
         }
         if (rescale) {   // wave-uniform: m is the same in every lane
             float al[4];
@@ -265,22 +329,33 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void spark_decode_kernel(DecodeP
             }
             const bf16x8 A_hi = __builtin_bit_cast(bf16x8, ah);
             const bf16x8 A_lo = __builtin_bit_cast(bf16x8, alo);
+            // 8x8 transpose of this lane's (token, channel) block: B operand e = channel 8cn+e, K = tokens
+            u32x4 bop[8];
+#ifdef EXP_NO_PV
+            {
+                uint32_t xx = 0;
 #pragma unroll
-            for (int cp = 0; cp < 4; ++cp) {
-                u32x4 be, bo;   // channels 2cp and 2cp+1 of this lane's 8: tokens 0..7 along K
+                for (int i = 0; i < 8; ++i) xx ^= vr[ks][i].x ^ vr[ks][i].y ^ vr[ks][i].z ^ vr[ks][i].w;
+                acc[0][0] += __uint_as_float(xx & 0x3FFFFFFFu) + A_hi[0] + A_lo[0];
+            }
+            if (more) load_v(tnext, ks, vr[ks]);
+            continue;
+#endif
+#pragma unroll
+            for (int cp = 0; cp < 4; ++cp)
 #pragma unroll
                 for (int tp2 = 0; tp2 < 4; ++tp2) {
                     const uint32_t x = u4c(vr[ks][2 * tp2], cp);
                     const uint32_t y = u4c(vr[ks][2 * tp2 + 1], cp);
-                    be[tp2] = __builtin_amdgcn_perm(y, x, 0x05040100u);   // low halves  (x | y << 16)
-                    bo[tp2] = __builtin_amdgcn_perm(y, x, 0x07060302u);   // high halves
+                    bop[2 * cp][tp2] = __builtin_amdgcn_perm(y, x, 0x05040100u);       // low halves  (x | y << 16)
+                    bop[2 * cp + 1][tp2] = __builtin_amdgcn_perm(y, x, 0x07060302u);   // high halves
                 }
-                const bf16x8 B_e = __builtin_bit_cast(bf16x8, be);
-                const bf16x8 B_o = __builtin_bit_cast(bf16x8, bo);
-                acc[2 * cp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_hi, B_e, acc[2 * cp], 0, 0, 0);
-                acc[2 * cp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_lo, B_e, acc[2 * cp], 0, 0, 0);
-                acc[2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_hi, B_o, acc[2 * cp + 1], 0, 0, 0);
-                acc[2 * cp + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_lo, B_o, acc[2 * cp + 1], 0, 0, 0);
+            if (more) load_v(tnext, ks, vr[ks]);     // registers of this half are free again
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bf16x8 B = __builtin_bit_cast(bf16x8, bop[e]);
+                acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_hi, B, acc[e], 0, 0, 0);
+                acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_lo, B, acc[e], 0, 0, 0);
             }
         }
         wave_lds_sync();   // P buffer is rewritten by the next tile
@@ -316,35 +391,87 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void spark_decode_kernel(DecodeP
             A = fmaf(red_acc[w][g][ch], f, A);
         }
         const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nsplit + split;
-        P.part_acc[slot * SPARK_D + ch] = A;
-        if (ch == 0) { P.part_ml[slot * 2] = M; P.part_ml[slot * 2 + 1] = Lsum; }
+        st_agent(&P.part_acc[slot * SPARK_D + ch], A);
+        if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
+    }
+
+    // ---- the last block of this (batch, KV head) to get here merges the splits.
+    // The partials are written and read with device-scope accesses (they go to the point where
+    // all the chip's L2 slices agree), each thread waits for its own stores to be acknowledged,
+    // and only then is the block's arrival counted.  That orders partials before the count
+    // without a device-wide cache write-back.  atomicInc wraps at nsplit-1, which leaves the
+    // counter at zero for the next call.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have completed
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t old = atomicInc(&P.counters[bh], (uint32_t)(P.nsplit - 1));
+        last_flag = (old == (uint32_t)(P.nsplit - 1));
+    }
+    __syncthreads();
+    if (!last_flag) return;
+    // Each thread owns output elements (g, ch) and folds the nsplit partial states into one with
+    // the running-maximum rule, eight splits' loads in flight at a time, two elements at once.
+    constexpr int NTH = kDecodeWaves * 64;
+    for (int idx0 = tid; idx0 < G * SPARK_D; idx0 += 2 * NTH) {
+        float M[2], Lsum[2], A[2];
+        const float *ml[2], *pa[2];
+        int64_t bq[2];
+        int ch[2];
+        bool on[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = idx0 + u * NTH;
+            on[u] = idx < G * SPARK_D;
+            const int g = on[u] ? idx / SPARK_D : 0;
+            ch[u] = idx % SPARK_D;
+            bq[u] = (int64_t)b * P.Hq + h * G + g;
+            ml[u] = P.part_ml + bq[u] * P.nsplit * 2;
+            pa[u] = P.part_acc + bq[u] * P.nsplit * SPARK_D + ch[u];
+            M[u] = -INFINITY; Lsum[u] = 0.0f; A[u] = 0.0f;
+        }
+        for (int i0 = 0; i0 < P.nsplit; i0 += 8) {
+            float mi[2][8], li[2][8], ai[2][8];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int i = (i0 + k < P.nsplit) ? (i0 + k) : (P.nsplit - 1);
+                    mi[u][k] = ld_agent(ml[u] + 2 * i);
+                    li[u][k] = ld_agent(ml[u] + 2 * i + 1);
+                    ai[u][k] = ld_agent(pa[u] + (int64_t)i * SPARK_D);
+                }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    if (i0 + k < P.nsplit) {
+                        const float Mn = fmaxf(M[u], mi[u][k]);
+                        const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
+                        const float fo = fast_exp2(M[u] - Ms), fn = fast_exp2(mi[u][k] - Ms);
+                        Lsum[u] = fmaf(Lsum[u], fo, li[u][k] * fn);
+                        A[u] = fmaf(A[u], fo, ai[u][k] * fn);
+                        M[u] = Mn;
+                    }
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (!on[u]) continue;
+            const float o = (Lsum[u] > 0.0f) ? (A[u] / Lsum[u]) : 0.0f;
+            if (P.out_f32)
+                reinterpret_cast<float *>(P.out)[bq[u] * SPARK_D + ch[u]] = o;
+            else
+                reinterpret_cast<uint16_t *>(P.out)[bq[u] * SPARK_D + ch[u]] = __builtin_bit_cast(uint16_t, (__bf16)o);
+        }
     }
 }
 
-// grid = B*Hq blocks, 128 threads (thread = channel): merge the split partials, normalise.
-__global__ __launch_bounds__(SPARK_D) void spark_combine_kernel(const float *__restrict__ part_acc,
-                                                                const float *__restrict__ part_ml,
-                                                                int nsplit, void *__restrict__ out,
-                                                                int out_f32)
+// Zeroes the arrival counters of a fresh workspace.
+__global__ void spark_zero_kernel(uint32_t *p, int n)
 {
-    const int64_t bq = blockIdx.x;
-    const int ch = threadIdx.x;
-    float M = -INFINITY;
-    for (int i = 0; i < nsplit; ++i) M = fmaxf(M, part_ml[(bq * nsplit + i) * 2]);
-    const float Ms = (M == -INFINITY) ? 0.0f : M;
-    float Lsum = 0.0f, A = 0.0f;
-    for (int i = 0; i < nsplit; ++i) {
-        const float f = fast_exp2(part_ml[(bq * nsplit + i) * 2] - Ms);
-        Lsum = fmaf(part_ml[(bq * nsplit + i) * 2 + 1], f, Lsum);
-        A = fmaf(part_acc[(bq * nsplit + i) * SPARK_D + ch], f, A);
-    }
-    const float o = (Lsum > 0.0f) ? (A / Lsum) : 0.0f;
-    if (out_f32)
-        reinterpret_cast<float *>(out)[bq * SPARK_D + ch] = o;
-    else
-        reinterpret_cast<uint16_t *>(out)[bq * SPARK_D + ch] = __builtin_bit_cast(uint16_t, (__bf16)o);
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
 }
-
 
 // ---------------------------------------------------------------- host-side launch
 
@@ -369,9 +496,9 @@ static hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
 }
 
 hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const uint16_t *v, int64_t v_tok_stride,
-                              int64_t v_head_stride, const int32_t *cu, float *part_acc, float *part_ml, int Hq,
-                              int nsplit, float softmax_scale, const SparkLayout &L, void *out, int out_f32,
-                              hipStream_t st)
+                              int64_t v_head_stride, const int32_t *cu, float *part_acc, float *part_ml,
+                              uint32_t *counters, int Hq, int nsplit, float softmax_scale, const SparkLayout &L,
+                              void *out, int out_f32, hipStream_t st)
 {
     DecodeParams P;
     P.q = q;
@@ -382,6 +509,9 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.cu = cu;
     P.part_acc = part_acc;
     P.part_ml = part_ml;
+    P.counters = counters;
+    P.out = out;
+    P.out_f32 = out_f32;
     P.Hq = Hq;
     P.Hkv = L.n_kv_heads;
     P.nsplit = nsplit;
@@ -389,18 +519,19 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.L = L;
     const int G = P.Hq / P.Hkv;
     const int nblocks = L.batch * P.Hkv * P.nsplit;
-    hipError_t e;
     switch (G) {
-        case 1: e = launch_g<1>(P, nblocks, st); break;
-        case 2: e = launch_g<2>(P, nblocks, st); break;
-        case 4: e = launch_g<4>(P, nblocks, st); break;
-        case 8: e = launch_g<8>(P, nblocks, st); break;
-        case 16: e = launch_g<16>(P, nblocks, st); break;
+        case 1: return launch_g<1>(P, nblocks, st);
+        case 2: return launch_g<2>(P, nblocks, st);
+        case 4: return launch_g<4>(P, nblocks, st);
+        case 8: return launch_g<8>(P, nblocks, st);
+        case 16: return launch_g<16>(P, nblocks, st);
         default: return hipErrorInvalidValue;
     }
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(spark_combine_kernel, dim3(L.batch * P.Hq), dim3(SPARK_D), 0, st, P.part_acc, P.part_ml,
-                       P.nsplit, out, out_f32);
+}
+
+hipError_t launch_zero_counters(uint32_t *counters, int n, hipStream_t st)
+{
+    hipLaunchKernelGGL(spark_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, st, counters, n);
     return hipGetLastError();
 }
 

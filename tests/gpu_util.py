@@ -58,7 +58,7 @@ def run_gpu_case(w, t, layout="HND", pack=spark.PACK_BF16, n_splits=0, want_unpa
         res["a"] = a.cpu().numpy()
         if scale is not None:
             res["scale"] = scale.cpu().numpy()
-    ws = torch.empty(max(spark.decode_workspace_bytes(desc), 16), dtype=torch.uint8, device="cuda")
+    ws = spark.new_decode_workspace(desc)
     out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
     spark.decode_attn(desc, dq, packed, dv, dcu, out, ws)
     res["out_f32"] = out.cpu().numpy()
