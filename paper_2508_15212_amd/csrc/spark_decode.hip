@@ -95,8 +95,14 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
+#ifndef SPARK_DECODE_PIPE
+#define SPARK_DECODE_PIPE 0
+#endif
+// resident blocks per compute unit the register budget is held to: three where the kernel fits
+// 168 registers without spilling (small groups, short rows), else two
+constexpr int decode_min_blocks(int G, int TCT) { return (G <= 4 && TCT > 0 && TCT <= 40) ? 3 : 2; }
 template <int G, int TCT, int INT8>
-__global__ __launch_bounds__(kDecodeWaves * 64, 2) void spark_decode_kernel(DecodeParams P)
+__global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void spark_decode_kernel(DecodeParams P)
 {
     constexpr int GP = ((G + 1 + 3) / 4) * 4;   // floats per table entry: G queries, 1/a, pad
     constexpr int VAL0 = INT8 ? 6 : 5;
@@ -195,6 +201,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void spark_decode_kernel(Deco
         load_v(tile, 0, vr[0]);
         load_v(tile, 1, vr[1]);
     }
+    constexpr bool PIPE = SPARK_DECODE_PIPE;
     // (the first tile's loads are already in flight while the table is built)
     // ---- per-step query prep: table {q_g[j] * scale * log2e, 1/a[j]} and R_g
     if (tid < SPARK_D) {
@@ -230,8 +237,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void spark_decode_kernel(Deco
         uint32_t r[NR];
 #pragma unroll
         for (int d = 0; d < NR; ++d) r[d] = rn[d];
-        if (more) load_row(tnext, rn);
-
         // ---- scores, lane = token
         const float mu = __uint_as_float(r[4]);
         float s[G];
@@ -318,6 +323,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void spark_decode_kernel(Deco
                 for (int rr = 0; rr < 4; ++rr) acc[e][rr] *= al[rr];
         }
         wave_lds_sync();
+        if (PIPE && more) load_row(tnext, rn);
 
         // ---- P V on the matrix cores
 #pragma unroll
@@ -350,7 +356,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void spark_decode_kernel(Deco
                     bop[2 * cp][tp2] = __builtin_amdgcn_perm(y, x, 0x05040100u);       // low halves  (x | y << 16)
                     bop[2 * cp + 1][tp2] = __builtin_amdgcn_perm(y, x, 0x07060302u);   // high halves
                 }
-            if (more) load_v(tnext, ks, vr[ks]);     // registers of this half are free again
+            if (PIPE && more) load_v(tnext, ks, vr[ks]);     // registers of this half are free again
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const bf16x8 B = __builtin_bit_cast(bf16x8, bop[e]);
@@ -359,6 +365,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void spark_decode_kernel(Deco
             }
         }
         wave_lds_sync();   // P buffer is rewritten by the next tile
+        if (!PIPE && more) {
+            load_row(tnext, rn);
+            load_v(tnext, 0, vr[0]);
+            load_v(tnext, 1, vr[1]);
+        }
     }
 
     // ---- merge the 4 wavefronts, write the split partial
