@@ -27,6 +27,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per decode launch from rocprofv3 counters (FETCH_SIZE x 2.000 calibration + WRITE_SIZE),
+# per workload; measured once and recorded in profiles/decode_prune_cfg2_hbm_traffic.md.
+MEASURED_DECODE_TRAFFIC_BYTES = {("cfg2_llama8b_b8_32k_keep26", "bf16"): 2 * 336901 * 1024 + 1232 * 1024}
 
 
 def main() -> int:
@@ -117,6 +120,23 @@ def main() -> int:
     prune_ms = np.array([e[0].elapsed_time(e[1]) for e in evs])
     dec_ms = np.array([e[1].elapsed_time(e[2]) for e in evs])
 
+    # Streaming-read yardstick on this machine: the library's plain read kernel over one V copy
+    # (also the kernel of known size that scales the HBM byte counters of a profiler run).
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    probe_blocks = 1536
+    for c in range(ncopy):
+        spark.probe_read(vs[c], sink, probe_blocks)
+    torch.cuda.synchronize()
+    pev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(9)]
+    for i, (a, b) in enumerate(pev):
+        a.record()
+        spark.probe_read(vs[i % ncopy], sink, probe_blocks)
+        b.record()
+    torch.cuda.synchronize()
+    probe_us = float(np.median([a.elapsed_time(b) for a, b in pev]) * 1e3)
+    probe_bytes = vs[0].numel() * vs[0].element_size()
+    probe_gbs = probe_bytes / (probe_us * 1e-6) / 1e9
+
     rows = total * hkv
     row_bytes = (pbytes - 256 - 2 * ((w.batch * hkv * D * 4 + 255) // 256 * 256)) / (
         hkv * ((total + 63) // 64) * 64)
@@ -156,8 +176,15 @@ def main() -> int:
                   "pct_of_8TBps": round(100 * prune_gbs / HBM_PEAK_GBS, 1),
                   "Mtokens_per_s": round(total / prune_us, 2) if prune_us > 0 else None},
         "roofline": {"bound": "hbm", "achieved": round(dec_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(dec_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_DECODE_TRAFFIC_BYTES.get((w.name, "int8" if args.int8 else "bf16"))
+                     if not args.keep else None,
+                     "algorithmic_bytes": dec_alg_bytes,
                      "kernel": "spark_decode_kernel, HIP events around spark_decode_attn"},
+        "stream_read_ceiling": {"GBps": round(probe_gbs, 1), "us": round(probe_us, 2),
+                                "MB": round(probe_bytes / 1e6, 1),
+                                "decode_pct_of_ceiling": round(100 * dec_gbs / probe_gbs, 1),
+                                "kernel": "spark_probe_read_kernel, %d blocks" % probe_blocks},
         "packed_row_bytes": row_bytes,
         "input_generation_s": round(gen_s, 1),
     }

@@ -95,12 +95,12 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-#ifndef SPARK_DECODE_PIPE
-#define SPARK_DECODE_PIPE 0
-#endif
 // resident blocks per compute unit the register budget is held to: three where the kernel fits
 // 168 registers without spilling (small groups, short rows), else two
-constexpr int decode_min_blocks(int G, int TCT) { return (G <= 4 && TCT > 0 && TCT <= 40) ? 3 : 2; }
+#ifndef SPARK_MB
+#define SPARK_MB 3
+#endif
+constexpr int decode_min_blocks(int G, int TCT) { return (G <= 4 && TCT > 0 && TCT <= 40) ? SPARK_MB : 2; }
 template <int G, int TCT, int INT8>
 __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void spark_decode_kernel(DecodeParams P)
 {
@@ -183,9 +183,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         }
     };
 
-    // Software pipeline: the packed row of tile i+1 is requested before the scores of tile i are
-    // computed, and each half of V for tile i+1 is requested as soon as the registers of the same
-    // half of tile i have been turned into MFMA operands.
+    // A wavefront keeps one tile in flight: the loads of tile i+1 are issued when tile i is done.
+    // (Requesting further ahead was measured slower: more outstanding requests per wavefront cost
+    // more in DRAM efficiency than the extra overlap gained.)
     uint32_t rn[NR];
     uint4 vr[2][8];
     // Tiles are visited in rotated order, a different rotation per block.  The order does not
@@ -201,7 +201,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         load_v(tile, 0, vr[0]);
         load_v(tile, 1, vr[1]);
     }
-    constexpr bool PIPE = SPARK_DECODE_PIPE;
     // (the first tile's loads are already in flight while the table is built)
     // ---- per-step query prep: table {q_g[j] * scale * log2e, 1/a[j]} and R_g
     if (tid < SPARK_D) {
@@ -234,9 +233,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         const bool more = kidx + kDecodeWaves < nts;            // wave-uniform
         const int tnext = tile_of(more ? kidx + kDecodeWaves : kidx);
 
-        uint32_t r[NR];
-#pragma unroll
-        for (int d = 0; d < NR; ++d) r[d] = rn[d];
+        uint32_t (&r)[NR] = rn;
         // ---- scores, lane = token
         const float mu = __uint_as_float(r[4]);
         float s[G];
@@ -323,7 +320,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                 for (int rr = 0; rr < 4; ++rr) acc[e][rr] *= al[rr];
         }
         wave_lds_sync();
-        if (PIPE && more) load_row(tnext, rn);
 
         // ---- P V on the matrix cores
 #pragma unroll
@@ -356,7 +352,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                     bop[2 * cp][tp2] = __builtin_amdgcn_perm(y, x, 0x05040100u);       // low halves  (x | y << 16)
                     bop[2 * cp + 1][tp2] = __builtin_amdgcn_perm(y, x, 0x07060302u);   // high halves
                 }
-            if (PIPE && more) load_v(tnext, ks, vr[ks]);     // registers of this half are free again
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const bf16x8 B = __builtin_bit_cast(bf16x8, bop[e]);
@@ -365,7 +360,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             }
         }
         wave_lds_sync();   // P buffer is rewritten by the next tile
-        if (!PIPE && more) {
+        if (more) {   // request the next tile; its latency is covered by the other resident wavefronts
             load_row(tnext, rn);
             load_v(tnext, 0, vr[0]);
             load_v(tnext, 1, vr[1]);
