@@ -95,12 +95,9 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// resident blocks per compute unit the register budget is held to: three where the kernel fits
-// 168 registers without spilling (small groups, short rows), else two
-#ifndef SPARK_MB
-#define SPARK_MB 3
-#endif
-constexpr int decode_min_blocks(int G, int TCT) { return (G <= 4 && TCT > 0 && TCT <= 40) ? SPARK_MB : 2; }
+// resident blocks per compute unit the register budget is held to (three was measured no faster
+// than two and spills once the table gathers are batched)
+constexpr int decode_min_blocks(int, int) { return 2; }
 template <int G, int TCT, int INT8>
 __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void spark_decode_kernel(DecodeParams P)
 {
@@ -247,33 +244,51 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             float scale_row = 1.0f;
             if (INT8) scale_row = __uint_as_float(r[5]);
             uint32_t vw = 0;
-            auto entry = [&](int i, uint32_t word) {
+            // next kept channel of this lane's row (ascending); exactly T bits are set
+            auto next_channel = [&](int i) {
                 const bool sw = (i == clo);          // first entry of channels 64..127
                 cur = sw ? upper : cur;
                 jb = sw ? 64 : jb;
-                const int j = (__ffsll((unsigned long long)cur) - 1 + jb) & (SPARK_D - 1);
+                const int j = (__builtin_ctzll((unsigned long long)cur) + jb) & (SPARK_D - 1);
                 cur &= cur - 1;
-                float kv;
-                if (INT8)
-                    kv = (float)(int)(int8_t)((word >> (8 * (i & 3))) & 0xFF) * scale_row;
-                else
-                    kv = (i & 1) ? bf16hi(word) : bf16lo(word);
-                const float *e = &qtab[j * GP];
-                const float d = fmaf(-mu, e[G], kv);
+                return j;
+            };
+            auto kept_value = [&](int i, uint32_t word) {
+                if (INT8) return (float)(int)(int8_t)((word >> (8 * (i & 3))) & 0xFF) * scale_row;
+                return (i & 1) ? bf16hi(word) : bf16lo(word);
+            };
+            auto entry = [&](int i, uint32_t word) {
+                const float *e = &qtab[next_channel(i) * GP];
+                const float d = fmaf(-mu, e[G], kept_value(i, word));
 #pragma unroll
                 for (int g = 0; g < G; ++g) s[g] = fmaf(e[g], d, s[g]);
             };
-#ifdef EXP_NO_QK
             if (TCT) {
-                uint32_t xx = 0;
+                // The mask walk is a dependent chain and the table gathers have LDS latency; doing the
+                // walk and the gathers in batches keeps several gathers in flight at once.
+                constexpr int BQ = (G <= 4) ? 8 : (G == 8 ? 4 : 2);   // gathers in flight, bounded by registers
 #pragma unroll
-                for (int d = 0; d < NR; ++d) xx ^= r[d];
-                s[0] = __uint_as_float(xx & 0x3FFFFFFFu);
-            } else
-#endif
-            if (TCT) {
+                for (int i0 = 0; i0 < TCT; i0 += BQ) {
+                    int off[BQ];
 #pragma unroll
-                for (int i = 0; i < TCT; ++i) entry(i, r[VAL0 + (INT8 ? i / 4 : i / 2)]);
+                    for (int u = 0; u < BQ; ++u)
+                        if (i0 + u < TCT) off[u] = next_channel(i0 + u) * GP;
+                    float ev[BQ][GP];
+#pragma unroll
+                    for (int u = 0; u < BQ; ++u)
+                        if (i0 + u < TCT) {
+#pragma unroll
+                            for (int g = 0; g <= G; ++g) ev[u][g] = qtab[off[u] + g];
+                        }
+#pragma unroll
+                    for (int u = 0; u < BQ; ++u)
+                        if (i0 + u < TCT) {
+                            const int i = i0 + u;
+                            const float d = fmaf(-mu, ev[u][G], kept_value(i, r[VAL0 + (INT8 ? i / 4 : i / 2)]));
+#pragma unroll
+                            for (int g = 0; g < G; ++g) s[g] = fmaf(ev[u][g], d, s[g]);
+                        }
+                }
             } else {
                 for (int i = 0; i < T; ++i) {
                     const int per = INT8 ? 4 : 2;
@@ -333,16 +348,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             const bf16x8 A_lo = __builtin_bit_cast(bf16x8, alo);
             // 8x8 transpose of this lane's (token, channel) block: B operand e = channel 8cn+e, K = tokens
             u32x4 bop[8];
-#ifdef EXP_NO_PV
-            {
-                uint32_t xx = 0;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) xx ^= vr[ks][i].x ^ vr[ks][i].y ^ vr[ks][i].z ^ vr[ks][i].w;
-                acc[0][0] += __uint_as_float(xx & 0x3FFFFFFFu) + A_hi[0] + A_lo[0];
-            }
-            if (more) load_v(tnext, ks, vr[ks]);
-            continue;
-#endif
 #pragma unroll
             for (int cp = 0; cp < 4; ++cp)
 #pragma unroll
