@@ -6,7 +6,7 @@
 //
 // Kernels
 //   spark_window_stat_kernel  a[b,h,j] = mean_g | mean_t Q_win[b,g,t,j] |  in float64, stored
-//                             as float32 together with 1/a.
+//                             as float32 together with 1/a (G*128 threads per (b, h)).
 //   spark_prune_kernel        one wavefront per tile (64 tokens of one KV head).  For each
 //                             token the 128 saliencies sit two per lane (channels 2l, 2l+1);
 //                             the T-th largest is found by a most-significant-bit-first
@@ -28,25 +28,38 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_
 
 // ---------------------------------------------------------------- window statistic
 
-// grid = batch * Hkv blocks, 128 threads (thread = channel).  Sums run in the order
-// t ascending, then g ascending, all in float64; every sum of bf16 inputs this short is
-// exact, so the single rounding to float32 at the end decides a's bits.
-__global__ __launch_bounds__(128) void spark_window_stat_kernel(const uint16_t *__restrict__ qwin,
-                                                                int Hq, int Hkv, int W,
-                                                                uint8_t *__restrict__ packed,
-                                                                SparkLayout L)
+// grid = batch * Hkv blocks, min(G, 8) * 128 threads: thread (g, j) sums head g's window column j in
+// float64 (t ascending), thread (0, j) then adds the G absolute means in g order -- the same order
+// of operations as a plain loop nest.  Every sum of bf16 inputs this short is exact in float64, so
+// the single rounding to float32 at the end decides a's bits.
+__global__ __launch_bounds__(8 * SPARK_D) void spark_window_stat_kernel(const uint16_t *__restrict__ qwin,
+                                                                     int Hq, int Hkv, int W,
+                                                                     uint8_t *__restrict__ packed,
+                                                                     SparkLayout L)
 {
+    __shared__ double absmean[16][SPARK_D];
     const int bh = blockIdx.x;
     const int b = bh / Hkv, h = bh % Hkv;
-    const int j = threadIdx.x;
-    const int G = Hq / Hkv;
-    double s = 0.0;
-    for (int g = 0; g < G; ++g) {
+    const int j = threadIdx.x % SPARK_D, g0 = threadIdx.x / SPARK_D;
+    const int G = Hq / Hkv, GT = blockDim.x / SPARK_D;      // GT = min(G, 8) head slots
+    for (int g = g0; g < G; g += GT) {
         const uint16_t *src = qwin + ((int64_t)(b * Hq + h * G + g) * W) * SPARK_D + j;
         double qs = 0.0;
-        for (int t = 0; t < W; ++t) qs += (double)bf16_bits_to_float(src[(int64_t)t * SPARK_D]);
-        s += fabs(qs / (double)W);
+        int t = 0;
+        for (; t + 8 <= W; t += 8) {          // eight loads in flight, added in order
+            uint16_t x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = src[(int64_t)(t + u) * SPARK_D];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) qs += (double)bf16_bits_to_float(x[u]);
+        }
+        for (; t < W; ++t) qs += (double)bf16_bits_to_float(src[(int64_t)t * SPARK_D]);
+        absmean[g][j] = fabs(qs / (double)W);
     }
+    __syncthreads();
+    if (g0 != 0) return;
+    double s = 0.0;
+    for (int gg = 0; gg < G; ++gg) s += absmean[gg][j];
     const float a32 = (float)(s / (double)G);
     float *a_out = reinterpret_cast<float *>(packed + L.off_a);
     float *inva_out = reinterpret_cast<float *>(packed + L.off_inva);
@@ -150,7 +163,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     float mureg = 0.0f;                                     // lane t: sum of pruned saliencies
 
     // Rows are fetched a block ahead: while block tb is searched, block tb+PF is in flight.
-    constexpr int PF = 16;
+    constexpr int PF = 8;
     uint32_t xc[PF];
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
@@ -192,15 +205,16 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                     keep0 = keep1 = true;
                 } else {
                     // T-th largest key: set bits from the top while at least T keys stay >= prefix
+                    // (fully unrolled: the probe is then 2 vector compares and ~8 scalar instructions,
+                    // with the candidate and the prefix held in scalar registers)
                     uint32_t p = 0;
                     bool exact = false;
+#pragma unroll
                     for (int bit = 30; bit >= 0; --bit) {
                         const uint32_t cand = p | (1u << bit);
                         const int c = __popcll(__ballot(key0 >= cand)) + __popcll(__ballot(key1 >= cand));
-                        if (c >= T) {
-                            p = cand;
-                            if (c == T) { exact = true; break; }
-                        }
+                        p = (c >= T) ? cand : p;
+                        if (c == T) { exact = true; break; }
                     }
                     if (exact) {          // exactly T keys are >= p: that is the kept set
                         keep0 = key0 >= p;
@@ -358,7 +372,7 @@ __global__ void spark_unpack_kernel(const uint8_t *__restrict__ packed, SparkLay
 hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
                         const int32_t *cu, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st)
 {
-    hipLaunchKernelGGL(spark_window_stat_kernel, dim3(L.batch * L.n_kv_heads), dim3(SPARK_D), 0, st, qwin, Hq,
+    hipLaunchKernelGGL(spark_window_stat_kernel, dim3(L.batch * L.n_kv_heads), dim3(((Hq / L.n_kv_heads) < 8 ? (Hq / L.n_kv_heads) : 8) * SPARK_D), 0, st, qwin, Hq,
                        L.n_kv_heads, W, packed, L);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
