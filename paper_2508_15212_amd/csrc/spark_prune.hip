@@ -83,6 +83,7 @@ __global__ __launch_bounds__(8 * SPARK_D) void spark_window_stat_kernel(const ui
 
 constexpr int kPruneWaves = 4;      // wavefronts per block, one tile each
 constexpr int kPsumTokens = 16;     // tokens whose pruned-saliency partials are held before a flush
+constexpr int kHistBins = 64;       // one 64-bin digit histogram per wavefront
 constexpr int kPsumStride = 65;     // words per token in the partial-sum buffer (odd: no bank clash)
 
 // words per token in the LDS staging row: mask, mu, (scale), then T bf16 values
@@ -96,7 +97,8 @@ __host__ __device__ inline int spark_stage_words(const SparkLayout &L)
 __host__ inline size_t spark_prune_lds_bytes(const SparkLayout &L)
 {
     return (size_t)kPruneWaves *
-           ((size_t)SPARK_TILE_TOKENS * spark_stage_words(L) * 4 + (size_t)kPsumTokens * kPsumStride * 4);
+           ((size_t)SPARK_TILE_TOKENS * spark_stage_words(L) * 4 + (size_t)kPsumTokens * kPsumStride * 4 +
+            kHistBins * 4);
 }
 
 // bits 0..15 of x spread to the even bit positions of a 32-bit word
@@ -113,6 +115,27 @@ __device__ __forceinline__ uint32_t spread16(uint32_t x)
 __device__ __forceinline__ int mbcnt64(uint64_t m)   // set bits of m below this lane
 {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+}
+
+// Inclusive prefix sum over the 64 lanes (lane l gets x_0 + ... + x_l) with data-parallel-primitive
+// moves: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of row 0 / 2 is added
+// to row 1 / 3 and the last lane of row 1 to rows 2 and 3.  Lanes with no source add 0.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);   // row_shr 1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);   // row_shr 2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);   // row_shr 4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);   // row_shr 8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);   // row_bcast 15 -> rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);   // row_bcast 31 -> rows 2, 3
+    return v;
+}
+
+__device__ __forceinline__ void prune_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 template <int INT8>
@@ -133,8 +156,10 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     const int B = L.batch;
     const int sw = spark_stage_words(L);
     uint32_t *stage = reinterpret_cast<uint32_t *>(smem) +
-                      (size_t)wave * (SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride);
+                      (size_t)wave * (SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride + kHistBins);
     float *psum = reinterpret_cast<float *>(stage + SPARK_TILE_TOKENS * sw);
+    uint32_t *hist = stage + SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride;
+    int ebase = -1;   // lowest exponent of the histogram window; -1 = no hint yet (first row of the tile)
     uint16_t *stage16 = reinterpret_cast<uint16_t *>(stage);
 
     const float2 *a_all = reinterpret_cast<const float2 *>(packed + L.off_a);
@@ -204,17 +229,76 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                 if (T >= SPARK_D) {
                     keep0 = keep1 = true;
                 } else {
-                    // T-th largest key: set bits from the top while at least T keys stay >= prefix
-                    // (fully unrolled: the probe is then 2 vector compares and ~8 scalar instructions,
-                    // with the candidate and the prefix held in scalar registers)
+                    // T-th largest key.  The search is most-significant-bit first: keep a prefix p such
+                    // that at least T keys are >= p, try to set the next bit.  The top 14 bits (8 exponent,
+                    // 6 mantissa) are normally settled by two 64-bin counting passes: lanes add their keys'
+                    // digits to an LDS histogram stored highest digit first, lane l reads bin l, a wave
+                    // prefix sum turns that into "keys with digit >= d", and a ballot finds the digit
+                    // where the count reaches T.  The exponent pass looks through a 64-exponent window
+                    // placed around the previous row's threshold; a threshold at the window's edge, or
+                    // no hint yet, falls back to probing every bit.
                     uint32_t p = 0;
                     bool exact = false;
+                    int first_bit = 30;
+                    if (ebase >= 0) {
+                        const int ex0 = (int)(key0 >> 23), ex1 = (int)(key1 >> 23);
+                        hist[lane] = 0u;
+                        prune_lds_sync();
+                        {
+                            int d0 = ex0 - ebase, d1 = ex1 - ebase;
+                            d0 = d0 < 0 ? 0 : (d0 > 63 ? 63 : d0);
+                            d1 = d1 < 0 ? 0 : (d1 > 63 ? 63 : d1);
+                            atomicAdd(&hist[63 - d0], 1u);
+                            atomicAdd(&hist[63 - d1], 1u);
+                        }
+                        prune_lds_sync();
+                        const uint32_t s1 = wave_inclusive_sum(hist[lane]);      // keys with digit >= 63 - lane
+                        const int l1 = __builtin_ctzll(__ballot(s1 >= (uint32_t)T));   // s1 of lane 63 is 128 >= T
+                        const int dstar = 63 - l1;
+                        const bool inside = (dstar > 0 || ebase == 0) && (dstar < 63 || ebase + 63 >= 255);
+                        if (inside) {
+                            const int E = ebase + dstar;
+                            const int above1 = l1 > 0 ? __builtin_amdgcn_readlane((int)s1, l1 - 1) : 0;   // exponent > E
+                            prune_lds_sync();
+                            hist[lane] = 0u;
+                            prune_lds_sync();
+                            if (ex0 == E) atomicAdd(&hist[63 - (int)((key0 >> 17) & 63u)], 1u);
+                            if (ex1 == E) atomicAdd(&hist[63 - (int)((key1 >> 17) & 63u)], 1u);
+                            prune_lds_sync();
+                            const uint32_t s2 = wave_inclusive_sum(hist[lane]);
+                            const int need2 = T - above1;                                    // >= 1
+                            const int l2 = __builtin_ctzll(__ballot(s2 >= (uint32_t)need2));  // lane 63 qualifies
+                            const int ge = above1 + __builtin_amdgcn_readlane((int)s2, l2);  // keys >= p
+                            p = ((uint32_t)E << 23) | ((uint32_t)(63 - l2) << 17);
+                            first_bit = 16;
+                            exact = (ge == T);
+                            prune_lds_sync();
+                        }
+                    }
+                    if (!exact) {
+                        if (first_bit == 16) {
+                            // (fully unrolled: a probe is 2 vector compares and ~8 scalar instructions,
+                            // with the candidate and the prefix held in scalar registers)
 #pragma unroll
-                    for (int bit = 30; bit >= 0; --bit) {
-                        const uint32_t cand = p | (1u << bit);
-                        const int c = __popcll(__ballot(key0 >= cand)) + __popcll(__ballot(key1 >= cand));
-                        p = (c >= T) ? cand : p;
-                        if (c == T) { exact = true; break; }
+                            for (int bit = 16; bit >= 0; --bit) {
+                                const uint32_t cand = p | (1u << bit);
+                                const int c = __popcll(__ballot(key0 >= cand)) + __popcll(__ballot(key1 >= cand));
+                                p = (c >= T) ? cand : p;
+                                if (c == T) { exact = true; break; }
+                            }
+                        } else {
+                            for (int bit = 30; bit >= 0; --bit) {
+                                const uint32_t cand = p | (1u << bit);
+                                const int c = __popcll(__ballot(key0 >= cand)) + __popcll(__ballot(key1 >= cand));
+                                p = (c >= T) ? cand : p;
+                                if (c == T) { exact = true; break; }
+                            }
+                        }
+                    }
+                    {   // centre the next row's exponent window on this row's threshold
+                        int eb = (int)(p >> 23) - 32;
+                        eb = eb < 0 ? 0 : (eb > 255 - 63 ? 255 - 63 : eb);
+                        ebase = eb;
                     }
                     if (exact) {          // exactly T keys are >= p: that is the kept set
                         keep0 = key0 >= p;
