@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                       (size_t)wave * (SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride + kHistBins);
     float *psum = reinterpret_cast<float *>(stage + SPARK_TILE_TOKENS * sw);
     uint32_t *hist = stage + SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride;
-    int ebase = -1;   // lowest exponent of the histogram window; -1 = no hint yet (first row of the tile)
+    int ehint = -1;   // exponent of the previous row's threshold; -1 = none yet (first row of the tile)
     uint16_t *stage16 = reinterpret_cast<uint16_t *>(stage);
 
     const float2 *a_all = reinterpret_cast<const float2 *>(packed + L.off_a);
@@ -230,42 +230,53 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                     keep0 = keep1 = true;
                 } else {
                     // T-th largest key.  The search is most-significant-bit first: keep a prefix p such
-                    // that at least T keys are >= p, try to set the next bit.  The top 14 bits (8 exponent,
-                    // 6 mantissa) are normally settled by two 64-bin counting passes: lanes add their keys'
-                    // digits to an LDS histogram stored highest digit first, lane l reads bin l, a wave
-                    // prefix sum turns that into "keys with digit >= d", and a ballot finds the digit
-                    // where the count reaches T.  The exponent pass looks through a 64-exponent window
-                    // placed around the previous row's threshold; a threshold at the window's edge, or
-                    // no hint yet, falls back to probing every bit.
+                    // that at least T keys are >= p, try to set the next bit; every probe is two wave
+                    // ballots and two scalar popcounts.  Two shortcuts settle the top 14 bits: the
+                    // exponent is found by stepping from the previous row's, and the next six bits by
+                    // one counting pass (lanes add their keys' digits to a 64-bin LDS histogram stored
+                    // highest digit first, lane l reads bin l, a wave prefix sum turns that into "keys
+                    // with digit >= d", a ballot finds the digit where the count reaches what is still
+                    // needed).  The first row of a tile has no hint and probes every bit.
                     uint32_t p = 0;
                     bool exact = false;
                     int first_bit = 30;
-                    if (ebase >= 0) {
-                        const int ex0 = (int)(key0 >> 23), ex1 = (int)(key1 >> 23);
-                        hist[lane] = 0u;
-                        prune_lds_sync();
-                        {
-                            int d0 = ex0 - ebase, d1 = ex1 - ebase;
-                            d0 = d0 < 0 ? 0 : (d0 > 63 ? 63 : d0);
-                            d1 = d1 < 0 ? 0 : (d1 > 63 ? 63 : d1);
-                            atomicAdd(&hist[63 - d0], 1u);
-                            atomicAdd(&hist[63 - d1], 1u);
+                    if (ehint >= 0) {
+                        auto count_ge = [&](uint32_t x) {
+                            return __popcll(__ballot(key0 >= x)) + __popcll(__ballot(key1 >= x));
+                        };
+                        // exponent of the threshold: largest E with at least T keys >= 2^E, found by
+                        // stepping from the previous row's exponent (rows of one head differ by a few
+                        // octaves at most, so this takes two or three probes)
+                        int E = ehint;
+                        int cE = count_ge((uint32_t)E << 23);
+                        int above1;                      // keys with exponent > E
+                        if (cE >= T) {
+                            above1 = 0;
+                            while (E < 255) {
+                                const int c2 = count_ge((uint32_t)(E + 1) << 23);
+                                if (c2 < T) { above1 = c2; break; }
+                                ++E;
+                                cE = c2;
+                            }
+                        } else {
+                            do {                         // E = 0 always qualifies (all 128 keys are >= 0)
+                                above1 = cE;
+                                --E;
+                                cE = count_ge((uint32_t)E << 23);
+                            } while (cE < T);
                         }
-                        prune_lds_sync();
-                        const uint32_t s1 = wave_inclusive_sum(hist[lane]);      // keys with digit >= 63 - lane
-                        const int l1 = __builtin_ctzll(__ballot(s1 >= (uint32_t)T));   // s1 of lane 63 is 128 >= T
-                        const int dstar = 63 - l1;
-                        const bool inside = (dstar > 0 || ebase == 0) && (dstar < 63 || ebase + 63 >= 255);
-                        if (inside) {
-                            const int E = ebase + dstar;
-                            const int above1 = l1 > 0 ? __builtin_amdgcn_readlane((int)s1, l1 - 1) : 0;   // exponent > E
-                            prune_lds_sync();
+                        if (cE == T) {
+                            p = (uint32_t)E << 23;
+                            exact = true;
+                        } else {
+                            // next six bits: counting pass over the keys whose exponent is E
+                            const int ex0 = (int)(key0 >> 23), ex1 = (int)(key1 >> 23);
                             hist[lane] = 0u;
                             prune_lds_sync();
                             if (ex0 == E) atomicAdd(&hist[63 - (int)((key0 >> 17) & 63u)], 1u);
                             if (ex1 == E) atomicAdd(&hist[63 - (int)((key1 >> 17) & 63u)], 1u);
                             prune_lds_sync();
-                            const uint32_t s2 = wave_inclusive_sum(hist[lane]);
+                            const uint32_t s2 = wave_inclusive_sum(hist[lane]);   // keys in E with digit >= 63 - lane
                             const int need2 = T - above1;                                    // >= 1
                             const int l2 = __builtin_ctzll(__ballot(s2 >= (uint32_t)need2));  // lane 63 qualifies
                             const int ge = above1 + __builtin_amdgcn_readlane((int)s2, l2);  // keys >= p
@@ -295,11 +306,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                             }
                         }
                     }
-                    {   // centre the next row's exponent window on this row's threshold
-                        int eb = (int)(p >> 23) - 32;
-                        eb = eb < 0 ? 0 : (eb > 255 - 63 ? 255 - 63 : eb);
-                        ebase = eb;
-                    }
+                    ehint = (int)(p >> 23);   // the next row starts from this row's exponent
                     if (exact) {          // exactly T keys are >= p: that is the kept set
                         keep0 = key0 >= p;
                         keep1 = key1 >= p;
