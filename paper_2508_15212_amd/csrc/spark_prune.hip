@@ -176,7 +176,8 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
         }
         b = lo;
     }
-    int64_t seq_end = cu[b + 1];
+    // tokens left in the current sequence counted from the tile's first token (total < 2^31)
+    int seq_end_t = (int)((int64_t)cu[b + 1] - n0);   // token index within the tile where the sequence ends
     // lane l owns channels 2l (low half of its 32-bit load) and 2l+1 (high half)
     float2 a01 = a_all[((int64_t)b * L.n_kv_heads + h) * (SPARK_D / 2) + lane];
 
@@ -209,12 +210,11 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
             const int t = tb + u;
             const uint32_t xx = xc[u];
             if (t < nvalid) {   // wave-uniform
-                const int64_t n = n0 + t;
-                if (n >= seq_end) {      // rare: the tile crosses into the next non-empty sequence
+                if (t >= seq_end_t) {    // rare: the tile crosses into the next non-empty sequence
                     do {
                         ++b;
-                        seq_end = cu[b + 1];
-                    } while (n >= seq_end);
+                        seq_end_t = (int)((int64_t)cu[b + 1] - n0);
+                    } while (t >= seq_end_t);
                     a01 = a_all[((int64_t)b * L.n_kv_heads + h) * (SPARK_D / 2) + lane];
                     // finish this load here, inside the rare branch: otherwise the wait for it
                     // lands after the join and drains the prefetched K rows on every token
