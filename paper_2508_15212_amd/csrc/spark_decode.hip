@@ -502,6 +502,8 @@ static hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
         return launch_one<G, 0, 1>(P, nblocks, st);
     }
     if (T == 26) return launch_one<G, 26, 0>(P, nblocks, st);
+    if (T == 25) return launch_one<G, 25, 0>(P, nblocks, st);
+    if (T == 38) return launch_one<G, 38, 0>(P, nblocks, st);
     if (T == 64) return launch_one<G, 64, 0>(P, nblocks, st);
     return launch_one<G, 0, 0>(P, nblocks, st);
 }
