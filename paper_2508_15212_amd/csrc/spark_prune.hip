@@ -131,6 +131,22 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
     return v;
 }
 
+// Four wave-uniform values into lane `lane_id` (wave-uniform) of four registers; the other lanes
+// keep theirs.  (The lane selector of v_writelane travels in M0 because the value is a scalar
+// register already.)
+__device__ __forceinline__ void write_lane4(uint32_t &a, uint32_t &b, uint32_t &c, uint32_t &d, uint32_t va,
+                                            uint32_t vb, uint32_t vc, uint32_t vd, int lane_id)
+{
+    asm("s_mov_b32 m0, %8\n\t"
+        "v_writelane_b32 %0, %4, m0\n\t"
+        "v_writelane_b32 %1, %5, m0\n\t"
+        "v_writelane_b32 %2, %6, m0\n\t"
+        "v_writelane_b32 %3, %7, m0"
+        : "+v"(a), "+v"(b), "+v"(c), "+v"(d)
+        : "s"(va), "s"(vb), "s"(vc), "s"(vd), "s"(lane_id)
+        : "m0");
+}
+
 __device__ __forceinline__ void prune_lds_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -326,13 +342,14 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                 const int pos0 = mbcnt64(kb0) + mbcnt64(kb1);
                 const int pos1 = pos0 + (keep0 ? 1 : 0);
                 uint16_t *vrow = stage16 + (size_t)t * sw * 2 + L.val0 * 2;
-                if (keep0) vrow[pos0] = (uint16_t)xx;
-                if (keep1) vrow[pos1] = (uint16_t)(xx >> 16);
-                const bool mine = (lane == t);
-                e_lo = mine ? (uint32_t)kb0 : e_lo;
-                e_hi = mine ? (uint32_t)(kb0 >> 32) : e_hi;
-                o_lo = mine ? (uint32_t)kb1 : o_lo;
-                o_hi = mine ? (uint32_t)(kb1 >> 32) : o_hi;
+                // every lane stores; a pruned value goes to a per-lane scratch word (the histogram,
+                // which is cleared before each use) instead of masking lanes off around the store
+                uint16_t *dump = reinterpret_cast<uint16_t *>(hist + lane);
+                *(keep0 ? vrow + pos0 : dump) = (uint16_t)xx;
+                *(keep1 ? vrow + pos1 : dump) = (uint16_t)(xx >> 16);
+                // lane t keeps the ballots of token t
+                write_lane4(e_lo, e_hi, o_lo, o_hi, (uint32_t)kb0, (uint32_t)(kb0 >> 32), (uint32_t)kb1,
+                            (uint32_t)(kb1 >> 32), t);
                 psum[(t & (kPsumTokens - 1)) * kPsumStride + lane] = (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
             }
             if ((t & (kPsumTokens - 1)) == kPsumTokens - 1) {
