@@ -58,20 +58,22 @@ int pick_splits(const spark_desc *d)
     return (int)want;
 }
 
-// Streaming-read yardstick: every lane pulls 16-byte words grid-stride and folds them into one
-// value that is stored only to keep the loads alive.
-__global__ __launch_bounds__(256) void spark_probe_read_kernel(const uint4 *__restrict__ src, size_t n16,
+// Streaming-read yardstick: every lane pulls 16-byte words grid-stride (non-temporal, as the decode
+// kernel does) and folds them into one value that is stored only to keep the loads alive.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void spark_probe_read_kernel(const u32x4 *__restrict__ src, size_t n16,
                                                                uint32_t *__restrict__ sink)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     uint32_t acc = 0;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
+                    c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
         acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
     }
     for (; i < n16; i += stride) {
-        const uint4 a = src[i];
+        const u32x4 a = __builtin_nontemporal_load(src + i);
         acc ^= a.x ^ a.y ^ a.z ^ a.w;
     }
     if (acc == 0x9E3779B9u) sink[0] = acc;
@@ -91,7 +93,7 @@ spark_status spark_probe_read(const void *src, size_t bytes, void *sink, int32_t
     if (!src || !sink || bytes < 16 || n_blocks < 1 || !aligned(src, 16) || !aligned(sink, 4))
         return SPARK_ERR_INVALID_ARG;
     hipLaunchKernelGGL(spark_probe_read_kernel, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<const uint4 *>(src), bytes / 16, static_cast<uint32_t *>(sink));
+                       static_cast<const u32x4 *>(src), bytes / 16, static_cast<uint32_t *>(sink));
     return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }
 

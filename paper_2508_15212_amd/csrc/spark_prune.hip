@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
         const int tt = (u < nvalid) ? u : (nvalid - 1);
-        xc[u] = krow[(int64_t)tt * row_stride];
+        xc[u] = __builtin_nontemporal_load(krow + (int64_t)tt * row_stride);
     }
 
     for (int tb = 0; tb < SPARK_TILE_TOKENS; tb += PF) {
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
         for (int u = 0; u < PF; ++u) {
             int tn = tb + PF + u;
             tn = (tn < nvalid) ? tn : (nvalid - 1);
-            xn[u] = krow[(int64_t)tn * row_stride];
+            xn[u] = __builtin_nontemporal_load(krow + (int64_t)tn * row_stride);
         }
 #pragma unroll
         for (int u = 0; u < PF; ++u) {

@@ -62,3 +62,26 @@ def test_bad_descriptions_are_rejected_on_the_host():
     assert lib.spark_unpack(ctypes.byref(d), None, None, None, None, None, None, None) == 1
     assert lib.spark_prune(ctypes.byref(_desc(head_dim=64)), None, None, None, None, None, 0, None) == 2
     assert lib.spark_status_string(3) == b"workspace too small"
+
+
+def test_alignment_strides_and_workspace_are_checked_before_any_launch():
+    """Fake (never dereferenced) device addresses: every one of these calls must fail on the host."""
+    lib = spark.load()
+    d = _desc()
+    A = 0x7F0000000000            # 256-byte aligned fake address
+    ok_ws = spark.decode_workspace_bytes(d)
+    # misaligned packed buffer / V pointer / workspace
+    assert lib.spark_prune(ctypes.byref(d), A, A, A, A + 64, None, 0, None) == 1
+    assert lib.spark_decode_attn(ctypes.byref(d), A, A + 8, A, A, A, A, ok_ws, None) == 1
+    assert lib.spark_decode_attn(ctypes.byref(d), A, A, A + 2, A, A, A, ok_ws, None) == 1
+    assert lib.spark_decode_attn(ctypes.byref(d), A, A, A, A, A, A + 4, ok_ws, None) == 1
+    # workspace one byte short
+    assert lib.spark_decode_attn(ctypes.byref(d), A, A, A, A, A, A, ok_ws - 1, None) == 3
+    assert lib.spark_decode_workspace_init(ctypes.byref(d), A, ok_ws - 1, None) == 3
+    # strides that would break 16-byte row alignment, or rows that overlap
+    assert lib.spark_prune(ctypes.byref(_desc(k_token_stride=130)), A, A, A, A, None, 0, None) == 1
+    assert lib.spark_prune(ctypes.byref(_desc(k_token_stride=64)), A, A, A, A, None, 0, None) == 1
+    assert lib.spark_decode_attn(ctypes.byref(_desc(v_head_stride=100)), A, A, A, A, A, A, ok_ws, None) == 1
+    assert lib.spark_prune(ctypes.byref(_desc(window=0)), A, A, A, A, None, 0, None) == 1
+    assert lib.spark_probe_read(None, 1024, A, 4, None) == 1
+    assert lib.spark_probe_read(A, 8, A, 4, None) == 1
