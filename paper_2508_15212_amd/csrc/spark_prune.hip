@@ -83,7 +83,7 @@ __global__ __launch_bounds__(8 * SPARK_D) void spark_window_stat_kernel(const ui
 
 constexpr int kPruneWaves = 4;      // wavefronts per block, one tile each
 constexpr int kPsumTokens = 16;     // tokens whose pruned-saliency partials are held before a flush
-constexpr int kHistBins = 64;       // one 64-bin digit histogram per wavefront
+constexpr int kHistBins = 64;       // one 64-bin digit histogram per wavefront (+ 64 spare words)
 constexpr int kPsumStride = 65;     // words per token in the partial-sum buffer (odd: no bank clash)
 
 // words per token in the LDS staging row: mask, mu, (scale), then T bf16 values
@@ -98,7 +98,7 @@ __host__ inline size_t spark_prune_lds_bytes(const SparkLayout &L)
 {
     return (size_t)kPruneWaves *
            ((size_t)SPARK_TILE_TOKENS * spark_stage_words(L) * 4 + (size_t)kPsumTokens * kPsumStride * 4 +
-            kHistBins * 4);
+            2 * kHistBins * 4);
 }
 
 // bits 0..15 of x spread to the even bit positions of a 32-bit word
@@ -172,10 +172,9 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     const int B = L.batch;
     const int sw = spark_stage_words(L);
     uint32_t *stage = reinterpret_cast<uint32_t *>(smem) +
-                      (size_t)wave * (SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride + kHistBins);
+                      (size_t)wave * (SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride + 2 * kHistBins);
     float *psum = reinterpret_cast<float *>(stage + SPARK_TILE_TOKENS * sw);
     uint32_t *hist = stage + SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride;
-    int ehint = -1;   // exponent of the previous row's threshold; -1 = none yet (first row of the tile)
     uint16_t *stage16 = reinterpret_cast<uint16_t *>(stage);
 
     const float2 *a_all = reinterpret_cast<const float2 *>(packed + L.off_a);
@@ -213,6 +212,31 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
         xc[u] = __builtin_nontemporal_load(krow + (int64_t)tt * row_stride);
     }
 
+    // T-th largest key of a row.  The search is most-significant-bit first on the float32 bit pattern:
+    // keep a prefix p such that at least T keys are >= p and try to extend it; a probe is two wave
+    // ballots and two scalar popcounts.  Two shortcuts settle the top 14 bits: the exponent E (largest
+    // with at least T keys >= 2^E) is found by stepping from the previous row's -- rows of one head
+    // rarely differ by more than an octave -- and the next six bits by one counting pass (lanes add
+    // their keys' digits to a 64-bin LDS histogram stored highest digit first, lane l reads bin l, a
+    // wave prefix sum turns that into "keys with digit >= d", a ballot finds the digit where the count
+    // reaches what is still needed).  The search stops as soon as exactly T keys are >= p.
+    int E;
+    {   // first row: E by bisection over the 256 exponents
+        const uint32_t xx = xc[0];
+        const uint32_t key0 = __float_as_uint(__fmul_rn(a01.x, fabsf(__uint_as_float(xx << 16))));
+        const uint32_t key1 = __float_as_uint(__fmul_rn(a01.y, fabsf(__uint_as_float(xx & 0xFFFF0000u))));
+        int lo = 0, hi = 256;   // at least T keys are >= lo << 23, fewer are >= hi << 23
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            const uint32_t x = (uint32_t)mid << 23;
+            const int c = __popcll(__ballot(key0 >= x)) + __popcll(__ballot(key1 >= x));
+            if (c >= T) lo = mid; else hi = mid;
+        }
+        E = lo;
+    }
+
+    // Every one of the 64 rows is processed; rows past the last token repeat the last one and are
+    // overwritten by the epilogue.
     for (int tb = 0; tb < SPARK_TILE_TOKENS; tb += PF) {
         uint32_t xn[PF];
 #pragma unroll
@@ -225,8 +249,8 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
         for (int u = 0; u < PF; ++u) {
             const int t = tb + u;
             const uint32_t xx = xc[u];
-            if (t < nvalid) {   // wave-uniform
-                if (t >= seq_end_t) {    // rare: the tile crosses into the next non-empty sequence
+            if (__builtin_expect(t >= seq_end_t, 0)) {    // rare: the tile crosses into the next non-empty sequence
+                if (t < nvalid) {
                     do {
                         ++b;
                         seq_end_t = (int)((int64_t)cu[b + 1] - n0);
@@ -236,128 +260,95 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                     // lands after the join and drains the prefetched K rows on every token
                     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
                 }
-                // saliency: one float32 multiply, never fused
-                const float w0 = __fmul_rn(a01.x, fabsf(__uint_as_float(xx << 16)));
-                const float w1 = __fmul_rn(a01.y, fabsf(__uint_as_float(xx & 0xFFFF0000u)));
-                const uint32_t key0 = __float_as_uint(w0), key1 = __float_as_uint(w1);
-
-                bool keep0, keep1;
-                if (T >= SPARK_D) {
-                    keep0 = keep1 = true;
-                } else {
-                    // T-th largest key.  The search is most-significant-bit first: keep a prefix p such
-                    // that at least T keys are >= p, try to set the next bit; every probe is two wave
-                    // ballots and two scalar popcounts.  Two shortcuts settle the top 14 bits: the
-                    // exponent is found by stepping from the previous row's, and the next six bits by
-                    // one counting pass (lanes add their keys' digits to a 64-bin LDS histogram stored
-                    // highest digit first, lane l reads bin l, a wave prefix sum turns that into "keys
-                    // with digit >= d", a ballot finds the digit where the count reaches what is still
-                    // needed).  The first row of a tile has no hint and probes every bit.
-                    uint32_t p = 0;
-                    bool exact = false;
-                    int first_bit = 30;
-                    if (ehint >= 0) {
-                        auto count_ge = [&](uint32_t x) {
-                            return __popcll(__ballot(key0 >= x)) + __popcll(__ballot(key1 >= x));
-                        };
-                        // exponent of the threshold: largest E with at least T keys >= 2^E, found by
-                        // stepping from the previous row's exponent (rows of one head differ by a few
-                        // octaves at most, so this takes two or three probes)
-                        int E = ehint;
-                        int cE = count_ge((uint32_t)E << 23);
-                        int above1;                      // keys with exponent > E
-                        if (cE >= T) {
-                            above1 = 0;
-                            while (E < 255) {
-                                const int c2 = count_ge((uint32_t)(E + 1) << 23);
-                                if (c2 < T) { above1 = c2; break; }
-                                ++E;
-                                cE = c2;
-                            }
-                        } else {
-                            do {                         // E = 0 always qualifies (all 128 keys are >= 0)
-                                above1 = cE;
-                                --E;
-                                cE = count_ge((uint32_t)E << 23);
-                            } while (cE < T);
-                        }
-                        if (cE == T) {
-                            p = (uint32_t)E << 23;
-                            exact = true;
-                        } else {
-                            // next six bits: counting pass over the keys whose exponent is E
-                            const int ex0 = (int)(key0 >> 23), ex1 = (int)(key1 >> 23);
-                            hist[lane] = 0u;
-                            prune_lds_sync();
-                            if (ex0 == E) atomicAdd(&hist[63 - (int)((key0 >> 17) & 63u)], 1u);
-                            if (ex1 == E) atomicAdd(&hist[63 - (int)((key1 >> 17) & 63u)], 1u);
-                            prune_lds_sync();
-                            const uint32_t s2 = wave_inclusive_sum(hist[lane]);   // keys in E with digit >= 63 - lane
-                            const int need2 = T - above1;                                    // >= 1
-                            const int l2 = __builtin_ctzll(__ballot(s2 >= (uint32_t)need2));  // lane 63 qualifies
-                            const int ge = above1 + __builtin_amdgcn_readlane((int)s2, l2);  // keys >= p
-                            p = ((uint32_t)E << 23) | ((uint32_t)(63 - l2) << 17);
-                            first_bit = 16;
-                            exact = (ge == T);
-                            prune_lds_sync();
-                        }
-                    }
-                    if (!exact) {
-                        if (first_bit == 16) {
-                            // (fully unrolled: a probe is 2 vector compares and ~8 scalar instructions,
-                            // with the candidate and the prefix held in scalar registers)
-#pragma unroll
-                            for (int bit = 16; bit >= 0; --bit) {
-                                const uint32_t cand = p | (1u << bit);
-                                const int c = __popcll(__ballot(key0 >= cand)) + __popcll(__ballot(key1 >= cand));
-                                p = (c >= T) ? cand : p;
-                                if (c == T) { exact = true; break; }
-                            }
-                        } else {
-                            for (int bit = 30; bit >= 0; --bit) {
-                                const uint32_t cand = p | (1u << bit);
-                                const int c = __popcll(__ballot(key0 >= cand)) + __popcll(__ballot(key1 >= cand));
-                                p = (c >= T) ? cand : p;
-                                if (c == T) { exact = true; break; }
-                            }
-                        }
-                    }
-                    ehint = (int)(p >> 23);   // the next row starts from this row's exponent
-                    if (exact) {          // exactly T keys are >= p: that is the kept set
-                        keep0 = key0 >= p;
-                        keep1 = key1 >= p;
-                    } else {              // p is the T-th largest value and it is tied
-                        const bool eq0 = (key0 == p), eq1 = (key1 == p);
-                        const uint64_t q0 = __ballot(eq0), q1 = __ballot(eq1);
-                        const int need = T - __popcll(__ballot(key0 > p)) - __popcll(__ballot(key1 > p));
-                        // tied channels below 2l: both halves of every lower lane; below 2l+1: plus own even
-                        const int r0 = mbcnt64(q0) + mbcnt64(q1);
-                        const int r1 = r0 + (eq0 ? 1 : 0);
-                        keep0 = (key0 > p) || (eq0 && r0 < need);   // lower channel first
-                        keep1 = (key1 > p) || (eq1 && r1 < need);
-                    }
-                }
-                const uint64_t kb0 = __ballot(keep0), kb1 = __ballot(keep1);
-                // slot of each kept value = number of kept channels below it
-                const int pos0 = mbcnt64(kb0) + mbcnt64(kb1);
-                const int pos1 = pos0 + (keep0 ? 1 : 0);
-                uint16_t *vrow = stage16 + (size_t)t * sw * 2 + L.val0 * 2;
-                // every lane stores; a pruned value goes to a per-lane scratch word (the histogram,
-                // which is cleared before each use) instead of masking lanes off around the store
-                uint16_t *dump = reinterpret_cast<uint16_t *>(hist + lane);
-                *(keep0 ? vrow + pos0 : dump) = (uint16_t)xx;
-                *(keep1 ? vrow + pos1 : dump) = (uint16_t)(xx >> 16);
-                // lane t keeps the ballots of token t
-                write_lane4(e_lo, e_hi, o_lo, o_hi, (uint32_t)kb0, (uint32_t)(kb0 >> 32), (uint32_t)kb1,
-                            (uint32_t)(kb1 >> 32), t);
-                psum[(t & (kPsumTokens - 1)) * kPsumStride + lane] = (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
             }
+            // saliency: one float32 multiply, never fused
+            const float w0 = __fmul_rn(a01.x, fabsf(__uint_as_float(xx << 16)));
+            const float w1 = __fmul_rn(a01.y, fabsf(__uint_as_float(xx & 0xFFFF0000u)));
+            const uint32_t key0 = __float_as_uint(w0), key1 = __float_as_uint(w1);
+            auto count_ge = [&](uint32_t x) {
+                return __popcll(__ballot(key0 >= x)) + __popcll(__ballot(key1 >= x));
+            };
+
+            // exponent: in the common case the previous row's E still has cE >= T > above1
+            int cE = count_ge((uint32_t)E << 23);
+            int above1 = count_ge(((uint32_t)E + 1u) << 23);      // keys with exponent > E
+            if (__builtin_expect(!((uint32_t)(T - 1 - above1) < (uint32_t)(cE - above1)), 0)) {
+                if (cE >= T) {      // then above1 >= T as well: step up (2^256 is above every key)
+                    do {
+                        ++E;
+                        cE = above1;
+                        above1 = count_ge(((uint32_t)E + 1u) << 23);
+                    } while (above1 >= T);
+                } else {            // step down (E = 0 always qualifies: all 128 keys are >= 0)
+                    do {
+                        above1 = cE;
+                        --E;
+                        cE = count_ge((uint32_t)E << 23);
+                    } while (cE < T);
+                }
+            }
+            // next six bits: counting pass over the keys whose exponent is E; the others land in a
+            // spare word (bins 64..127) that is never read
+            hist[lane] = 0u;
+            prune_lds_sync();
+            {
+                const uint32_t top = ((uint32_t)E << 6) | 63u;
+                const uint32_t d0 = top - (key0 >> 17), d1 = top - (key1 >> 17);
+                const uint32_t spare = (uint32_t)(kHistBins + lane);   // one spare word per lane: no pile-up
+                atomicAdd(&hist[d0 < spare ? d0 : spare], 1u);
+                atomicAdd(&hist[d1 < spare ? d1 : spare], 1u);
+            }
+            prune_lds_sync();
+            const uint32_t s2 = wave_inclusive_sum(hist[lane]);   // keys in octave E with digit >= 63 - lane
+            const int need2 = T - above1;                                     // >= 1
+            const int l2 = __builtin_ctzll(__ballot(s2 >= (uint32_t)need2));  // lane 63 qualifies
+            const int ge = above1 + __builtin_amdgcn_readlane((int)s2, l2);   // keys >= p
+            uint32_t p = ((uint32_t)E << 23) | ((uint32_t)(63 - l2) << 17);
+            prune_lds_sync();
+            int tied = 0;
+            if (ge != T) {
+                // remaining 17 bits (a probe is 2 vector compares and ~8 scalar instructions, with
+                // the candidate and the prefix held in scalar registers)
+                tied = 1;
+#pragma unroll
+                for (int bit = 16; bit >= 0; --bit) {
+                    const uint32_t cand = p | (1u << bit);
+                    const int c = count_ge(cand);
+                    p = (c >= T) ? cand : p;
+                    if (c == T) { tied = 0; break; }
+                }
+            }
+            // exactly T keys are >= p, unless p is the T-th largest value and it is tied
+            uint64_t kb0 = __ballot(key0 >= p), kb1 = __ballot(key1 >= p);
+            if (__builtin_expect(tied, 0)) {
+                const bool eq0 = (key0 == p), eq1 = (key1 == p);
+                const uint64_t q0 = __ballot(eq0), q1 = __ballot(eq1);
+                const int need = T - __popcll(__ballot(key0 > p)) - __popcll(__ballot(key1 > p));
+                // tied channels below 2l: both halves of every lower lane; below 2l+1: plus own even
+                const int r0 = mbcnt64(q0) + mbcnt64(q1);
+                const int r1 = r0 + (eq0 ? 1 : 0);
+                kb0 = __ballot((key0 > p) || (eq0 && r0 < need));   // lower channel first
+                kb1 = __ballot((key1 > p) || (eq1 && r1 < need));
+            }
+            const bool keep0 = __builtin_amdgcn_inverse_ballot_w64(kb0);
+            const bool keep1 = __builtin_amdgcn_inverse_ballot_w64(kb1);
+            // slot of each kept value = number of kept channels below it
+            const int pos0 = mbcnt64(kb0) + mbcnt64(kb1);
+            const int pos1 = pos0 + (keep0 ? 1 : 0);
+            uint16_t *vrow = stage16 + (size_t)t * sw * 2 + L.val0 * 2;
+            // every lane stores; a pruned value goes to the lane's spare word instead of masking
+            // lanes off around the store
+            uint16_t *dump = reinterpret_cast<uint16_t *>(hist + kHistBins + lane);
+            *(keep0 ? vrow + pos0 : dump) = (uint16_t)xx;
+            *(keep1 ? vrow + pos1 : dump) = (uint16_t)(xx >> 16);
+            // lane t keeps the ballots of token t
+            write_lane4(e_lo, e_hi, o_lo, o_hi, (uint32_t)kb0, (uint32_t)(kb0 >> 32), (uint32_t)kb1,
+                        (uint32_t)(kb1 >> 32), t);
+            psum[(t & (kPsumTokens - 1)) * kPsumStride + lane] = (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
             if ((t & (kPsumTokens - 1)) == kPsumTokens - 1) {
                 // 16 tokens' partials are in LDS: lane (tt, qq) adds 16 of token tt's 64 partials,
                 // two butterfly steps finish the sum in every lane of column tt
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                prune_lds_sync();
                 const int tt = lane & 15, qq = lane >> 4;
                 float s = 0.0f;
 #pragma unroll
@@ -365,9 +356,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                 s += __shfl_xor(s, 16);
                 s += __shfl_xor(s, 32);
                 if (qq == (t >> 4)) mureg = s;
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                prune_lds_sync();
             }
         }
 #pragma unroll
