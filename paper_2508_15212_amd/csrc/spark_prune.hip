@@ -82,9 +82,7 @@ __global__ __launch_bounds__(8 * SPARK_D) void spark_window_stat_kernel(const ui
 // ---------------------------------------------------------------- top-T selection + pack
 
 constexpr int kPruneWaves = 4;      // wavefronts per block, one tile each
-constexpr int kPsumTokens = 16;     // tokens whose pruned-saliency partials are held before a flush
 constexpr int kHistBins = 64;       // one 64-bin digit histogram per wavefront (+ 64 spare words)
-constexpr int kPsumStride = 65;     // words per token in the partial-sum buffer (odd: no bank clash)
 
 // words per token in the LDS staging row: mask, mu, (scale), then T bf16 values
 __host__ __device__ inline int spark_stage_words(const SparkLayout &L)
@@ -97,8 +95,7 @@ __host__ __device__ inline int spark_stage_words(const SparkLayout &L)
 __host__ inline size_t spark_prune_lds_bytes(const SparkLayout &L)
 {
     return (size_t)kPruneWaves *
-           ((size_t)SPARK_TILE_TOKENS * spark_stage_words(L) * 4 + (size_t)kPsumTokens * kPsumStride * 4 +
-            2 * kHistBins * 4);
+           ((size_t)SPARK_TILE_TOKENS * spark_stage_words(L) * 4 + 2 * kHistBins * 4);
 }
 
 // bits 0..15 of x spread to the even bit positions of a 32-bit word
@@ -147,6 +144,18 @@ __device__ __forceinline__ void write_lane4(uint32_t &a, uint32_t &b, uint32_t &
         : "m0");
 }
 
+// Pairwise step of a transposing reduction.  A and B hold one partial per lane for two tokens;
+// the result holds A[l] + A[partner(l)] in the lanes where `hi` is false and B[l] + B[partner(l)]
+// where it is true.  CTRL is a data-parallel-primitive pattern whose partner differs in exactly the
+// lane bit that `hi` tests (and in no lower bit).  Four such steps fold 16 tokens x 64 lanes into
+// one register with token (l & 15) summed over the 16 lanes of l's row.
+template <int CTRL>
+__device__ __forceinline__ float fold_pair(float A, float B, bool hi)
+{
+    const float stay = hi ? B : A, go = hi ? A : B;
+    return stay + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(go), CTRL, 0xF, 0xF, true));
+}
+
 __device__ __forceinline__ void prune_lds_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -172,9 +181,8 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     const int B = L.batch;
     const int sw = spark_stage_words(L);
     uint32_t *stage = reinterpret_cast<uint32_t *>(smem) +
-                      (size_t)wave * (SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride + 2 * kHistBins);
-    float *psum = reinterpret_cast<float *>(stage + SPARK_TILE_TOKENS * sw);
-    uint32_t *hist = stage + SPARK_TILE_TOKENS * sw + kPsumTokens * kPsumStride;
+                      (size_t)wave * (SPARK_TILE_TOKENS * sw + 2 * kHistBins);
+    uint32_t *hist = stage + SPARK_TILE_TOKENS * sw;
     uint16_t *stage16 = reinterpret_cast<uint16_t *>(stage);
 
     const float2 *a_all = reinterpret_cast<const float2 *>(packed + L.off_a);
@@ -201,7 +209,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
 
     // lane t collects, for token t, the ballots of kept even channels (e) and kept odd channels (o)
     uint32_t e_lo = 0, e_hi = 0, o_lo = 0, o_hi = 0;
-    float mureg = 0.0f;                                     // lane t: sum of pruned saliencies
+    float mureg = 0.0f, fprev = 0.0f;                       // lane t: sum of pruned saliencies
 
     // Rows are fetched a block ahead: while block tb is searched, block tb+PF is in flight.
     constexpr int PF = 8;
@@ -245,6 +253,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
             tn = (tn < nvalid) ? tn : (nvalid - 1);
             xn[u] = __builtin_nontemporal_load(krow + (int64_t)tn * row_stride);
         }
+        float ps[PF];
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int t = tb + u;
@@ -344,19 +353,25 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
             // lane t keeps the ballots of token t
             write_lane4(e_lo, e_hi, o_lo, o_hi, (uint32_t)kb0, (uint32_t)(kb0 >> 32), (uint32_t)kb1,
                         (uint32_t)(kb1 >> 32), t);
-            psum[(t & (kPsumTokens - 1)) * kPsumStride + lane] = (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
-            if ((t & (kPsumTokens - 1)) == kPsumTokens - 1) {
-                // 16 tokens' partials are in LDS: lane (tt, qq) adds 16 of token tt's 64 partials,
-                // two butterfly steps finish the sum in every lane of column tt
-                prune_lds_sync();
-                const int tt = lane & 15, qq = lane >> 4;
-                float s = 0.0f;
-#pragma unroll
-                for (int c = 0; c < 16; ++c) s += psum[tt * kPsumStride + qq * 16 + c];
+            ps[u] = (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
+        }
+        // pruned-saliency sums: fold the 8 tokens' per-lane partials into one register (token u in the
+        // lanes with l & 7 == u), pair it with the previous block's, finish across the four rows
+        {
+            const float f01 = fold_pair<0xB1>(ps[0], ps[1], lane & 1);     // quad_perm [1,0,3,2]
+            const float f23 = fold_pair<0xB1>(ps[2], ps[3], lane & 1);
+            const float f45 = fold_pair<0xB1>(ps[4], ps[5], lane & 1);
+            const float f67 = fold_pair<0xB1>(ps[6], ps[7], lane & 1);
+            const float f03 = fold_pair<0x4E>(f01, f23, lane & 2);         // quad_perm [2,3,0,1]
+            const float f47 = fold_pair<0x4E>(f45, f67, lane & 2);
+            const float f07 = fold_pair<0x124>(f03, f47, lane & 4);        // row_ror 4
+            if (tb & PF) {
+                float s = fold_pair<0x128>(fprev, f07, lane & 8);          // row_ror 8
                 s += __shfl_xor(s, 16);
                 s += __shfl_xor(s, 32);
-                if (qq == (t >> 4)) mureg = s;
-                prune_lds_sync();
+                if ((lane >> 4) == (tb >> 4)) mureg = s;
+            } else {
+                fprev = f07;
             }
         }
 #pragma unroll
