@@ -278,42 +278,39 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                 return __popcll(__ballot(key0 >= x)) + __popcll(__ballot(key1 >= x));
             };
 
-            // exponent: in the common case the previous row's E still has cE >= T > above1
-            int cE = count_ge((uint32_t)E << 23);
+            // exponent: in the common case the previous row's E still has (keys >= 2^E) >= T > above1
             int above1 = count_ge(((uint32_t)E + 1u) << 23);      // keys with exponent > E
-            if (__builtin_expect(!((uint32_t)(T - 1 - above1) < (uint32_t)(cE - above1)), 0)) {
-                if (cE >= T) {      // then above1 >= T as well: step up (2^256 is above every key)
-                    do {
-                        ++E;
-                        cE = above1;
-                        above1 = count_ge(((uint32_t)E + 1u) << 23);
-                    } while (above1 >= T);
-                } else {            // step down (E = 0 always qualifies: all 128 keys are >= 0)
-                    do {
-                        above1 = cE;
-                        --E;
-                        cE = count_ge((uint32_t)E << 23);
-                    } while (cE < T);
-                }
+            while (__builtin_expect(above1 >= T, 0)) {            // step up (2^256 is above every key)
+                ++E;
+                above1 = count_ge(((uint32_t)E + 1u) << 23);
             }
             // next six bits: counting pass over the keys whose exponent is E; the others land in a
-            // spare word (bins 64..127) that is never read
-            hist[lane] = 0u;
-            prune_lds_sync();
-            {
-                const uint32_t top = ((uint32_t)E << 6) | 63u;
-                const uint32_t d0 = top - (key0 >> 17), d1 = top - (key1 >> 17);
-                const uint32_t spare = (uint32_t)(kHistBins + lane);   // one spare word per lane: no pile-up
-                atomicAdd(&hist[d0 < spare ? d0 : spare], 1u);
-                atomicAdd(&hist[d1 < spare ? d1 : spare], 1u);
+            // spare word (bins 64..127) that is never read.  If the octave turns out to hold fewer
+            // keys than are still needed, all of it counts as "above" and the pass moves one octave
+            // down (octave 0 ends this: it holds every key not above it).
+            uint32_t s2;
+            uint64_t reached;
+            for (;;) {
+                hist[lane] = 0u;
+                prune_lds_sync();
+                {
+                    const uint32_t top = ((uint32_t)E << 6) | 63u;
+                    const uint32_t d0 = top - (key0 >> 17), d1 = top - (key1 >> 17);
+                    const uint32_t spare = (uint32_t)(kHistBins + lane);   // one spare word per lane: no pile-up
+                    atomicAdd(&hist[d0 < spare ? d0 : spare], 1u);
+                    atomicAdd(&hist[d1 < spare ? d1 : spare], 1u);
+                }
+                prune_lds_sync();
+                s2 = wave_inclusive_sum(hist[lane]);              // keys in octave E with digit >= 63 - lane
+                prune_lds_sync();
+                reached = __ballot(s2 >= (uint32_t)(T - above1)); // T - above1 >= 1
+                if (__builtin_expect(reached != 0, 1)) break;
+                above1 += __builtin_amdgcn_readlane((int)s2, 63);
+                --E;
             }
-            prune_lds_sync();
-            const uint32_t s2 = wave_inclusive_sum(hist[lane]);   // keys in octave E with digit >= 63 - lane
-            const int need2 = T - above1;                                     // >= 1
-            const int l2 = __builtin_ctzll(__ballot(s2 >= (uint32_t)need2));  // lane 63 qualifies
+            const int l2 = __builtin_ctzll(reached);
             const int ge = above1 + __builtin_amdgcn_readlane((int)s2, l2);   // keys >= p
             uint32_t p = ((uint32_t)E << 23) | ((uint32_t)(63 - l2) << 17);
-            prune_lds_sync();
             int tied = 0;
             if (ge != T) {
                 // remaining 17 bits (a probe is 2 vector compares and ~8 scalar instructions, with
@@ -342,7 +339,11 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
             const bool keep0 = __builtin_amdgcn_inverse_ballot_w64(kb0);
             const bool keep1 = __builtin_amdgcn_inverse_ballot_w64(kb1);
             // slot of each kept value = number of kept channels below it
-            const int pos0 = mbcnt64(kb0) + mbcnt64(kb1);
+            const int pos0 = (int)__builtin_amdgcn_mbcnt_hi(
+                (uint32_t)(kb1 >> 32),
+                __builtin_amdgcn_mbcnt_lo((uint32_t)kb1,
+                                          __builtin_amdgcn_mbcnt_hi((uint32_t)(kb0 >> 32),
+                                                                    __builtin_amdgcn_mbcnt_lo((uint32_t)kb0, 0))));
             const int pos1 = pos0 + (keep0 ? 1 : 0);
             uint16_t *vrow = stage16 + (size_t)t * sw * 2 + L.val0 * 2;
             // every lane stores; a pruned value goes to the lane's spare word instead of masking
