@@ -152,3 +152,22 @@ def test_window_scale_invariance_on_gpu():
     r4 = run_gpu_case(w, t)
     assert np.array_equal(r1["mask"], r4["mask"])
     assert np.abs(r1["out_f32"] - r4["out_f32"]).max() < 1e-5
+
+
+@pytest.mark.parametrize("lo,hi,with_decode", [(-12, 3, True), (-100, 20, False), (-145, -115, False)])
+def test_token_scales_jump_by_many_octaves(lo, hi, with_decode):
+    """Neighbouring tokens whose key norms differ by powers of two far apart: the threshold search
+    starts each row from the previous row's exponent and has to walk up or down from it."""
+    w = wl.small(name=f"octaves{lo}_{hi}", batch=2, n_q_heads=8, n_kv_heads=2, keep=26, seqlens=(200, 131), seed=99)
+    t = wl.generate(w)
+    rng = np.random.default_rng(99)
+    kf = wl.bf16_bits_to_f32(t.k)                                   # [Hkv, total, D]
+    e = rng.integers(lo, hi + 1, size=kf.shape[:2]).astype(np.float32)
+    e[:, 5::17] = lo                                                # runs of abrupt changes
+    e[:, 6::17] = hi
+    t.k = wl.f32_to_bf16_bits((kf * np.exp2(e)[..., None]).astype(np.float32))   # exact: a power of two
+    a32, pr, ref = _oracle_all(w, t)
+    res = run_gpu_case(w, t)
+    _check_prune(res, a32, pr)
+    if with_decode:
+        _check_out(res, ref, w.name)
