@@ -41,7 +41,7 @@ extern "C" {
 typedef enum {
     SPARK_OK = 0,
     SPARK_ERR_INVALID_ARG = 1,      /* NULL pointer, non-positive size, bad stride/alignment */
-    SPARK_ERR_UNSUPPORTED = 2,      /* head_dim != 128, group size not in {1,2,4,8,16}, ... */
+    SPARK_ERR_UNSUPPORTED = 2,      /* head_dim != 128, group size not in {1,2,4,8,16}, token stride of K above 2^24 */
     SPARK_ERR_WORKSPACE_TOO_SMALL = 3,
     SPARK_ERR_HIP = 4               /* the HIP runtime reported an error at launch */
 } spark_status;
@@ -104,7 +104,8 @@ int32_t spark_decode_splits(const spark_desc *desc);
  * bf16 bits, ascending channel; or int8 codes = round(k / scale), scale = max|k| / 127, for
  * SPARK_PACK_INT8) and mu, plus a per (batch, KV head); all inside `packed_out`.
  *
- *   k_bf16     in   dense keys, bf16, addressed with k_*_stride
+ *   k_bf16     in   dense keys, bf16, addressed with k_*_stride; k_token_stride <= 2^24 elements
+ *                   (SPARK_ERR_UNSUPPORTED beyond that)
  *   qwin_bf16  in   [batch, n_q_heads, window, 128] bf16, contiguous
  *   cu_seqlens in   int32 [batch+1]
  *   packed_out out  spark_packed_bytes(desc) bytes, 256-byte aligned; fully overwritten

@@ -162,6 +162,8 @@ spark_status spark_prune(const spark_desc *desc, const void *k_bf16, const void 
     if (!k_bf16 || !qwin_bf16 || !cu_seqlens || !packed_out) return SPARK_ERR_INVALID_ARG;
     if (desc->window < 1) return SPARK_ERR_INVALID_ARG;
     if (!strides_ok(desc->k_token_stride, desc->k_head_stride)) return SPARK_ERR_INVALID_ARG;
+    // the prune kernel addresses the 64 rows of a tile with 32-bit byte offsets from the tile's first row
+    if (desc->k_token_stride > ((int64_t)1 << 24)) return SPARK_ERR_UNSUPPORTED;
     if (!aligned(k_bf16, 2) || !aligned(qwin_bf16, 2) || !aligned(packed_out, 256)) return SPARK_ERR_INVALID_ARG;
     const SparkLayout L = layout_of(desc);
     const hipError_t e = spark::launch_prune(static_cast<const uint16_t *>(k_bf16), desc->k_token_stride,

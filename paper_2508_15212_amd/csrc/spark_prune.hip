@@ -163,7 +163,9 @@ __device__ __forceinline__ void prune_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int INT8>
+// FULL: the launch covers the tiles that hold all 64 tokens (the first total_tokens / 64 of every head);
+// otherwise it covers the one partly filled last tile of every head, one wavefront each.
+template <int INT8, bool FULL>
 __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     const uint16_t *__restrict__ k, int64_t k_tok_stride, int64_t k_head_stride,
     const int32_t *__restrict__ cu, uint8_t *__restrict__ packed, SparkLayout L)
@@ -174,9 +176,10 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     // (tile, token loop, search state) in scalar registers
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t wt = (int64_t)blockIdx.x * kPruneWaves + wave;
-    if (wt >= L.n_tiles * L.n_kv_heads) return;   // whole wavefront leaves; no block barrier is used
-    const int h = (int)(wt / L.n_tiles);
-    const int64_t tile = wt % L.n_tiles;
+    const int64_t full_tiles = L.total_tokens / SPARK_TILE_TOKENS;
+    if (wt >= (FULL ? full_tiles : 1) * L.n_kv_heads) return;   // whole wavefront leaves; no block barrier is used
+    const int h = FULL ? (int)(wt / full_tiles) : (int)wt;
+    const int64_t tile = FULL ? wt % full_tiles : full_tiles;
     const int T = L.T;
     const int B = L.batch;
     const int sw = spark_stage_words(L);
@@ -187,7 +190,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
 
     const float2 *a_all = reinterpret_cast<const float2 *>(packed + L.off_a);
     const int64_t n0 = tile * SPARK_TILE_TOKENS;
-    const int nvalid = (int)((L.total_tokens - n0 < SPARK_TILE_TOKENS) ? (L.total_tokens - n0) : SPARK_TILE_TOKENS);
+    const int nvalid = FULL ? SPARK_TILE_TOKENS : (int)(L.total_tokens - n0);
 
     // sequence of the first token: largest b with cu[b] <= n0 (skips empty sequences)
     int b = 0;
@@ -204,21 +207,43 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     // lane l owns channels 2l (low half of its 32-bit load) and 2l+1 (high half)
     float2 a01 = a_all[((int64_t)b * L.n_kv_heads + h) * (SPARK_D / 2) + lane];
 
-    const uint32_t *krow = reinterpret_cast<const uint32_t *>(k + n0 * k_tok_stride + (int64_t)h * k_head_stride) + lane;
-    const int64_t row_stride = k_tok_stride / 2;   // in 32-bit words (the ABI requires even strides)
+    // Row addresses: a wave-uniform base (scalar registers) plus one 32-bit per-lane offset per row of
+    // a block of PF rows, set up once; a block's eight loads then cost no address arithmetic.
+    constexpr int PF = 8;
+    const char *kbase = reinterpret_cast<const char *>(k + n0 * k_tok_stride + (int64_t)h * k_head_stride);
+    const uint32_t stride_b = (uint32_t)k_tok_stride * 2u;   // bytes per token row (the host checks the range)
+    uint32_t voff[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u) voff[u] = (uint32_t)lane * 4u + (uint32_t)u * stride_b;
+    // rows tb0 .. tb0+PF-1 of the tile into x; in a partly filled tile rows past the last token repeat
+    // the last one
+    auto load_block = [&](uint32_t (&x)[PF], int tb0) __attribute__((always_inline)) {
+        if constexpr (FULL) {
+            const char *sb = kbase + (size_t)((uint32_t)tb0 * stride_b);
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                asm volatile("" : "+v"(voff[u]));   // keeps the 32-bit offset next to its load (scalar base + offset form)
+                x[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(sb + voff[u]));
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const int tt = (tb0 + u < nvalid) ? (tb0 + u) : (nvalid - 1);
+                const char *sb = kbase + (size_t)((uint32_t)tt * stride_b);
+                asm volatile("" : "+v"(voff[0]));
+                x[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(sb + voff[0]));
+            }
+        }
+    };
 
     // lane t collects, for token t, the ballots of kept even channels (e) and kept odd channels (o)
     uint32_t e_lo = 0, e_hi = 0, o_lo = 0, o_hi = 0;
-    float mureg = 0.0f, fprev = 0.0f;                       // lane t: sum of pruned saliencies
+    float mureg = 0.0f;                                     // lane t: sum of pruned saliencies
 
-    // Rows are fetched a block ahead: while block tb is searched, block tb+PF is in flight.
-    constexpr int PF = 8;
-    uint32_t xc[PF];
-#pragma unroll
-    for (int u = 0; u < PF; ++u) {
-        const int tt = (u < nvalid) ? u : (nvalid - 1);
-        xc[u] = __builtin_nontemporal_load(krow + (int64_t)tt * row_stride);
-    }
+    // Rows are fetched a block ahead: while one block of PF rows is searched the next is in flight,
+    // in two register sets that swap roles.
+    uint32_t xa[PF], xb[PF];
+    load_block(xa, 0);
 
     // T-th largest key of a row.  The search is most-significant-bit first on the float32 bit pattern:
     // keep a prefix p such that at least T keys are >= p and try to extend it; a probe is two wave
@@ -230,7 +255,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     // reaches what is still needed).  The search stops as soon as exactly T keys are >= p.
     int E;
     {   // first row: E by bisection over the 256 exponents
-        const uint32_t xx = xc[0];
+        const uint32_t xx = xa[0];
         const uint32_t key0 = __float_as_uint(__fmul_rn(a01.x, fabsf(__uint_as_float(xx << 16))));
         const uint32_t key1 = __float_as_uint(__fmul_rn(a01.y, fabsf(__uint_as_float(xx & 0xFFFF0000u))));
         int lo = 0, hi = 256;   // at least T keys are >= lo << 23, fewer are >= hi << 23
@@ -243,21 +268,14 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
         E = lo;
     }
 
-    // Every one of the 64 rows is processed; rows past the last token repeat the last one and are
-    // overwritten by the epilogue.
-    for (int tb = 0; tb < SPARK_TILE_TOKENS; tb += PF) {
-        uint32_t xn[PF];
-#pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            int tn = tb + PF + u;
-            tn = (tn < nvalid) ? tn : (nvalid - 1);
-            xn[u] = __builtin_nontemporal_load(krow + (int64_t)tn * row_stride);
-        }
+    // searches and stages the PF rows held in x (tokens tb .. tb+PF-1); returns their pruned-saliency
+    // partials folded into one register (token tb + u in the lanes with l & 7 == u)
+    auto do_block = [&](const uint32_t (&x)[PF], int tb) __attribute__((always_inline)) -> float {
         float ps[PF];
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int t = tb + u;
-            const uint32_t xx = xc[u];
+            const uint32_t xx = x[u];
             if (__builtin_expect(t >= seq_end_t, 0)) {    // rare: the tile crosses into the next non-empty sequence
                 if (t < nvalid) {
                     do {
@@ -316,13 +334,15 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                 // remaining 17 bits (a probe is 2 vector compares and ~8 scalar instructions, with
                 // the candidate and the prefix held in scalar registers)
                 tied = 1;
-#pragma unroll
-                for (int bit = 16; bit >= 0; --bit) {
-                    const uint32_t cand = p | (1u << bit);
+                uint32_t bit = 1u << 16;
+#pragma nounroll
+                do {
+                    const uint32_t cand = p | bit;
                     const int c = count_ge(cand);
                     p = (c >= T) ? cand : p;
                     if (c == T) { tied = 0; break; }
-                }
+                    bit >>= 1;
+                } while (bit != 0u);
             }
             // exactly T keys are >= p, unless p is the T-th largest value and it is tied
             uint64_t kb0 = __ballot(key0 >= p), kb1 = __ballot(key1 >= p);
@@ -356,27 +376,27 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                         (uint32_t)(kb1 >> 32), t);
             ps[u] = (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
         }
-        // pruned-saliency sums: fold the 8 tokens' per-lane partials into one register (token u in the
-        // lanes with l & 7 == u), pair it with the previous block's, finish across the four rows
-        {
-            const float f01 = fold_pair<0xB1>(ps[0], ps[1], lane & 1);     // quad_perm [1,0,3,2]
-            const float f23 = fold_pair<0xB1>(ps[2], ps[3], lane & 1);
-            const float f45 = fold_pair<0xB1>(ps[4], ps[5], lane & 1);
-            const float f67 = fold_pair<0xB1>(ps[6], ps[7], lane & 1);
-            const float f03 = fold_pair<0x4E>(f01, f23, lane & 2);         // quad_perm [2,3,0,1]
-            const float f47 = fold_pair<0x4E>(f45, f67, lane & 2);
-            const float f07 = fold_pair<0x124>(f03, f47, lane & 4);        // row_ror 4
-            if (tb & PF) {
-                float s = fold_pair<0x128>(fprev, f07, lane & 8);          // row_ror 8
-                s += __shfl_xor(s, 16);
-                s += __shfl_xor(s, 32);
-                if ((lane >> 4) == (tb >> 4)) mureg = s;
-            } else {
-                fprev = f07;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < PF; ++u) xc[u] = xn[u];
+        const float f01 = fold_pair<0xB1>(ps[0], ps[1], lane & 1);     // quad_perm [1,0,3,2]
+        const float f23 = fold_pair<0xB1>(ps[2], ps[3], lane & 1);
+        const float f45 = fold_pair<0xB1>(ps[4], ps[5], lane & 1);
+        const float f67 = fold_pair<0xB1>(ps[6], ps[7], lane & 1);
+        const float f03 = fold_pair<0x4E>(f01, f23, lane & 2);         // quad_perm [2,3,0,1]
+        const float f47 = fold_pair<0x4E>(f45, f67, lane & 2);
+        return fold_pair<0x124>(f03, f47, lane & 4);                   // row_ror 4
+    };
+
+    // Every one of the 64 rows is processed; rows past the last token repeat the last one and are
+    // overwritten by the epilogue.
+    for (int tb = 0; tb < SPARK_TILE_TOKENS; tb += 2 * PF) {
+        load_block(xb, tb + PF);
+        const float fa = do_block(xa, tb);
+        if (tb + 2 * PF < SPARK_TILE_TOKENS) load_block(xa, tb + 2 * PF);
+        const float fb = do_block(xb, tb + PF);
+        // pruned-saliency sums of these 16 tokens: pair the two blocks, finish across the four rows
+        float s = fold_pair<0x128>(fa, fb, lane & 8);                  // row_ror 8
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if ((lane >> 4) == (tb >> 4)) mureg = s;
     }
 
     // ---- row epilogue, lane = token
@@ -489,28 +509,25 @@ hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_
                        L.n_kv_heads, W, packed, L);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int64_t waves = L.n_tiles * L.n_kv_heads;
-    if (waves == 0) return hipSuccess;
-    const int nblocks = (int)((waves + kPruneWaves - 1) / kPruneWaves);
     const size_t lds = spark_prune_lds_bytes(L);
-    if (L.int8) {
+    auto launch = [&](auto kern, int64_t waves) -> hipError_t {
+        if (waves == 0) return hipSuccess;
         if (lds > 48 * 1024) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&spark_prune_kernel<1>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
+            hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e2 != hipSuccess) return e2;
         }
-        hipLaunchKernelGGL(spark_prune_kernel<1>, dim3(nblocks), dim3(kPruneWaves * 64), lds, st, k, k_tok_stride,
-                           k_head_stride, cu, packed, L);
-    } else {
-        if (lds > 48 * 1024) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&spark_prune_kernel<0>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        hipLaunchKernelGGL(spark_prune_kernel<0>, dim3(nblocks), dim3(kPruneWaves * 64), lds, st, k, k_tok_stride,
-                           k_head_stride, cu, packed, L);
-    }
-    return hipGetLastError();
+        const int nblocks = (int)((waves + kPruneWaves - 1) / kPruneWaves);
+        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(kPruneWaves * 64), lds, st, k, k_tok_stride, k_head_stride, cu,
+                           packed, L);
+        return hipGetLastError();
+    };
+    // the tiles that hold 64 tokens, then (if the token count is not a multiple of 64) each head's last tile
+    const int64_t full_waves = (L.total_tokens / SPARK_TILE_TOKENS) * L.n_kv_heads;
+    const int64_t tail_waves = (L.total_tokens % SPARK_TILE_TOKENS) ? L.n_kv_heads : 0;
+    e = L.int8 ? launch(&spark_prune_kernel<1, true>, full_waves) : launch(&spark_prune_kernel<0, true>, full_waves);
+    if (e != hipSuccess) return e;
+    return L.int8 ? launch(&spark_prune_kernel<1, false>, tail_waves) : launch(&spark_prune_kernel<0, false>, tail_waves);
 }
 
 hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *mask_out, void *vals_out,
