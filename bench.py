@@ -35,13 +35,13 @@ MEASURED_DECODE_TRAFFIC_BYTES = {("cfg2_llama8b_b8_32k_keep26", "bf16"): 2 * 336
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline metric)")
     ap.add_argument("--keep", type=int, default=0, help="override T")
     ap.add_argument("--int8", action="store_true", help="int8 storage of the kept entries")
     ap.add_argument("--splits", type=int, default=0)
-    ap.add_argument("--copies", type=int, default=3, help="input copies rotated to defeat the 256 MB cache")
+    ap.add_argument("--copies", type=int, default=4, help="input copies rotated to defeat the 256 MB cache")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--decode-only", action="store_true", help="time decode alone (profiling aid)")
     args = ap.parse_args()

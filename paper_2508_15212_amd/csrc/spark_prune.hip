@@ -449,19 +449,22 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     }
     // ---- coalesced tile write: section q holds words 4q..4q+3 of every token
     uint8_t *tile_out = packed + L.off_tiles + ((int64_t)h * L.n_tiles + tile) * L.tile_bytes;
+    // (written once, read by another kernel much later: non-temporal, like the loads)
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     for (int q = 0; q < L.nq; ++q) {
-        uint4 v;
+        u32x4 v;
         v.x = row[4 * q + 0];
         v.y = row[4 * q + 1];
         v.z = row[4 * q + 2];
         v.w = row[4 * q + 3];
-        *reinterpret_cast<uint4 *>(tile_out + (size_t)q * 1024 + lane * 16) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(tile_out + (size_t)q * 1024 + lane * 16));
     }
     if (L.tail2) {
-        uint2 v;
+        u32x2 v;
         v.x = row[4 * L.nq + 0];
         v.y = row[4 * L.nq + 1];
-        *reinterpret_cast<uint2 *>(tile_out + (size_t)L.nq * 1024 + lane * 8) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(tile_out + (size_t)L.nq * 1024 + lane * 8));
     }
 }
 
