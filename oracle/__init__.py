@@ -41,6 +41,7 @@ def lib() -> ctypes.CDLL:
         _lib = ctypes.CDLL(build())
         _lib.oracle_max_threads.restype = ctypes.c_int
         _lib.oracle_prune.restype = ctypes.c_int
+        _lib.oracle_prune_values.restype = ctypes.c_int
     return _lib
 
 
@@ -135,6 +136,42 @@ def quant_int8(pr: Pruned) -> Pruned:
     out = Pruned(pr.mask, pr.kept, pr.mu64, pr.mu32, pr.gap, pr.a32, pr.w, pr.T, pr.D)
     out.codes, out.scale = codes, scale
     return out
+
+
+@dataclass
+class PrunedValues:
+    """The value cache after channel pruning (appendix on pruning value-cache channels)."""
+    mask: np.ndarray     # uint32 [total, Hkv, ceil(D/32)]
+    kept: np.ndarray     # uint16 [total, Hkv, Tv], original bf16 bits, ascending channel
+    gap: np.ndarray      # float64 [total, Hkv]  relative margin between Tv-th and (Tv+1)-th |v|
+    T: int
+    D: int
+
+    def near_ties(self, rel=1e-6) -> int:
+        return int(np.count_nonzero(self.gap < rel))
+
+
+def prune_values(v: np.ndarray, layout: str, Tv: int) -> PrunedValues:
+    """Per (token, KV head): keep the Tv channels of largest |v| (ties: lower channel)."""
+    v, ts, hs, total, hkv, d = _strided(v, layout)
+    mw = (d + 31) // 32
+    mask = np.empty((total, hkv, mw), np.uint32)
+    kept = np.empty((total, hkv, Tv), np.uint16)
+    gap = np.empty((total, hkv), np.float64)
+    rc = lib().oracle_prune_values(_p(v), ctypes.c_int64(ts), ctypes.c_int64(hs), ctypes.c_int64(total),
+                                   hkv, d, int(Tv), _p(mask), _p(kept), _p(gap))
+    if rc != 0:
+        raise ValueError("oracle_prune_values: bad arguments")
+    return PrunedValues(mask, kept, gap, int(Tv), d)
+
+
+def expand_values(pv: PrunedValues) -> np.ndarray:
+    """Dense value rows as decode consumes them: kept entries at their channels, pruned entries 0.
+    Returns uint16 [total, Hkv, D] (layout "NHD"); pass it as V to the decode functions."""
+    total, hkv, _ = pv.mask.shape
+    vt = np.empty((total, hkv, pv.D), np.uint16)
+    lib().oracle_expand_values(_p(pv.mask), _p(pv.kept), ctypes.c_int64(total), hkv, pv.D, pv.T, _p(vt))
+    return vt
 
 
 def _decode(fn, q, pr: Pruned, v, layout, cu, scale, want_probs):

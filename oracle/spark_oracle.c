@@ -24,8 +24,9 @@
  * Parity pins (tests that hold this file to something other than itself): the hand
  * worked example under tests/golden, keep-all == dense attention == a library softmax
  * attention, brute-force subset optimality of Eq. (7), the exact-recovery construction,
- * window-scale invariance, and the invariants listed in tests/test_oracle_pins.py.
- * No function in this file is "parity unpinned".
+ * window-scale invariance, and the invariants listed in tests/test_oracle_pins.py; the
+ * value-cache functions by brute-force subset optimality, a second hand-worked case and
+ * an independent masked-matrix product.  No function in this file is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -218,6 +219,84 @@ void oracle_quant_int8(const uint16_t *kept, int64_t rows, int T, int8_t *codes,
             if (rq < -127.0f) rq = -127.0f;
             codes[r * T + i] = (int8_t)rq;
         }
+    }
+}
+
+/* ------------------------------------------------------------- value cache */
+
+/*
+ * Channel pruning of the value cache, App. "Pruning Value Cache Channels" (the extension
+ * that prunes keys and values together, lambda_k + lambda_v).
+ *
+ * Values cannot be scored against a query, so the score of channel j of token t is the
+ * magnitude of the entry itself ("norm-based": the 2-norm of a scalar is its absolute
+ * value), and the T_v channels of largest |v| are retained per (token, KV head):
+ *     order = channels sorted by |V[n,h,j]| descending, equal magnitudes by ascending j
+ *     kept  = first Tv of order;  mask bit j = 1 iff kept
+ *     V-hat = kept entries' original bf16 bits in ascending channel order
+ *     gap   = (|v|_(Tv) - |v|_(Tv+1)) / |v|_(Tv)   (0 when |v|_(Tv) == 0; +inf when Tv == D)
+ * |v| of a bf16 entry is exact in binary32, so the kept set is a pure function of bits.
+ * Reading of the appendix (it is brief): the pruned entries are dropped and nothing is
+ * cached in their place -- it says that values need no scaling or recombination because
+ * they are consumed directly by the weighted sum -- so they contribute 0 at decode.
+ *
+ * v: element (n,h,j) at v[n*tok_stride + h*head_stride + j]; mask [total,Hkv,ceil(D/32)];
+ * kept [total,Hkv,Tv]; gap [total,Hkv].  Returns 0, or -1 on bad arguments.
+ */
+int oracle_prune_values(const uint16_t *v, int64_t tok_stride, int64_t head_stride,
+                        int64_t total, int Hkv, int D, int Tv, uint32_t *mask, uint16_t *kept,
+                        double *gap)
+{
+    if (D < 1 || D > 1024 || Tv < 1 || Tv > D || Hkv < 1 || total < 0) return -1;
+    const int MW = (D + 31) / 32;
+    int64_t n;
+#pragma omp parallel for schedule(static)
+    for (n = 0; n < total; ++n) {
+        float mag[1024];
+        int order[1024];
+        for (int h = 0; h < Hkv; ++h) {
+            const uint16_t *vrow = v + n * tok_stride + (int64_t)h * head_stride;
+            const int64_t row = n * Hkv + h;
+            for (int j = 0; j < D; ++j) mag[j] = fabsf(bf16_bits_to_f32(vrow[j]));
+            /* stable insertion sort of channel indices: magnitude descending, ties by index */
+            for (int j = 0; j < D; ++j) {
+                int p = j;
+                while (p > 0 && mag[order[p - 1]] < mag[j]) {
+                    order[p] = order[p - 1];
+                    --p;
+                }
+                order[p] = j;
+            }
+            for (int m = 0; m < MW; ++m) mask[row * MW + m] = 0u;
+            for (int i = 0; i < Tv; ++i) mask[row * MW + order[i] / 32] |= (1u << (order[i] % 32));
+            int c = 0;
+            for (int j = 0; j < D; ++j)
+                if (mask[row * MW + j / 32] >> (j % 32) & 1u) kept[row * Tv + c++] = vrow[j];
+            if (Tv == D)
+                gap[row] = INFINITY;
+            else {
+                const double hi = (double)mag[order[Tv - 1]], lo = (double)mag[order[Tv]];
+                gap[row] = (hi > 0.0) ? (hi - lo) / hi : 0.0;
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * The value rows as decode sees them: kept entries back at their channels, every pruned
+ * entry 0 (see above).  vtilde [total,Hkv,D] bf16 bits; feeding it to the decode functions
+ * below as V is decode attention over a cache with pruned keys AND pruned values.
+ */
+void oracle_expand_values(const uint32_t *mask, const uint16_t *kept, int64_t total, int Hkv,
+                          int D, int Tv, uint16_t *vtilde)
+{
+    const int MW = (D + 31) / 32;
+    for (int64_t row = 0; row < total * Hkv; ++row) {
+        int c = 0;
+        for (int j = 0; j < D; ++j)
+            vtilde[row * D + j] =
+                (mask[row * MW + j / 32] >> (j % 32) & 1u) ? kept[row * Tv + c++] : (uint16_t)0;
     }
 }
 

@@ -366,3 +366,96 @@ def test_int8_variant_closed_form_properties():
                          pr.gap[:1], pr.a32, None, pr.T, pr.D)
     zq = oracle.quant_int8(zero)
     assert np.all(zq.scale == 0) and np.all(zq.codes == 0)
+
+
+# ------------------------------------------------------------------ value-cache pruning pins
+
+with open(os.path.join(HERE, "golden", "handworked.json")) as fh:
+    _VCASES = json.load(fh)["value_cases"]
+
+
+@pytest.mark.parametrize("case", _VCASES, ids=[c["name"] for c in _VCASES])
+def test_handworked_value_pruning(case):
+    kc = next(c for c in _CASES if c["name"] == case["key_case"])
+    Hkv, D, T, S = (kc[x] for x in ("Hkv", "D", "T", "S"))
+    qwin, k, q, v = _bits(kc["qwin"]), _bits(kc["k"]), _bits(kc["q"]), _bits(case["v"])
+    cu = np.array([0, S], np.int32)
+    exp = case["expect"]
+    _, _, a32 = oracle.window_stat(qwin, Hkv)
+    pr = oracle.prune(k, "NHD", a32, cu, T)
+    pv = oracle.prune_values(v, "NHD", case["Tv"])
+    for n in range(S):
+        assert _kept_channels(pv.mask[n, 0], D) == exp["kept_channels"][n][0]
+    assert np.array_equal(fb(pv.kept), np.asarray(exp["kept_values"], np.float32))
+    vt = oracle.expand_values(pv)
+    assert np.array_equal(fb(vt), np.asarray(exp["vtilde"], np.float32))
+    out = oracle.decode_literal(q, pr, vt, "NHD", cu)
+    assert np.allclose(out, np.asarray(exp["out"], np.float64), rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("D,Tv", [(6, 1), (7, 3), (8, 4), (10, 5), (10, 9)])
+def test_value_selection_is_the_brute_force_optimum(D, Tv):
+    """The kept set maximises the retained magnitude sum over all C(D, Tv) subsets, and among the
+    maximisers it is the lexicographically smallest (ties towards lower channels)."""
+    rng = np.random.default_rng(300 + 10 * D + Tv)
+    S, Hkv = 40, 2
+    v = rng.integers(-3, 4, size=(S, Hkv, D)).astype(np.float32) * 0.5     # many ties, zeros
+    pv = oracle.prune_values(bf(v), "NHD", Tv)
+    for n in range(S):
+        for h in range(Hkv):
+            mag = np.abs(v[n, h]).astype(np.float64)
+            best, best_sets = -1.0, []
+            for sub in itertools.combinations(range(D), Tv):
+                tot = float(sum(mag[j] for j in sub))
+                if tot > best + 1e-12:
+                    best, best_sets = tot, [sub]
+                elif abs(tot - best) <= 1e-12:
+                    best_sets.append(sub)
+            got = tuple(_kept_channels(pv.mask[n, h], D))
+            assert len(got) == Tv and got in best_sets and got == min(best_sets)
+            assert np.array_equal(fb(pv.kept[n, h]), v[n, h][list(got)])
+
+
+def test_value_pruning_invariants_layouts_and_masked_product():
+    w, t = _random_small(11, Hq=8, Hkv=2, T=26)
+    D, Tv = w.head_dim, 48
+    vf = fb(t.v)                                                          # [Hkv,total,D]
+    pv = oracle.prune_values(t.v, t.layout, Tv)
+    pv2 = oracle.prune_values(np.ascontiguousarray(t.v.transpose(1, 0, 2)), "NHD", Tv)
+    assert np.array_equal(pv.mask, pv2.mask) and np.array_equal(pv.kept, pv2.kept)   # layout-independent
+    bits = np.unpackbits(pv.mask.view(np.uint8), axis=-1, bitorder="little").astype(bool)   # [total,Hkv,D]
+    assert np.all(bits.sum(-1) == Tv)
+    mag = np.abs(vf).transpose(1, 0, 2)                                   # [total,Hkv,D]
+    kept_min = np.where(bits, mag, np.inf).min(-1)
+    pruned_max = np.where(~bits, mag, -np.inf).max(-1)
+    assert np.all(kept_min >= pruned_max)
+    # on equality across the cut the kept channel has the lower index
+    for n, h in zip(*np.nonzero(kept_min == pruned_max)):
+        c = kept_min[n, h]
+        kept_eq = [j for j in range(D) if bits[n, h, j] and mag[n, h, j] == c]
+        pruned_eq = [j for j in range(D) if not bits[n, h, j] and mag[n, h, j] == c]
+        assert max(kept_eq) < min(pruned_eq)
+    # the expanded rows are the original rows times the 0/1 mask, and decode over them is the
+    # probability-weighted sum of those masked rows (probabilities do not depend on V)
+    vt = oracle.expand_values(pv)
+    assert np.array_equal(fb(vt), np.where(bits, vf.transpose(1, 0, 2), 0.0).astype(np.float32))
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    out, probs = oracle.decode_literal(t.q, pr, vt, "NHD", t.cu, want_probs=True)
+    _, probs_dense_v = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu, want_probs=True)
+    assert np.array_equal(probs, probs_dense_v)
+    G = w.n_q_heads // w.n_kv_heads
+    masked = np.where(bits, vf.transpose(1, 0, 2), 0.0).astype(np.float64)
+    for b in range(w.batch):
+        n0, n1 = int(t.cu[b]), int(t.cu[b + 1])
+        for g in range(w.n_q_heads):
+            ref = probs[g, n0:n1] @ masked[n0:n1, g // G, :]
+            assert np.allclose(out[b, g], ref, rtol=0, atol=1e-13)
+
+
+def test_keep_all_values_is_the_unpruned_value_cache():
+    w, t = _random_small(12, Hq=4, Hkv=2, T=26)
+    pv = oracle.prune_values(t.v, t.layout, w.head_dim)
+    assert np.all(np.isinf(pv.gap))
+    vt = oracle.expand_values(pv)
+    assert np.array_equal(vt, t.v.transpose(1, 0, 2))
