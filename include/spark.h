@@ -66,6 +66,8 @@ typedef struct spark_desc {
     float   softmax_scale;    /* 0 => 1/sqrt(head_dim) */
     int32_t n_splits;         /* sequence splits per (batch, KV head) in decode; 0 => library picks.
                                  Must be the same for the workspace query and the call. */
+    int32_t keep_v;           /* T_v in [1, D]: channels kept per (token, KV head) of the VALUE cache, used by
+                                 the *_values entry points only; 0 where values stay dense */
 } spark_desc;
 
 /* Size in bytes of the packed key cache for this description (depends on batch, n_kv_heads,
@@ -153,6 +155,32 @@ spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const
 spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *mask_out,
                           void *vals_out, float *mu_out, float *scale_out, float *a_out,
                           void *hip_stream);
+
+/*
+ * Channel pruning of the value cache.
+ * [App. "Pruning Value Cache Channels": per token the importance of a value channel is the magnitude of
+ *  the entry itself; only the top-T_v channels are retained; values need no scaling or recombination
+ *  because the weighted sum consumes them directly -- read here as: a pruned entry contributes 0]
+ *
+ *   kept_v(n,h) = the keep_v channels of largest |V[n,h,j]|; equal magnitudes: lower channel first
+ * and writes, per (token, KV head), the 128-bit channel mask and the kept entries (original bf16 bits,
+ * ascending channel) into `packed_v_out`.  No query, window or sequence boundary enters.
+ *
+ *   v_bf16        in   dense values, bf16, addressed with v_*_stride (v_token_stride <= 2^24 elements)
+ *   packed_v_out  out  spark_packed_values_bytes(desc) bytes, 256-byte aligned; fully overwritten
+ * Uses desc->n_kv_heads, head_dim, keep_v, total_tokens and the v strides.
+ */
+size_t spark_packed_values_bytes(const spark_desc *desc);   /* 0 if the description is invalid or keep_v == 0 */
+spark_status spark_prune_values(const spark_desc *desc, const void *v_bf16, void *packed_v_out,
+                                void *hip_stream);
+
+/*
+ * Canonical export of a packed value cache (parity tests and debugging).  Either output may be NULL.
+ *   mask_out  uint32 [total_tokens, n_kv_heads, 4]       bit j%32 of word j/32 = channel j kept
+ *   vals_out  uint16 [total_tokens, n_kv_heads, keep_v]  kept entries (bf16 bits), ascending channel
+ */
+spark_status spark_unpack_values(const spark_desc *desc, const void *packed_v, uint32_t *mask_out,
+                                 void *vals_out, void *hip_stream);
 
 /*
  * Measurement aid, not part of the method: reads `bytes` (a multiple of 16) from `src` once with

@@ -18,7 +18,8 @@ PACK_BF16, PACK_INT8 = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
 
 EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspace", "spark_decode_workspace_init", "spark_decode_splits",
-           "spark_prune", "spark_decode_attn", "spark_unpack", "spark_probe_read", "spark_status_string"]
+           "spark_prune", "spark_decode_attn", "spark_unpack", "spark_probe_read", "spark_status_string",
+           "spark_packed_values_bytes", "spark_prune_values", "spark_unpack_values"]
 
 
 class SparkError(RuntimeError):
@@ -35,6 +36,7 @@ class SparkDesc(ctypes.Structure):
         ("k_token_stride", ctypes.c_int64), ("k_head_stride", ctypes.c_int64),
         ("v_token_stride", ctypes.c_int64), ("v_head_stride", ctypes.c_int64),
         ("softmax_scale", ctypes.c_float), ("n_splits", ctypes.c_int32),
+        ("keep_v", ctypes.c_int32),
     ]
 
 
@@ -72,6 +74,12 @@ def load() -> ctypes.CDLL:
     lib.spark_decode_attn.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.spark_unpack.restype = ctypes.c_int
     lib.spark_unpack.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
+    lib.spark_packed_values_bytes.restype = ctypes.c_size_t
+    lib.spark_packed_values_bytes.argtypes = [dp]
+    lib.spark_prune_values.restype = ctypes.c_int
+    lib.spark_prune_values.argtypes = [dp, vp, vp, vp]
+    lib.spark_unpack_values.restype = ctypes.c_int
+    lib.spark_unpack_values.argtypes = [dp, vp, vp, vp, vp]
     lib.spark_probe_read.restype = ctypes.c_int
     lib.spark_probe_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, vp]
     lib.spark_status_string.restype = ctypes.c_char_p
@@ -132,6 +140,21 @@ def decode_attn(desc: SparkDesc, q: torch.Tensor, packed: torch.Tensor, v: torch
     rc = load().spark_decode_attn(ctypes.byref(desc), _ptr(q), _ptr(packed), _ptr(v), _ptr(cu), _ptr(out),
                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "spark_decode_attn")
+
+
+def packed_values_bytes(desc: SparkDesc) -> int:
+    return int(load().spark_packed_values_bytes(ctypes.byref(desc)))
+
+
+def prune_values(desc: SparkDesc, v: torch.Tensor, packed_v: torch.Tensor) -> None:
+    """spark_prune_values: v bf16-bit tensor on the device; packed_v a uint8 buffer of packed_values_bytes()."""
+    rc = load().spark_prune_values(ctypes.byref(desc), _ptr(v), _ptr(packed_v), _stream())
+    _check(rc, "spark_prune_values")
+
+
+def unpack_values(desc: SparkDesc, packed_v: torch.Tensor, mask=None, vals=None) -> None:
+    rc = load().spark_unpack_values(ctypes.byref(desc), _ptr(packed_v), _ptr(mask), _ptr(vals), _stream())
+    _check(rc, "spark_unpack_values")
 
 
 def unpack(desc: SparkDesc, packed: torch.Tensor, mask=None, vals=None, mu=None, scale=None, a=None) -> None:

@@ -19,6 +19,7 @@ bool desc_ok(const spark_desc *d, spark_status *why)
     if (d->keep < 1 || d->keep > d->head_dim) return false;
     if (d->n_q_heads % d->n_kv_heads) return false;
     if (d->n_splits < 0 || d->n_splits > 4096) return false;
+    if (d->keep_v < 0 || d->keep_v > d->head_dim) return false;
     *why = SPARK_ERR_UNSUPPORTED;
     if (d->head_dim != SPARK_D) return false;
     const int G = d->n_q_heads / d->n_kv_heads;
@@ -32,6 +33,11 @@ bool desc_ok(const spark_desc *d, spark_status *why)
 SparkLayout layout_of(const spark_desc *d)
 {
     return spark_make_layout(d->keep, d->pack_dtype == SPARK_PACK_INT8, d->batch, d->n_kv_heads, d->total_tokens);
+}
+
+SparkLayout values_layout_of(const spark_desc *d)
+{
+    return spark_make_values_layout(d->keep_v, d->n_kv_heads, d->total_tokens);
 }
 
 bool strides_ok(int64_t tok, int64_t head)
@@ -170,6 +176,38 @@ spark_status spark_prune(const spark_desc *desc, const void *k_bf16, const void 
                                              desc->k_head_stride, static_cast<const uint16_t *>(qwin_bf16),
                                              cu_seqlens, static_cast<uint8_t *>(packed_out), L, desc->n_q_heads,
                                              desc->window, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
+}
+
+size_t spark_packed_values_bytes(const spark_desc *desc)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why) || desc->keep_v < 1) return 0;
+    return (size_t)values_layout_of(desc).total_bytes;
+}
+
+spark_status spark_prune_values(const spark_desc *desc, const void *v_bf16, void *packed_v_out, void *hip_stream)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (desc->keep_v < 1 || !v_bf16 || !packed_v_out) return SPARK_ERR_INVALID_ARG;
+    if (!strides_ok(desc->v_token_stride, desc->v_head_stride)) return SPARK_ERR_INVALID_ARG;
+    if (desc->v_token_stride > ((int64_t)1 << 24)) return SPARK_ERR_UNSUPPORTED;
+    if (!aligned(v_bf16, 2) || !aligned(packed_v_out, 256)) return SPARK_ERR_INVALID_ARG;
+    const hipError_t e = spark::launch_prune_values(static_cast<const uint16_t *>(v_bf16), desc->v_token_stride,
+                                                    desc->v_head_stride, static_cast<uint8_t *>(packed_v_out),
+                                                    values_layout_of(desc), static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
+}
+
+spark_status spark_unpack_values(const spark_desc *desc, const void *packed_v, uint32_t *mask_out, void *vals_out,
+                                 void *hip_stream)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (desc->keep_v < 1 || !packed_v) return SPARK_ERR_INVALID_ARG;
+    const hipError_t e = spark::launch_unpack(static_cast<const uint8_t *>(packed_v), values_layout_of(desc), mask_out,
+                                              vals_out, nullptr, nullptr, nullptr, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }
 

@@ -12,6 +12,10 @@ struct DecodeParams;
 hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
                         const int32_t *cu, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st);
 
+// value-cache channel pruning: per (token, KV head) the L.T channels of largest |v| (L from spark_make_values_layout)
+hipError_t launch_prune_values(const uint16_t *v, int64_t v_tok_stride, int64_t v_head_stride, uint8_t *packed,
+                               const SparkLayout &L, hipStream_t st);
+
 hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *mask_out, void *vals_out,
                          float *mu_out, float *scale_out, float *a_out, hipStream_t st);
 

@@ -6,6 +6,7 @@
 //
 //   bf16 storage : [ m0 m1 m2 m3 | mu | v0 v1 ... v(nv-1) | pad ]   nv = ceil(T/2)
 //   int8 storage : [ m0 m1 m2 m3 | mu | scale | c0 ... c(nv-1) | pad ]   nv = ceil(T/4)
+//   value cache  : [ m0 m1 m2 m3 | v0 v1 ... v(nv-1) | pad ]        (pruned entries are dropped: no statistic)
 //
 // m0..m3 is the 128-bit channel mask (bit j%32 of word j/32 = channel j kept), mu the
 // mean saliency of the pruned channels, v* the kept entries in ascending channel order
@@ -37,6 +38,7 @@
 struct SparkLayout {
     int32_t T;            // kept channels per row
     int32_t int8;         // 1 = int8 codes + scale
+    int32_t values;       // 1 = packed VALUE cache: rows carry no mu word and there is no a / 1/a section
     int32_t nv;           // value words per row
     int32_t val0;         // index of the first value word in a row
     int32_t ndw;          // words per row (even)
@@ -58,6 +60,7 @@ static inline SPARK_HD SparkLayout spark_make_layout(int T, int int8, int batch,
     SparkLayout L;
     L.T = T;
     L.int8 = int8;
+    L.values = 0;
     L.nv = int8 ? (T + 3) / 4 : (T + 1) / 2;
     L.val0 = int8 ? 6 : 5;
     int ndw = L.val0 + L.nv;
@@ -75,6 +78,21 @@ static inline SPARK_HD SparkLayout spark_make_layout(int T, int int8, int batch,
     L.off_inva = L.off_a + apad;
     L.off_tiles = L.off_inva + apad;
     L.total_bytes = L.off_tiles + (int64_t)n_kv_heads * L.n_tiles * L.tile_bytes;
+    return L;
+}
+
+// Packed value cache (value-channel pruning): same tiles, rows [ m0 m1 m2 m3 | v0 ... v(nv-1) | pad ].
+static inline SPARK_HD SparkLayout spark_make_values_layout(int Tv, int n_kv_heads, int64_t total_tokens)
+{
+    SparkLayout L = spark_make_layout(Tv, 0, 0, n_kv_heads, total_tokens);
+    L.values = 1;
+    L.val0 = 4;
+    const int ndw = L.val0 + L.nv;
+    L.ndw = (ndw + 1) & ~1;
+    L.nq = L.ndw / 4;
+    L.tail2 = (L.ndw % 4) ? 1 : 0;
+    L.tile_bytes = SPARK_TILE_TOKENS * 4 * L.ndw;
+    L.total_bytes = L.off_tiles + (int64_t)n_kv_heads * L.n_tiles * L.tile_bytes;   // off_tiles = 256: batch = 0
     return L;
 }
 

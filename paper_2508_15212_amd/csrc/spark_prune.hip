@@ -165,7 +165,9 @@ __device__ __forceinline__ void prune_lds_sync()
 
 // FULL: the launch covers the tiles that hold all 64 tokens (the first total_tokens / 64 of every head);
 // otherwise it covers the one partly filled last tile of every head, one wavefront each.
-template <int INT8, bool FULL>
+// VALUES: the rows are value-cache rows (App. "Pruning Value Cache Channels"): the score of a channel is
+// |v| itself, there is no channel weight, no sequence bookkeeping and no statistic of the pruned set.
+template <int INT8, bool FULL, bool VALUES>
 __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     const uint16_t *__restrict__ k, int64_t k_tok_stride, int64_t k_head_stride,
     const int32_t *__restrict__ cu, uint8_t *__restrict__ packed, SparkLayout L)
@@ -194,18 +196,19 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
 
     // sequence of the first token: largest b with cu[b] <= n0 (skips empty sequences)
     int b = 0;
-    {
+    int seq_end_t = 0x7FFFFFFF;   // token index within the tile where the current sequence ends
+    // lane l owns channels 2l (low half of its 32-bit load) and 2l+1 (high half)
+    float2 a01 = make_float2(1.0f, 1.0f);
+    if constexpr (!VALUES) {
         int lo = 0, hi = B;     // invariant: cu[lo] <= n0 < cu[hi]
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
             if (cu[mid] <= n0) lo = mid; else hi = mid;
         }
         b = lo;
+        seq_end_t = (int)((int64_t)cu[b + 1] - n0);   // total < 2^31
+        a01 = a_all[((int64_t)b * L.n_kv_heads + h) * (SPARK_D / 2) + lane];
     }
-    // tokens left in the current sequence counted from the tile's first token (total < 2^31)
-    int seq_end_t = (int)((int64_t)cu[b + 1] - n0);   // token index within the tile where the sequence ends
-    // lane l owns channels 2l (low half of its 32-bit load) and 2l+1 (high half)
-    float2 a01 = a_all[((int64_t)b * L.n_kv_heads + h) * (SPARK_D / 2) + lane];
 
     // Row addresses: a wave-uniform base (scalar registers) plus one 32-bit per-lane offset per row of
     // a block of PF rows, set up once; a block's eight loads then cost no address arithmetic.
@@ -276,7 +279,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
         for (int u = 0; u < PF; ++u) {
             const int t = tb + u;
             const uint32_t xx = x[u];
-            if (__builtin_expect(t >= seq_end_t, 0)) {    // rare: the tile crosses into the next non-empty sequence
+            if (!VALUES && __builtin_expect(t >= seq_end_t, 0)) {    // rare: the tile crosses into the next non-empty sequence
                 if (t < nvalid) {
                     do {
                         ++b;
@@ -374,8 +377,9 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
             // lane t keeps the ballots of token t
             write_lane4(e_lo, e_hi, o_lo, o_hi, (uint32_t)kb0, (uint32_t)(kb0 >> 32), (uint32_t)kb1,
                         (uint32_t)(kb1 >> 32), t);
-            ps[u] = (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
+            ps[u] = VALUES ? 0.0f : (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
         }
+        if constexpr (VALUES) return 0.0f;
         const float f01 = fold_pair<0xB1>(ps[0], ps[1], lane & 1);     // quad_perm [1,0,3,2]
         const float f23 = fold_pair<0xB1>(ps[2], ps[3], lane & 1);
         const float f45 = fold_pair<0xB1>(ps[4], ps[5], lane & 1);
@@ -392,11 +396,13 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
         const float fa = do_block(xa, tb);
         if (tb + 2 * PF < SPARK_TILE_TOKENS) load_block(xa, tb + 2 * PF);
         const float fb = do_block(xb, tb + PF);
-        // pruned-saliency sums of these 16 tokens: pair the two blocks, finish across the four rows
-        float s = fold_pair<0x128>(fa, fb, lane & 8);                  // row_ror 8
-        s += __shfl_xor(s, 16);
-        s += __shfl_xor(s, 32);
-        if ((lane >> 4) == (tb >> 4)) mureg = s;
+        if constexpr (!VALUES) {
+            // pruned-saliency sums of these 16 tokens: pair the two blocks, finish across the four rows
+            float s = fold_pair<0x128>(fa, fb, lane & 8);                  // row_ror 8
+            s += __shfl_xor(s, 16);
+            s += __shfl_xor(s, 32);
+            if ((lane >> 4) == (tb >> 4)) mureg = s;
+        }
     }
 
     // ---- row epilogue, lane = token
@@ -405,7 +411,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const bool valid = lane < nvalid;
     uint32_t *row = stage + (size_t)lane * sw;
-    const float mu = (valid && T < SPARK_D) ? (mureg / (float)(SPARK_D - T)) : 0.0f;
+    const float mu = (!VALUES && valid && T < SPARK_D) ? (mureg / (float)(SPARK_D - T)) : 0.0f;
     // channel-ordered mask: bit 2l of the row = even ballot bit l, bit 2l+1 = odd ballot bit l.
     // Rows past the last token carry a well-formed mask (channels 0..T-1) and zero values, so a
     // reader that walks exactly T bits never runs off the mask.
@@ -414,9 +420,9 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     row[1] = valid ? (spread16(e_lo >> 16) | (spread16(o_lo >> 16) << 1)) : low_bits(T - 32);
     row[2] = valid ? (spread16(e_hi) | (spread16(o_hi) << 1)) : low_bits(T - 64);
     row[3] = valid ? (spread16(e_hi >> 16) | (spread16(o_hi >> 16) << 1)) : low_bits(T - 96);
-    row[4] = __float_as_uint(mu);
+    if (!VALUES) row[4] = __float_as_uint(mu);
     if (!valid) {
-        for (int d = 5; d < sw; ++d) row[d] = 0u;
+        for (int d = VALUES ? 4 : 5; d < sw; ++d) row[d] = 0u;
     } else {
         const int vend = L.val0 + (T + 1) / 2;               // one past the last staged bf16 word
         if (T & 1) row[vend - 1] &= 0xFFFFu;                 // unused upper half of the last word
@@ -489,7 +495,7 @@ __global__ void spark_unpack_kernel(const uint8_t *__restrict__ packed, SparkLay
     };
     if (mask_out)
         for (int m = 0; m < 4; ++m) mask_out[idx * 4 + m] = word(m);
-    if (mu_out) mu_out[idx] = __uint_as_float(word(4));
+    if (mu_out && !L.values) mu_out[idx] = __uint_as_float(word(4));
     if (L.int8) {
         if (scale_out) scale_out[idx] = __uint_as_float(word(5));
         if (vals_out) {
@@ -505,13 +511,13 @@ __global__ void spark_unpack_kernel(const uint8_t *__restrict__ packed, SparkLay
 
 // ---------------------------------------------------------------- host-side launch
 
-hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
-                        const int32_t *cu, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st)
+namespace {
+
+// the tiles that hold 64 tokens, then (if the token count is not a multiple of 64) each head's last tile
+template <bool VALUES>
+hipError_t launch_tiles(const uint16_t *x, int64_t tok_stride, int64_t head_stride, const int32_t *cu,
+                        uint8_t *packed, const SparkLayout &L, hipStream_t st)
 {
-    hipLaunchKernelGGL(spark_window_stat_kernel, dim3(L.batch * L.n_kv_heads), dim3(((Hq / L.n_kv_heads) < 8 ? (Hq / L.n_kv_heads) : 8) * SPARK_D), 0, st, qwin, Hq,
-                       L.n_kv_heads, W, packed, L);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     const size_t lds = spark_prune_lds_bytes(L);
     auto launch = [&](auto kern, int64_t waves) -> hipError_t {
         if (waves == 0) return hipSuccess;
@@ -521,16 +527,52 @@ hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_
             if (e2 != hipSuccess) return e2;
         }
         const int nblocks = (int)((waves + kPruneWaves - 1) / kPruneWaves);
-        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(kPruneWaves * 64), lds, st, k, k_tok_stride, k_head_stride, cu,
+        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(kPruneWaves * 64), lds, st, x, tok_stride, head_stride, cu,
                            packed, L);
         return hipGetLastError();
     };
-    // the tiles that hold 64 tokens, then (if the token count is not a multiple of 64) each head's last tile
     const int64_t full_waves = (L.total_tokens / SPARK_TILE_TOKENS) * L.n_kv_heads;
     const int64_t tail_waves = (L.total_tokens % SPARK_TILE_TOKENS) ? L.n_kv_heads : 0;
-    e = L.int8 ? launch(&spark_prune_kernel<1, true>, full_waves) : launch(&spark_prune_kernel<0, true>, full_waves);
+    hipError_t e = L.int8 ? launch(&spark_prune_kernel<1, true, VALUES>, full_waves)
+                          : launch(&spark_prune_kernel<0, true, VALUES>, full_waves);
     if (e != hipSuccess) return e;
-    return L.int8 ? launch(&spark_prune_kernel<1, false>, tail_waves) : launch(&spark_prune_kernel<0, false>, tail_waves);
+    return L.int8 ? launch(&spark_prune_kernel<1, false, VALUES>, tail_waves)
+                  : launch(&spark_prune_kernel<0, false, VALUES>, tail_waves);
+}
+
+__global__ void spark_values_header_kernel(uint8_t *packed, SparkLayout L)
+{
+    const int j = threadIdx.x;
+    uint32_t v = 0;
+    if (j == 0) v = SPARK_MAGIC;
+    if (j == 1) v = (uint32_t)L.T;
+    if (j == 4) v = (uint32_t)L.n_kv_heads;
+    if (j == 5) v = (uint32_t)L.total_tokens;
+    if (j == 6) v = (uint32_t)L.ndw;
+    if (j == 7) v = 1u;   // value cache
+    reinterpret_cast<uint32_t *>(packed)[j] = v;
+}
+
+}  // namespace
+
+hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
+                        const int32_t *cu, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st)
+{
+    hipLaunchKernelGGL(spark_window_stat_kernel, dim3(L.batch * L.n_kv_heads),
+                       dim3(((Hq / L.n_kv_heads) < 8 ? (Hq / L.n_kv_heads) : 8) * SPARK_D), 0, st, qwin, Hq,
+                       L.n_kv_heads, W, packed, L);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_tiles<false>(k, k_tok_stride, k_head_stride, cu, packed, L, st);
+}
+
+hipError_t launch_prune_values(const uint16_t *v, int64_t v_tok_stride, int64_t v_head_stride, uint8_t *packed,
+                               const SparkLayout &L, hipStream_t st)
+{
+    hipLaunchKernelGGL(spark_values_header_kernel, dim3(1), dim3(64), 0, st, packed, L);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_tiles<true>(v, v_tok_stride, v_head_stride, nullptr, packed, L, st);
 }
 
 hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *mask_out, void *vals_out,
