@@ -175,6 +175,21 @@ spark_status spark_prune_values(const spark_desc *desc, const void *v_bf16, void
                                 void *hip_stream);
 
 /*
+ * One decode step of attention over the packed key cache AND the packed value cache.
+ * [Sec. "SparK", Channel Recovery, for the scores, as in spark_decode_attn; App. "Pruning Value Cache
+ *  Channels" for the values: a pruned value entry contributes 0 to the weighted sum]
+ *
+ *   out[b,g,:] = sum_n softmax_n(s[g,:])[n] * Vtilde[n,h,:],  Vtilde[n,h,j] = V[n,h,j] if kept_v else 0
+ *
+ * Arguments as spark_decode_attn, with `packed_v` (written by spark_prune_values with the same
+ * n_kv_heads / keep_v / total_tokens) in place of the dense values; desc->pack_dtype must be
+ * SPARK_PACK_BF16.  Workspace and split count are those of spark_decode_attn.
+ */
+spark_status spark_decode_attn_values(const spark_desc *desc, const void *q_bf16, const void *packed,
+                                      const void *packed_v, const int32_t *cu_seqlens, void *out,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Canonical export of a packed value cache (parity tests and debugging).  Either output may be NULL.
  *   mask_out  uint32 [total_tokens, n_kv_heads, 4]       bit j%32 of word j/32 = channel j kept
  *   vals_out  uint16 [total_tokens, n_kv_heads, keep_v]  kept entries (bf16 bits), ascending channel

@@ -19,7 +19,7 @@ OUT_BF16, OUT_F32 = 0, 1
 
 EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspace", "spark_decode_workspace_init", "spark_decode_splits",
            "spark_prune", "spark_decode_attn", "spark_unpack", "spark_probe_read", "spark_status_string",
-           "spark_packed_values_bytes", "spark_prune_values", "spark_unpack_values"]
+           "spark_packed_values_bytes", "spark_prune_values", "spark_unpack_values", "spark_decode_attn_values"]
 
 
 class SparkError(RuntimeError):
@@ -78,6 +78,8 @@ def load() -> ctypes.CDLL:
     lib.spark_packed_values_bytes.argtypes = [dp]
     lib.spark_prune_values.restype = ctypes.c_int
     lib.spark_prune_values.argtypes = [dp, vp, vp, vp]
+    lib.spark_decode_attn_values.restype = ctypes.c_int
+    lib.spark_decode_attn_values.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.spark_unpack_values.restype = ctypes.c_int
     lib.spark_unpack_values.argtypes = [dp, vp, vp, vp, vp]
     lib.spark_probe_read.restype = ctypes.c_int
@@ -150,6 +152,14 @@ def prune_values(desc: SparkDesc, v: torch.Tensor, packed_v: torch.Tensor) -> No
     """spark_prune_values: v bf16-bit tensor on the device; packed_v a uint8 buffer of packed_values_bytes()."""
     rc = load().spark_prune_values(ctypes.byref(desc), _ptr(v), _ptr(packed_v), _stream())
     _check(rc, "spark_prune_values")
+
+
+def decode_attn_values(desc: SparkDesc, q: torch.Tensor, packed: torch.Tensor, packed_v: torch.Tensor,
+                       cu: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor) -> None:
+    rc = load().spark_decode_attn_values(ctypes.byref(desc), _ptr(q), _ptr(packed), _ptr(packed_v), _ptr(cu),
+                                         _ptr(out), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "spark_decode_attn_values")
 
 
 def unpack_values(desc: SparkDesc, packed_v: torch.Tensor, mask=None, vals=None) -> None:

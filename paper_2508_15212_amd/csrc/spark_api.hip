@@ -211,19 +211,30 @@ spark_status spark_unpack_values(const spark_desc *desc, const void *packed_v, u
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }
 
-spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const void *packed, const void *v_bf16,
-                               const int32_t *cu_seqlens, void *out, void *workspace, size_t workspace_bytes,
-                               void *hip_stream)
+namespace {
+
+spark_status decode_common(const spark_desc *desc, const void *q_bf16, const void *packed, const void *v_bf16,
+                           const void *packed_v, const int32_t *cu_seqlens, void *out, void *workspace,
+                           size_t workspace_bytes, void *hip_stream)
 {
     spark_status why;
     if (!desc_ok(desc, &why)) return why;
-    if (!q_bf16 || !packed || !v_bf16 || !cu_seqlens || !out || !workspace) return SPARK_ERR_INVALID_ARG;
-    if (!strides_ok(desc->v_token_stride, desc->v_head_stride)) return SPARK_ERR_INVALID_ARG;
-    if (!aligned(v_bf16, 16) || !aligned(packed, 256) || !aligned(workspace, 16) || !aligned(q_bf16, 2) ||
-        !aligned(out, 4))
+    if (!q_bf16 || !packed || !cu_seqlens || !out || !workspace) return SPARK_ERR_INVALID_ARG;
+    if (packed_v) {
+        if (desc->keep_v < 1) return SPARK_ERR_INVALID_ARG;
+        if (desc->pack_dtype != SPARK_PACK_BF16) return SPARK_ERR_UNSUPPORTED;
+        if (!aligned(packed_v, 256)) return SPARK_ERR_INVALID_ARG;
+    } else {
+        if (!v_bf16) return SPARK_ERR_INVALID_ARG;
+        if (!strides_ok(desc->v_token_stride, desc->v_head_stride)) return SPARK_ERR_INVALID_ARG;
+        if (!aligned(v_bf16, 16)) return SPARK_ERR_INVALID_ARG;
+    }
+    if (!aligned(packed, 256) || !aligned(workspace, 16) || !aligned(q_bf16, 2) || !aligned(out, 4))
         return SPARK_ERR_INVALID_ARG;
     if (workspace_bytes < spark_decode_workspace(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
     const SparkLayout L = layout_of(desc);
+    SparkLayout Lv = L;
+    if (packed_v) Lv = values_layout_of(desc);
     const int nsplit = pick_splits(desc);
     const size_t slots = (size_t)desc->batch * desc->n_q_heads * nsplit;
     float *part_acc = static_cast<float *>(workspace);
@@ -232,10 +243,31 @@ spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const
     const float scale = desc->softmax_scale != 0.0f ? desc->softmax_scale : 1.0f / sqrtf((float)SPARK_D);
     const hipError_t e = spark::launch_decode_attn(
         static_cast<const uint16_t *>(q_bf16), static_cast<const uint8_t *>(packed),
-        static_cast<const uint16_t *>(v_bf16), desc->v_token_stride, desc->v_head_stride, cu_seqlens, part_acc,
-        part_ml, counters, desc->n_q_heads, nsplit, scale, L, out, desc->out_dtype == SPARK_OUT_F32,
+        static_cast<const uint16_t *>(v_bf16), desc->v_token_stride, desc->v_head_stride,
+        static_cast<const uint8_t *>(packed_v), packed_v ? &Lv : nullptr, cu_seqlens, part_acc, part_ml, counters,
+        desc->n_q_heads, nsplit, scale, L, out, desc->out_dtype == SPARK_OUT_F32,
         static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
+}
+
+}  // namespace
+
+spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const void *packed, const void *v_bf16,
+                               const int32_t *cu_seqlens, void *out, void *workspace, size_t workspace_bytes,
+                               void *hip_stream)
+{
+    if (!v_bf16) return SPARK_ERR_INVALID_ARG;
+    return decode_common(desc, q_bf16, packed, v_bf16, nullptr, cu_seqlens, out, workspace, workspace_bytes,
+                         hip_stream);
+}
+
+spark_status spark_decode_attn_values(const spark_desc *desc, const void *q_bf16, const void *packed,
+                                      const void *packed_v, const int32_t *cu_seqlens, void *out, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream)
+{
+    if (!packed_v) return SPARK_ERR_INVALID_ARG;
+    return decode_common(desc, q_bf16, packed, nullptr, packed_v, cu_seqlens, out, workspace, workspace_bytes,
+                         hip_stream);
 }
 
 spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *mask_out, void *vals_out,

@@ -17,6 +17,9 @@
 //      query heads, K = tokens), split into a high and a low bf16 part so P keeps ~16
 //      significant bits; V rows are read 16 bytes per lane, transposed in registers with
 //      byte permutes into B operands (K = tokens, N = channels) and accumulated in float32.
+// With a channel-pruned VALUE cache (App. "Pruning Value Cache Channels": pruned entries are dropped, i.e.
+// contribute 0) step 3 reads packed value rows instead: lane = token walks its row's mask and scatters the
+// kept entries into a zero-filled dense [channel][token] bf16 tile in LDS, which then feeds the same MFMAs.
 // Split partials (m, l, unnormalised output) go to the workspace; the block that arrives last at
 // its (batch, KV head) counter merges them and writes the output, so one launch does the step.
 #include <hip/hip_runtime.h>
@@ -34,7 +37,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct DecodeParams {
     const uint16_t *q;       // [B, Hq, 128] bf16
     const uint8_t *packed;   // packed key cache
-    const uint16_t *v;       // dense values
+    const uint16_t *v;       // dense values (NULL when the value cache is packed)
+    const uint8_t *packed_v; // packed value cache (value-channel pruning), else NULL
+    SparkLayout Lv;          // its layout
     int64_t v_tok_stride, v_head_stride;
     const int32_t *cu;       // [B+1]
     float *part_acc;         // [B*Hq*nsplit][128]
@@ -101,9 +106,14 @@ constexpr int decode_min_blocks(int, int) { return 2; }
 // The cache is read once per step: the streaming loads carry the non-temporal hint so they do not
 // displace each other in the L2 / memory-side cache (measured: 129 us -> 118 us on the 32K workload).
 #define NT_LOAD(p) __builtin_nontemporal_load(p)
-template <int G, int TCT, int INT8>
+// TVC: 0 = dense values; > 0 = packed values with that many kept channels per row (row held in registers);
+// -1 = packed values, any count (row words read from memory as they are needed).
+template <int G, int TCT, int INT8, int TVC>
 __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void spark_decode_kernel(DecodeParams P)
 {
+    constexpr bool PV = (TVC != 0);             // packed value cache
+    constexpr int NVW = PV ? (TVC > 0 ? (((4 + (TVC + 1) / 2) + 1) & ~1) : 4) : 1;   // value-row words in registers
+    constexpr int VTILE = SPARK_D * SPARK_TILE_TOKENS * 2;   // dense bf16 tile [channel][token] in LDS
     constexpr int GP = ((G + 1 + 3) / 4) * 4;   // floats per table entry: G queries, 1/a, pad
     constexpr int VAL0 = INT8 ? 6 : 5;
     constexpr int NV_CT = INT8 ? (TCT + 3) / 4 : (TCT + 1) / 2;
@@ -113,7 +123,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     __shared__ __align__(16) float qtab[SPARK_D * GP];
     __shared__ float Rsh[16];
     __shared__ __align__(16) uint16_t Pbuf[kDecodeWaves][2][G][64];
-    __shared__ __align__(16) float red_acc[kDecodeWaves][G][SPARK_D];
+    // per wavefront: the dense value tile (packed values), reused for the accumulators at the end
+    constexpr int BIG = PV ? VTILE : G * SPARK_D * 4;
+    __shared__ __align__(16) uint8_t big[kDecodeWaves][BIG];
     __shared__ float red_m[kDecodeWaves][G], red_l[kDecodeWaves][G];
     __shared__ int last_flag;
 
@@ -150,7 +162,12 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     // index i, token 32*ks + 4*i + tg' (the same order in which V rows are fetched)
     const int ppos = (lane & 32) | ((lane & 3) << 3) | ((lane & 31) >> 2);
     const uint8_t *tiles = P.packed + L.off_tiles + (int64_t)h * L.n_tiles * L.tile_bytes;
-    const uint16_t *vbase = P.v + (int64_t)h * P.v_head_stride + cn * 8;
+    const uint16_t *vbase = PV ? nullptr : P.v + (int64_t)h * P.v_head_stride + cn * 8;
+    const SparkLayout &Lv = P.Lv;
+    const uint8_t *vtiles = PV ? P.packed_v + Lv.off_tiles + (int64_t)h * Lv.n_tiles * Lv.tile_bytes : nullptr;
+    uint8_t *dense = big[wave];
+    // this lane's token inside a dense row: 16-byte chunk ppos / 8 (XOR-swizzled by channel), then 2 bytes per token
+    const uint32_t cbase = (uint32_t)(((ppos >> 3) << 4) | ((ppos & 7) << 1));
 
     constexpr int NR = TCT ? NDW_CT : 6;    // row words held in registers
     auto load_row = [&](int tile, uint32_t (&r)[NR]) {
@@ -173,9 +190,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     };
     // half a tile of V: lane (tg, cn) takes 16 bytes (channels 8cn..8cn+7) of rows 4i + tg, so that
     // one load instruction of the wavefront covers 4 consecutive rows (1 KB when rows are contiguous)
-    auto load_v = [&](int tile, int ks, uint4 (&vh)[8]) {
+    auto load_v = [&](int tile, int ks, uint4 (&vh)[PV ? 1 : 8]) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < (PV ? 0 : 8); ++i) {
             int n = tile * SPARK_TILE_TOKENS + 32 * ks + 4 * i + tg;
             n = (n < s0) ? s0 : n;
             n = (n > s1 - 1) ? (s1 - 1) : n;     // rows outside the sequence get p = 0
@@ -184,11 +201,31 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         }
     };
 
+    // packed value row of this lane's token: mask words, then the kept entries (coalesced sections as for keys)
+    auto load_vrow = [&](int tile, uint32_t (&r)[NVW]) {
+        const uint8_t *tp = vtiles + (int64_t)tile * Lv.tile_bytes;
+        if (TVC > 0) {
+#pragma unroll
+            for (int qd = 0; qd < NVW / 4; ++qd) {
+                const u32x4 x = NT_LOAD(reinterpret_cast<const u32x4 *>(tp + qd * 1024 + lane * 16));
+                r[4 * qd + 0] = x.x; r[4 * qd + 1] = x.y; r[4 * qd + 2] = x.z; r[4 * qd + 3] = x.w;
+            }
+            if (NVW % 4) {
+                const uint2 x = *reinterpret_cast<const uint2 *>(tp + (NVW / 4) * 1024 + lane * 8);
+                r[4 * (NVW / 4) + 0] = x.x; r[4 * (NVW / 4) + 1] = x.y;
+            }
+        } else {
+            const u32x4 x = NT_LOAD(reinterpret_cast<const u32x4 *>(tp + lane * 16));   // the mask
+            r[0] = x.x; r[1] = x.y; r[2] = x.z; r[3] = x.w;
+        }
+    };
+
     // A wavefront keeps one tile in flight: the loads of tile i+1 are issued when tile i is done.
     // (Requesting further ahead was measured slower: more outstanding requests per wavefront cost
     // more in DRAM efficiency than the extra overlap gained.)
     uint32_t rn[NR];
-    uint4 vr[2][8];
+    uint4 vr[2][PV ? 1 : 8];
+    uint32_t vrow[NVW];
     // Tiles are visited in rotated order, a different rotation per block.  The order does not
     // matter to the running softmax, and it keeps the blocks (whose V chunks start at large
     // power-of-two distances) from sweeping the memory channels in lockstep.
@@ -199,8 +236,12 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     int tile = tile_of(kidx);
     if (kidx < nts) {
         load_row(tile, rn);
-        load_v(tile, 0, vr[0]);
-        load_v(tile, 1, vr[1]);
+        if constexpr (PV) {
+            load_vrow(tile, vrow);
+        } else {
+            load_v(tile, 0, vr[0]);
+            load_v(tile, 1, vr[1]);
+        }
     }
     // (the first tile's loads are already in flight while the table is built)
     // ---- per-step query prep: table {q_g[j] * scale * log2e, 1/a[j]} and R_g
@@ -340,39 +381,106 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         }
         wave_lds_sync();
 
-        // ---- P V on the matrix cores
+        if constexpr (PV) {
+            // ---- packed values: zero the dense tile, scatter this token's kept entries into it
+            {
+                const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            uint4 ah = {0, 0, 0, 0}, alo = {0, 0, 0, 0};
-            if (cn < G) {
-                ah = *reinterpret_cast<const uint4 *>(&Pbuf[wave][0][cn][32 * ks + 8 * tg]);
-                alo = *reinterpret_cast<const uint4 *>(&Pbuf[wave][1][cn][32 * ks + 8 * tg]);
+                for (int i = 0; i < VTILE / (64 * 16); ++i)
+                    *reinterpret_cast<u32x4 *>(dense + (i * 64 + lane) * 16) = z;
             }
-            const bf16x8 A_hi = __builtin_bit_cast(bf16x8, ah);
-            const bf16x8 A_lo = __builtin_bit_cast(bf16x8, alo);
-            // 8x8 transpose of this lane's (token, channel) block: B operand e = channel 8cn+e, K = tokens
-            u32x4 bop[8];
+            wave_lds_sync();
+            {
+                uint64_t cur = ((uint64_t)vrow[1] << 32) | vrow[0];
+                const uint64_t upper = ((uint64_t)vrow[3] << 32) | vrow[2];
+                const int clo = __popc(vrow[0]) + __popc(vrow[1]);
+                int jb = 0;
+                auto next_vchannel = [&](int i) {
+                    const bool sw = (i == clo);          // first entry of channels 64..127
+                    cur = sw ? upper : cur;
+                    jb = sw ? 64 : jb;
+                    const int j = (__builtin_ctzll((unsigned long long)cur) + jb) & (SPARK_D - 1);
+                    cur &= cur - 1;
+                    return j;
+                };
+                auto put = [&](int j, uint16_t val) {
+                    *reinterpret_cast<uint16_t *>(dense + j * 128 + (cbase ^ (uint32_t)((j & 7) << 4))) = val;
+                };
+                if (TVC > 0) {
 #pragma unroll
-            for (int cp = 0; cp < 4; ++cp)
-#pragma unroll
-                for (int tp2 = 0; tp2 < 4; ++tp2) {
-                    const uint32_t x = u4c(vr[ks][2 * tp2], cp);
-                    const uint32_t y = u4c(vr[ks][2 * tp2 + 1], cp);
-                    bop[2 * cp][tp2] = __builtin_amdgcn_perm(y, x, 0x05040100u);       // low halves  (x | y << 16)
-                    bop[2 * cp + 1][tp2] = __builtin_amdgcn_perm(y, x, 0x07060302u);   // high halves
+                    for (int i = 0; i < TVC; ++i) {
+                        const uint32_t w = vrow[4 + i / 2];
+                        put(next_vchannel(i), (i & 1) ? (uint16_t)(w >> 16) : (uint16_t)w);
+                    }
+                } else {
+                    const uint8_t *vtp = vtiles + (int64_t)tile * Lv.tile_bytes;
+                    uint32_t w = 0;
+                    for (int i = 0; i < Lv.T; ++i) {
+                        if ((i & 1) == 0)
+                            w = *reinterpret_cast<const uint32_t *>(vtp + spark_tile_word_offset(Lv, lane, 4 + i / 2));
+                        put(next_vchannel(i), (i & 1) ? (uint16_t)(w >> 16) : (uint16_t)w);
+                    }
                 }
+            }
+            wave_lds_sync();
+            // ---- P V on the matrix cores: B operand e = channel 16e + cn, K = 8 tokens of one chunk
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const bf16x8 B = __builtin_bit_cast(bf16x8, bop[e]);
-                acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_hi, B, acc[e], 0, 0, 0);
-                acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_lo, B, acc[e], 0, 0, 0);
+            for (int ks = 0; ks < 2; ++ks) {
+                uint4 ah = {0, 0, 0, 0}, alo = {0, 0, 0, 0};
+                if (cn < G) {
+                    ah = *reinterpret_cast<const uint4 *>(&Pbuf[wave][0][cn][32 * ks + 8 * tg]);
+                    alo = *reinterpret_cast<const uint4 *>(&Pbuf[wave][1][cn][32 * ks + 8 * tg]);
+                }
+                const bf16x8 A_hi = __builtin_bit_cast(bf16x8, ah);
+                const bf16x8 A_lo = __builtin_bit_cast(bf16x8, alo);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint4 bv = *reinterpret_cast<const uint4 *>(
+                        dense + (16 * e + cn) * 128 + (((4 * ks + tg) ^ (cn & 7)) << 4));
+                    const bf16x8 B = __builtin_bit_cast(bf16x8, bv);
+                    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_hi, B, acc[e], 0, 0, 0);
+                    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_lo, B, acc[e], 0, 0, 0);
+                }
+            }
+        } else {
+            // ---- P V on the matrix cores
+    #pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                uint4 ah = {0, 0, 0, 0}, alo = {0, 0, 0, 0};
+                if (cn < G) {
+                    ah = *reinterpret_cast<const uint4 *>(&Pbuf[wave][0][cn][32 * ks + 8 * tg]);
+                    alo = *reinterpret_cast<const uint4 *>(&Pbuf[wave][1][cn][32 * ks + 8 * tg]);
+                }
+                const bf16x8 A_hi = __builtin_bit_cast(bf16x8, ah);
+                const bf16x8 A_lo = __builtin_bit_cast(bf16x8, alo);
+                // 8x8 transpose of this lane's (token, channel) block: B operand e = channel 8cn+e, K = tokens
+                u32x4 bop[8];
+    #pragma unroll
+                for (int cp = 0; cp < 4; ++cp)
+    #pragma unroll
+                    for (int tp2 = 0; tp2 < 4; ++tp2) {
+                        const uint32_t x = u4c(vr[ks][2 * tp2], cp);
+                        const uint32_t y = u4c(vr[ks][2 * tp2 + 1], cp);
+                        bop[2 * cp][tp2] = __builtin_amdgcn_perm(y, x, 0x05040100u);       // low halves  (x | y << 16)
+                        bop[2 * cp + 1][tp2] = __builtin_amdgcn_perm(y, x, 0x07060302u);   // high halves
+                    }
+    #pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bf16x8 B = __builtin_bit_cast(bf16x8, bop[e]);
+                    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_hi, B, acc[e], 0, 0, 0);
+                    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_lo, B, acc[e], 0, 0, 0);
+                }
             }
         }
         wave_lds_sync();   // P buffer is rewritten by the next tile
         if (more) {   // request the next tile; its latency is covered by the other resident wavefronts
             load_row(tnext, rn);
-            load_v(tnext, 0, vr[0]);
-            load_v(tnext, 1, vr[1]);
+            if constexpr (PV) {
+                load_vrow(tnext, vrow);
+            } else {
+                load_v(tnext, 0, vr[0]);
+                load_v(tnext, 1, vr[1]);
+            }
         }
     }
 
@@ -383,12 +491,17 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         if (lane == 0) { red_m[wave][g] = m[g]; red_l[wave][g] = lt; }
     }
     // accumulator layout: lane (tg, cn), register rr of acc[e] = head 4*tg + rr, channel 8*cn + e
+    // (dense values) or 16*e + cn (packed values)
+    wave_lds_sync();   // the dense value tile of this wavefront is no longer read
+    auto red_acc = [&](int w, int g, int ch) -> float & {
+        return reinterpret_cast<float *>(big[w])[g * SPARK_D + ch];
+    };
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
         const int g = 4 * tg + rr;
         if (g < G) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) red_acc[wave][g][8 * cn + e] = acc[e][rr];
+            for (int e = 0; e < 8; ++e) red_acc(wave, g, PV ? (16 * e + cn) : (8 * cn + e)) = acc[e][rr];
         }
     }
     __syncthreads();
@@ -403,7 +516,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         for (int w = 0; w < kDecodeWaves; ++w) {
             const float f = fast_exp2(red_m[w][g] - Ms);
             Lsum = fmaf(red_l[w][g], f, Lsum);
-            A = fmaf(red_acc[w][g][ch], f, A);
+            A = fmaf(red_acc(w, g, ch), f, A);
         }
         const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nsplit + split;
         st_agent(&P.part_acc[slot * SPARK_D + ch], A);
@@ -490,30 +603,49 @@ __global__ void spark_zero_kernel(uint32_t *p, int n)
 
 // ---------------------------------------------------------------- host-side launch
 
-template <int G, int TCT, int INT8>
+template <int G, int TCT, int INT8, int TVC>
 static hipError_t launch_one(const DecodeParams &P, int nblocks, hipStream_t st)
 {
-    hipLaunchKernelGGL((spark_decode_kernel<G, TCT, INT8>), dim3(nblocks), dim3(kDecodeWaves * 64), 0, st, P);
+    hipLaunchKernelGGL((spark_decode_kernel<G, TCT, INT8, TVC>), dim3(nblocks), dim3(kDecodeWaves * 64), 0, st, P);
     return hipGetLastError();
+}
+
+// packed values: row lengths 64 / 38 / 26 with the row in registers, anything else generic
+template <int G, int TCT>
+static hipError_t launch_pv(const DecodeParams &P, int nblocks, hipStream_t st)
+{
+    switch (P.Lv.T) {
+        case 64: return launch_one<G, TCT, 0, 64>(P, nblocks, st);
+        case 38: return launch_one<G, TCT, 0, 38>(P, nblocks, st);
+        case 26: return launch_one<G, TCT, 0, 26>(P, nblocks, st);
+        default: return launch_one<G, TCT, 0, -1>(P, nblocks, st);
+    }
 }
 
 template <int G>
 static hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
 {
     const int T = P.L.T;
-    if (P.L.int8) {
-        if (T == 26) return launch_one<G, 26, 1>(P, nblocks, st);
-        return launch_one<G, 0, 1>(P, nblocks, st);
+    if (P.packed_v) {
+        if (P.L.int8) return hipErrorInvalidValue;   // (the host rejects this combination before it gets here)
+        if (T == 26) return launch_pv<G, 26>(P, nblocks, st);
+        if (T == 64) return launch_pv<G, 64>(P, nblocks, st);
+        return launch_pv<G, 0>(P, nblocks, st);
     }
-    if (T == 26) return launch_one<G, 26, 0>(P, nblocks, st);
-    if (T == 25) return launch_one<G, 25, 0>(P, nblocks, st);
-    if (T == 38) return launch_one<G, 38, 0>(P, nblocks, st);
-    if (T == 64) return launch_one<G, 64, 0>(P, nblocks, st);
-    return launch_one<G, 0, 0>(P, nblocks, st);
+    if (P.L.int8) {
+        if (T == 26) return launch_one<G, 26, 1, 0>(P, nblocks, st);
+        return launch_one<G, 0, 1, 0>(P, nblocks, st);
+    }
+    if (T == 26) return launch_one<G, 26, 0, 0>(P, nblocks, st);
+    if (T == 25) return launch_one<G, 25, 0, 0>(P, nblocks, st);
+    if (T == 38) return launch_one<G, 38, 0, 0>(P, nblocks, st);
+    if (T == 64) return launch_one<G, 64, 0, 0>(P, nblocks, st);
+    return launch_one<G, 0, 0, 0>(P, nblocks, st);
 }
 
 hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const uint16_t *v, int64_t v_tok_stride,
-                              int64_t v_head_stride, const int32_t *cu, float *part_acc, float *part_ml,
+                              int64_t v_head_stride, const uint8_t *packed_v, const SparkLayout *Lv,
+                              const int32_t *cu, float *part_acc, float *part_ml,
                               uint32_t *counters, int Hq, int nsplit, float softmax_scale, const SparkLayout &L,
                               void *out, int out_f32, hipStream_t st)
 {
@@ -521,6 +653,8 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.q = q;
     P.packed = packed;
     P.v = v;
+    P.packed_v = packed_v;
+    P.Lv = Lv ? *Lv : L;
     P.v_tok_stride = v_tok_stride;
     P.v_head_stride = v_head_stride;
     P.cu = cu;

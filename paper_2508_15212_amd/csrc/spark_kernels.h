@@ -19,9 +19,11 @@ hipError_t launch_prune_values(const uint16_t *v, int64_t v_tok_stride, int64_t 
 hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *mask_out, void *vals_out,
                          float *mu_out, float *scale_out, float *a_out, hipStream_t st);
 
-// q [B,Hq,128] bf16; the caller splits the workspace into part_acc / part_ml / counters
+// q [B,Hq,128] bf16; the caller splits the workspace into part_acc / part_ml / counters.
+// Values are either dense (v, strides; packed_v = NULL) or a packed value cache (packed_v, Lv; v = NULL).
 hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const uint16_t *v, int64_t v_tok_stride,
-                              int64_t v_head_stride, const int32_t *cu, float *part_acc, float *part_ml,
+                              int64_t v_head_stride, const uint8_t *packed_v, const SparkLayout *Lv,
+                              const int32_t *cu, float *part_acc, float *part_ml,
                               uint32_t *counters, int Hq, int nsplit, float softmax_scale, const SparkLayout &L,
                               void *out, int out_f32, hipStream_t st);
 

@@ -52,3 +52,68 @@ def test_value_selection_layouts_ties_zero_rows(layout):
     _, _, mask, vals = _prune_values_gpu(w, vbits, 48, layout)
     assert np.array_equal(mask, pv.mask)
     assert np.array_equal(vals, pv.kept)
+
+
+MAX_ABS, MEAN_ABS = 1e-2, 1e-3
+
+
+def _decode_kv_case(w, Tv, t=None, n_splits=0, layout="HND"):
+    """prune keys, prune values, decode over both packed caches; compare with the oracle."""
+    t = wl.generate(w) if t is None else t
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    pv = oracle.prune_values(t.v, t.layout, Tv)
+    ref = oracle.decode_literal(t.q, pr, oracle.expand_values(pv), "NHD", t.cu)
+
+    k = t.k if layout == "HND" else np.ascontiguousarray(t.k.transpose(1, 0, 2))
+    desc, packed_v, mask_v, vals_v = _prune_values_gpu(w, t.v, Tv, layout)
+    assert np.array_equal(mask_v, pv.mask) and np.array_equal(vals_v, pv.kept)
+    desc.n_splits = n_splits
+    dk, dqw, dq = to_dev(k), to_dev(t.qwin), to_dev(t.q)
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.empty(max(spark.packed_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    spark.prune(desc, dk, dqw, dcu, packed)
+    ws = spark.new_decode_workspace(desc)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    spark.decode_attn_values(desc, dq, packed, packed_v, dcu, out, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    err = np.abs(got.astype(np.float64) - ref)
+    print(f"{w.name} Tv={Tv}: decode max|err|={err.max():.3e} mean|err|={err.mean():.3e}")
+    assert np.all(np.isfinite(got))
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+    return got, ref
+
+
+@pytest.mark.parametrize("T,Tv", [(26, 64), (26, 38), (26, 26), (64, 64), (64, 38), (38, 64), (26, 100), (38, 77),
+                                  (26, 1), (64, 128), (128, 128)])
+def test_decode_over_pruned_keys_and_values(T, Tv):
+    _decode_kv_case(wl.small(name=f"kv{T}_{Tv}", keep=T, seqlens=(130, 321), seed=300 + T + Tv), Tv)
+
+
+@pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 2), (8, 2), (16, 1)])
+def test_decode_values_group_sizes(G, Hkv):
+    _decode_kv_case(wl.small(name=f"kv_gqa{G}", n_q_heads=G * Hkv, n_kv_heads=Hkv, keep=26, seqlens=(257, 64, 190),
+                             batch=3, seed=340 + G), 64)
+
+
+def test_decode_values_ragged_empty_single_and_layout():
+    w = wl.small(name="kv_ragged", batch=6, seqlens=(0, 1, 63, 64, 65, 0), keep=26, seed=360)
+    got, _ = _decode_kv_case(w, 64)
+    assert np.all(got[0] == 0) and np.all(got[5] == 0)
+    _decode_kv_case(wl.small(name="kv_nhd", seqlens=(333, 129), seed=361), 64, layout="NHD")
+
+
+@pytest.mark.parametrize("ns", [1, 3, 7])
+def test_decode_values_split_counts(ns):
+    _decode_kv_case(wl.small(name=f"kv_splits{ns}", batch=2, seqlens=(1500, 700), keep=26, seed=370), 64, n_splits=ns)
+
+
+def test_keep_all_values_equals_dense_value_decode():
+    """Tv = D stores every entry: the result must agree with the dense-value entry point."""
+    from tests.gpu_util import run_gpu_case
+    w = wl.small(name="kv_all", keep=26, seqlens=(300, 141), seed=380)
+    t = wl.generate(w)
+    got, _ = _decode_kv_case(w, 128, t=t)
+    dense = run_gpu_case(w, t, want_unpack=False, want_bf16=False)["out_f32"]
+    assert np.abs(got - dense).max() < 1e-5
