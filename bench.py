@@ -40,6 +40,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline metric)")
     ap.add_argument("--keep", type=int, default=0, help="override T")
     ap.add_argument("--int8", action="store_true", help="int8 storage of the kept entries")
+    ap.add_argument("--keep-v", type=int, default=0,
+                    help="also prune the value cache to this many channels per row (0 = values stay dense)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--copies", type=int, default=4, help="input copies rotated to defeat the 256 MB cache")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -81,6 +83,8 @@ def main() -> int:
     desc.k_token_stride = desc.v_token_stride = D
     desc.k_head_stride = desc.v_head_stride = total * D
     desc.n_splits = args.splits
+    desc.keep_v = args.keep_v
+    Tv = args.keep_v
 
     ncopy = max(1, args.copies)
     k0, v0 = dev(t.k), dev(t.v)
@@ -90,10 +94,24 @@ def main() -> int:
     cu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
     pbytes = spark.packed_bytes(desc)
     packs = [torch.empty(pbytes, dtype=torch.uint8, device="cuda") for _ in range(ncopy)]
+    packvs = ([torch.empty(spark.packed_values_bytes(desc), dtype=torch.uint8, device="cuda") for _ in range(ncopy)]
+              if Tv else None)
     ws = spark.new_decode_workspace(desc)
     out = torch.empty((w.batch, hq, D), dtype=torch.bfloat16, device="cuda")
-    for c in range(ncopy):
+
+    def prune_all(c):
         spark.prune(desc, ks[c], qwin, cu, packs[c])
+        if Tv:
+            spark.prune_values(desc, vs[c], packvs[c])
+
+    def decode(c, d=desc, o=out):
+        if Tv:
+            spark.decode_attn_values(d, q, packs[c], packvs[c], cu, o, ws)
+        else:
+            spark.decode_attn(d, q, packs[c], vs[c], cu, o, ws)
+
+    for c in range(ncopy):
+        prune_all(c)
     torch.cuda.synchronize()
 
     def step(i, ev=None):
@@ -101,10 +119,10 @@ def main() -> int:
         if ev is not None:
             ev[0].record()
         if not args.decode_only:
-            spark.prune(desc, ks[c], qwin, cu, packs[c])
+            prune_all(c)
         if ev is not None:
             ev[1].record()
-        spark.decode_attn(desc, q, packs[c], vs[c], cu, out, ws)
+        decode(c)
         if ev is not None:
             ev[2].record()
 
@@ -141,8 +159,11 @@ def main() -> int:
     row_bytes = (pbytes - 256 - 2 * ((w.batch * hkv * D * 4 + 255) // 256 * 256)) / (
         hkv * ((total + 63) // 64) * 64)
     k_row = (T + 16 + 4 + 4) if args.int8 else (2 * T + 16 + 4)      # kept entries + mask + mu (+ scale)
-    dec_alg_bytes = rows * (k_row + 2 * D)                            # packed K row + dense V row
+    v_row = (2 * Tv + 16) if Tv else 2 * D                            # kept entries + mask, or the dense row
+    dec_alg_bytes = rows * (k_row + v_row)                            # packed K row + V row
     prune_alg_bytes = rows * (2 * D + k_row) + w.batch * hq * w.window * D * 2
+    if Tv:
+        prune_alg_bytes += rows * (2 * D + v_row)
     dec_us = float(dec_ms.mean() * 1e3)
     prune_us = float(prune_ms.mean() * 1e3)
     dec_gbs = dec_alg_bytes / (dec_us * 1e-6) / 1e9
@@ -164,8 +185,10 @@ def main() -> int:
         "config": {
             "workload": w.name, "batch": w.batch, "n_q_heads": hq, "n_kv_heads": hkv, "head_dim": D,
             "context": int(w.seqlens.max()), "total_tokens": total, "keep": T, "window": w.window,
-            "pack": "int8" if args.int8 else "bf16", "splits": spark.decode_splits(desc),
-            "input_copies_rotated": ncopy, "seed": w.seed, "step": "spark_prune + spark_decode_attn",
+            "pack": "int8" if args.int8 else "bf16", "keep_v": Tv if Tv else None,
+            "splits": spark.decode_splits(desc),
+            "input_copies_rotated": ncopy, "seed": w.seed, "step": ("spark_prune + spark_prune_values + spark_decode_attn_values" if Tv
+                                                              else "spark_prune + spark_decode_attn"),
         },
         "decode": {"us_mean": round(dec_us, 2), "us_min": round(float(dec_ms.min() * 1e3), 2),
                    "us_median": round(float(np.median(dec_ms) * 1e3), 2),
@@ -178,7 +201,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": round(dec_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_DECODE_TRAFFIC_BYTES.get((w.name, "int8" if args.int8 else "bf16"))
-                     if not args.keep else None,
+                     if not (args.keep or Tv) else None,
                      "algorithmic_bytes": dec_alg_bytes,
                      "kernel": "spark_decode_kernel, HIP events around spark_decode_attn"},
         "stream_read_ceiling": {"GBps": round(probe_gbs, 1), "us": round(probe_us, 2),
@@ -199,7 +222,12 @@ def main() -> int:
         if args.int8:
             pr = oracle.quant_int8(pr)
         t1 = time.perf_counter()
-        ref = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
+        if Tv:
+            pv = oracle.prune_values(t.v, t.layout, Tv)
+            t1 = time.perf_counter()
+            ref = oracle.decode_literal(t.q, pr, oracle.expand_values(pv), "NHD", t.cu)
+        else:
+            ref = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
         t2 = time.perf_counter()
         result["cpu_baseline"] = {
             "value": round((t2 - t1) * 1e6, 0), "unit": "us/step (decode attention)", "cores": threads,
@@ -213,9 +241,13 @@ def main() -> int:
         desc32 = spark.SparkDesc.from_buffer_copy(desc)
         desc32.out_dtype = spark.OUT_F32
         out32 = torch.empty((w.batch, hq, D), dtype=torch.float32, device="cuda")
-        spark.decode_attn(desc32, q, packs[c], vs[c], cu, out32, ws)
+        decode(c, desc32, out32)
         torch.cuda.synchronize()
         err = np.abs(out32.cpu().numpy().astype(np.float64) - ref)
+        if Tv:
+            mask_v = torch.empty((total, hkv, 4), dtype=torch.int32, device="cuda")
+            spark.unpack_values(desc, packvs[c], mask_v, None)
+            result["value_masks_bit_exact"] = bool(np.array_equal(mask_v.cpu().numpy().view(np.uint32), pv.mask))
         result["parity"] = {"masks_bit_exact": bool(np.array_equal(mask.cpu().numpy().view(np.uint32), pr.mask)),
                             "near_tie_rows_gap_lt_1e-6": pr.near_ties(), "rows": int(rows),
                             "decode_max_abs_err": float(err.max()), "decode_mean_abs_err": float(err.mean())}
