@@ -18,8 +18,11 @@
 //      significant bits; V rows are read 16 bytes per lane, transposed in registers with
 //      byte permutes into B operands (K = tokens, N = channels) and accumulated in float32.
 // With a channel-pruned VALUE cache (App. "Pruning Value Cache Channels": pruned entries are dropped, i.e.
-// contribute 0) step 3 reads packed value rows instead: lane = token walks its row's mask and scatters the
-// kept entries into a zero-filled dense [channel][token] bf16 tile in LDS, which then feeds the same MFMAs.
+// contribute 0) step 3 reads packed value rows instead (lane = token, coalesced), parks them in LDS and
+// rebuilds the dense 16-byte pieces the MFMA path wants with lane = (token, group of 8 channels): the
+// group's mask byte and the number of kept entries before it locate a window of 8 candidates in the
+// packed row, and a 256-entry table of byte-permute selectors spreads the candidates to their channels
+// (zeros elsewhere).  The cost does not depend on how many entries a row keeps.
 // Split partials (m, l, unnormalised output) go to the workspace; the block that arrives last at
 // its (batch, KV head) counter merges them and writes the output, so one launch does the step.
 #include <hip/hip_runtime.h>
@@ -113,8 +116,12 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
 {
     constexpr bool PV = (TVC != 0);             // packed value cache
     constexpr int NVW = PV ? (TVC > 0 ? (((4 + (TVC + 1) / 2) + 1) & ~1) : 4) : 1;   // value-row words in registers
-    constexpr int VTILE = SPARK_D * SPARK_TILE_TOKENS * 2;   // dense bf16 tile [channel][token] in LDS
-    constexpr int GP = ((G + 1 + 3) / 4) * 4;   // floats per table entry: G queries, 1/a, pad
+    // LDS row stride (words) of a parked value row: >= the row, and = 4 mod 8 so that 16-byte row writes of
+    // consecutive tokens fall on different banks; a row kept whole in registers is NVW words, the longest is 68
+    constexpr int RSV = PV ? (TVC > 0 ? 8 * ((NVW + 3) / 8) + 4 : 68) : 1;
+    // floats per table entry: G queries, 1/a, pad -- a multiple of 4 (16-byte gathers) that is 4 mod 8, so
+    // that the entries of different channels start in all eight 16-byte bank groups, not in half of them
+    constexpr int GP = 8 * ((G + 1 + 3) / 8) + 4;
     constexpr int VAL0 = INT8 ? 6 : 5;
     constexpr int NV_CT = INT8 ? (TCT + 3) / 4 : (TCT + 1) / 2;
     constexpr int NDW_CT = (VAL0 + NV_CT + 1) & ~1;
@@ -123,9 +130,16 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     __shared__ __align__(16) float qtab[SPARK_D * GP];
     __shared__ float Rsh[16];
     __shared__ __align__(16) uint16_t Pbuf[kDecodeWaves][2][G][64];
-    // per wavefront: the dense value tile (packed values), reused for the accumulators at the end
-    constexpr int BIG = PV ? VTILE : G * SPARK_D * 4;
-    __shared__ __align__(16) uint8_t big[kDecodeWaves][BIG];
+    // per wavefront: the accumulators at the end; with packed values, before that, the parked value rows
+    // (+ slack: the candidate window may read 4 words past a row)
+    constexpr int RED_BYTES = G * SPARK_D * 4, RAW_BYTES = (SPARK_TILE_TOKENS * RSV + 8) * 4;
+    constexpr int WBUF = (PV && RAW_BYTES > RED_BYTES) ? RAW_BYTES : RED_BYTES;
+    __shared__ __align__(16) uint8_t wbuf[kDecodeWaves][WBUF];
+    // packed values: per token 16 x {kept entries before the group, the group's mask byte}; the selector
+    // table (12 words per entry, 6 used: the odd stride spreads the entries over the LDS banks)
+    constexpr int LUTW = 12;
+    __shared__ __align__(16) uint32_t vmeta[PV ? kDecodeWaves : 1][PV ? SPARK_TILE_TOKENS * 8 : 1];
+    __shared__ __align__(16) uint32_t vlut[PV ? 256 * LUTW : 1];
     __shared__ float red_m[kDecodeWaves][G], red_l[kDecodeWaves][G];
     __shared__ int last_flag;
 
@@ -165,9 +179,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     const uint16_t *vbase = PV ? nullptr : P.v + (int64_t)h * P.v_head_stride + cn * 8;
     const SparkLayout &Lv = P.Lv;
     const uint8_t *vtiles = PV ? P.packed_v + Lv.off_tiles + (int64_t)h * Lv.n_tiles * Lv.tile_bytes : nullptr;
-    uint8_t *dense = big[wave];
-    // this lane's token inside a dense row: 16-byte chunk ppos / 8 (XOR-swizzled by channel), then 2 bytes per token
-    const uint32_t cbase = (uint32_t)(((ppos >> 3) << 4) | ((ppos & 7) << 1));
+    const int rsv = (TVC > 0) ? RSV : 8 * ((Lv.ndw + 3) / 8) + 4;   // parked-row stride in words
 
     constexpr int NR = TCT ? NDW_CT : 6;    // row words held in registers
     auto load_row = [&](int tile, uint32_t (&r)[NR]) {
@@ -190,9 +202,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     };
     // half a tile of V: lane (tg, cn) takes 16 bytes (channels 8cn..8cn+7) of rows 4i + tg, so that
     // one load instruction of the wavefront covers 4 consecutive rows (1 KB when rows are contiguous)
-    auto load_v = [&](int tile, int ks, uint4 (&vh)[PV ? 1 : 8]) {
+    auto load_v = [&](int tile, int ks, uint4 (&vh)[8]) {
 #pragma unroll
-        for (int i = 0; i < (PV ? 0 : 8); ++i) {
+        for (int i = 0; i < 8; ++i) {
             int n = tile * SPARK_TILE_TOKENS + 32 * ks + 4 * i + tg;
             n = (n < s0) ? s0 : n;
             n = (n > s1 - 1) ? (s1 - 1) : n;     // rows outside the sequence get p = 0
@@ -224,7 +236,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     // (Requesting further ahead was measured slower: more outstanding requests per wavefront cost
     // more in DRAM efficiency than the extra overlap gained.)
     uint32_t rn[NR];
-    uint4 vr[2][PV ? 1 : 8];
+    uint4 vr[2][8];
     uint32_t vrow[NVW];
     // Tiles are visited in rotated order, a different rotation per block.  The order does not
     // matter to the running softmax, and it keeps the blocks (whose V chunks start at large
@@ -244,6 +256,36 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         }
     }
     // (the first tile's loads are already in flight while the table is built)
+    if constexpr (PV) {
+        // Selector table, entry b = mask byte of a group of 8 channels.  The group's kept entries are the
+        // first popcount(b) of a window of 8 candidates = 16 bytes Q0..Q3; output word o holds channels
+        // 2o, 2o+1.  A byte-permute picks from two words (selector 0-3: second operand, 4-7: first, 0x0C:
+        // zero): words 0, 1 need candidates 0..3 only -> one permute of (Q1, Q0); words 2, 3 may reach
+        // into Q2, Q3 -> the OR of a permute of (Q1, Q0) and one of (Q3, Q2).
+        const uint32_t bmask = (uint32_t)tid;
+        uint32_t sel[6];
+#pragma unroll
+        for (int k = 0; k < 6; ++k) sel[k] = 0x0C0C0C0Cu;
+        int rnk = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool on = (bmask >> e) & 1u;
+            const int o = e >> 1, sh = (e & 1) * 16;      // output word, bit position of its half
+            const int src = 2 * rnk;                       // candidate's first byte in the window
+            const uint32_t two = (uint32_t)((src & 7) | (((src & 7) + 1) << 8)) << sh;
+            const uint32_t keep = ~(0xFFFFu << sh);
+            if (o < 2) {
+                if (on) sel[o] = (sel[o] & keep) | two;
+            } else {
+                if (on && src < 8) sel[2 * o - 2] = (sel[2 * o - 2] & keep) | two;
+                if (on && src >= 8) sel[2 * o - 1] = (sel[2 * o - 1] & keep) | two;
+            }
+            rnk += on ? 1 : 0;
+        }
+        u32x4 lo4 = {sel[0], sel[1], sel[2], sel[3]}, hi4 = {sel[4], sel[5], 0u, 0u};
+        *reinterpret_cast<u32x4 *>(&vlut[tid * LUTW]) = lo4;
+        *reinterpret_cast<u32x4 *>(&vlut[tid * LUTW + 4]) = hi4;
+    }
     // ---- per-step query prep: table {q_g[j] * scale * log2e, 1/a[j]} and R_g
     if (tid < SPARK_D) {
         const int j = tid;
@@ -382,70 +424,84 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         wave_lds_sync();
 
         if constexpr (PV) {
-            // ---- packed values: zero the dense tile, scatter this token's kept entries into it
-            {
-                const u32x4 z = {0u, 0u, 0u, 0u};
+            // ---- packed values: park this token's row in LDS with its per-group bookkeeping
+            uint32_t *raw = reinterpret_cast<uint32_t *>(wbuf[wave]);
+            uint32_t mk[4];
+            if (TVC > 0) {
 #pragma unroll
-                for (int i = 0; i < VTILE / (64 * 16); ++i)
-                    *reinterpret_cast<u32x4 *>(dense + (i * 64 + lane) * 16) = z;
+                for (int qd = 0; qd < NVW / 4; ++qd) {
+                    u32x4 x = {vrow[4 * qd], vrow[4 * qd + 1], vrow[4 * qd + 2], vrow[4 * qd + 3]};
+                    *reinterpret_cast<u32x4 *>(&raw[lane * RSV + 4 * qd]) = x;
+                }
+                if (NVW % 4) {
+                    raw[lane * RSV + 4 * (NVW / 4)] = vrow[4 * (NVW / 4)];
+                    raw[lane * RSV + 4 * (NVW / 4) + 1] = vrow[4 * (NVW / 4) + 1];
+                }
+            } else {
+                // any row length: straight from memory, no prefetch
+                const uint8_t *vtp = vtiles + (int64_t)tile * Lv.tile_bytes;
+                for (int qd = 1; qd < Lv.nq; ++qd) {
+                    const u32x4 x = NT_LOAD(reinterpret_cast<const u32x4 *>(vtp + qd * 1024 + lane * 16));
+                    *reinterpret_cast<u32x4 *>(&raw[lane * rsv + 4 * qd]) = x;
+                }
+                if (Lv.tail2) {
+                    const uint2 x = *reinterpret_cast<const uint2 *>(vtp + Lv.nq * 1024 + lane * 8);
+                    raw[lane * rsv + 4 * Lv.nq] = x.x;
+                    raw[lane * rsv + 4 * Lv.nq + 1] = x.y;
+                }
+            }
+#pragma unroll
+            for (int w4 = 0; w4 < 4; ++w4) mk[w4] = vrow[w4];
+            {
+                // 16 halfwords: (kept entries in lower groups) << 8 | mask byte of the group
+                uint32_t meta[8];
+                uint32_t before = 0;
+#pragma unroll
+                for (int c = 0; c < 16; ++c) {
+                    const uint32_t byte = (mk[c >> 2] >> (8 * (c & 3))) & 0xFFu;
+                    const uint32_t hw = (before << 8) | byte;
+                    if (c & 1) meta[c >> 1] |= hw << 16; else meta[c >> 1] = hw;
+                    before += __popc(byte);
+                }
+                u32x4 m0 = {meta[0], meta[1], meta[2], meta[3]}, m1 = {meta[4], meta[5], meta[6], meta[7]};
+                *reinterpret_cast<u32x4 *>(&vmeta[wave][lane * 8]) = m0;
+                *reinterpret_cast<u32x4 *>(&vmeta[wave][lane * 8 + 4]) = m1;
             }
             wave_lds_sync();
-            {
-                uint64_t cur = ((uint64_t)vrow[1] << 32) | vrow[0];
-                const uint64_t upper = ((uint64_t)vrow[3] << 32) | vrow[2];
-                const int clo = __popc(vrow[0]) + __popc(vrow[1]);
-                int jb = 0;
-                auto next_vchannel = [&](int i) {
-                    const bool sw = (i == clo);          // first entry of channels 64..127
-                    cur = sw ? upper : cur;
-                    jb = sw ? 64 : jb;
-                    const int j = (__builtin_ctzll((unsigned long long)cur) + jb) & (SPARK_D - 1);
-                    cur &= cur - 1;
-                    return j;
-                };
-                auto put = [&](int j, uint16_t val) {
-                    *reinterpret_cast<uint16_t *>(dense + j * 128 + (cbase ^ (uint32_t)((j & 7) << 4))) = val;
-                };
-                if (TVC > 0) {
-#pragma unroll
-                    for (int i = 0; i < TVC; ++i) {
-                        const uint32_t w = vrow[4 + i / 2];
-                        put(next_vchannel(i), (i & 1) ? (uint16_t)(w >> 16) : (uint16_t)w);
-                    }
-                } else {
-                    const uint8_t *vtp = vtiles + (int64_t)tile * Lv.tile_bytes;
-                    uint32_t w = 0;
-                    for (int i = 0; i < Lv.T; ++i) {
-                        if ((i & 1) == 0)
-                            w = *reinterpret_cast<const uint32_t *>(vtp + spark_tile_word_offset(Lv, lane, 4 + i / 2));
-                        put(next_vchannel(i), (i & 1) ? (uint16_t)(w >> 16) : (uint16_t)w);
-                    }
-                }
-            }
-            wave_lds_sync();
-            // ---- P V on the matrix cores: B operand e = channel 16e + cn, K = 8 tokens of one chunk
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                uint4 ah = {0, 0, 0, 0}, alo = {0, 0, 0, 0};
-                if (cn < G) {
-                    ah = *reinterpret_cast<const uint4 *>(&Pbuf[wave][0][cn][32 * ks + 8 * tg]);
-                    alo = *reinterpret_cast<const uint4 *>(&Pbuf[wave][1][cn][32 * ks + 8 * tg]);
-                }
-                const bf16x8 A_hi = __builtin_bit_cast(bf16x8, ah);
-                const bf16x8 A_lo = __builtin_bit_cast(bf16x8, alo);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint4 bv = *reinterpret_cast<const uint4 *>(
-                        dense + (16 * e + cn) * 128 + (((4 * ks + tg) ^ (cn & 7)) << 4));
-                    const bf16x8 B = __builtin_bit_cast(bf16x8, bv);
-                    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_hi, B, acc[e], 0, 0, 0);
-                    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_lo, B, acc[e], 0, 0, 0);
-                }
-            }
-        } else {
+        }
+        {
             // ---- P V on the matrix cores
     #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
+                if constexpr (PV) {
+                    // rebuild the dense pieces of this half tile: lane (tg, cn) makes channels 8cn..8cn+7 of
+                    // tokens 32ks + 4i + tg (four at a time, to bound the registers in flight)
+                    const uint32_t *raw = reinterpret_cast<const uint32_t *>(wbuf[wave]);
+                    const uint16_t *meta16 = reinterpret_cast<const uint16_t *>(vmeta[wave]);
+    #pragma unroll
+                    for (int i0 = 0; i0 < 8; i0 += 4) {
+    #pragma unroll
+                        for (int i = i0; i < i0 + 4; ++i) {
+                            const int t = 32 * ks + 4 * i + tg;
+                            const uint32_t hw = meta16[t * 16 + cn];
+                            const uint32_t byte = hw & 0xFFu, before = hw >> 8;
+                            const uint32_t *win = &raw[t * rsv + 4 + (before >> 1)];   // 8 candidates start here ...
+                            const uint32_t sh = (before & 1u) << 4;                     // ... or one halfword further
+                            const uint32_t d0 = win[0], d1 = win[1], d2 = win[2], d3 = win[3], d4 = win[4];
+                            const uint32_t q0 = __builtin_amdgcn_alignbit(d1, d0, sh);
+                            const uint32_t q1 = __builtin_amdgcn_alignbit(d2, d1, sh);
+                            const uint32_t q2 = __builtin_amdgcn_alignbit(d3, d2, sh);
+                            const uint32_t q3 = __builtin_amdgcn_alignbit(d4, d3, sh);
+                            const u32x4 sa = *reinterpret_cast<const u32x4 *>(&vlut[byte * LUTW]);
+                            const uint2 sb = *reinterpret_cast<const uint2 *>(&vlut[byte * LUTW + 4]);
+                            vr[ks][i].x = __builtin_amdgcn_perm(q1, q0, sa.x);
+                            vr[ks][i].y = __builtin_amdgcn_perm(q1, q0, sa.y);
+                            vr[ks][i].z = __builtin_amdgcn_perm(q1, q0, sa.z) | __builtin_amdgcn_perm(q3, q2, sa.w);
+                            vr[ks][i].w = __builtin_amdgcn_perm(q1, q0, sb.x) | __builtin_amdgcn_perm(q3, q2, sb.y);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
                 uint4 ah = {0, 0, 0, 0}, alo = {0, 0, 0, 0};
                 if (cn < G) {
                     ah = *reinterpret_cast<const uint4 *>(&Pbuf[wave][0][cn][32 * ks + 8 * tg]);
@@ -491,17 +547,16 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         if (lane == 0) { red_m[wave][g] = m[g]; red_l[wave][g] = lt; }
     }
     // accumulator layout: lane (tg, cn), register rr of acc[e] = head 4*tg + rr, channel 8*cn + e
-    // (dense values) or 16*e + cn (packed values)
-    wave_lds_sync();   // the dense value tile of this wavefront is no longer read
+    wave_lds_sync();   // this wavefront's parked value rows are no longer read
     auto red_acc = [&](int w, int g, int ch) -> float & {
-        return reinterpret_cast<float *>(big[w])[g * SPARK_D + ch];
+        return reinterpret_cast<float *>(wbuf[w])[g * SPARK_D + ch];
     };
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
         const int g = 4 * tg + rr;
         if (g < G) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) red_acc(wave, g, PV ? (16 * e + cn) : (8 * cn + e)) = acc[e][rr];
+            for (int e = 0; e < 8; ++e) red_acc(wave, g, 8 * cn + e) = acc[e][rr];
         }
     }
     __syncthreads();
