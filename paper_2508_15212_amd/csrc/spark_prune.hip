@@ -345,7 +345,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                     p = (c >= T) ? cand : p;
                     if (c == T) { tied = 0; break; }
                     bit >>= 1;
-                } while (bit != 0u);
+                } while (bit != (VALUES ? (1u << 15) : 0u));   // |v| of a bf16 entry has no bits below 16
             }
             // exactly T keys are >= p, unless p is the T-th largest value and it is tied
             uint64_t kb0 = __ballot(key0 >= p), kb1 = __ballot(key1 >= p);
