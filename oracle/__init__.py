@@ -204,6 +204,29 @@ def decode_fused(q, pr: Pruned, v, layout, cu, scale=None):
     return _decode("fused", q, pr, v, layout, cu, scale, False)
 
 
+def decode_literal_tail(q, pr: Pruned, v, layout, cu, tail_k, tail_v, tail_len, scale=None):
+    """Decode over the pruned prefix followed by appended, never-pruned rows.
+    tail_k, tail_v uint16 [B, cap, Hkv, D]; tail_len int32 [B]."""
+    q = _c(q, np.uint16)
+    b, hq, d = q.shape
+    v, ts, hs, total, hkv, dv = _strided(v, layout)
+    assert dv == d == pr.D
+    cu = _c(cu, np.int32)
+    tail_k, tail_v = _c(tail_k, np.uint16), _c(tail_v, np.uint16)
+    tail_len = _c(tail_len, np.int32)
+    cap = tail_k.shape[1]
+    assert tail_k.shape == (b, cap, hkv, d) == tail_v.shape and tail_len.shape == (b,)
+    assert np.all((tail_len >= 0) & (tail_len <= cap))
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    out = np.empty((b, hq, d), np.float64)
+    lib().oracle_decode_literal_tail(_p(q), _p(pr.mask), _p(pr.kept), _p(pr.codes), _p(pr.scale), _p(pr.mu32),
+                                     _p(pr.a32), _p(v), ctypes.c_int64(ts), ctypes.c_int64(hs), _p(cu),
+                                     _p(tail_k), _p(tail_v), _p(tail_len), int(cap), b, hq, hkv, d, pr.T,
+                                     ctypes.c_double(scale), _p(out))
+    return out
+
+
 def dense_attn(q, k, v, layout, cu, scale=None):
     """Eq. (4) on the unpruned cache."""
     q = _c(q, np.uint16)

@@ -26,7 +26,8 @@
  * attention, brute-force subset optimality of Eq. (7), the exact-recovery construction,
  * window-scale invariance, and the invariants listed in tests/test_oracle_pins.py; the
  * value-cache functions by brute-force subset optimality, a second hand-worked case and
- * an independent masked-matrix product.  No function in this file is "parity unpinned".
+ * an independent masked-matrix product; the appended-token decode by a third hand-worked
+ * case, dense attention on the concatenated cache (keep-all) and the empty-tail identity.  No function in this file is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -431,6 +432,76 @@ void oracle_decode_fused(const uint16_t *q, const uint32_t *mask, const uint16_t
                              v_tok_stride, D, out + ((int64_t)b * Hq + g) * D, NULL);
         free(s);
         free(r);
+    }
+}
+
+/*
+ * Decode attention when tokens have been appended after prefill.
+ * Sec. "Preliminaries": at every decode step the new token's key and value are concatenated to
+ * the cache; Sec. "SparK": pruning happens once, at prefill.  So the cache of sequence b is the
+ * S_b pruned prefix rows followed by L_b appended rows that were never pruned (reading: appended
+ * rows stay dense; the paper does not say that they are pruned later).  The literal form: rebuild
+ * K-tilde for the prefix as in oracle_decode_literal, use the appended keys as they are, one
+ * softmax over all S_b + L_b scores, weighted sum over the prefix values followed by the
+ * appended values (Eq. (4) on the concatenated cache).
+ *
+ * tail_k, tail_v [B, cap, Hkv, D] bf16 bits; tail_len [B], 0 <= tail_len[b] <= cap.
+ * Other arguments as oracle_decode_literal; out [B,Hq,D] double.
+ */
+void oracle_decode_literal_tail(const uint16_t *q, const uint32_t *mask, const uint16_t *kept_bf16,
+                                const int8_t *codes, const float *scale, const float *mu32,
+                                const float *a32, const uint16_t *v, int64_t v_tok_stride,
+                                int64_t v_head_stride, const int32_t *cu, const uint16_t *tail_k,
+                                const uint16_t *tail_v, const int32_t *tail_len, int cap, int B,
+                                int Hq, int Hkv, int D, int T, double softmax_scale, double *out)
+{
+    const int G = Hq / Hkv;
+    const int MW = (D + 31) / 32;
+    int bg;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bg = 0; bg < B * Hq; ++bg) {
+        const int b = bg / Hq, g = bg % Hq, h = g / G;
+        const int64_t n0 = cu[b], S = cu[b + 1] - cu[b], Lb = tail_len[b], N = S + Lb;
+        const float *a = a32 + ((int64_t)b * Hkv + h) * D;
+        const uint16_t *qrow = q + ((int64_t)b * Hq + g) * D;
+        double *s = (double *)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+        double *ktilde = (double *)malloc(sizeof(double) * (size_t)D);
+        double *o = out + ((int64_t)b * Hq + g) * D;
+        for (int64_t t = 0; t < S; ++t) {
+            const int64_t row = (n0 + t) * Hkv + h;
+            int c = 0;
+            for (int j = 0; j < D; ++j) {
+                if (mask[row * MW + j / 32] >> (j % 32) & 1u)
+                    ktilde[j] = kept_value(kept_bf16, codes, scale, row, T, c++);
+                else
+                    ktilde[j] = (a[j] != 0.0f) ? (double)mu32[row] / (double)a[j] : 0.0;
+            }
+            double dot = 0.0;
+            for (int j = 0; j < D; ++j) dot += bf16_bits_to_f64(qrow[j]) * ktilde[j];
+            s[t] = softmax_scale * dot;
+        }
+        for (int64_t t = 0; t < Lb; ++t) {
+            const uint16_t *krow = tail_k + (((int64_t)b * cap + t) * Hkv + h) * D;
+            double dot = 0.0;
+            for (int j = 0; j < D; ++j) dot += bf16_bits_to_f64(qrow[j]) * bf16_bits_to_f64(krow[j]);
+            s[S + t] = softmax_scale * dot;
+        }
+        for (int j = 0; j < D; ++j) o[j] = 0.0;
+        if (N > 0) {
+            double m = s[0];
+            for (int64_t t = 1; t < N; ++t)
+                if (s[t] > m) m = s[t];
+            double z = 0.0;
+            for (int64_t t = 0; t < N; ++t) z += exp(s[t] - m);
+            for (int64_t t = 0; t < N; ++t) {
+                const double p = exp(s[t] - m) / z;
+                const uint16_t *vrow = (t < S) ? v + (n0 + t) * v_tok_stride + (int64_t)h * v_head_stride
+                                               : tail_v + (((int64_t)b * cap + (t - S)) * Hkv + h) * D;
+                for (int j = 0; j < D; ++j) o[j] += p * bf16_bits_to_f64(vrow[j]);
+            }
+        }
+        free(s);
+        free(ktilde);
     }
 }
 

@@ -459,3 +459,72 @@ def test_keep_all_values_is_the_unpruned_value_cache():
     assert np.all(np.isinf(pv.gap))
     vt = oracle.expand_values(pv)
     assert np.array_equal(vt, t.v.transpose(1, 0, 2))
+
+
+# ------------------------------------------------------------------ appended (never pruned) tokens
+
+with open(os.path.join(HERE, "golden", "handworked.json")) as fh:
+    _TCASES = json.load(fh)["tail_cases"]
+
+
+@pytest.mark.parametrize("case", _TCASES, ids=[c["name"] for c in _TCASES])
+def test_handworked_tail(case):
+    kc = next(c for c in _CASES if c["name"] == case["key_case"])
+    Hkv, T, S = (kc[x] for x in ("Hkv", "T", "S"))
+    qwin, k, v, q = _bits(kc["qwin"]), _bits(kc["k"]), _bits(kc["v"]), _bits(kc["q"])
+    cu = np.array([0, S], np.int32)
+    _, _, a32 = oracle.window_stat(qwin, Hkv)
+    pr = oracle.prune(k, "NHD", a32, cu, T)
+    out = oracle.decode_literal_tail(q, pr, v, "NHD", cu, _bits(case["tail_k"]), _bits(case["tail_v"]),
+                                     np.asarray(case["tail_len"], np.int32))
+    assert np.allclose(out, np.asarray(case["expect"]["out"], np.float64), rtol=0, atol=1e-15)
+
+
+def _random_tail(w, seed, cap):
+    rng = np.random.default_rng(seed)
+    shape = (w.batch, cap, w.n_kv_heads, w.head_dim)
+    tk = bf(rng.standard_normal(shape).astype(np.float32))
+    tv = bf(rng.standard_normal(shape).astype(np.float32))
+    tl = rng.integers(0, cap + 1, size=w.batch).astype(np.int32)
+    return tk, tv, tl
+
+
+def test_tail_keep_all_is_dense_attention_on_the_concatenated_cache():
+    w, t = _random_small(21, Hq=8, Hkv=2, T=128)
+    tk, tv, tl = _random_tail(w, 21, cap=9)
+    tl[0] = 9
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.head_dim)               # T = D: nothing pruned
+    got = oracle.decode_literal_tail(t.q, pr, t.v, t.layout, t.cu, tk, tv, tl)
+    # the same cache written out as one dense cache per sequence: prefix rows, then appended rows
+    kk = t.k.transpose(1, 0, 2)                                           # [total,Hkv,D]
+    vv = t.v.transpose(1, 0, 2)
+    ks, vs, cu2 = [], [], [0]
+    for b in range(w.batch):
+        n0, n1 = int(t.cu[b]), int(t.cu[b + 1])
+        ks += [kk[n0:n1], tk[b, :tl[b]]]
+        vs += [vv[n0:n1], tv[b, :tl[b]]]
+        cu2.append(cu2[-1] + (n1 - n0) + int(tl[b]))
+    ref = oracle.dense_attn(t.q, np.ascontiguousarray(np.concatenate(ks)), np.ascontiguousarray(np.concatenate(vs)),
+                            "NHD", np.asarray(cu2, np.int32))
+    assert np.allclose(got, ref, rtol=0, atol=1e-13)
+
+
+def test_tail_empty_is_plain_decode_and_tail_only_is_dense_attention():
+    w, t = _random_small(22, Hq=4, Hkv=2, T=26)
+    tk, tv, tl = _random_tail(w, 22, cap=5)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    zero = np.zeros(w.batch, np.int32)
+    assert np.array_equal(oracle.decode_literal_tail(t.q, pr, t.v, t.layout, t.cu, tk, tv, zero),
+                          oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu))
+    # a sequence with no prefix: attention over its appended rows alone
+    w0, t0 = _random_small(23, Hq=4, Hkv=2, T=26)
+    cu0 = np.zeros(w0.batch + 1, np.int32)
+    empty = oracle.prune(t0.k[:, :0], t0.layout, a32[:w0.batch], cu0, w0.keep)
+    tl2 = np.full(w0.batch, 5, np.int32)
+    got = oracle.decode_literal_tail(t0.q, empty, t0.v[:, :0], t0.layout, cu0, tk[:w0.batch], tv[:w0.batch], tl2)
+    cu5 = (np.arange(w0.batch + 1) * 5).astype(np.int32)
+    ref = oracle.dense_attn(t0.q, np.ascontiguousarray(tk[:w0.batch].reshape(-1, w0.n_kv_heads, w0.head_dim)),
+                            np.ascontiguousarray(tv[:w0.batch].reshape(-1, w0.n_kv_heads, w0.head_dim)), "NHD", cu5)
+    assert np.allclose(got, ref, rtol=0, atol=1e-13)
