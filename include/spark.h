@@ -68,6 +68,8 @@ typedef struct spark_desc {
                                  Must be the same for the workspace query and the call. */
     int32_t keep_v;           /* T_v in [1, D]: channels kept per (token, KV head) of the VALUE cache, used by
                                  the *_values entry points only; 0 where values stay dense */
+    int32_t tail_capacity;    /* rows per sequence in the appended-token buffers of spark_decode_attn_tail;
+                                 0 elsewhere */
 } spark_desc;
 
 /* Size in bytes of the packed key cache for this description (depends on batch, n_kv_heads,
@@ -155,6 +157,28 @@ spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const
 spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *mask_out,
                           void *vals_out, float *mu_out, float *scale_out, float *a_out,
                           void *hip_stream);
+
+/*
+ * One decode step when tokens have been appended after prefill.
+ * [Sec. "Preliminaries": every decode step concatenates the new token's key and value to the cache;
+ *  Sec. "SparK": channels are pruned once, at prefill -- so appended rows are kept dense]
+ *
+ * The cache of sequence b is its pruned prefix (packed keys + dense values, as in spark_decode_attn)
+ * followed by tail_len[b] appended rows; scores of appended rows are plain scale * <q, k>; one softmax
+ * runs over prefix and appended rows together, and the output sums over both value sets.
+ *
+ *   tail_k_bf16, tail_v_bf16  in  [batch, tail_capacity, n_kv_heads, 128] bf16, contiguous, 16-byte aligned;
+ *                                 row i < tail_len[b] of sequence b is its i-th appended token
+ *   tail_len                  in  int32 [batch] (device), 0 <= tail_len[b] <= desc->tail_capacity
+ * Everything else as spark_decode_attn (same workspace).  Appending a token is the caller's copy into row
+ * tail_len[b]; re-pruning a full tail into a new packed cache is a spark_prune call on those rows.
+ * Two launches: a small kernel leaves the appended rows' softmax state in a spare workspace slot, the
+ * decode kernel folds it in with the sequence splits.
+ */
+spark_status spark_decode_attn_tail(const spark_desc *desc, const void *q_bf16, const void *packed,
+                                    const void *v_bf16, const int32_t *cu_seqlens, const void *tail_k_bf16,
+                                    const void *tail_v_bf16, const int32_t *tail_len, void *out,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Channel pruning of the value cache.

@@ -20,6 +20,7 @@ bool desc_ok(const spark_desc *d, spark_status *why)
     if (d->n_q_heads % d->n_kv_heads) return false;
     if (d->n_splits < 0 || d->n_splits > 4096) return false;
     if (d->keep_v < 0 || d->keep_v > d->head_dim) return false;
+    if (d->tail_capacity < 0) return false;
     *why = SPARK_ERR_UNSUPPORTED;
     if (d->head_dim != SPARK_D) return false;
     const int G = d->n_q_heads / d->n_kv_heads;
@@ -139,7 +140,7 @@ size_t spark_decode_workspace(const spark_desc *desc)
 {
     spark_status why;
     if (!desc_ok(desc, &why)) return 0;
-    const size_t slots = (size_t)desc->batch * desc->n_q_heads * pick_splits(desc);
+    const size_t slots = (size_t)desc->batch * desc->n_q_heads * (pick_splits(desc) + 1);
     return slots * (SPARK_D + 2) * sizeof(float) + counter_bytes(desc);
 }
 
@@ -150,7 +151,7 @@ spark_status spark_decode_workspace_init(const spark_desc *desc, void *workspace
     if (!desc_ok(desc, &why)) return why;
     if (!workspace || !aligned(workspace, 16)) return SPARK_ERR_INVALID_ARG;
     if (workspace_bytes < spark_decode_workspace(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
-    const size_t slots = (size_t)desc->batch * desc->n_q_heads * pick_splits(desc);
+    const size_t slots = (size_t)desc->batch * desc->n_q_heads * (pick_splits(desc) + 1);
     uint32_t *counters = reinterpret_cast<uint32_t *>(static_cast<float *>(workspace) + slots * (SPARK_D + 2));
     const hipError_t e = spark::launch_zero_counters(counters, desc->batch * desc->n_kv_heads,
                                                      static_cast<hipStream_t>(hip_stream));
@@ -215,7 +216,8 @@ namespace {
 
 spark_status decode_common(const spark_desc *desc, const void *q_bf16, const void *packed, const void *v_bf16,
                            const void *packed_v, const int32_t *cu_seqlens, void *out, void *workspace,
-                           size_t workspace_bytes, void *hip_stream)
+                           size_t workspace_bytes, void *hip_stream, const void *tail_k = nullptr,
+                           const void *tail_v = nullptr, const int32_t *tail_len = nullptr)
 {
     spark_status why;
     if (!desc_ok(desc, &why)) return why;
@@ -231,12 +233,16 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
     }
     if (!aligned(packed, 256) || !aligned(workspace, 16) || !aligned(q_bf16, 2) || !aligned(out, 4))
         return SPARK_ERR_INVALID_ARG;
+    if (tail_k) {
+        if (!tail_v || !tail_len || desc->tail_capacity < 1) return SPARK_ERR_INVALID_ARG;
+        if (!aligned(tail_k, 16) || !aligned(tail_v, 16) || !aligned(tail_len, 4)) return SPARK_ERR_INVALID_ARG;
+    }
     if (workspace_bytes < spark_decode_workspace(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
     const SparkLayout L = layout_of(desc);
     SparkLayout Lv = L;
     if (packed_v) Lv = values_layout_of(desc);
     const int nsplit = pick_splits(desc);
-    const size_t slots = (size_t)desc->batch * desc->n_q_heads * nsplit;
+    const size_t slots = (size_t)desc->batch * desc->n_q_heads * (nsplit + 1);
     float *part_acc = static_cast<float *>(workspace);
     float *part_ml = part_acc + slots * SPARK_D;
     uint32_t *counters = reinterpret_cast<uint32_t *>(part_ml + slots * 2);
@@ -246,7 +252,8 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
         static_cast<const uint16_t *>(v_bf16), desc->v_token_stride, desc->v_head_stride,
         static_cast<const uint8_t *>(packed_v), packed_v ? &Lv : nullptr, cu_seqlens, part_acc, part_ml, counters,
         desc->n_q_heads, nsplit, scale, L, out, desc->out_dtype == SPARK_OUT_F32,
-        static_cast<hipStream_t>(hip_stream));
+        static_cast<const uint16_t *>(tail_k), static_cast<const uint16_t *>(tail_v), tail_len,
+        desc->tail_capacity, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }
 
@@ -259,6 +266,16 @@ spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const
     if (!v_bf16) return SPARK_ERR_INVALID_ARG;
     return decode_common(desc, q_bf16, packed, v_bf16, nullptr, cu_seqlens, out, workspace, workspace_bytes,
                          hip_stream);
+}
+
+spark_status spark_decode_attn_tail(const spark_desc *desc, const void *q_bf16, const void *packed, const void *v_bf16,
+                                    const int32_t *cu_seqlens, const void *tail_k_bf16, const void *tail_v_bf16,
+                                    const int32_t *tail_len, void *out, void *workspace, size_t workspace_bytes,
+                                    void *hip_stream)
+{
+    if (!v_bf16 || !tail_k_bf16) return SPARK_ERR_INVALID_ARG;
+    return decode_common(desc, q_bf16, packed, v_bf16, nullptr, cu_seqlens, out, workspace, workspace_bytes,
+                         hip_stream, tail_k_bf16, tail_v_bf16, tail_len);
 }
 
 spark_status spark_decode_attn_values(const spark_desc *desc, const void *q_bf16, const void *packed,

@@ -51,6 +51,8 @@ struct DecodeParams {
     void *out;               // [B, Hq, 128] bf16 or float32
     int out_f32;
     int Hq, Hkv, nsplit;
+    int nslots;              // partial slots per (batch, q head): nsplit + 1 (the last one is the appended rows')
+    int nmerge;              // partials the last block folds: nsplit, or nsplit + 1 when appended rows exist
     float scale_log2;        // softmax scale * log2(e)
     SparkLayout L;
 };
@@ -573,7 +575,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             Lsum = fmaf(red_l[w][g], f, Lsum);
             A = fmaf(red_acc(w, g, ch), f, A);
         }
-        const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nsplit + split;
+        const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + split;
         st_agent(&P.part_acc[slot * SPARK_D + ch], A);
         if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
     }
@@ -608,17 +610,17 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             const int g = on[u] ? idx / SPARK_D : 0;
             ch[u] = idx % SPARK_D;
             bq[u] = (int64_t)b * P.Hq + h * G + g;
-            ml[u] = P.part_ml + bq[u] * P.nsplit * 2;
-            pa[u] = P.part_acc + bq[u] * P.nsplit * SPARK_D + ch[u];
+            ml[u] = P.part_ml + bq[u] * P.nslots * 2;
+            pa[u] = P.part_acc + bq[u] * P.nslots * SPARK_D + ch[u];
             M[u] = -INFINITY; Lsum[u] = 0.0f; A[u] = 0.0f;
         }
-        for (int i0 = 0; i0 < P.nsplit; i0 += 8) {
+        for (int i0 = 0; i0 < P.nmerge; i0 += 8) {
             float mi[2][8], li[2][8], ai[2][8];
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    const int i = (i0 + k < P.nsplit) ? (i0 + k) : (P.nsplit - 1);
+                    const int i = (i0 + k < P.nmerge) ? (i0 + k) : (P.nmerge - 1);
                     mi[u][k] = ld_agent(ml[u] + 2 * i);
                     li[u][k] = ld_agent(ml[u] + 2 * i + 1);
                     ai[u][k] = ld_agent(pa[u] + (int64_t)i * SPARK_D);
@@ -627,7 +629,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    if (i0 + k < P.nsplit) {
+                    if (i0 + k < P.nmerge) {
                         const float Mn = fmaxf(M[u], mi[u][k]);
                         const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
                         const float fo = fast_exp2(M[u] - Ms), fn = fast_exp2(mi[u][k] - Ms);
@@ -646,6 +648,117 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             else
                 reinterpret_cast<uint16_t *>(P.out)[bq[u] * SPARK_D + ch[u]] = __builtin_bit_cast(uint16_t, (__bf16)o);
         }
+    }
+}
+
+// ---------------------------------------------------------------- appended (never pruned) rows
+
+// [Sec. "Preliminaries": each decode step concatenates the new token's key and value to the cache; pruning
+//  happens once, at prefill, so these rows stay dense.]  One block per (batch, KV head) runs plain attention
+// over the sequence's appended rows and leaves the softmax state (m, l, unnormalised output) in the extra
+// partial slot; the decode kernel, launched after it on the same stream, folds that slot in with the
+// sequence splits.  tail_k / tail_v are [B, cap, Hkv, 128] bf16, tail_len [B].
+struct TailParams {
+    const uint16_t *q;
+    const uint16_t *tail_k, *tail_v;
+    const int32_t *tail_len;
+    float *part_acc, *part_ml;
+    int cap, Hq, Hkv, nslots, slot;
+    float scale_log2;
+};
+
+template <int G>
+__global__ __launch_bounds__(kDecodeWaves * 64) void spark_tail_partial_kernel(TailParams P)
+{
+    __shared__ float qs[G][SPARK_D];
+    __shared__ float Psh[kDecodeWaves][G][64];
+    __shared__ float red_acc[kDecodeWaves][G][SPARK_D];
+    __shared__ float red_m[kDecodeWaves][G], red_l[kDecodeWaves][G];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int bh = blockIdx.x, h = bh % P.Hkv, b = bh / P.Hkv;
+    int len = P.tail_len[b];
+    len = len < 0 ? 0 : (len > P.cap ? P.cap : len);
+    for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
+        const int g = idx / SPARK_D, j = idx % SPARK_D;
+        qs[g][j] = bf16lo(P.q[((int64_t)b * P.Hq + h * G + g) * SPARK_D + j]) * P.scale_log2;
+    }
+    __syncthreads();
+    float m[G], l[G], acc[G][2];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.0f; acc[g][0] = acc[g][1] = 0.0f; }
+    const int64_t row0 = (int64_t)b * P.cap;
+    for (int c0 = wave * 64; c0 < len; c0 += kDecodeWaves * 64) {
+        // scores, lane = token
+        const int t = c0 + lane;
+        const bool valid = t < len;
+        const uint16_t *krow = P.tail_k + ((row0 + (valid ? t : len - 1)) * P.Hkv + h) * SPARK_D;
+        float s[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) s[g] = 0.0f;
+        for (int c = 0; c < SPARK_D / 8; ++c) {
+            const uint4 x = *reinterpret_cast<const uint4 *>(krow + 8 * c);
+            const float kf[8] = {bf16lo(x.x), bf16hi(x.x), bf16lo(x.y), bf16hi(x.y),
+                                 bf16lo(x.z), bf16hi(x.z), bf16lo(x.w), bf16hi(x.w)};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int g = 0; g < G; ++g) s[g] = fmaf(qs[g][8 * c + e], kf[e], s[g]);
+        }
+        // online softmax (log2 domain); probabilities to LDS
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float sg = valid ? s[g] : -INFINITY;
+            const float mnew = fmaxf(m[g], wave_max(sg));          // finite: lane 0 of the chunk is valid
+            const float alpha = fast_exp2(m[g] - mnew);             // m = -inf -> 0
+            const float p = fast_exp2(sg - mnew);
+            m[g] = mnew;
+            l[g] = fmaf(l[g], alpha, p);
+            acc[g][0] *= alpha;
+            acc[g][1] *= alpha;
+            Psh[wave][g][lane] = p;
+        }
+        wave_lds_sync();
+        // weighted sum, lane = channels 2l, 2l+1
+        const int nval = (len - c0 < 64) ? (len - c0) : 64;
+        for (int tt = 0; tt < nval; ++tt) {
+            const uint32_t vw = *reinterpret_cast<const uint32_t *>(
+                P.tail_v + ((row0 + c0 + tt) * P.Hkv + h) * SPARK_D + 2 * lane);
+            const float v0 = bf16lo(vw), v1 = bf16hi(vw);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float p = Psh[wave][g][tt];
+                acc[g][0] = fmaf(p, v0, acc[g][0]);
+                acc[g][1] = fmaf(p, v1, acc[g][1]);
+            }
+        }
+        wave_lds_sync();
+    }
+    // merge the wavefronts and write the partial
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float lt = wave_sum(l[g]);
+        if (lane == 0) { red_m[wave][g] = m[g]; red_l[wave][g] = lt; }
+        red_acc[wave][g][2 * lane] = acc[g][0];
+        red_acc[wave][g][2 * lane + 1] = acc[g][1];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
+        const int g = idx / SPARK_D, ch = idx % SPARK_D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) M = fmaxf(M, red_m[w][g]);
+        const float Ms = (M == -INFINITY) ? 0.0f : M;
+        float Lsum = 0.0f, A = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) {
+            const float f = fast_exp2(red_m[w][g] - Ms);
+            Lsum = fmaf(red_l[w][g], f, Lsum);
+            A = fmaf(red_acc[w][g][ch], f, A);
+        }
+        const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + P.slot;
+        P.part_acc[slot * SPARK_D + ch] = A;
+        if (ch == 0) { P.part_ml[slot * 2] = M; P.part_ml[slot * 2 + 1] = Lsum; }
     }
 }
 
@@ -702,8 +815,36 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
                               int64_t v_head_stride, const uint8_t *packed_v, const SparkLayout *Lv,
                               const int32_t *cu, float *part_acc, float *part_ml,
                               uint32_t *counters, int Hq, int nsplit, float softmax_scale, const SparkLayout &L,
-                              void *out, int out_f32, hipStream_t st)
+                              void *out, int out_f32, const uint16_t *tail_k, const uint16_t *tail_v,
+                              const int32_t *tail_len, int tail_cap, hipStream_t st)
 {
+    const int Gq = Hq / L.n_kv_heads;
+    if (tail_k) {
+        TailParams Tp;
+        Tp.q = q;
+        Tp.tail_k = tail_k;
+        Tp.tail_v = tail_v;
+        Tp.tail_len = tail_len;
+        Tp.part_acc = part_acc;
+        Tp.part_ml = part_ml;
+        Tp.cap = tail_cap;
+        Tp.Hq = Hq;
+        Tp.Hkv = L.n_kv_heads;
+        Tp.nslots = nsplit + 1;
+        Tp.slot = nsplit;
+        Tp.scale_log2 = softmax_scale * 1.44269504088896340736f;
+        const dim3 grid(L.batch * L.n_kv_heads), block(kDecodeWaves * 64);
+        switch (Gq) {
+            case 1: hipLaunchKernelGGL(spark_tail_partial_kernel<1>, grid, block, 0, st, Tp); break;
+            case 2: hipLaunchKernelGGL(spark_tail_partial_kernel<2>, grid, block, 0, st, Tp); break;
+            case 4: hipLaunchKernelGGL(spark_tail_partial_kernel<4>, grid, block, 0, st, Tp); break;
+            case 8: hipLaunchKernelGGL(spark_tail_partial_kernel<8>, grid, block, 0, st, Tp); break;
+            case 16: hipLaunchKernelGGL(spark_tail_partial_kernel<16>, grid, block, 0, st, Tp); break;
+            default: return hipErrorInvalidValue;
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     DecodeParams P;
     P.q = q;
     P.packed = packed;
@@ -721,6 +862,8 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.Hq = Hq;
     P.Hkv = L.n_kv_heads;
     P.nsplit = nsplit;
+    P.nslots = nsplit + 1;
+    P.nmerge = nsplit + (tail_k ? 1 : 0);
     P.scale_log2 = softmax_scale * 1.44269504088896340736f;
     P.L = L;
     const int G = P.Hq / P.Hkv;

@@ -21,11 +21,13 @@ hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *
 
 // q [B,Hq,128] bf16; the caller splits the workspace into part_acc / part_ml / counters.
 // Values are either dense (v, strides; packed_v = NULL) or a packed value cache (packed_v, Lv; v = NULL).
+// Partial slots per (batch, q head): nsplit + 1; tail_k != NULL adds the appended rows [B, tail_cap, Hkv, 128].
 hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const uint16_t *v, int64_t v_tok_stride,
                               int64_t v_head_stride, const uint8_t *packed_v, const SparkLayout *Lv,
                               const int32_t *cu, float *part_acc, float *part_ml,
                               uint32_t *counters, int Hq, int nsplit, float softmax_scale, const SparkLayout &L,
-                              void *out, int out_f32, hipStream_t st);
+                              void *out, int out_f32, const uint16_t *tail_k, const uint16_t *tail_v,
+                              const int32_t *tail_len, int tail_cap, hipStream_t st);
 
 hipError_t launch_zero_counters(uint32_t *counters, int n, hipStream_t st);
 
