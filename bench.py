@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--int8", action="store_true", help="int8 storage of the kept entries")
     ap.add_argument("--keep-v", type=int, default=0,
                     help="also prune the value cache to this many channels per row (0 = values stay dense)")
+    ap.add_argument("--tail", type=int, default=0,
+                    help="appended never-pruned rows per sequence (decode through spark_decode_attn_tail)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--copies", type=int, default=4, help="input copies rotated to defeat the 256 MB cache")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -85,6 +87,11 @@ def main() -> int:
     desc.n_splits = args.splits
     desc.keep_v = args.keep_v
     Tv = args.keep_v
+    ntail = args.tail
+    desc.tail_capacity = ntail
+    if ntail and Tv:
+        print("bench.py: --tail and --keep-v are separate entry points; pick one", file=sys.stderr)
+        return 2
 
     ncopy = max(1, args.copies)
     k0, v0 = dev(t.k), dev(t.v)
@@ -104,8 +111,19 @@ def main() -> int:
         if Tv:
             spark.prune_values(desc, vs[c], packvs[c])
 
+    if ntail:
+        rng = np.random.default_rng(w.seed + 7)
+        tshape = (w.batch, ntail, hkv, D)
+        tail_k_np = wl.f32_to_bf16_bits(rng.standard_normal(tshape).astype(np.float32))
+        tail_v_np = wl.f32_to_bf16_bits(rng.standard_normal(tshape).astype(np.float32))
+        tail_len_np = np.full(w.batch, ntail, np.int32)
+        tail_k, tail_v = dev(tail_k_np), dev(tail_v_np)
+        tail_len = torch.from_numpy(tail_len_np).cuda()
+
     def decode(c, d=desc, o=out):
-        if Tv:
+        if ntail:
+            spark.decode_attn_tail(d, q, packs[c], vs[c], cu, tail_k, tail_v, tail_len, o, ws)
+        elif Tv:
             spark.decode_attn_values(d, q, packs[c], packvs[c], cu, o, ws)
         else:
             spark.decode_attn(d, q, packs[c], vs[c], cu, o, ws)
@@ -161,6 +179,7 @@ def main() -> int:
     k_row = (T + 16 + 4 + 4) if args.int8 else (2 * T + 16 + 4)      # kept entries + mask + mu (+ scale)
     v_row = (2 * Tv + 16) if Tv else 2 * D                            # kept entries + mask, or the dense row
     dec_alg_bytes = rows * (k_row + v_row)                            # packed K row + V row
+    dec_alg_bytes += w.batch * ntail * hkv * 4 * D                    # appended rows: dense K and V
     prune_alg_bytes = rows * (2 * D + k_row) + w.batch * hq * w.window * D * 2
     if Tv:
         prune_alg_bytes += rows * (2 * D + v_row)
@@ -185,9 +204,10 @@ def main() -> int:
         "config": {
             "workload": w.name, "batch": w.batch, "n_q_heads": hq, "n_kv_heads": hkv, "head_dim": D,
             "context": int(w.seqlens.max()), "total_tokens": total, "keep": T, "window": w.window,
-            "pack": "int8" if args.int8 else "bf16", "keep_v": Tv if Tv else None,
+            "pack": "int8" if args.int8 else "bf16", "keep_v": Tv if Tv else None, "tail_rows_per_sequence": ntail if ntail else None,
             "splits": spark.decode_splits(desc),
             "input_copies_rotated": ncopy, "seed": w.seed, "step": ("spark_prune + spark_prune_values + spark_decode_attn_values" if Tv
+                                                              else "spark_prune + spark_decode_attn_tail" if ntail
                                                               else "spark_prune + spark_decode_attn"),
         },
         "decode": {"us_mean": round(dec_us, 2), "us_min": round(float(dec_ms.min() * 1e3), 2),
@@ -201,7 +221,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": round(dec_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dec_gbs / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_DECODE_TRAFFIC_BYTES.get((w.name, "int8" if args.int8 else "bf16"))
-                     if not (args.keep or Tv) else None,
+                     if not (args.keep or Tv or ntail) else None,
                      "algorithmic_bytes": dec_alg_bytes,
                      "kernel": "spark_decode_kernel, HIP events around spark_decode_attn"},
         "stream_read_ceiling": {"GBps": round(probe_gbs, 1), "us": round(probe_us, 2),
@@ -226,6 +246,8 @@ def main() -> int:
             pv = oracle.prune_values(t.v, t.layout, Tv)
             t1 = time.perf_counter()
             ref = oracle.decode_literal(t.q, pr, oracle.expand_values(pv), "NHD", t.cu)
+        elif ntail:
+            ref = oracle.decode_literal_tail(t.q, pr, t.v, t.layout, t.cu, tail_k_np, tail_v_np, tail_len_np)
         else:
             ref = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
         t2 = time.perf_counter()

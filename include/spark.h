@@ -69,7 +69,8 @@ typedef struct spark_desc {
     int32_t keep_v;           /* T_v in [1, D]: channels kept per (token, KV head) of the VALUE cache, used by
                                  the *_values entry points only; 0 where values stay dense */
     int32_t tail_capacity;    /* rows per sequence in the appended-token buffers of spark_decode_attn_tail;
-                                 0 elsewhere */
+                                 0 elsewhere.  Enters the decode workspace size: keep it the same for the
+                                 workspace query, its init and the calls. */
 } spark_desc;
 
 /* Size in bytes of the packed key cache for this description (depends on batch, n_kv_heads,
@@ -172,8 +173,8 @@ spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *
  *   tail_len                  in  int32 [batch] (device), 0 <= tail_len[b] <= desc->tail_capacity
  * Everything else as spark_decode_attn (same workspace).  Appending a token is the caller's copy into row
  * tail_len[b]; re-pruning a full tail into a new packed cache is a spark_prune call on those rows.
- * Two launches: a small kernel leaves the appended rows' softmax state in a spare workspace slot, the
- * decode kernel folds it in with the sequence splits.
+ * Still one launch: extra blocks of the decode grid (one per 256 rows of capacity and (batch, KV head)) leave
+ * the appended rows' softmax state in spare workspace slots and are counted like sequence splits.
  */
 spark_status spark_decode_attn_tail(const spark_desc *desc, const void *q_bf16, const void *packed,
                                     const void *v_bf16, const int32_t *cu_seqlens, const void *tail_k_bf16,

@@ -20,7 +20,7 @@ bool desc_ok(const spark_desc *d, spark_status *why)
     if (d->n_q_heads % d->n_kv_heads) return false;
     if (d->n_splits < 0 || d->n_splits > 4096) return false;
     if (d->keep_v < 0 || d->keep_v > d->head_dim) return false;
-    if (d->tail_capacity < 0) return false;
+    if (d->tail_capacity < 0 || d->tail_capacity > (1 << 20)) return false;
     *why = SPARK_ERR_UNSUPPORTED;
     if (d->head_dim != SPARK_D) return false;
     const int G = d->n_q_heads / d->n_kv_heads;
@@ -86,6 +86,14 @@ __global__ __launch_bounds__(256) void spark_probe_read_kernel(const u32x4 *__re
     if (acc == 0x9E3779B9u) sink[0] = acc;
 }
 
+// partial slots per (batch, q head): the sequence splits plus one per 256 rows of appended-token capacity
+// (at least one, so a workspace serves calls with and without appended rows)
+size_t partial_slots(const spark_desc *d)
+{
+    const int tail_slots = d->tail_capacity > 0 ? (d->tail_capacity + 255) / 256 : 1;
+    return (size_t)pick_splits(d) + (size_t)tail_slots;
+}
+
 size_t counter_bytes(const spark_desc *d)
 {
     return (((size_t)d->batch * d->n_kv_heads * sizeof(uint32_t)) + 15) & ~(size_t)15;
@@ -140,7 +148,7 @@ size_t spark_decode_workspace(const spark_desc *desc)
 {
     spark_status why;
     if (!desc_ok(desc, &why)) return 0;
-    const size_t slots = (size_t)desc->batch * desc->n_q_heads * (pick_splits(desc) + 1);
+    const size_t slots = (size_t)desc->batch * desc->n_q_heads * partial_slots(desc);
     return slots * (SPARK_D + 2) * sizeof(float) + counter_bytes(desc);
 }
 
@@ -151,7 +159,7 @@ spark_status spark_decode_workspace_init(const spark_desc *desc, void *workspace
     if (!desc_ok(desc, &why)) return why;
     if (!workspace || !aligned(workspace, 16)) return SPARK_ERR_INVALID_ARG;
     if (workspace_bytes < spark_decode_workspace(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
-    const size_t slots = (size_t)desc->batch * desc->n_q_heads * (pick_splits(desc) + 1);
+    const size_t slots = (size_t)desc->batch * desc->n_q_heads * partial_slots(desc);
     uint32_t *counters = reinterpret_cast<uint32_t *>(static_cast<float *>(workspace) + slots * (SPARK_D + 2));
     const hipError_t e = spark::launch_zero_counters(counters, desc->batch * desc->n_kv_heads,
                                                      static_cast<hipStream_t>(hip_stream));
@@ -242,7 +250,7 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
     SparkLayout Lv = L;
     if (packed_v) Lv = values_layout_of(desc);
     const int nsplit = pick_splits(desc);
-    const size_t slots = (size_t)desc->batch * desc->n_q_heads * (nsplit + 1);
+    const size_t slots = (size_t)desc->batch * desc->n_q_heads * partial_slots(desc);
     float *part_acc = static_cast<float *>(workspace);
     float *part_ml = part_acc + slots * SPARK_D;
     uint32_t *counters = reinterpret_cast<uint32_t *>(part_ml + slots * 2);

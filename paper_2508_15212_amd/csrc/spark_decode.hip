@@ -51,8 +51,12 @@ struct DecodeParams {
     void *out;               // [B, Hq, 128] bf16 or float32
     int out_f32;
     int Hq, Hkv, nsplit;
-    int nslots;              // partial slots per (batch, q head): nsplit + 1 (the last one is the appended rows')
-    int nmerge;              // partials the last block folds: nsplit, or nsplit + 1 when appended rows exist
+    int nslots;              // partial slots per (batch, q head): nsplit + ntail_slots (the last ones are the appended rows')
+    int nmerge;              // partials the last block folds: nsplit, or nsplit + ntail when appended rows exist
+    int ntail;               // blocks per (batch, KV head) for the appended rows, 256 rows each (0: none)
+    const uint16_t *tail_k, *tail_v;   // appended never-pruned rows [B, tail_cap, Hkv, 128] bf16, or NULL
+    const int32_t *tail_len;           // [B]
+    int tail_cap;
     float scale_log2;        // softmax scale * log2(e)
     SparkLayout L;
 };
@@ -105,6 +109,119 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
+// ---------------------------------------------------------------- appended (never pruned) rows
+
+// [Sec. "Preliminaries": each decode step concatenates the new token's key and value to the cache; pruning
+//  happens once, at prefill, so these rows stay dense.]  One extra block per (batch, KV head) of the decode
+// grid runs plain attention over the sequence's appended rows and leaves the softmax state (m, l,
+// unnormalised output) in the spare partial slot; it then takes part in the arrival count like a sequence
+// split, so whichever block comes last folds it in.  qs [G][128] and Psh [4][G][64] are LDS scratch.
+template <int G>
+__device__ __forceinline__ void tail_partial(const DecodeParams &P, int b, int h, int part, float *qs, float *Psh,
+                                             float (*red_m)[G], float (*red_l)[G], float *red_acc /* [4][G][128] */)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int len = P.tail_len[b];
+    len = len < 0 ? 0 : (len > P.tail_cap ? P.tail_cap : len);
+    // this block's share: rows [256 * part, 256 * part + 256)
+    const int first = part * kDecodeWaves * 64;
+    len = (len < first + kDecodeWaves * 64) ? len : first + kDecodeWaves * 64;
+    for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
+        const int g = idx / SPARK_D, j = idx % SPARK_D;
+        qs[g * SPARK_D + j] = bf16lo(P.q[((int64_t)b * P.Hq + h * G + g) * SPARK_D + j]) * P.scale_log2;
+    }
+    __syncthreads();
+    float m[G], l[G], acc[G][2];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.0f; acc[g][0] = acc[g][1] = 0.0f; }
+    const int64_t row0 = (int64_t)b * P.tail_cap;
+    float *pw = Psh + wave * G * 64;
+    for (int c0 = first + wave * 64; c0 < len; c0 += kDecodeWaves * 64) {   // (one pass)
+        // scores, lane = token
+        const int t = c0 + lane;
+        const bool valid = t < len;
+        const uint16_t *krow = P.tail_k + ((row0 + (valid ? t : len - 1)) * P.Hkv + h) * SPARK_D;
+        float s[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) s[g] = 0.0f;
+#pragma unroll 4
+        for (int c = 0; c < SPARK_D / 8; ++c) {
+            const uint4 x = *reinterpret_cast<const uint4 *>(krow + 8 * c);
+            const float kf[8] = {bf16lo(x.x), bf16hi(x.x), bf16lo(x.y), bf16hi(x.y),
+                                 bf16lo(x.z), bf16hi(x.z), bf16lo(x.w), bf16hi(x.w)};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int g = 0; g < G; ++g) s[g] = fmaf(qs[g * SPARK_D + 8 * c + e], kf[e], s[g]);
+        }
+        // online softmax (log2 domain); probabilities to LDS
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float sg = valid ? s[g] : -INFINITY;
+            const float mnew = fmaxf(m[g], wave_max(sg));          // finite: lane 0 of the chunk is valid
+            const float alpha = fast_exp2(m[g] - mnew);             // m = -inf -> 0
+            const float p = fast_exp2(sg - mnew);
+            m[g] = mnew;
+            l[g] = fmaf(l[g], alpha, p);
+            acc[g][0] *= alpha;
+            acc[g][1] *= alpha;
+            pw[g * 64 + lane] = p;
+        }
+        wave_lds_sync();
+        // weighted sum, lane = channels 2l, 2l+1; eight value rows in flight
+        const int nval = (len - c0 < 64) ? (len - c0) : 64;
+        const uint16_t *vbase = P.tail_v + ((row0 + c0) * P.Hkv + h) * SPARK_D + 2 * lane;
+        const int64_t vstep = (int64_t)P.Hkv * SPARK_D;
+        for (int t0 = 0; t0 < nval; t0 += 8) {
+            uint32_t vw[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int tt = (t0 + u < nval) ? (t0 + u) : (nval - 1);
+                vw[u] = *reinterpret_cast<const uint32_t *>(vbase + tt * vstep);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool on = t0 + u < nval;
+                const float v0 = bf16lo(vw[u]), v1 = bf16hi(vw[u]);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const float p = on ? pw[g * 64 + ((t0 + u) & 63)] : 0.0f;
+                    acc[g][0] = fmaf(p, v0, acc[g][0]);
+                    acc[g][1] = fmaf(p, v1, acc[g][1]);
+                }
+            }
+        }
+        wave_lds_sync();
+    }
+    // merge the wavefronts and write the partial (device-scope stores, as the sequence splits do)
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float lt = wave_sum(l[g]);
+        if (lane == 0) { red_m[wave][g] = m[g]; red_l[wave][g] = lt; }
+        red_acc[(wave * G + g) * SPARK_D + 2 * lane] = acc[g][0];
+        red_acc[(wave * G + g) * SPARK_D + 2 * lane + 1] = acc[g][1];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
+        const int g = idx / SPARK_D, ch = idx % SPARK_D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) M = fmaxf(M, red_m[w][g]);
+        const float Ms = (M == -INFINITY) ? 0.0f : M;
+        float Lsum = 0.0f, A = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) {
+            const float f = fast_exp2(red_m[w][g] - Ms);
+            Lsum = fmaf(red_l[w][g], f, Lsum);
+            A = fmaf(red_acc[(w * G + g) * SPARK_D + ch], f, A);
+        }
+        const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + P.nsplit + part;
+        st_agent(&P.part_acc[slot * SPARK_D + ch], A);
+        if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
+    }
+}
+
 // resident blocks per compute unit the register budget is held to (three was measured no faster
 // than two and spills once the table gathers are batched)
 constexpr int decode_min_blocks(int, int) { return 2; }
@@ -150,9 +267,18 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep tile addressing scalar
     const SparkLayout &L = P.L;
     const int T = TCT ? TCT : L.T;
-    const int split = blockIdx.x % P.nsplit;
-    const int bh = blockIdx.x / P.nsplit;
+    // blocks [0, B * Hkv * nsplit) are sequence splits; when rows have been appended after prefill, B * Hkv *
+    // ntail more blocks follow, each taking 256 of a (batch, KV head)'s appended rows
+    const int nmain = (int)L.batch * P.Hkv * P.nsplit;
+    const bool is_tail = (int)blockIdx.x >= nmain;      // block-uniform
+    const int split = is_tail ? P.nsplit : (int)(blockIdx.x % P.nsplit);
+    const int bh = is_tail ? ((int)blockIdx.x - nmain) / P.ntail : (int)(blockIdx.x / P.nsplit);
     const int h = bh % P.Hkv, b = bh / P.Hkv;
+    if (is_tail) {
+        static_assert(sizeof(qtab) >= G * SPARK_D * 4 && sizeof(Pbuf) >= kDecodeWaves * G * 64 * 4, "LDS reuse");
+        tail_partial<G>(P, b, h, ((int)blockIdx.x - nmain) % P.ntail, qtab, reinterpret_cast<float *>(&Pbuf[0][0][0][0]), red_m, red_l,
+                        reinterpret_cast<float *>(&wbuf[0][0]));
+    } else {
     const int s0 = P.cu[b], s1 = P.cu[b + 1];
 
     // ---- tiles of this split
@@ -579,18 +705,19 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         st_agent(&P.part_acc[slot * SPARK_D + ch], A);
         if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
     }
+    }   // sequence split
 
     // ---- the last block of this (batch, KV head) to get here merges the splits.
     // The partials are written and read with device-scope accesses (they go to the point where
     // all the chip's L2 slices agree), each thread waits for its own stores to be acknowledged,
     // and only then is the block's arrival counted.  That orders partials before the count
-    // without a device-wide cache write-back.  atomicInc wraps at nsplit-1, which leaves the
+    // without a device-wide cache write-back.  atomicInc wraps at the number of arrivals - 1, which leaves the
     // counter at zero for the next call.
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have completed
     __syncthreads();
     if (tid == 0) {
-        const uint32_t old = atomicInc(&P.counters[bh], (uint32_t)(P.nsplit - 1));
-        last_flag = (old == (uint32_t)(P.nsplit - 1));
+        const uint32_t old = atomicInc(&P.counters[bh], (uint32_t)(P.nmerge - 1));
+        last_flag = (old == (uint32_t)(P.nmerge - 1));
     }
     __syncthreads();
     if (!last_flag) return;
@@ -651,117 +778,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     }
 }
 
-// ---------------------------------------------------------------- appended (never pruned) rows
-
-// [Sec. "Preliminaries": each decode step concatenates the new token's key and value to the cache; pruning
-//  happens once, at prefill, so these rows stay dense.]  One block per (batch, KV head) runs plain attention
-// over the sequence's appended rows and leaves the softmax state (m, l, unnormalised output) in the extra
-// partial slot; the decode kernel, launched after it on the same stream, folds that slot in with the
-// sequence splits.  tail_k / tail_v are [B, cap, Hkv, 128] bf16, tail_len [B].
-struct TailParams {
-    const uint16_t *q;
-    const uint16_t *tail_k, *tail_v;
-    const int32_t *tail_len;
-    float *part_acc, *part_ml;
-    int cap, Hq, Hkv, nslots, slot;
-    float scale_log2;
-};
-
-template <int G>
-__global__ __launch_bounds__(kDecodeWaves * 64) void spark_tail_partial_kernel(TailParams P)
-{
-    __shared__ float qs[G][SPARK_D];
-    __shared__ float Psh[kDecodeWaves][G][64];
-    __shared__ float red_acc[kDecodeWaves][G][SPARK_D];
-    __shared__ float red_m[kDecodeWaves][G], red_l[kDecodeWaves][G];
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int bh = blockIdx.x, h = bh % P.Hkv, b = bh / P.Hkv;
-    int len = P.tail_len[b];
-    len = len < 0 ? 0 : (len > P.cap ? P.cap : len);
-    for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
-        const int g = idx / SPARK_D, j = idx % SPARK_D;
-        qs[g][j] = bf16lo(P.q[((int64_t)b * P.Hq + h * G + g) * SPARK_D + j]) * P.scale_log2;
-    }
-    __syncthreads();
-    float m[G], l[G], acc[G][2];
-#pragma unroll
-    for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.0f; acc[g][0] = acc[g][1] = 0.0f; }
-    const int64_t row0 = (int64_t)b * P.cap;
-    for (int c0 = wave * 64; c0 < len; c0 += kDecodeWaves * 64) {
-        // scores, lane = token
-        const int t = c0 + lane;
-        const bool valid = t < len;
-        const uint16_t *krow = P.tail_k + ((row0 + (valid ? t : len - 1)) * P.Hkv + h) * SPARK_D;
-        float s[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) s[g] = 0.0f;
-        for (int c = 0; c < SPARK_D / 8; ++c) {
-            const uint4 x = *reinterpret_cast<const uint4 *>(krow + 8 * c);
-            const float kf[8] = {bf16lo(x.x), bf16hi(x.x), bf16lo(x.y), bf16hi(x.y),
-                                 bf16lo(x.z), bf16hi(x.z), bf16lo(x.w), bf16hi(x.w)};
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-#pragma unroll
-                for (int g = 0; g < G; ++g) s[g] = fmaf(qs[g][8 * c + e], kf[e], s[g]);
-        }
-        // online softmax (log2 domain); probabilities to LDS
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float sg = valid ? s[g] : -INFINITY;
-            const float mnew = fmaxf(m[g], wave_max(sg));          // finite: lane 0 of the chunk is valid
-            const float alpha = fast_exp2(m[g] - mnew);             // m = -inf -> 0
-            const float p = fast_exp2(sg - mnew);
-            m[g] = mnew;
-            l[g] = fmaf(l[g], alpha, p);
-            acc[g][0] *= alpha;
-            acc[g][1] *= alpha;
-            Psh[wave][g][lane] = p;
-        }
-        wave_lds_sync();
-        // weighted sum, lane = channels 2l, 2l+1
-        const int nval = (len - c0 < 64) ? (len - c0) : 64;
-        for (int tt = 0; tt < nval; ++tt) {
-            const uint32_t vw = *reinterpret_cast<const uint32_t *>(
-                P.tail_v + ((row0 + c0 + tt) * P.Hkv + h) * SPARK_D + 2 * lane);
-            const float v0 = bf16lo(vw), v1 = bf16hi(vw);
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float p = Psh[wave][g][tt];
-                acc[g][0] = fmaf(p, v0, acc[g][0]);
-                acc[g][1] = fmaf(p, v1, acc[g][1]);
-            }
-        }
-        wave_lds_sync();
-    }
-    // merge the wavefronts and write the partial
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const float lt = wave_sum(l[g]);
-        if (lane == 0) { red_m[wave][g] = m[g]; red_l[wave][g] = lt; }
-        red_acc[wave][g][2 * lane] = acc[g][0];
-        red_acc[wave][g][2 * lane + 1] = acc[g][1];
-    }
-    __syncthreads();
-    for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
-        const int g = idx / SPARK_D, ch = idx % SPARK_D;
-        float M = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kDecodeWaves; ++w) M = fmaxf(M, red_m[w][g]);
-        const float Ms = (M == -INFINITY) ? 0.0f : M;
-        float Lsum = 0.0f, A = 0.0f;
-#pragma unroll
-        for (int w = 0; w < kDecodeWaves; ++w) {
-            const float f = fast_exp2(red_m[w][g] - Ms);
-            Lsum = fmaf(red_l[w][g], f, Lsum);
-            A = fmaf(red_acc[w][g][ch], f, A);
-        }
-        const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + P.slot;
-        P.part_acc[slot * SPARK_D + ch] = A;
-        if (ch == 0) { P.part_ml[slot * 2] = M; P.part_ml[slot * 2 + 1] = Lsum; }
-    }
-}
-
 // Zeroes the arrival counters of a fresh workspace.
 __global__ void spark_zero_kernel(uint32_t *p, int n)
 {
@@ -818,33 +834,6 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
                               void *out, int out_f32, const uint16_t *tail_k, const uint16_t *tail_v,
                               const int32_t *tail_len, int tail_cap, hipStream_t st)
 {
-    const int Gq = Hq / L.n_kv_heads;
-    if (tail_k) {
-        TailParams Tp;
-        Tp.q = q;
-        Tp.tail_k = tail_k;
-        Tp.tail_v = tail_v;
-        Tp.tail_len = tail_len;
-        Tp.part_acc = part_acc;
-        Tp.part_ml = part_ml;
-        Tp.cap = tail_cap;
-        Tp.Hq = Hq;
-        Tp.Hkv = L.n_kv_heads;
-        Tp.nslots = nsplit + 1;
-        Tp.slot = nsplit;
-        Tp.scale_log2 = softmax_scale * 1.44269504088896340736f;
-        const dim3 grid(L.batch * L.n_kv_heads), block(kDecodeWaves * 64);
-        switch (Gq) {
-            case 1: hipLaunchKernelGGL(spark_tail_partial_kernel<1>, grid, block, 0, st, Tp); break;
-            case 2: hipLaunchKernelGGL(spark_tail_partial_kernel<2>, grid, block, 0, st, Tp); break;
-            case 4: hipLaunchKernelGGL(spark_tail_partial_kernel<4>, grid, block, 0, st, Tp); break;
-            case 8: hipLaunchKernelGGL(spark_tail_partial_kernel<8>, grid, block, 0, st, Tp); break;
-            case 16: hipLaunchKernelGGL(spark_tail_partial_kernel<16>, grid, block, 0, st, Tp); break;
-            default: return hipErrorInvalidValue;
-        }
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
     DecodeParams P;
     P.q = q;
     P.packed = packed;
@@ -862,12 +851,18 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.Hq = Hq;
     P.Hkv = L.n_kv_heads;
     P.nsplit = nsplit;
-    P.nslots = nsplit + 1;
-    P.nmerge = nsplit + (tail_k ? 1 : 0);
+    const int tail_slots = tail_cap > 0 ? (tail_cap + kDecodeWaves * 64 - 1) / (kDecodeWaves * 64) : 1;
+    P.ntail = tail_k ? tail_slots : 0;
+    P.nslots = nsplit + tail_slots;
+    P.nmerge = nsplit + P.ntail;
+    P.tail_k = tail_k;
+    P.tail_v = tail_v;
+    P.tail_len = tail_len;
+    P.tail_cap = tail_cap;
     P.scale_log2 = softmax_scale * 1.44269504088896340736f;
     P.L = L;
     const int G = P.Hq / P.Hkv;
-    const int nblocks = L.batch * P.Hkv * P.nsplit;
+    const int nblocks = L.batch * P.Hkv * (P.nsplit + P.ntail);
     switch (G) {
         case 1: return launch_g<1>(P, nblocks, st);
         case 2: return launch_g<2>(P, nblocks, st);
