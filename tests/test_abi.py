@@ -85,3 +85,36 @@ def test_alignment_strides_and_workspace_are_checked_before_any_launch():
     assert lib.spark_prune(ctypes.byref(_desc(window=0)), A, A, A, A, None, 0, None) == 1
     assert lib.spark_probe_read(None, 1024, A, 4, None) == 1
     assert lib.spark_probe_read(A, 8, A, 4, None) == 1
+
+
+def test_value_cache_and_tail_entry_points_check_their_arguments_on_the_host():
+    lib = spark.load()
+    A = 0x7F0000000000
+    rows = 8 * 32768 * 8
+    # value cache: rows of 16 mask bytes + 2 bytes per kept entry, no statistic, no a section
+    assert spark.packed_values_bytes(_desc(keep_v=64)) == 256 + rows * 144
+    assert spark.packed_values_bytes(_desc(keep_v=26)) == 256 + rows * 72       # 68 -> rows are 8-byte multiples
+    assert spark.packed_values_bytes(_desc()) == 0                               # keep_v = 0: values stay dense
+    assert spark.packed_values_bytes(_desc(keep_v=129)) == 0
+    d = _desc(keep_v=64)
+    ok_ws = spark.decode_workspace_bytes(d)
+    assert lib.spark_prune_values(ctypes.byref(_desc()), A, A, None) == 1        # keep_v missing
+    assert lib.spark_prune_values(ctypes.byref(d), None, A, None) == 1
+    assert lib.spark_prune_values(ctypes.byref(d), A, A + 64, None) == 1         # packed buffer misaligned
+    assert lib.spark_prune_values(ctypes.byref(_desc(keep_v=64, v_token_stride=1 << 25)), A, A, None) == 2
+    assert lib.spark_decode_attn_values(ctypes.byref(d), A, A, None, A, A, A, ok_ws, None) == 1
+    assert lib.spark_decode_attn_values(ctypes.byref(_desc()), A, A, A, A, A, A, ok_ws, None) == 1
+    assert lib.spark_decode_attn_values(ctypes.byref(_desc(keep_v=64, pack_dtype=spark.PACK_INT8)), A, A, A, A, A, A,
+                                        ok_ws, None) == 2
+    assert lib.spark_unpack_values(ctypes.byref(d), None, None, None, None) == 1
+    # appended rows: capacity enters the workspace size (one spare slot per 256 rows)
+    dt = _desc(tail_capacity=600)
+    ns = spark.decode_splits(dt)
+    assert spark.decode_workspace_bytes(dt) == 8 * 32 * (ns + 3) * 130 * 4 + 8 * 8 * 4
+    ws_t = spark.decode_workspace_bytes(dt)
+    assert lib.spark_decode_attn_tail(ctypes.byref(dt), A, A, A, A, None, A, A, A, A, ws_t, None) == 1
+    assert lib.spark_decode_attn_tail(ctypes.byref(dt), A, A, A, A, A, None, A, A, A, ws_t, None) == 1
+    assert lib.spark_decode_attn_tail(ctypes.byref(dt), A, A, A, A, A + 8, A, A, A, A, ws_t, None) == 1
+    assert lib.spark_decode_attn_tail(ctypes.byref(_desc()), A, A, A, A, A, A, A, A, A, ws_t, None) == 1   # capacity 0
+    assert lib.spark_decode_attn_tail(ctypes.byref(dt), A, A, A, A, A, A, A, A, A, ws_t - 1, None) == 3
+    assert spark.packed_bytes(_desc(tail_capacity=-1)) == 0

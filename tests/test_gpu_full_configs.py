@@ -77,3 +77,61 @@ def test_config4_ragged_batch64_keep64():
 def test_config5_qwen32b_131k(int8):
     w, t = _tensors(5)
     _check(w, t, int8=int8)
+
+
+def test_config2_pruned_values_keep64():
+    """Keys at T = 26 and values at T_v = 64 (the appendix's joint pruning), every row and output checked."""
+    import torch
+    from tests.gpu_util import make_desc, to_dev
+    w, t = _tensors(2)
+    Tv = 64
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    pv = oracle.prune_values(t.v, t.layout, Tv)
+    ref = oracle.decode_literal(t.q, pr, oracle.expand_values(pv), "NHD", t.cu)
+    desc = make_desc(w)
+    desc.keep_v = Tv
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.empty(spark.packed_bytes(desc), dtype=torch.uint8, device="cuda")
+    packed_v = torch.empty(spark.packed_values_bytes(desc), dtype=torch.uint8, device="cuda")
+    dv = to_dev(t.v)
+    spark.prune(desc, to_dev(t.k), to_dev(t.qwin), dcu, packed)
+    spark.prune_values(desc, dv, packed_v)
+    del dv
+    mask = torch.empty((w.total, w.n_kv_heads, 4), dtype=torch.int32, device="cuda")
+    vals = torch.empty((w.total, w.n_kv_heads, Tv), dtype=torch.int16, device="cuda")
+    spark.unpack_values(desc, packed_v, mask, vals)
+    print(f"{w.name} Tv={Tv}: value near-ties(<1e-6)={pv.near_ties()} of {pv.gap.size}")
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), pv.mask), "kept value-channel sets differ"
+    assert np.array_equal(vals.cpu().numpy().view(np.uint16), pv.kept)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    spark.decode_attn_values(desc, to_dev(t.q), packed, packed_v, dcu, out, spark.new_decode_workspace(desc))
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    print(f"   decode max|err|={err.max():.3e} mean|err|={err.mean():.3e}")
+    assert err.max() <= 1e-2 and err.mean() <= 1e-3
+
+
+def test_config2_with_128_appended_rows():
+    import torch
+    from tests.gpu_util import make_desc, to_dev
+    w, t = _tensors(2)
+    cap = 128
+    rng = np.random.default_rng(5)
+    shape = (w.batch, cap, w.n_kv_heads, w.head_dim)
+    tk = wl.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    tv = wl.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    tl = rng.integers(1, cap + 1, size=w.batch).astype(np.int32)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    ref = oracle.decode_literal_tail(t.q, pr, t.v, t.layout, t.cu, tk, tv, tl)
+    desc = make_desc(w)
+    desc.tail_capacity = cap
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.empty(spark.packed_bytes(desc), dtype=torch.uint8, device="cuda")
+    spark.prune(desc, to_dev(t.k), to_dev(t.qwin), dcu, packed)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    spark.decode_attn_tail(desc, to_dev(t.q), packed, to_dev(t.v), dcu, to_dev(tk), to_dev(tv),
+                           torch.from_numpy(tl).cuda(), out, spark.new_decode_workspace(desc))
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    print(f"{w.name} + appended rows {tl.tolist()}: decode max|err|={err.max():.3e} mean|err|={err.mean():.3e}")
+    assert err.max() <= 1e-2 and err.mean() <= 1e-3
