@@ -214,6 +214,14 @@ spark_status spark_decode_attn_values(const spark_desc *desc, const void *q_bf16
                                       const void *packed_v, const int32_t *cu_seqlens, void *out,
                                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* spark_decode_attn_values with appended, never-pruned rows (arguments as in spark_decode_attn_tail; the
+ * appended values are dense like the appended keys). */
+spark_status spark_decode_attn_values_tail(const spark_desc *desc, const void *q_bf16, const void *packed,
+                                           const void *packed_v, const int32_t *cu_seqlens,
+                                           const void *tail_k_bf16, const void *tail_v_bf16,
+                                           const int32_t *tail_len, void *out, void *workspace,
+                                           size_t workspace_bytes, void *hip_stream);
+
 /*
  * Canonical export of a packed value cache (parity tests and debugging).  Either output may be NULL.
  *   mask_out  uint32 [total_tokens, n_kv_heads, 4]       bit j%32 of word j/32 = channel j kept

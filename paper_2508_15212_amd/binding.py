@@ -19,7 +19,8 @@ OUT_BF16, OUT_F32 = 0, 1
 
 EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspace", "spark_decode_workspace_init", "spark_decode_splits",
            "spark_prune", "spark_decode_attn", "spark_unpack", "spark_probe_read", "spark_status_string",
-           "spark_packed_values_bytes", "spark_prune_values", "spark_unpack_values", "spark_decode_attn_values", "spark_decode_attn_tail"]
+           "spark_packed_values_bytes", "spark_prune_values", "spark_unpack_values", "spark_decode_attn_values", "spark_decode_attn_tail",
+           "spark_decode_attn_values_tail"]
 
 
 class SparkError(RuntimeError):
@@ -82,6 +83,8 @@ def load() -> ctypes.CDLL:
     lib.spark_decode_attn_values.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.spark_decode_attn_tail.restype = ctypes.c_int
     lib.spark_decode_attn_tail.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.spark_decode_attn_values_tail.restype = ctypes.c_int
+    lib.spark_decode_attn_values_tail.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.spark_unpack_values.restype = ctypes.c_int
     lib.spark_unpack_values.argtypes = [dp, vp, vp, vp, vp]
     lib.spark_probe_read.restype = ctypes.c_int
@@ -171,6 +174,15 @@ def decode_attn_tail(desc: SparkDesc, q: torch.Tensor, packed: torch.Tensor, v: 
                                        _ptr(tail_v), _ptr(tail_len), _ptr(out), _ptr(workspace),
                                        workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "spark_decode_attn_tail")
+
+
+def decode_attn_values_tail(desc: SparkDesc, q: torch.Tensor, packed: torch.Tensor, packed_v: torch.Tensor,
+                            cu: torch.Tensor, tail_k: torch.Tensor, tail_v: torch.Tensor, tail_len: torch.Tensor,
+                            out: torch.Tensor, workspace: torch.Tensor) -> None:
+    rc = load().spark_decode_attn_values_tail(ctypes.byref(desc), _ptr(q), _ptr(packed), _ptr(packed_v), _ptr(cu),
+                                              _ptr(tail_k), _ptr(tail_v), _ptr(tail_len), _ptr(out), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "spark_decode_attn_values_tail")
 
 
 def unpack_values(desc: SparkDesc, packed_v: torch.Tensor, mask=None, vals=None) -> None:

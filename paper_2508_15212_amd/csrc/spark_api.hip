@@ -295,6 +295,17 @@ spark_status spark_decode_attn_values(const spark_desc *desc, const void *q_bf16
                          hip_stream);
 }
 
+spark_status spark_decode_attn_values_tail(const spark_desc *desc, const void *q_bf16, const void *packed,
+                                           const void *packed_v, const int32_t *cu_seqlens,
+                                           const void *tail_k_bf16, const void *tail_v_bf16,
+                                           const int32_t *tail_len, void *out, void *workspace,
+                                           size_t workspace_bytes, void *hip_stream)
+{
+    if (!packed_v || !tail_k_bf16) return SPARK_ERR_INVALID_ARG;
+    return decode_common(desc, q_bf16, packed, nullptr, packed_v, cu_seqlens, out, workspace, workspace_bytes,
+                         hip_stream, tail_k_bf16, tail_v_bf16, tail_len);
+}
+
 spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *mask_out, void *vals_out,
                           float *mu_out, float *scale_out, float *a_out, void *hip_stream)
 {

@@ -69,3 +69,32 @@ def test_tail_with_empty_prefix_and_empty_tail():
     w = wl.small(name="tail_edges", batch=6, seqlens=(0, 1, 63, 64, 65, 0), keep=26, seed=430)
     got, _ = _tail_case(w, cap=8, tail_len=(5, 0, 8, 1, 0, 0), seed=430)
     assert np.all(got[5] == 0)          # neither prefix nor appended rows: zero output
+
+
+def test_tail_together_with_pruned_values():
+    """Packed keys + packed values + appended dense rows in one call."""
+    w = wl.small(name="tail_kv", batch=3, n_q_heads=8, n_kv_heads=2, keep=26, seqlens=(257, 64, 190), seed=440)
+    t = wl.generate(w)
+    cap, Tv = 40, 64
+    rng = np.random.default_rng(440)
+    shape = (w.batch, cap, w.n_kv_heads, w.head_dim)
+    tk = wl.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    tv = wl.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    tl = np.asarray((40, 7, 0), np.int32)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    pv = oracle.prune_values(t.v, t.layout, Tv)
+    ref = oracle.decode_literal_tail(t.q, pr, oracle.expand_values(pv), "NHD", t.cu, tk, tv, tl)
+    desc = make_desc(w)
+    desc.keep_v, desc.tail_capacity = Tv, cap
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.empty(max(spark.packed_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    packed_v = torch.empty(max(spark.packed_values_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    spark.prune(desc, to_dev(t.k), to_dev(t.qwin), dcu, packed)
+    spark.prune_values(desc, to_dev(t.v), packed_v)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    spark.decode_attn_values_tail(desc, to_dev(t.q), packed, packed_v, dcu, to_dev(tk), to_dev(tv),
+                                  torch.from_numpy(tl).cuda(), out, spark.new_decode_workspace(desc))
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    print(f"tail + pruned values: max|err|={err.max():.3e} mean|err|={err.mean():.3e}")
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
