@@ -135,7 +135,7 @@ spark_status spark_prune(const spark_desc *desc, const void *k_bf16, const void 
  *   packed     in   written by spark_prune with the same batch / n_kv_heads / keep /
  *                   pack_dtype / total_tokens and the same cu_seqlens
  *   v_bf16     in   dense values, bf16, addressed with v_*_stride
- *   out        out  [batch, n_q_heads, 128], bf16 or float32 per desc->out_dtype
+ *   out        out  [batch, n_q_heads, 128], bf16 or float32 per desc->out_dtype, 8-byte aligned
  *   workspace       spark_decode_workspace(desc) bytes, 16-byte aligned, prepared with
  *                   spark_decode_workspace_init (split partials and arrival counters)
  * One kernel launch: the sequence is split over blocks, and the block that finishes last for a

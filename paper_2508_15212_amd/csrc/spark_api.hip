@@ -239,7 +239,7 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
         if (!strides_ok(desc->v_token_stride, desc->v_head_stride)) return SPARK_ERR_INVALID_ARG;
         if (!aligned(v_bf16, 16)) return SPARK_ERR_INVALID_ARG;
     }
-    if (!aligned(packed, 256) || !aligned(workspace, 16) || !aligned(q_bf16, 2) || !aligned(out, 4))
+    if (!aligned(packed, 256) || !aligned(workspace, 16) || !aligned(q_bf16, 2) || !aligned(out, 8))
         return SPARK_ERR_INVALID_ARG;
     if (tail_k) {
         if (!tail_v || !tail_len || desc->tail_capacity < 1) return SPARK_ERR_INVALID_ARG;

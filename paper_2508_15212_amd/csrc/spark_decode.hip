@@ -721,9 +721,62 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     }
     __syncthreads();
     if (!last_flag) return;
-    // Each thread owns output elements (g, ch) and folds the nsplit partial states into one with
-    // the running-maximum rule, eight splits' loads in flight at a time, two elements at once.
     constexpr int NTH = kDecodeWaves * 64;
+    if (P.nmerge <= 256) {
+        // The (m, l) pairs of all partials go to LDS first (one 8-byte device-scope load each); then each
+        // thread owns two adjacent output channels of one head and folds the partials' accumulators with
+        // sixteen 8-byte loads in flight.  (The per-wavefront buffers are free: every thread passed the
+        // barrier above after its last read of them.)
+        float2 *mlsh = reinterpret_cast<float2 *>(&wbuf[0][0]);     // [G][nmerge]
+        static_assert(sizeof(wbuf) >= (size_t)G * 256 * sizeof(float2), "LDS reuse");
+        for (int idx = tid; idx < G * P.nmerge; idx += NTH) {
+            const int g = idx / P.nmerge, i = idx % P.nmerge;
+            const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + i;
+            const uint64_t raw = __hip_atomic_load(reinterpret_cast<const uint64_t *>(P.part_ml + slot * 2),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            mlsh[idx] = make_float2(__uint_as_float((uint32_t)raw), __uint_as_float((uint32_t)(raw >> 32)));
+        }
+        __syncthreads();
+        for (int e = tid; e < G * (SPARK_D / 2); e += NTH) {
+            const int g = e / (SPARK_D / 2), c2 = e % (SPARK_D / 2);
+            const float2 *mlg = mlsh + g * P.nmerge;
+            float M = -INFINITY;
+            for (int i = 0; i < P.nmerge; ++i) M = fmaxf(M, mlg[i].x);
+            const float Ms = (M == -INFINITY) ? 0.0f : M;
+            const int64_t bq = (int64_t)b * P.Hq + h * G + g;
+            const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + bq * P.nslots * SPARK_D + 2 * c2);
+            float Lsum = 0.0f, A0 = 0.0f, A1 = 0.0f;
+            for (int i0 = 0; i0 < P.nmerge; i0 += 16) {
+                uint64_t av[16];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const int i = (i0 + k < P.nmerge) ? (i0 + k) : (P.nmerge - 1);
+                    av[k] = __hip_atomic_load(pa + (int64_t)i * (SPARK_D / 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    if (i0 + k < P.nmerge) {
+                        const float2 mlv = mlg[i0 + k];
+                        const float f = fast_exp2(mlv.x - Ms);      // m = -inf -> 0
+                        Lsum = fmaf(mlv.y, f, Lsum);
+                        A0 = fmaf(__uint_as_float((uint32_t)av[k]), f, A0);
+                        A1 = fmaf(__uint_as_float((uint32_t)(av[k] >> 32)), f, A1);
+                    }
+                }
+            }
+            const float o0 = (Lsum > 0.0f) ? (A0 / Lsum) : 0.0f, o1 = (Lsum > 0.0f) ? (A1 / Lsum) : 0.0f;
+            if (P.out_f32) {
+                reinterpret_cast<float2 *>(P.out)[bq * (SPARK_D / 2) + c2] = make_float2(o0, o1);
+            } else {
+                const uint32_t packed2 = (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o0) |
+                                         ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o1) << 16);
+                reinterpret_cast<uint32_t *>(P.out)[bq * (SPARK_D / 2) + c2] = packed2;
+            }
+        }
+        return;
+    }
+    // More than 256 partials: each thread owns output elements (g, ch) and folds the partial states one by
+    // one with the running-maximum rule, eight splits' loads in flight at a time, two elements at once.
     for (int idx0 = tid; idx0 < G * SPARK_D; idx0 += 2 * NTH) {
         float M[2], Lsum[2], A[2];
         const float *ml[2], *pa[2];
