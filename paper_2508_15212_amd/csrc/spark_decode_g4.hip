@@ -1,0 +1,6 @@
+// Decode-attention kernels for query groups of 4 heads per KV head.
+#include "spark_decode_kernel.h"
+
+namespace spark {
+template hipError_t launch_g<4>(const DecodeParams &, int, hipStream_t);
+}

@@ -1,0 +1,879 @@
+// Decode attention over the packed (channel-pruned) key cache for gfx950 (wave64).
+//
+// [Sec. "SparK", "Channel Recovery": pruned entry (n, j) is rebuilt as mu_n / a_j (the
+//  degenerate recovery function) and the scores are those of standard attention on the
+//  rebuilt keys; Sec. "Preliminaries", Eq. (4): softmax over the cached tokens, then P V.]
+//
+// The rebuilt key row is never formed.  With d_nj = k_nj - mu_n / a_j for kept channels,
+//     <q_g, ktilde_n> = sum_{j kept} q_gj d_nj + mu_n * R_g,   R_g = sum_j q_gj / a_j,
+// so a token costs T gathers from a 128-entry table {q_0j .. q_(G-1)j, 1/a_j} held in LDS.
+//
+// Work decomposition: one block of 4 wavefronts per (batch, KV head, sequence split); each
+// wavefront streams whole tiles of 64 tokens.  Per tile:
+//   1. lane = token: read the packed row (coalesced, see spark_layout.h), walk its mask
+//      bits, accumulate the G scores of the KV head's query group in float32;
+//   2. online softmax per query head (running maximum m, per-lane partial sums l);
+//   3. probabilities go through LDS into the A operand of the 16x16x32 bf16 MFMA (rows =
+//      query heads, K = tokens), split into a high and a low bf16 part so P keeps ~16
+//      significant bits; V rows are read 16 bytes per lane, transposed in registers with
+//      byte permutes into B operands (K = tokens, N = channels) and accumulated in float32.
+// With a channel-pruned VALUE cache (App. "Pruning Value Cache Channels": pruned entries are dropped, i.e.
+// contribute 0) step 3 reads packed value rows instead (lane = token, coalesced), parks them in LDS and
+// rebuilds the dense 16-byte pieces the MFMA path wants with lane = (token, group of 8 channels): the
+// group's mask byte and the number of kept entries before it locate a window of 8 candidates in the
+// packed row, and a 256-entry table of byte-permute selectors spreads the candidates to their channels
+// (zeros elsewhere).  The cost does not depend on how many entries a row keeps.
+// Split partials (m, l, unnormalised output) go to the workspace; the block that arrives last at
+// its (batch, KV head) counter merges them and writes the output, so one launch does the step.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "spark_kernels.h"
+#include "spark_layout.h"
+
+namespace spark {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct DecodeParams {
+    const uint16_t *q;       // [B, Hq, 128] bf16
+    const uint8_t *packed;   // packed key cache
+    const uint16_t *v;       // dense values (NULL when the value cache is packed)
+    const uint8_t *packed_v; // packed value cache (value-channel pruning), else NULL
+    SparkLayout Lv;          // its layout
+    int64_t v_tok_stride, v_head_stride;
+    const int32_t *cu;       // [B+1]
+    float *part_acc;         // [B*Hq*nsplit][128]
+    float *part_ml;          // [B*Hq*nsplit][2]  (m in log2 units, l)
+    uint32_t *counters;      // [B*Hkv] arrival counters, zero between calls
+    void *out;               // [B, Hq, 128] bf16 or float32
+    int out_f32;
+    int Hq, Hkv, nsplit;
+    int nslots;              // partial slots per (batch, q head): nsplit + ntail_slots (the last ones are the appended rows')
+    int nmerge;              // partials the last block folds: nsplit, or nsplit + ntail when appended rows exist
+    int ntail;               // blocks per (batch, KV head) for the appended rows, 256 rows each (0: none)
+    const uint16_t *tail_k, *tail_v;   // appended never-pruned rows [B, tail_cap, Hkv, 128] bf16, or NULL
+    const int32_t *tail_len;           // [B]
+    int tail_cap;
+    float scale_log2;        // softmax scale * log2(e)
+    SparkLayout L;
+};
+
+constexpr int kDecodeWaves = 4;
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    // LDS operations of one wavefront execute in order; this only stops the compiler from
+    // moving accesses across the point where lanes exchange data through LDS.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Maximum over the 64 lanes, returned wave-uniform.  Data-parallel-primitive moves: two quad
+// permutes and two row rotates leave each row of 16 lanes holding its row maximum, two row
+// broadcasts fold the four rows into lane 63.  Lanes a step does not address keep their value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_max_step(float x)
+{
+    const int xi = __float_as_int(x);
+    const float y = __int_as_float(__builtin_amdgcn_update_dpp(xi, xi, CTRL, ROW_MASK, 0xF, false));
+    return fmaxf(x, y);
+}
+
+__device__ __forceinline__ float wave_max(float x)
+{
+    x = dpp_max_step<0xB1, 0xF>(x);    // quad_perm [1,0,3,2]
+    x = dpp_max_step<0x4E, 0xF>(x);    // quad_perm [2,3,0,1]
+    x = dpp_max_step<0x124, 0xF>(x);   // row_ror 4
+    x = dpp_max_step<0x128, 0xF>(x);   // row_ror 8
+    x = dpp_max_step<0x142, 0xA>(x);   // row_bcast 15 into rows 1 and 3
+    x = dpp_max_step<0x143, 0xC>(x);   // row_bcast 31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+// device-scope (all XCDs) relaxed store / load of one float
+__device__ __forceinline__ void st_agent(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_agent(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ uint32_t u4c(const uint4 &v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// ---------------------------------------------------------------- appended (never pruned) rows
+
+// [Sec. "Preliminaries": each decode step concatenates the new token's key and value to the cache; pruning
+//  happens once, at prefill, so these rows stay dense.]  One extra block per (batch, KV head) of the decode
+// grid runs plain attention over the sequence's appended rows and leaves the softmax state (m, l,
+// unnormalised output) in the spare partial slot; it then takes part in the arrival count like a sequence
+// split, so whichever block comes last folds it in.  qs [G][128] and Psh [4][G][64] are LDS scratch.
+template <int G>
+__device__ __forceinline__ void tail_partial(const DecodeParams &P, int b, int h, int part, float *qs, float *Psh,
+                                             float (*red_m)[G], float (*red_l)[G], float *red_acc /* [4][G][128] */)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int len = P.tail_len[b];
+    len = len < 0 ? 0 : (len > P.tail_cap ? P.tail_cap : len);
+    // this block's share: rows [256 * part, 256 * part + 256)
+    const int first = part * kDecodeWaves * 64;
+    len = (len < first + kDecodeWaves * 64) ? len : first + kDecodeWaves * 64;
+    for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
+        const int g = idx / SPARK_D, j = idx % SPARK_D;
+        qs[g * SPARK_D + j] = bf16lo(P.q[((int64_t)b * P.Hq + h * G + g) * SPARK_D + j]) * P.scale_log2;
+    }
+    __syncthreads();
+    float m[G], l[G], acc[G][2];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.0f; acc[g][0] = acc[g][1] = 0.0f; }
+    const int64_t row0 = (int64_t)b * P.tail_cap;
+    float *pw = Psh + wave * G * 64;
+    for (int c0 = first + wave * 64; c0 < len; c0 += kDecodeWaves * 64) {   // (one pass)
+        // scores, lane = token
+        const int t = c0 + lane;
+        const bool valid = t < len;
+        const uint16_t *krow = P.tail_k + ((row0 + (valid ? t : len - 1)) * P.Hkv + h) * SPARK_D;
+        float s[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) s[g] = 0.0f;
+#pragma unroll 4
+        for (int c = 0; c < SPARK_D / 8; ++c) {
+            const uint4 x = *reinterpret_cast<const uint4 *>(krow + 8 * c);
+            const float kf[8] = {bf16lo(x.x), bf16hi(x.x), bf16lo(x.y), bf16hi(x.y),
+                                 bf16lo(x.z), bf16hi(x.z), bf16lo(x.w), bf16hi(x.w)};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int g = 0; g < G; ++g) s[g] = fmaf(qs[g * SPARK_D + 8 * c + e], kf[e], s[g]);
+        }
+        // online softmax (log2 domain); probabilities to LDS
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float sg = valid ? s[g] : -INFINITY;
+            const float mnew = fmaxf(m[g], wave_max(sg));          // finite: lane 0 of the chunk is valid
+            const float alpha = fast_exp2(m[g] - mnew);             // m = -inf -> 0
+            const float p = fast_exp2(sg - mnew);
+            m[g] = mnew;
+            l[g] = fmaf(l[g], alpha, p);
+            acc[g][0] *= alpha;
+            acc[g][1] *= alpha;
+            pw[g * 64 + lane] = p;
+        }
+        wave_lds_sync();
+        // weighted sum, lane = channels 2l, 2l+1; eight value rows in flight
+        const int nval = (len - c0 < 64) ? (len - c0) : 64;
+        const uint16_t *vbase = P.tail_v + ((row0 + c0) * P.Hkv + h) * SPARK_D + 2 * lane;
+        const int64_t vstep = (int64_t)P.Hkv * SPARK_D;
+        for (int t0 = 0; t0 < nval; t0 += 8) {
+            uint32_t vw[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int tt = (t0 + u < nval) ? (t0 + u) : (nval - 1);
+                vw[u] = *reinterpret_cast<const uint32_t *>(vbase + tt * vstep);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool on = t0 + u < nval;
+                const float v0 = bf16lo(vw[u]), v1 = bf16hi(vw[u]);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const float p = on ? pw[g * 64 + ((t0 + u) & 63)] : 0.0f;
+                    acc[g][0] = fmaf(p, v0, acc[g][0]);
+                    acc[g][1] = fmaf(p, v1, acc[g][1]);
+                }
+            }
+        }
+        wave_lds_sync();
+    }
+    // merge the wavefronts and write the partial (device-scope stores, as the sequence splits do)
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float lt = wave_sum(l[g]);
+        if (lane == 0) { red_m[wave][g] = m[g]; red_l[wave][g] = lt; }
+        red_acc[(wave * G + g) * SPARK_D + 2 * lane] = acc[g][0];
+        red_acc[(wave * G + g) * SPARK_D + 2 * lane + 1] = acc[g][1];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
+        const int g = idx / SPARK_D, ch = idx % SPARK_D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) M = fmaxf(M, red_m[w][g]);
+        const float Ms = (M == -INFINITY) ? 0.0f : M;
+        float Lsum = 0.0f, A = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) {
+            const float f = fast_exp2(red_m[w][g] - Ms);
+            Lsum = fmaf(red_l[w][g], f, Lsum);
+            A = fmaf(red_acc[(w * G + g) * SPARK_D + ch], f, A);
+        }
+        const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + P.nsplit + part;
+        st_agent(&P.part_acc[slot * SPARK_D + ch], A);
+        if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
+    }
+}
+
+// resident blocks per compute unit the register budget is held to (three was measured no faster
+// than two and spills once the table gathers are batched)
+constexpr int decode_min_blocks(int, int) { return 2; }
+// The cache is read once per step: the streaming loads carry the non-temporal hint so they do not
+// displace each other in the L2 / memory-side cache (measured: 129 us -> 118 us on the 32K workload).
+#define NT_LOAD(p) __builtin_nontemporal_load(p)
+// TVC: 0 = dense values; > 0 = packed values with that many kept channels per row (row held in registers);
+// -1 = packed values, any count (row words read from memory as they are needed).
+template <int G, int TCT, int INT8, int TVC>
+__global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void spark_decode_kernel(DecodeParams P)
+{
+    constexpr bool PV = (TVC != 0);             // packed value cache
+    constexpr int NVW = PV ? (TVC > 0 ? (((4 + (TVC + 1) / 2) + 1) & ~1) : 4) : 1;   // value-row words in registers
+    // LDS row stride (words) of a parked value row: >= the row, and = 4 mod 8 so that 16-byte row writes of
+    // consecutive tokens fall on different banks; a row kept whole in registers is NVW words, the longest is 68
+    constexpr int RSV = PV ? (TVC > 0 ? 8 * ((NVW + 3) / 8) + 4 : 68) : 1;
+    // floats per table entry: G queries, 1/a, pad -- a multiple of 4 (16-byte gathers) that is 4 mod 8, so
+    // that the entries of different channels start in all eight 16-byte bank groups, not in half of them
+    constexpr int GP = 8 * ((G + 1 + 3) / 8) + 4;
+    constexpr int VAL0 = INT8 ? 6 : 5;
+    constexpr int NV_CT = INT8 ? (TCT + 3) / 4 : (TCT + 1) / 2;
+    constexpr int NDW_CT = (VAL0 + NV_CT + 1) & ~1;
+    constexpr int NQ_CT = NDW_CT / 4;
+
+    __shared__ __align__(16) float qtab[SPARK_D * GP];
+    __shared__ float Rsh[16];
+    __shared__ __align__(16) uint16_t Pbuf[kDecodeWaves][2][G][64];
+    // per wavefront: the accumulators at the end; with packed values, before that, the parked value rows
+    // (+ slack: the candidate window may read 4 words past a row)
+    constexpr int RED_BYTES = G * SPARK_D * 4, RAW_BYTES = (SPARK_TILE_TOKENS * RSV + 8) * 4;
+    constexpr int WBUF = (PV && RAW_BYTES > RED_BYTES) ? RAW_BYTES : RED_BYTES;
+    __shared__ __align__(16) uint8_t wbuf[kDecodeWaves][WBUF];
+    // packed values: per token 16 x {kept entries before the group, the group's mask byte}; the selector
+    // table (12 words per entry, 6 used: the odd stride spreads the entries over the LDS banks)
+    constexpr int LUTW = 12;
+    __shared__ __align__(16) uint32_t vmeta[PV ? kDecodeWaves : 1][PV ? SPARK_TILE_TOKENS * 8 : 1];
+    __shared__ __align__(16) uint32_t vlut[PV ? 256 * LUTW : 1];
+    __shared__ float red_m[kDecodeWaves][G], red_l[kDecodeWaves][G];
+    __shared__ int last_flag;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep tile addressing scalar
+    const SparkLayout &L = P.L;
+    const int T = TCT ? TCT : L.T;
+    // blocks [0, B * Hkv * nsplit) are sequence splits; when rows have been appended after prefill, B * Hkv *
+    // ntail more blocks follow, each taking 256 of a (batch, KV head)'s appended rows
+    const int nmain = (int)L.batch * P.Hkv * P.nsplit;
+    const bool is_tail = (int)blockIdx.x >= nmain;      // block-uniform
+    const int split = is_tail ? P.nsplit : (int)(blockIdx.x % P.nsplit);
+    const int bh = is_tail ? ((int)blockIdx.x - nmain) / P.ntail : (int)(blockIdx.x / P.nsplit);
+    const int h = bh % P.Hkv, b = bh / P.Hkv;
+    if (is_tail) {
+        static_assert(sizeof(qtab) >= G * SPARK_D * 4 && sizeof(Pbuf) >= kDecodeWaves * G * 64 * 4, "LDS reuse");
+        tail_partial<G>(P, b, h, ((int)blockIdx.x - nmain) % P.ntail, qtab, reinterpret_cast<float *>(&Pbuf[0][0][0][0]), red_m, red_l,
+                        reinterpret_cast<float *>(&wbuf[0][0]));
+    } else {
+    const int s0 = P.cu[b], s1 = P.cu[b + 1];
+
+    // ---- tiles of this split
+    int t_begin = 0, t_end = 0;
+    if (s1 > s0) {
+        const int tf = s0 / SPARK_TILE_TOKENS, tl = (s1 - 1) / SPARK_TILE_TOKENS;
+        const int ntile = tl - tf + 1;
+        const int chunk = (ntile + P.nsplit - 1) / P.nsplit;
+        t_begin = tf + split * chunk;
+        t_end = t_begin + chunk;
+        if (t_end > tl + 1) t_end = tl + 1;
+    }
+
+    float m[G], l[G], R[G];
+    f32x4 acc[8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.0f; }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int tg = lane >> 4, cn = lane & 15;
+    // slot of this lane's token in the P buffer: MFMA lane group tg' = token % 4 holds, as its K
+    // index i, token 32*ks + 4*i + tg' (the same order in which V rows are fetched)
+    const int ppos = (lane & 32) | ((lane & 3) << 3) | ((lane & 31) >> 2);
+    const uint8_t *tiles = P.packed + L.off_tiles + (int64_t)h * L.n_tiles * L.tile_bytes;
+    const uint16_t *vbase = PV ? nullptr : P.v + (int64_t)h * P.v_head_stride + cn * 8;
+    const SparkLayout &Lv = P.Lv;
+    const uint8_t *vtiles = PV ? P.packed_v + Lv.off_tiles + (int64_t)h * Lv.n_tiles * Lv.tile_bytes : nullptr;
+    const int rsv = (TVC > 0) ? RSV : 8 * ((Lv.ndw + 3) / 8) + 4;   // parked-row stride in words
+
+    constexpr int NR = TCT ? NDW_CT : 6;    // row words held in registers
+    auto load_row = [&](int tile, uint32_t (&r)[NR]) {
+        const uint8_t *tp = tiles + (int64_t)tile * L.tile_bytes;
+        if (TCT) {
+#pragma unroll
+            for (int qd = 0; qd < NQ_CT; ++qd) {
+                const u32x4 x = NT_LOAD(reinterpret_cast<const u32x4 *>(tp + qd * 1024 + lane * 16));
+                r[4 * qd + 0] = x.x; r[4 * qd + 1] = x.y; r[4 * qd + 2] = x.z; r[4 * qd + 3] = x.w;
+            }
+            if (NDW_CT % 4) {
+                const uint2 x = *reinterpret_cast<const uint2 *>(tp + NQ_CT * 1024 + lane * 8);
+                r[4 * NQ_CT + 0] = x.x; r[4 * NQ_CT + 1] = x.y;
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < 6; ++d)
+                r[d] = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, d));
+        }
+    };
+    // half a tile of V: lane (tg, cn) takes 16 bytes (channels 8cn..8cn+7) of rows 4i + tg, so that
+    // one load instruction of the wavefront covers 4 consecutive rows (1 KB when rows are contiguous)
+    auto load_v = [&](int tile, int ks, uint4 (&vh)[8]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int n = tile * SPARK_TILE_TOKENS + 32 * ks + 4 * i + tg;
+            n = (n < s0) ? s0 : n;
+            n = (n > s1 - 1) ? (s1 - 1) : n;     // rows outside the sequence get p = 0
+            const u32x4 x = NT_LOAD(reinterpret_cast<const u32x4 *>(vbase + (int64_t)n * P.v_tok_stride));
+            vh[i] = make_uint4(x.x, x.y, x.z, x.w);
+        }
+    };
+
+    // packed value row of this lane's token: mask words, then the kept entries (coalesced sections as for keys)
+    auto load_vrow = [&](int tile, uint32_t (&r)[NVW]) {
+        const uint8_t *tp = vtiles + (int64_t)tile * Lv.tile_bytes;
+        if (TVC > 0) {
+#pragma unroll
+            for (int qd = 0; qd < NVW / 4; ++qd) {
+                const u32x4 x = NT_LOAD(reinterpret_cast<const u32x4 *>(tp + qd * 1024 + lane * 16));
+                r[4 * qd + 0] = x.x; r[4 * qd + 1] = x.y; r[4 * qd + 2] = x.z; r[4 * qd + 3] = x.w;
+            }
+            if (NVW % 4) {
+                const uint2 x = *reinterpret_cast<const uint2 *>(tp + (NVW / 4) * 1024 + lane * 8);
+                r[4 * (NVW / 4) + 0] = x.x; r[4 * (NVW / 4) + 1] = x.y;
+            }
+        } else {
+            const u32x4 x = NT_LOAD(reinterpret_cast<const u32x4 *>(tp + lane * 16));   // the mask
+            r[0] = x.x; r[1] = x.y; r[2] = x.z; r[3] = x.w;
+        }
+    };
+
+    // A wavefront keeps one tile in flight: the loads of tile i+1 are issued when tile i is done.
+    // (Requesting further ahead was measured slower: more outstanding requests per wavefront cost
+    // more in DRAM efficiency than the extra overlap gained.)
+    uint32_t rn[NR];
+    uint4 vr[2][8];
+    uint32_t vrow[NVW];
+    // Tiles are visited in rotated order, a different rotation per block.  The order does not
+    // matter to the running softmax, and it keeps the blocks (whose V chunks start at large
+    // power-of-two distances) from sweeping the memory channels in lockstep.
+    const int nts = t_end - t_begin;
+    const int rot = nts > 0 ? (int)((blockIdx.x * 37u) % (uint32_t)nts) : 0;
+    auto tile_of = [&](int k) { int li = k + rot; li = (li >= nts) ? li - nts : li; return t_begin + li; };
+    int kidx = wave;
+    int tile = tile_of(kidx);
+    if (kidx < nts) {
+        load_row(tile, rn);
+        if constexpr (PV) {
+            load_vrow(tile, vrow);
+        } else {
+            load_v(tile, 0, vr[0]);
+            load_v(tile, 1, vr[1]);
+        }
+    }
+    // (the first tile's loads are already in flight while the table is built)
+    if constexpr (PV) {
+        // Selector table, entry b = mask byte of a group of 8 channels.  The group's kept entries are the
+        // first popcount(b) of a window of 8 candidates = 16 bytes Q0..Q3; output word o holds channels
+        // 2o, 2o+1.  A byte-permute picks from two words (selector 0-3: second operand, 4-7: first, 0x0C:
+        // zero): words 0, 1 need candidates 0..3 only -> one permute of (Q1, Q0); words 2, 3 may reach
+        // into Q2, Q3 -> the OR of a permute of (Q1, Q0) and one of (Q3, Q2).
+        const uint32_t bmask = (uint32_t)tid;
+        uint32_t sel[6];
+#pragma unroll
+        for (int k = 0; k < 6; ++k) sel[k] = 0x0C0C0C0Cu;
+        int rnk = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool on = (bmask >> e) & 1u;
+            const int o = e >> 1, sh = (e & 1) * 16;      // output word, bit position of its half
+            const int src = 2 * rnk;                       // candidate's first byte in the window
+            const uint32_t two = (uint32_t)((src & 7) | (((src & 7) + 1) << 8)) << sh;
+            const uint32_t keep = ~(0xFFFFu << sh);
+            if (o < 2) {
+                if (on) sel[o] = (sel[o] & keep) | two;
+            } else {
+                if (on && src < 8) sel[2 * o - 2] = (sel[2 * o - 2] & keep) | two;
+                if (on && src >= 8) sel[2 * o - 1] = (sel[2 * o - 1] & keep) | two;
+            }
+            rnk += on ? 1 : 0;
+        }
+        u32x4 lo4 = {sel[0], sel[1], sel[2], sel[3]}, hi4 = {sel[4], sel[5], 0u, 0u};
+        *reinterpret_cast<u32x4 *>(&vlut[tid * LUTW]) = lo4;
+        *reinterpret_cast<u32x4 *>(&vlut[tid * LUTW + 4]) = hi4;
+    }
+    // ---- per-step query prep: table {q_g[j] * scale * log2e, 1/a[j]} and R_g
+    if (tid < SPARK_D) {
+        const int j = tid;
+        const float inva = reinterpret_cast<const float *>(P.packed + L.off_inva)[((int64_t)b * P.Hkv + h) * SPARK_D + j];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            qtab[j * GP + g] = bf16lo(P.q[((int64_t)b * P.Hq + h * G + g) * SPARK_D + j]) * P.scale_log2;
+        qtab[j * GP + G] = inva;
+#pragma unroll
+        for (int g = G + 1; g < GP; ++g) qtab[j * GP + g] = 0.0f;
+    }
+    __syncthreads();
+    for (int g = wave; g < G; g += kDecodeWaves) {
+        float r = qtab[lane * GP + g] * qtab[lane * GP + G] +
+                  qtab[(lane + 64) * GP + g] * qtab[(lane + 64) * GP + G];
+        r = wave_sum(r);
+        if (lane == 0) Rsh[g] = r;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < G; ++g) R[g] = Rsh[g];
+
+
+    for (; kidx < nts; kidx += kDecodeWaves) {
+        tile = tile_of(kidx);
+        const uint8_t *tp = tiles + (int64_t)tile * L.tile_bytes;
+        const int n_lane = tile * SPARK_TILE_TOKENS + lane;
+        const bool valid = (n_lane >= s0) && (n_lane < s1);
+        const bool more = kidx + kDecodeWaves < nts;            // wave-uniform
+        const int tnext = tile_of(more ? kidx + kDecodeWaves : kidx);
+
+        uint32_t (&r)[NR] = rn;
+        // ---- scores, lane = token
+        const float mu = __uint_as_float(r[4]);
+        float s[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) s[g] = 0.0f;
+        {
+            uint64_t cur = ((uint64_t)r[1] << 32) | r[0];
+            const uint64_t upper = ((uint64_t)r[3] << 32) | r[2];
+            const int clo = __popc(r[0]) + __popc(r[1]);
+            int jb = 0;
+            float scale_row = 1.0f;
+            if (INT8) scale_row = __uint_as_float(r[5]);
+            uint32_t vw = 0;
+            // next kept channel of this lane's row (ascending); exactly T bits are set
+            auto next_channel = [&](int i) {
+                const bool sw = (i == clo);          // first entry of channels 64..127
+                cur = sw ? upper : cur;
+                jb = sw ? 64 : jb;
+                const int j = (__builtin_ctzll((unsigned long long)cur) + jb) & (SPARK_D - 1);
+                cur &= cur - 1;
+                return j;
+            };
+            auto kept_value = [&](int i, uint32_t word) {
+                if (INT8) return (float)(int)(int8_t)((word >> (8 * (i & 3))) & 0xFF) * scale_row;
+                return (i & 1) ? bf16hi(word) : bf16lo(word);
+            };
+            auto entry = [&](int i, uint32_t word) {
+                const float *e = &qtab[next_channel(i) * GP];
+                const float d = fmaf(-mu, e[G], kept_value(i, word));
+#pragma unroll
+                for (int g = 0; g < G; ++g) s[g] = fmaf(e[g], d, s[g]);
+            };
+            if (TCT) {
+                // The mask walk is a dependent chain and the table gathers have LDS latency; doing the
+                // walk and the gathers in batches keeps several gathers in flight at once.
+                constexpr int BQ = (G <= 4) ? 8 : (G == 8 ? 4 : 2);   // gathers in flight, bounded by registers
+#pragma unroll
+                for (int i0 = 0; i0 < TCT; i0 += BQ) {
+                    int off[BQ];
+#pragma unroll
+                    for (int u = 0; u < BQ; ++u)
+                        if (i0 + u < TCT) off[u] = next_channel(i0 + u) * GP;
+                    float ev[BQ][GP];
+#pragma unroll
+                    for (int u = 0; u < BQ; ++u)
+                        if (i0 + u < TCT) {
+#pragma unroll
+                            for (int g = 0; g <= G; ++g) ev[u][g] = qtab[off[u] + g];
+                        }
+#pragma unroll
+                    for (int u = 0; u < BQ; ++u)
+                        if (i0 + u < TCT) {
+                            const int i = i0 + u;
+                            const float d = fmaf(-mu, ev[u][G], kept_value(i, r[VAL0 + (INT8 ? i / 4 : i / 2)]));
+#pragma unroll
+                            for (int g = 0; g < G; ++g) s[g] = fmaf(ev[u][g], d, s[g]);
+                        }
+                }
+            } else {
+                for (int i = 0; i < T; ++i) {
+                    const int per = INT8 ? 4 : 2;
+                    if (i % per == 0)
+                        vw = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, VAL0 + i / per));
+                    entry(i, vw);
+                }
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            s[g] = fmaf(mu, R[g], s[g]);
+            s[g] = valid ? s[g] : -INFINITY;
+        }
+
+        // ---- online softmax (log2 domain) and P -> LDS as bf16 high + low parts
+        bool rescale = false;
+        float alpha[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float tmax = wave_max(s[g]);
+            const float mnew = fmaxf(m[g], tmax);
+            const float msafe = (mnew == -INFINITY) ? 0.0f : mnew;
+            alpha[g] = fast_exp2(m[g] - msafe);            // m = -inf -> 0
+            rescale = rescale || (mnew != m[g]);
+            m[g] = mnew;
+            const float p = fast_exp2(s[g] - msafe);       // s = -inf -> 0
+            l[g] = fmaf(l[g], alpha[g], p);
+            const __bf16 ph = (__bf16)p;
+            const __bf16 pl = (__bf16)(p - (float)ph);
+            Pbuf[wave][0][g][ppos] = __builtin_bit_cast(uint16_t, ph);
+            Pbuf[wave][1][g][ppos] = __builtin_bit_cast(uint16_t, pl);
+        }
+        if (rescale) {   // wave-uniform: m is the same in every lane
+            float al[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) al[rr] = 1.0f;
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if ((g >> 2) == tg) al[g & 3] = alpha[g];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) acc[e][rr] *= al[rr];
+        }
+        wave_lds_sync();
+
+        if constexpr (PV) {
+            // ---- packed values: park this token's row in LDS with its per-group bookkeeping
+            uint32_t *raw = reinterpret_cast<uint32_t *>(wbuf[wave]);
+            uint32_t mk[4];
+            if (TVC > 0) {
+#pragma unroll
+                for (int qd = 0; qd < NVW / 4; ++qd) {
+                    u32x4 x = {vrow[4 * qd], vrow[4 * qd + 1], vrow[4 * qd + 2], vrow[4 * qd + 3]};
+                    *reinterpret_cast<u32x4 *>(&raw[lane * RSV + 4 * qd]) = x;
+                }
+                if (NVW % 4) {
+                    raw[lane * RSV + 4 * (NVW / 4)] = vrow[4 * (NVW / 4)];
+                    raw[lane * RSV + 4 * (NVW / 4) + 1] = vrow[4 * (NVW / 4) + 1];
+                }
+            } else {
+                // any row length: straight from memory, no prefetch
+                const uint8_t *vtp = vtiles + (int64_t)tile * Lv.tile_bytes;
+                for (int qd = 1; qd < Lv.nq; ++qd) {
+                    const u32x4 x = NT_LOAD(reinterpret_cast<const u32x4 *>(vtp + qd * 1024 + lane * 16));
+                    *reinterpret_cast<u32x4 *>(&raw[lane * rsv + 4 * qd]) = x;
+                }
+                if (Lv.tail2) {
+                    const uint2 x = *reinterpret_cast<const uint2 *>(vtp + Lv.nq * 1024 + lane * 8);
+                    raw[lane * rsv + 4 * Lv.nq] = x.x;
+                    raw[lane * rsv + 4 * Lv.nq + 1] = x.y;
+                }
+            }
+#pragma unroll
+            for (int w4 = 0; w4 < 4; ++w4) mk[w4] = vrow[w4];
+            {
+                // 16 halfwords: (kept entries in lower groups) << 8 | mask byte of the group
+                uint32_t meta[8];
+                uint32_t before = 0;
+#pragma unroll
+                for (int c = 0; c < 16; ++c) {
+                    const uint32_t byte = (mk[c >> 2] >> (8 * (c & 3))) & 0xFFu;
+                    const uint32_t hw = (before << 8) | byte;
+                    if (c & 1) meta[c >> 1] |= hw << 16; else meta[c >> 1] = hw;
+                    before += __popc(byte);
+                }
+                u32x4 m0 = {meta[0], meta[1], meta[2], meta[3]}, m1 = {meta[4], meta[5], meta[6], meta[7]};
+                *reinterpret_cast<u32x4 *>(&vmeta[wave][lane * 8]) = m0;
+                *reinterpret_cast<u32x4 *>(&vmeta[wave][lane * 8 + 4]) = m1;
+            }
+            wave_lds_sync();
+        }
+        {
+            // ---- P V on the matrix cores
+    #pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                if constexpr (PV) {
+                    // rebuild the dense pieces of this half tile: lane (tg, cn) makes channels 8cn..8cn+7 of
+                    // tokens 32ks + 4i + tg (four at a time, to bound the registers in flight)
+                    const uint32_t *raw = reinterpret_cast<const uint32_t *>(wbuf[wave]);
+                    const uint16_t *meta16 = reinterpret_cast<const uint16_t *>(vmeta[wave]);
+    #pragma unroll
+                    for (int i0 = 0; i0 < 8; i0 += 4) {
+    #pragma unroll
+                        for (int i = i0; i < i0 + 4; ++i) {
+                            const int t = 32 * ks + 4 * i + tg;
+                            const uint32_t hw = meta16[t * 16 + cn];
+                            const uint32_t byte = hw & 0xFFu, before = hw >> 8;
+                            const uint32_t *win = &raw[t * rsv + 4 + (before >> 1)];   // 8 candidates start here ...
+                            const uint32_t sh = (before & 1u) << 4;                     // ... or one halfword further
+                            const uint32_t d0 = win[0], d1 = win[1], d2 = win[2], d3 = win[3], d4 = win[4];
+                            const uint32_t q0 = __builtin_amdgcn_alignbit(d1, d0, sh);
+                            const uint32_t q1 = __builtin_amdgcn_alignbit(d2, d1, sh);
+                            const uint32_t q2 = __builtin_amdgcn_alignbit(d3, d2, sh);
+                            const uint32_t q3 = __builtin_amdgcn_alignbit(d4, d3, sh);
+                            const u32x4 sa = *reinterpret_cast<const u32x4 *>(&vlut[byte * LUTW]);
+                            const uint2 sb = *reinterpret_cast<const uint2 *>(&vlut[byte * LUTW + 4]);
+                            vr[ks][i].x = __builtin_amdgcn_perm(q1, q0, sa.x);
+                            vr[ks][i].y = __builtin_amdgcn_perm(q1, q0, sa.y);
+                            vr[ks][i].z = __builtin_amdgcn_perm(q1, q0, sa.z) | __builtin_amdgcn_perm(q3, q2, sa.w);
+                            vr[ks][i].w = __builtin_amdgcn_perm(q1, q0, sb.x) | __builtin_amdgcn_perm(q3, q2, sb.y);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                uint4 ah = {0, 0, 0, 0}, alo = {0, 0, 0, 0};
+                if (cn < G) {
+                    ah = *reinterpret_cast<const uint4 *>(&Pbuf[wave][0][cn][32 * ks + 8 * tg]);
+                    alo = *reinterpret_cast<const uint4 *>(&Pbuf[wave][1][cn][32 * ks + 8 * tg]);
+                }
+                const bf16x8 A_hi = __builtin_bit_cast(bf16x8, ah);
+                const bf16x8 A_lo = __builtin_bit_cast(bf16x8, alo);
+                // 8x8 transpose of this lane's (token, channel) block: B operand e = channel 8cn+e, K = tokens
+                u32x4 bop[8];
+    #pragma unroll
+                for (int cp = 0; cp < 4; ++cp)
+    #pragma unroll
+                    for (int tp2 = 0; tp2 < 4; ++tp2) {
+                        const uint32_t x = u4c(vr[ks][2 * tp2], cp);
+                        const uint32_t y = u4c(vr[ks][2 * tp2 + 1], cp);
+                        bop[2 * cp][tp2] = __builtin_amdgcn_perm(y, x, 0x05040100u);       // low halves  (x | y << 16)
+                        bop[2 * cp + 1][tp2] = __builtin_amdgcn_perm(y, x, 0x07060302u);   // high halves
+                    }
+    #pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bf16x8 B = __builtin_bit_cast(bf16x8, bop[e]);
+                    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_hi, B, acc[e], 0, 0, 0);
+                    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A_lo, B, acc[e], 0, 0, 0);
+                }
+            }
+        }
+        wave_lds_sync();   // P buffer is rewritten by the next tile
+        if (more) {   // request the next tile; its latency is covered by the other resident wavefronts
+            load_row(tnext, rn);
+            if constexpr (PV) {
+                load_vrow(tnext, vrow);
+            } else {
+                load_v(tnext, 0, vr[0]);
+                load_v(tnext, 1, vr[1]);
+            }
+        }
+    }
+
+    // ---- merge the 4 wavefronts, write the split partial
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float lt = wave_sum(l[g]);
+        if (lane == 0) { red_m[wave][g] = m[g]; red_l[wave][g] = lt; }
+    }
+    // accumulator layout: lane (tg, cn), register rr of acc[e] = head 4*tg + rr, channel 8*cn + e
+    wave_lds_sync();   // this wavefront's parked value rows are no longer read
+    auto red_acc = [&](int w, int g, int ch) -> float & {
+        return reinterpret_cast<float *>(wbuf[w])[g * SPARK_D + ch];
+    };
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int g = 4 * tg + rr;
+        if (g < G) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) red_acc(wave, g, 8 * cn + e) = acc[e][rr];
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
+        const int g = idx / SPARK_D, ch = idx % SPARK_D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) M = fmaxf(M, red_m[w][g]);
+        const float Ms = (M == -INFINITY) ? 0.0f : M;
+        float Lsum = 0.0f, A = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) {
+            const float f = fast_exp2(red_m[w][g] - Ms);
+            Lsum = fmaf(red_l[w][g], f, Lsum);
+            A = fmaf(red_acc(w, g, ch), f, A);
+        }
+        const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + split;
+        st_agent(&P.part_acc[slot * SPARK_D + ch], A);
+        if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
+    }
+    }   // sequence split
+
+    // ---- the last block of this (batch, KV head) to get here merges the splits.
+    // The partials are written and read with device-scope accesses (they go to the point where
+    // all the chip's L2 slices agree), each thread waits for its own stores to be acknowledged,
+    // and only then is the block's arrival counted.  That orders partials before the count
+    // without a device-wide cache write-back.  atomicInc wraps at the number of arrivals - 1, which leaves the
+    // counter at zero for the next call.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have completed
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t old = atomicInc(&P.counters[bh], (uint32_t)(P.nmerge - 1));
+        last_flag = (old == (uint32_t)(P.nmerge - 1));
+    }
+    __syncthreads();
+    if (!last_flag) return;
+    constexpr int NTH = kDecodeWaves * 64;
+    if (P.nmerge <= 256) {
+        // The (m, l) pairs of all partials go to LDS first (one 8-byte device-scope load each); then each
+        // thread owns two adjacent output channels of one head and folds the partials' accumulators with
+        // sixteen 8-byte loads in flight.  (The per-wavefront buffers are free: every thread passed the
+        // barrier above after its last read of them.)
+        float2 *mlsh = reinterpret_cast<float2 *>(&wbuf[0][0]);     // [G][nmerge]
+        static_assert(sizeof(wbuf) >= (size_t)G * 256 * sizeof(float2), "LDS reuse");
+        for (int idx = tid; idx < G * P.nmerge; idx += NTH) {
+            const int g = idx / P.nmerge, i = idx % P.nmerge;
+            const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + i;
+            const uint64_t raw = __hip_atomic_load(reinterpret_cast<const uint64_t *>(P.part_ml + slot * 2),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            mlsh[idx] = make_float2(__uint_as_float((uint32_t)raw), __uint_as_float((uint32_t)(raw >> 32)));
+        }
+        __syncthreads();
+        for (int e = tid; e < G * (SPARK_D / 2); e += NTH) {
+            const int g = e / (SPARK_D / 2), c2 = e % (SPARK_D / 2);
+            const float2 *mlg = mlsh + g * P.nmerge;
+            float M = -INFINITY;
+            for (int i = 0; i < P.nmerge; ++i) M = fmaxf(M, mlg[i].x);
+            const float Ms = (M == -INFINITY) ? 0.0f : M;
+            const int64_t bq = (int64_t)b * P.Hq + h * G + g;
+            const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + bq * P.nslots * SPARK_D + 2 * c2);
+            float Lsum = 0.0f, A0 = 0.0f, A1 = 0.0f;
+            for (int i0 = 0; i0 < P.nmerge; i0 += 16) {
+                uint64_t av[16];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const int i = (i0 + k < P.nmerge) ? (i0 + k) : (P.nmerge - 1);
+                    av[k] = __hip_atomic_load(pa + (int64_t)i * (SPARK_D / 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    if (i0 + k < P.nmerge) {
+                        const float2 mlv = mlg[i0 + k];
+                        const float f = fast_exp2(mlv.x - Ms);      // m = -inf -> 0
+                        Lsum = fmaf(mlv.y, f, Lsum);
+                        A0 = fmaf(__uint_as_float((uint32_t)av[k]), f, A0);
+                        A1 = fmaf(__uint_as_float((uint32_t)(av[k] >> 32)), f, A1);
+                    }
+                }
+            }
+            const float o0 = (Lsum > 0.0f) ? (A0 / Lsum) : 0.0f, o1 = (Lsum > 0.0f) ? (A1 / Lsum) : 0.0f;
+            if (P.out_f32) {
+                reinterpret_cast<float2 *>(P.out)[bq * (SPARK_D / 2) + c2] = make_float2(o0, o1);
+            } else {
+                const uint32_t packed2 = (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o0) |
+                                         ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o1) << 16);
+                reinterpret_cast<uint32_t *>(P.out)[bq * (SPARK_D / 2) + c2] = packed2;
+            }
+        }
+        return;
+    }
+    // More than 256 partials: each thread owns output elements (g, ch) and folds the partial states one by
+    // one with the running-maximum rule, eight splits' loads in flight at a time, two elements at once.
+    for (int idx0 = tid; idx0 < G * SPARK_D; idx0 += 2 * NTH) {
+        float M[2], Lsum[2], A[2];
+        const float *ml[2], *pa[2];
+        int64_t bq[2];
+        int ch[2];
+        bool on[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = idx0 + u * NTH;
+            on[u] = idx < G * SPARK_D;
+            const int g = on[u] ? idx / SPARK_D : 0;
+            ch[u] = idx % SPARK_D;
+            bq[u] = (int64_t)b * P.Hq + h * G + g;
+            ml[u] = P.part_ml + bq[u] * P.nslots * 2;
+            pa[u] = P.part_acc + bq[u] * P.nslots * SPARK_D + ch[u];
+            M[u] = -INFINITY; Lsum[u] = 0.0f; A[u] = 0.0f;
+        }
+        for (int i0 = 0; i0 < P.nmerge; i0 += 8) {
+            float mi[2][8], li[2][8], ai[2][8];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int i = (i0 + k < P.nmerge) ? (i0 + k) : (P.nmerge - 1);
+                    mi[u][k] = ld_agent(ml[u] + 2 * i);
+                    li[u][k] = ld_agent(ml[u] + 2 * i + 1);
+                    ai[u][k] = ld_agent(pa[u] + (int64_t)i * SPARK_D);
+                }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    if (i0 + k < P.nmerge) {
+                        const float Mn = fmaxf(M[u], mi[u][k]);
+                        const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
+                        const float fo = fast_exp2(M[u] - Ms), fn = fast_exp2(mi[u][k] - Ms);
+                        Lsum[u] = fmaf(Lsum[u], fo, li[u][k] * fn);
+                        A[u] = fmaf(A[u], fo, ai[u][k] * fn);
+                        M[u] = Mn;
+                    }
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (!on[u]) continue;
+            const float o = (Lsum[u] > 0.0f) ? (A[u] / Lsum[u]) : 0.0f;
+            if (P.out_f32)
+                reinterpret_cast<float *>(P.out)[bq[u] * SPARK_D + ch[u]] = o;
+            else
+                reinterpret_cast<uint16_t *>(P.out)[bq[u] * SPARK_D + ch[u]] = __builtin_bit_cast(uint16_t, (__bf16)o);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- host-side launch
+
+template <int G, int TCT, int INT8, int TVC>
+static hipError_t launch_one(const DecodeParams &P, int nblocks, hipStream_t st)
+{
+    hipLaunchKernelGGL((spark_decode_kernel<G, TCT, INT8, TVC>), dim3(nblocks), dim3(kDecodeWaves * 64), 0, st, P);
+    return hipGetLastError();
+}
+
+// packed values: row lengths 64 / 38 / 26 with the row in registers, anything else generic
+template <int G, int TCT>
+static hipError_t launch_pv(const DecodeParams &P, int nblocks, hipStream_t st)
+{
+    switch (P.Lv.T) {
+        case 64: return launch_one<G, TCT, 0, 64>(P, nblocks, st);
+        case 38: return launch_one<G, TCT, 0, 38>(P, nblocks, st);
+        case 26: return launch_one<G, TCT, 0, 26>(P, nblocks, st);
+        default: return launch_one<G, TCT, 0, -1>(P, nblocks, st);
+    }
+}
+
+// One instantiation per query-group size G; each lives in its own translation unit (spark_decode_g*.hip) so
+// that the units compile in parallel.
+template <int G>
+hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
+{
+    const int T = P.L.T;
+    if (P.packed_v) {
+        if (P.L.int8) return hipErrorInvalidValue;   // (the host rejects this combination before it gets here)
+        if (T == 26) return launch_pv<G, 26>(P, nblocks, st);
+        if (T == 64) return launch_pv<G, 64>(P, nblocks, st);
+        return launch_pv<G, 0>(P, nblocks, st);
+    }
+    if (P.L.int8) {
+        if (T == 26) return launch_one<G, 26, 1, 0>(P, nblocks, st);
+        return launch_one<G, 0, 1, 0>(P, nblocks, st);
+    }
+    if (T == 26) return launch_one<G, 26, 0, 0>(P, nblocks, st);
+    if (T == 25) return launch_one<G, 25, 0, 0>(P, nblocks, st);
+    if (T == 38) return launch_one<G, 38, 0, 0>(P, nblocks, st);
+    if (T == 64) return launch_one<G, 64, 0, 0>(P, nblocks, st);
+    return launch_one<G, 0, 0, 0>(P, nblocks, st);
+}
+
+}  // namespace spark
