@@ -48,21 +48,54 @@ bool strides_ok(int64_t tok, int64_t head)
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-// Splits per (batch, KV head).  The decode kernel keeps two 4-wave blocks resident per compute
-// unit (256 CUs), so 512 blocks stream the cache in a single round with no tail; aim for that,
-// but keep at least two tiles (128 tokens) per wavefront on an average-length sequence.
+// How the decode grid cuts the batch into blocks.  The decode kernel keeps two 4-wave blocks resident per
+// compute unit (256 CUs), so about 512 blocks stream the cache in a single round with no tail; a block should
+// still see at least 8 tiles (two per wavefront).  Sequences are cut into chunks of chunk_tiles tiles, so long
+// sequences of a ragged batch get more blocks than short ones; n_splits > 0 (or a batch too large for the
+// in-kernel numbering of the chunks) asks for the same number of chunks for every sequence instead.
+spark::DecodePlan plan_of(const spark_desc *d)
+{
+    spark::DecodePlan p;
+    p.tail_slots = d->tail_capacity > 0 ? (d->tail_capacity + 255) / 256 : 1;
+    const int64_t tiles = (d->total_tokens + SPARK_TILE_TOKENS - 1) / SPARK_TILE_TOKENS;
+    int64_t chunk = (tiles * d->n_kv_heads + 511) / 512;
+    // With many (batch, KV head) pairs the blocks of an evenly cut batch would already exceed what is resident
+    // at once, and every further round costs a block's fixed start-up and merge latency: then only sequences
+    // well above the average length are cut.
+    if ((int64_t)d->batch * d->n_kv_heads >= 256) chunk *= 2;
+    if (chunk < 8) chunk = 8;
+    p.chunk_tiles = (int)chunk;
+    p.fixed_splits = 0;
+    if (d->n_splits > 0) {
+        p.fixed_splits = d->n_splits;
+    } else if (d->batch > 256) {
+        const int64_t avg_tiles = (d->total_tokens / d->batch + SPARK_TILE_TOKENS - 1) / SPARK_TILE_TOKENS;
+        int64_t n = (avg_tiles + chunk - 1) / chunk;
+        p.fixed_splits = (int)(n < 1 ? 1 : (n > 4096 ? 4096 : n));
+    }
+    if (p.fixed_splits > 0)
+        p.nchunk_max = d->batch * p.fixed_splits;
+    else   // a sequence of len tokens spans at most len / 64 + 2 tiles, and rounding up costs at most one chunk
+        p.nchunk_max = (int)((tiles + 2 * (int64_t)d->batch) / chunk + d->batch + 1);
+    return p;
+}
+
+// chunks an average-length sequence is cut into (what spark_decode_splits reports)
 int pick_splits(const spark_desc *d)
 {
-    if (d->n_splits > 0) return d->n_splits;
-    const int64_t pairs = (int64_t)d->batch * d->n_kv_heads;
+    const spark::DecodePlan p = plan_of(d);
+    if (p.fixed_splits > 0) return p.fixed_splits;
     const int64_t avg_tiles = (d->total_tokens / d->batch + SPARK_TILE_TOKENS - 1) / SPARK_TILE_TOKENS;
-    int64_t want = (512 + pairs / 2) / pairs;
-    int64_t cap = avg_tiles / 8;
-    if (cap < 1) cap = 1;
-    if (want > cap) want = cap;
-    if (want < 1) want = 1;
-    if (want > 4096) want = 4096;
-    return (int)want;
+    const int64_t n = (avg_tiles + p.chunk_tiles - 1) / p.chunk_tiles;
+    return (int)(n < 1 ? 1 : n);
+}
+
+// partial slots in the workspace: one per (chunk, q head), then the appended rows' (one per 256 rows of
+// capacity, at least one, per (batch, q head), so a workspace serves calls with and without appended rows)
+size_t partial_slots(const spark_desc *d)
+{
+    const spark::DecodePlan p = plan_of(d);
+    return (size_t)p.nchunk_max * d->n_q_heads + (size_t)d->batch * d->n_q_heads * p.tail_slots;
 }
 
 // Streaming-read yardstick: every lane pulls 16-byte words grid-stride (non-temporal, as the decode
@@ -84,14 +117,6 @@ __global__ __launch_bounds__(256) void spark_probe_read_kernel(const u32x4 *__re
         acc ^= a.x ^ a.y ^ a.z ^ a.w;
     }
     if (acc == 0x9E3779B9u) sink[0] = acc;
-}
-
-// partial slots per (batch, q head): the sequence splits plus one per 256 rows of appended-token capacity
-// (at least one, so a workspace serves calls with and without appended rows)
-size_t partial_slots(const spark_desc *d)
-{
-    const int tail_slots = d->tail_capacity > 0 ? (d->tail_capacity + 255) / 256 : 1;
-    return (size_t)pick_splits(d) + (size_t)tail_slots;
 }
 
 size_t counter_bytes(const spark_desc *d)
@@ -148,7 +173,7 @@ size_t spark_decode_workspace(const spark_desc *desc)
 {
     spark_status why;
     if (!desc_ok(desc, &why)) return 0;
-    const size_t slots = (size_t)desc->batch * desc->n_q_heads * partial_slots(desc);
+    const size_t slots = partial_slots(desc);
     return slots * (SPARK_D + 2) * sizeof(float) + counter_bytes(desc);
 }
 
@@ -159,7 +184,7 @@ spark_status spark_decode_workspace_init(const spark_desc *desc, void *workspace
     if (!desc_ok(desc, &why)) return why;
     if (!workspace || !aligned(workspace, 16)) return SPARK_ERR_INVALID_ARG;
     if (workspace_bytes < spark_decode_workspace(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
-    const size_t slots = (size_t)desc->batch * desc->n_q_heads * partial_slots(desc);
+    const size_t slots = partial_slots(desc);
     uint32_t *counters = reinterpret_cast<uint32_t *>(static_cast<float *>(workspace) + slots * (SPARK_D + 2));
     const hipError_t e = spark::launch_zero_counters(counters, desc->batch * desc->n_kv_heads,
                                                      static_cast<hipStream_t>(hip_stream));
@@ -249,8 +274,8 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
     const SparkLayout L = layout_of(desc);
     SparkLayout Lv = L;
     if (packed_v) Lv = values_layout_of(desc);
-    const int nsplit = pick_splits(desc);
-    const size_t slots = (size_t)desc->batch * desc->n_q_heads * partial_slots(desc);
+    const spark::DecodePlan plan = plan_of(desc);
+    const size_t slots = partial_slots(desc);
     float *part_acc = static_cast<float *>(workspace);
     float *part_ml = part_acc + slots * SPARK_D;
     uint32_t *counters = reinterpret_cast<uint32_t *>(part_ml + slots * 2);
@@ -259,7 +284,7 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
         static_cast<const uint16_t *>(q_bf16), static_cast<const uint8_t *>(packed),
         static_cast<const uint16_t *>(v_bf16), desc->v_token_stride, desc->v_head_stride,
         static_cast<const uint8_t *>(packed_v), packed_v ? &Lv : nullptr, cu_seqlens, part_acc, part_ml, counters,
-        desc->n_q_heads, nsplit, scale, L, out, desc->out_dtype == SPARK_OUT_F32,
+        desc->n_q_heads, plan, scale, L, out, desc->out_dtype == SPARK_OUT_F32,
         static_cast<const uint16_t *>(tail_k), static_cast<const uint16_t *>(tail_v), tail_len,
         desc->tail_capacity, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;

@@ -20,7 +20,7 @@ __global__ void spark_zero_kernel(uint32_t *p, int n)
 hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const uint16_t *v, int64_t v_tok_stride,
                               int64_t v_head_stride, const uint8_t *packed_v, const SparkLayout *Lv,
                               const int32_t *cu, float *part_acc, float *part_ml,
-                              uint32_t *counters, int Hq, int nsplit, float softmax_scale, const SparkLayout &L,
+                              uint32_t *counters, int Hq, const DecodePlan &plan, float softmax_scale, const SparkLayout &L,
                               void *out, int out_f32, const uint16_t *tail_k, const uint16_t *tail_v,
                               const int32_t *tail_len, int tail_cap, hipStream_t st)
 {
@@ -40,11 +40,12 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.out_f32 = out_f32;
     P.Hq = Hq;
     P.Hkv = L.n_kv_heads;
-    P.nsplit = nsplit;
-    const int tail_slots = tail_cap > 0 ? (tail_cap + kDecodeWaves * 64 - 1) / (kDecodeWaves * 64) : 1;
-    P.ntail = tail_k ? tail_slots : 0;
-    P.nslots = nsplit + tail_slots;
-    P.nmerge = nsplit + P.ntail;
+    P.fixed_splits = plan.fixed_splits;
+    P.chunk_tiles = plan.chunk_tiles;
+    P.nchunk_max = plan.nchunk_max;
+    P.tail_slots = plan.tail_slots;
+    P.ntail = tail_k ? plan.tail_slots : 0;
+    P.tail_base = (int64_t)plan.nchunk_max * Hq;
     P.tail_k = tail_k;
     P.tail_v = tail_v;
     P.tail_len = tail_len;
@@ -52,7 +53,7 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.scale_log2 = softmax_scale * 1.44269504088896340736f;
     P.L = L;
     const int G = P.Hq / P.Hkv;
-    const int nblocks = L.batch * P.Hkv * (P.nsplit + P.ntail);
+    const int nblocks = P.Hkv * (P.nchunk_max + L.batch * P.ntail);
     switch (G) {
         case 1: return launch_g<1>(P, nblocks, st);
         case 2: return launch_g<2>(P, nblocks, st);

@@ -46,15 +46,23 @@ struct DecodeParams {
     SparkLayout Lv;          // its layout
     int64_t v_tok_stride, v_head_stride;
     const int32_t *cu;       // [B+1]
-    float *part_acc;         // [B*Hq*nsplit][128]
-    float *part_ml;          // [B*Hq*nsplit][2]  (m in log2 units, l)
+    float *part_acc;         // [slots][128]   partial softmax states, see slot numbering below
+    float *part_ml;          // [slots][2]     (m in log2 units, l)
     uint32_t *counters;      // [B*Hkv] arrival counters, zero between calls
     void *out;               // [B, Hq, 128] bf16 or float32
     int out_f32;
-    int Hq, Hkv, nsplit;
-    int nslots;              // partial slots per (batch, q head): nsplit + ntail_slots (the last ones are the appended rows')
-    int nmerge;              // partials the last block folds: nsplit, or nsplit + ntail when appended rows exist
+    int Hq, Hkv;
+    // How sequences are cut into blocks.  A sequence that spans ntile tiles gets
+    //   fixed_splits                           chunks if fixed_splits > 0,
+    //   max(1, ceil(ntile / chunk_tiles))      chunks otherwise (long sequences get more blocks than short ones),
+    // chunks are numbered through the batch (global chunk id), block = (global chunk, KV head); the host
+    // launches nchunk_max >= the true count and blocks past the last chunk leave at once.
+    // Slot of (global chunk c, q head) = c * Hq + head; the appended rows' slots follow at tail_base:
+    // ((b * Hq + head) * tail_slots + part).
+    int fixed_splits, chunk_tiles, nchunk_max;
     int ntail;               // blocks per (batch, KV head) for the appended rows, 256 rows each (0: none)
+    int tail_slots;          // slots reserved per (batch, q head) for them (>= max(1, ntail))
+    int64_t tail_base;       // = nchunk_max * Hq
     const uint16_t *tail_k, *tail_v;   // appended never-pruned rows [B, tail_cap, Hkv, 128] bf16, or NULL
     const int32_t *tail_len;           // [B]
     int tail_cap;
@@ -109,6 +117,61 @@ __device__ __forceinline__ uint32_t u4c(const uint4 &v, int c) { return c == 0 ?
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// Inclusive prefix sum over the 64 lanes (data-parallel-primitive moves: shifts by 1, 2, 4, 8 inside each row
+// of 16 lanes, then the last lane of row 0 / 2 into row 1 / 3 and the last lane of row 1 into rows 2, 3).
+__device__ __forceinline__ int wave_inclusive_sum_i32(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);   // row_shr 1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);   // row_shr 2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);   // row_shr 4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);   // row_shr 8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast 15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast 31 -> rows 2, 3
+    return v;
+}
+
+struct SeqChunks { int b, first, n; };   // sequence, global id of its first chunk, number of its chunks (0: none)
+
+// Finds the sequence that owns global chunk `gid` (want_b < 0) or describes sequence `want_b`.  Every lane of
+// the wavefront calls it with the same arguments and gets the same answer: 64 sequences are sized per step
+// (lane = sequence) and a wave prefix sum numbers their chunks.
+__device__ __forceinline__ SeqChunks locate_chunks(const DecodeParams &P, int B, int gid, int want_b, int lane)
+{
+    SeqChunks r = {0, 0, 0};
+    if (P.fixed_splits > 0) {
+        const int b = (want_b >= 0) ? want_b : gid / P.fixed_splits;
+        if (b < B) { r.b = b; r.first = b * P.fixed_splits; r.n = P.fixed_splits; }
+        return r;
+    }
+    int base = 0;
+    for (int b0 = 0; b0 < B; b0 += 64) {
+        const int bb = b0 + lane;
+        int n = 0;
+        if (bb < B) {
+            const int s0 = P.cu[bb], s1 = P.cu[bb + 1];
+            const int ntile = (s1 > s0) ? ((s1 - 1) / SPARK_TILE_TOKENS - s0 / SPARK_TILE_TOKENS + 1) : 0;
+            n = (ntile + P.chunk_tiles - 1) / P.chunk_tiles;
+            n = n < 1 ? 1 : n;     // an empty sequence still gets one block: somebody has to write its zeros
+        }
+        const int inc = wave_inclusive_sum_i32(n);
+        uint64_t hit;
+        if (want_b >= 0)
+            hit = (want_b >= b0 && want_b < b0 + 64) ? (1ull << (want_b - b0)) : 0ull;
+        else
+            hit = __ballot(base + inc > gid);
+        if (hit != 0ull) {
+            const int l = __builtin_ctzll(hit);
+            const int nn = __builtin_amdgcn_readlane(n, l), ii = __builtin_amdgcn_readlane(inc, l);
+            r.b = b0 + l;
+            r.first = base + ii - nn;
+            r.n = nn;
+            return r;
+        }
+        base += __builtin_amdgcn_readlane(inc, 63);
+    }
+    return r;
+}
 
 // ---------------------------------------------------------------- appended (never pruned) rows
 
@@ -217,7 +280,7 @@ __device__ __forceinline__ void tail_partial(const DecodeParams &P, int b, int h
             Lsum = fmaf(red_l[w][g], f, Lsum);
             A = fmaf(red_acc[(w * G + g) * SPARK_D + ch], f, A);
         }
-        const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + P.nsplit + part;
+        const int64_t slot = P.tail_base + ((int64_t)b * P.Hq + h * G + g) * P.tail_slots + part;
         st_agent(&P.part_acc[slot * SPARK_D + ch], A);
         if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
     }
@@ -268,16 +331,28 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep tile addressing scalar
     const SparkLayout &L = P.L;
     const int T = TCT ? TCT : L.T;
-    // blocks [0, B * Hkv * nsplit) are sequence splits; when rows have been appended after prefill, B * Hkv *
-    // ntail more blocks follow, each taking 256 of a (batch, KV head)'s appended rows
-    const int nmain = (int)L.batch * P.Hkv * P.nsplit;
+    // blocks [0, nchunk_max * Hkv) are (global chunk, KV head) pairs; when rows have been appended after
+    // prefill, B * Hkv * ntail more blocks follow, each taking 256 of a (batch, KV head)'s appended rows
+    const int nmain = P.nchunk_max * P.Hkv;
     const bool is_tail = (int)blockIdx.x >= nmain;      // block-uniform
-    const int split = is_tail ? P.nsplit : (int)(blockIdx.x % P.nsplit);
-    const int bh = is_tail ? ((int)blockIdx.x - nmain) / P.ntail : (int)(blockIdx.x / P.nsplit);
-    const int h = bh % P.Hkv, b = bh / P.Hkv;
+    const int tb = (int)blockIdx.x - nmain;
+    const int gid = is_tail ? -1 : (int)(blockIdx.x / P.Hkv);
+    const int h = is_tail ? (tb / P.ntail) % P.Hkv : (int)(blockIdx.x % P.Hkv);
+    const SeqChunks sc = locate_chunks(P, L.batch, gid, is_tail ? (tb / P.ntail) / P.Hkv : -1, lane);
+    if (sc.n == 0) return;                               // past the last chunk: the whole block leaves
+    const int b = sc.b;
+    const int bh = b * P.Hkv + h;
+    const int split = is_tail ? 0 : gid - sc.first;     // this block's chunk within its sequence
+    const int nsplit = sc.n;                             // chunks of this sequence
+    const int nmerge = nsplit + P.ntail;                 // partial states the last block folds
+    // partial slot of (q head index within the batch element's heads, i-th partial of this (batch, KV head))
+    auto slot_of = [&](int qh, int i) -> int64_t {
+        return (i < nsplit) ? (int64_t)(sc.first + i) * P.Hq + qh
+                            : P.tail_base + ((int64_t)b * P.Hq + qh) * P.tail_slots + (i - nsplit);
+    };
     if (is_tail) {
         static_assert(sizeof(qtab) >= G * SPARK_D * 4 && sizeof(Pbuf) >= kDecodeWaves * G * 64 * 4, "LDS reuse");
-        tail_partial<G>(P, b, h, ((int)blockIdx.x - nmain) % P.ntail, qtab, reinterpret_cast<float *>(&Pbuf[0][0][0][0]), red_m, red_l,
+        tail_partial<G>(P, b, h, tb % P.ntail, qtab, reinterpret_cast<float *>(&Pbuf[0][0][0][0]), red_m, red_l,
                         reinterpret_cast<float *>(&wbuf[0][0]));
     } else {
     const int s0 = P.cu[b], s1 = P.cu[b + 1];
@@ -287,7 +362,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     if (s1 > s0) {
         const int tf = s0 / SPARK_TILE_TOKENS, tl = (s1 - 1) / SPARK_TILE_TOKENS;
         const int ntile = tl - tf + 1;
-        const int chunk = (ntile + P.nsplit - 1) / P.nsplit;
+        const int chunk = (ntile + nsplit - 1) / nsplit;
         t_begin = tf + split * chunk;
         t_end = t_begin + chunk;
         if (t_end > tl + 1) t_end = tl + 1;
@@ -702,7 +777,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             Lsum = fmaf(red_l[w][g], f, Lsum);
             A = fmaf(red_acc(w, g, ch), f, A);
         }
-        const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + split;
+        const int64_t slot = slot_of(h * G + g, split);
         st_agent(&P.part_acc[slot * SPARK_D + ch], A);
         if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
     }
@@ -717,22 +792,22 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have completed
     __syncthreads();
     if (tid == 0) {
-        const uint32_t old = atomicInc(&P.counters[bh], (uint32_t)(P.nmerge - 1));
-        last_flag = (old == (uint32_t)(P.nmerge - 1));
+        const uint32_t old = atomicInc(&P.counters[bh], (uint32_t)(nmerge - 1));
+        last_flag = (old == (uint32_t)(nmerge - 1));
     }
     __syncthreads();
     if (!last_flag) return;
     constexpr int NTH = kDecodeWaves * 64;
-    if (P.nmerge <= 256) {
+    if (nmerge <= 256) {
         // The (m, l) pairs of all partials go to LDS first (one 8-byte device-scope load each); then each
         // thread owns two adjacent output channels of one head and folds the partials' accumulators with
         // sixteen 8-byte loads in flight.  (The per-wavefront buffers are free: every thread passed the
         // barrier above after its last read of them.)
         float2 *mlsh = reinterpret_cast<float2 *>(&wbuf[0][0]);     // [G][nmerge]
         static_assert(sizeof(wbuf) >= (size_t)G * 256 * sizeof(float2), "LDS reuse");
-        for (int idx = tid; idx < G * P.nmerge; idx += NTH) {
-            const int g = idx / P.nmerge, i = idx % P.nmerge;
-            const int64_t slot = ((int64_t)b * P.Hq + h * G + g) * P.nslots + i;
+        for (int idx = tid; idx < G * nmerge; idx += NTH) {
+            const int g = idx / nmerge, i = idx % nmerge;
+            const int64_t slot = slot_of(h * G + g, i);
             const uint64_t raw = __hip_atomic_load(reinterpret_cast<const uint64_t *>(P.part_ml + slot * 2),
                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             mlsh[idx] = make_float2(__uint_as_float((uint32_t)raw), __uint_as_float((uint32_t)(raw >> 32)));
@@ -740,23 +815,24 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         __syncthreads();
         for (int e = tid; e < G * (SPARK_D / 2); e += NTH) {
             const int g = e / (SPARK_D / 2), c2 = e % (SPARK_D / 2);
-            const float2 *mlg = mlsh + g * P.nmerge;
+            const float2 *mlg = mlsh + g * nmerge;
             float M = -INFINITY;
-            for (int i = 0; i < P.nmerge; ++i) M = fmaxf(M, mlg[i].x);
+            for (int i = 0; i < nmerge; ++i) M = fmaxf(M, mlg[i].x);
             const float Ms = (M == -INFINITY) ? 0.0f : M;
             const int64_t bq = (int64_t)b * P.Hq + h * G + g;
-            const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + bq * P.nslots * SPARK_D + 2 * c2);
+            const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + 2 * c2);
             float Lsum = 0.0f, A0 = 0.0f, A1 = 0.0f;
-            for (int i0 = 0; i0 < P.nmerge; i0 += 16) {
+            for (int i0 = 0; i0 < nmerge; i0 += 16) {
                 uint64_t av[16];
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
-                    const int i = (i0 + k < P.nmerge) ? (i0 + k) : (P.nmerge - 1);
-                    av[k] = __hip_atomic_load(pa + (int64_t)i * (SPARK_D / 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const int i = (i0 + k < nmerge) ? (i0 + k) : (nmerge - 1);
+                    av[k] = __hip_atomic_load(pa + slot_of(h * G + g, i) * (SPARK_D / 2), __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
                 }
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
-                    if (i0 + k < P.nmerge) {
+                    if (i0 + k < nmerge) {
                         const float2 mlv = mlg[i0 + k];
                         const float f = fast_exp2(mlv.x - Ms);      // m = -inf -> 0
                         Lsum = fmaf(mlv.y, f, Lsum);
@@ -780,7 +856,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     // one with the running-maximum rule, eight splits' loads in flight at a time, two elements at once.
     for (int idx0 = tid; idx0 < G * SPARK_D; idx0 += 2 * NTH) {
         float M[2], Lsum[2], A[2];
-        const float *ml[2], *pa[2];
+        int qh[2];
         int64_t bq[2];
         int ch[2];
         bool on[2];
@@ -790,27 +866,27 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             on[u] = idx < G * SPARK_D;
             const int g = on[u] ? idx / SPARK_D : 0;
             ch[u] = idx % SPARK_D;
-            bq[u] = (int64_t)b * P.Hq + h * G + g;
-            ml[u] = P.part_ml + bq[u] * P.nslots * 2;
-            pa[u] = P.part_acc + bq[u] * P.nslots * SPARK_D + ch[u];
+            qh[u] = h * G + g;
+            bq[u] = (int64_t)b * P.Hq + qh[u];
             M[u] = -INFINITY; Lsum[u] = 0.0f; A[u] = 0.0f;
         }
-        for (int i0 = 0; i0 < P.nmerge; i0 += 8) {
+        for (int i0 = 0; i0 < nmerge; i0 += 8) {
             float mi[2][8], li[2][8], ai[2][8];
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    const int i = (i0 + k < P.nmerge) ? (i0 + k) : (P.nmerge - 1);
-                    mi[u][k] = ld_agent(ml[u] + 2 * i);
-                    li[u][k] = ld_agent(ml[u] + 2 * i + 1);
-                    ai[u][k] = ld_agent(pa[u] + (int64_t)i * SPARK_D);
+                    const int i = (i0 + k < nmerge) ? (i0 + k) : (nmerge - 1);
+                    const int64_t slot = slot_of(qh[u], i);
+                    mi[u][k] = ld_agent(P.part_ml + slot * 2);
+                    li[u][k] = ld_agent(P.part_ml + slot * 2 + 1);
+                    ai[u][k] = ld_agent(P.part_acc + slot * SPARK_D + ch[u]);
                 }
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    if (i0 + k < P.nmerge) {
+                    if (i0 + k < nmerge) {
                         const float Mn = fmaxf(M[u], mi[u][k]);
                         const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
                         const float fo = fast_exp2(M[u] - Ms), fn = fast_exp2(mi[u][k] - Ms);

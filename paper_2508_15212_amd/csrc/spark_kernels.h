@@ -9,6 +9,14 @@ namespace spark {
 
 struct DecodeParams;
 
+// How the decode grid cuts sequences into blocks (chosen on the host from the description alone).
+struct DecodePlan {
+    int fixed_splits;   // > 0: every sequence is cut into this many chunks
+    int chunk_tiles;    // else: a sequence spanning ntile tiles gets max(1, ceil(ntile / chunk_tiles)) chunks
+    int nchunk_max;     // upper bound on the number of chunks in the batch (grid = nchunk_max * Hkv + tail blocks)
+    int tail_slots;     // partial slots reserved per (batch, q head) for appended rows
+};
+
 hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
                         const int32_t *cu, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st);
 
@@ -21,11 +29,12 @@ hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *
 
 // q [B,Hq,128] bf16; the caller splits the workspace into part_acc / part_ml / counters.
 // Values are either dense (v, strides; packed_v = NULL) or a packed value cache (packed_v, Lv; v = NULL).
-// Partial slots per (batch, q head): nsplit + 1; tail_k != NULL adds the appended rows [B, tail_cap, Hkv, 128].
+// Partial slots: plan.nchunk_max * Hq, then batch * Hq * plan.tail_slots; tail_k != NULL adds the appended rows
+// [B, tail_cap, Hkv, 128].
 hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const uint16_t *v, int64_t v_tok_stride,
                               int64_t v_head_stride, const uint8_t *packed_v, const SparkLayout *Lv,
                               const int32_t *cu, float *part_acc, float *part_ml,
-                              uint32_t *counters, int Hq, int nsplit, float softmax_scale, const SparkLayout &L,
+                              uint32_t *counters, int Hq, const DecodePlan &plan, float softmax_scale, const SparkLayout &L,
                               void *out, int out_f32, const uint16_t *tail_k, const uint16_t *tail_v,
                               const int32_t *tail_len, int tail_cap, hipStream_t st);
 

@@ -42,7 +42,10 @@ def test_size_queries_follow_the_layout():
     assert spark.packed_bytes(_desc(pack_dtype=spark.PACK_INT8)) == 256 + 2 * 8 * 8 * 128 * 4 + rows * 56
     ns = spark.decode_splits(d)
     assert ns >= 1
-    assert spark.decode_workspace_bytes(d) == 8 * 32 * (ns + 1) * 130 * 4 + 8 * 8 * 4   # one spare slot: appended rows
+    assert ns == 8                          # 4096 tiles x 8 heads / 512 blocks = chunks of 64 tiles; 512 / 64
+    # slots: one per (chunk, q head) for at most (4096 + 2 * 8) // 64 + 8 + 1 = 73 chunks, plus one spare per
+    # (batch, q head) for appended rows; 130 floats per slot; then the 8 * 8 arrival counters
+    assert spark.decode_workspace_bytes(d) == (73 * 32 + 8 * 32 * 1) * 130 * 4 + 8 * 8 * 4
     assert spark.decode_splits(_desc(n_splits=7)) == 7
     # partial last tile is padded to 64 tokens
     assert spark.packed_bytes(_desc(batch=1, total_tokens=65)) == 256 + 2 * 8 * 128 * 4 + 2 * 64 * 8 * 72
@@ -109,8 +112,7 @@ def test_value_cache_and_tail_entry_points_check_their_arguments_on_the_host():
     assert lib.spark_unpack_values(ctypes.byref(d), None, None, None, None) == 1
     # appended rows: capacity enters the workspace size (one spare slot per 256 rows)
     dt = _desc(tail_capacity=600)
-    ns = spark.decode_splits(dt)
-    assert spark.decode_workspace_bytes(dt) == 8 * 32 * (ns + 3) * 130 * 4 + 8 * 8 * 4
+    assert spark.decode_workspace_bytes(dt) == (73 * 32 + 8 * 32 * 3) * 130 * 4 + 8 * 8 * 4
     ws_t = spark.decode_workspace_bytes(dt)
     assert lib.spark_decode_attn_tail(ctypes.byref(dt), A, A, A, A, None, A, A, A, A, ws_t, None) == 1
     assert lib.spark_decode_attn_tail(ctypes.byref(dt), A, A, A, A, A, None, A, A, A, ws_t, None) == 1

@@ -171,3 +171,28 @@ def test_token_scales_jump_by_many_octaves(lo, hi, with_decode):
     _check_prune(res, a32, pr)
     if with_decode:
         _check_out(res, ref, w.name)
+
+
+def test_skewed_batch_long_sequences_get_more_blocks():
+    """One long sequence among short ones: the library cuts sequences into blocks by length (the long one
+    into many), short and empty ones get a single block."""
+    w = wl.small(name="skewed", batch=7, n_q_heads=8, n_kv_heads=2, keep=26, seqlens=(9000, 64, 0, 700, 1, 130, 2500),
+                 seed=120)
+    res, _, _ = _run(w)
+    assert np.all(res["out_f32"][2] == 0)
+
+
+def test_batch_larger_than_the_chunk_numbering_handles_in_one_pass():
+    """More than 256 sequences: every sequence gets the same number of blocks (the in-kernel numbering of
+    length-proportional chunks works on 64 sequences at a time and is not used for very large batches)."""
+    rng = np.random.default_rng(121)
+    lens = tuple(int(x) for x in rng.integers(0, 90, size=300))
+    w = wl.small(name="batch300", batch=300, n_q_heads=4, n_kv_heads=2, keep=26, seqlens=lens, seed=121)
+    _run(w)
+
+
+def test_batch_between_64_and_256_sequences():
+    rng = np.random.default_rng(122)
+    lens = tuple(int(x) for x in rng.integers(0, 200, size=150))
+    w = wl.small(name="batch150", batch=150, n_q_heads=4, n_kv_heads=2, keep=26, seqlens=lens, seed=122)
+    _run(w)
