@@ -64,8 +64,10 @@ typedef struct spark_desc {
     int64_t k_token_stride, k_head_stride;    /* dense K (spark_prune only) */
     int64_t v_token_stride, v_head_stride;    /* dense V (spark_decode_attn only) */
     float   softmax_scale;    /* 0 => 1/sqrt(head_dim) */
-    int32_t n_splits;         /* sequence splits per (batch, KV head) in decode; 0 => library picks.
-                                 Must be the same for the workspace query and the call. */
+    int32_t n_splits;         /* decode: > 0 cuts every sequence into this many blocks per KV head; 0 => the
+                                 library cuts sequences in proportion to their length (ragged batches:
+                                 long sequences get more blocks).  Must be the same for the workspace
+                                 query, its init and the calls. */
     int32_t keep_v;           /* T_v in [1, D]: channels kept per (token, KV head) of the VALUE cache, used by
                                  the *_values entry points only; 0 where values stay dense */
     int32_t tail_capacity;    /* rows per sequence in the appended-token buffers of spark_decode_attn_tail;
@@ -91,7 +93,7 @@ size_t spark_decode_workspace(const spark_desc *desc);
 spark_status spark_decode_workspace_init(const spark_desc *desc, void *workspace,
                                          size_t workspace_bytes, void *hip_stream);
 
-/* Number of sequence splits spark_decode_attn will use for this description. */
+/* Number of blocks per KV head spark_decode_attn uses for a sequence of average length. */
 int32_t spark_decode_splits(const spark_desc *desc);
 
 /*
