@@ -131,25 +131,27 @@ __device__ __forceinline__ int wave_inclusive_sum_i32(int v)
     return v;
 }
 
-struct SeqChunks { int b, first, n; };   // sequence, global id of its first chunk, number of its chunks (0: none)
+struct SeqChunks { int b, first, n, s0, s1; };   // sequence, global id of its first chunk, number of its chunks
+                                                  // (0: none), its token range
 
 // Finds the sequence that owns global chunk `gid` (want_b < 0) or describes sequence `want_b`.  Every lane of
 // the wavefront calls it with the same arguments and gets the same answer: 64 sequences are sized per step
 // (lane = sequence) and a wave prefix sum numbers their chunks.
 __device__ __forceinline__ SeqChunks locate_chunks(const DecodeParams &P, int B, int gid, int want_b, int lane)
 {
-    SeqChunks r = {0, 0, 0};
+    SeqChunks r = {0, 0, 0, 0, 0};
     if (P.fixed_splits > 0) {
         const int b = (want_b >= 0) ? want_b : gid / P.fixed_splits;
-        if (b < B) { r.b = b; r.first = b * P.fixed_splits; r.n = P.fixed_splits; }
+        if (b < B) { r.b = b; r.first = b * P.fixed_splits; r.n = P.fixed_splits; r.s0 = P.cu[b]; r.s1 = P.cu[b + 1]; }
         return r;
     }
     int base = 0;
     for (int b0 = 0; b0 < B; b0 += 64) {
         const int bb = b0 + lane;
-        int n = 0;
+        int n = 0, s0 = 0, s1 = 0;
         if (bb < B) {
-            const int s0 = P.cu[bb], s1 = P.cu[bb + 1];
+            s0 = P.cu[bb];
+            s1 = P.cu[bb + 1];
             const int ntile = (s1 > s0) ? ((s1 - 1) / SPARK_TILE_TOKENS - s0 / SPARK_TILE_TOKENS + 1) : 0;
             n = (ntile + P.chunk_tiles - 1) / P.chunk_tiles;
             n = n < 1 ? 1 : n;     // an empty sequence still gets one block: somebody has to write its zeros
@@ -166,6 +168,8 @@ __device__ __forceinline__ SeqChunks locate_chunks(const DecodeParams &P, int B,
             r.b = b0 + l;
             r.first = base + ii - nn;
             r.n = nn;
+            r.s0 = __builtin_amdgcn_readlane(s0, l);
+            r.s1 = __builtin_amdgcn_readlane(s1, l);
             return r;
         }
         base += __builtin_amdgcn_readlane(inc, 63);
@@ -355,7 +359,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         tail_partial<G>(P, b, h, tb % P.ntail, qtab, reinterpret_cast<float *>(&Pbuf[0][0][0][0]), red_m, red_l,
                         reinterpret_cast<float *>(&wbuf[0][0]));
     } else {
-    const int s0 = P.cu[b], s1 = P.cu[b + 1];
+    const int s0 = sc.s0, s1 = sc.s1;
 
     // ---- tiles of this split
     int t_begin = 0, t_end = 0;
@@ -777,11 +781,21 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             Lsum = fmaf(red_l[w][g], f, Lsum);
             A = fmaf(red_acc(w, g, ch), f, A);
         }
-        const int64_t slot = slot_of(h * G + g, split);
-        st_agent(&P.part_acc[slot * SPARK_D + ch], A);
-        if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
+        if (nmerge == 1) {   // the only block of this (batch, KV head): the result is final
+            const float o = (Lsum > 0.0f) ? (A / Lsum) : 0.0f;
+            const int64_t oi = ((int64_t)b * P.Hq + h * G + g) * SPARK_D + ch;
+            if (P.out_f32)
+                reinterpret_cast<float *>(P.out)[oi] = o;
+            else
+                reinterpret_cast<uint16_t *>(P.out)[oi] = __builtin_bit_cast(uint16_t, (__bf16)o);
+        } else {
+            const int64_t slot = slot_of(h * G + g, split);
+            st_agent(&P.part_acc[slot * SPARK_D + ch], A);
+            if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
+        }
     }
     }   // sequence split
+    if (nmerge == 1) return;   // (block-uniform)
 
     // ---- the last block of this (batch, KV head) to get here merges the splits.
     // The partials are written and read with device-scope accesses (they go to the point where
