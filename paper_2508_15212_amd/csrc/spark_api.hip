@@ -50,7 +50,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 // How the decode grid cuts the batch into blocks.  The decode kernel keeps two 4-wave blocks resident per
 // compute unit (256 CUs), so about 512 blocks stream the cache in a single round with no tail; a block should
-// still see at least 8 tiles (two per wavefront).  Sequences are cut into chunks of chunk_tiles tiles, so long
+// still see at least 4 tiles (one per wavefront).  Sequences are cut into chunks of chunk_tiles tiles, so long
 // sequences of a ragged batch get more blocks than short ones; n_splits > 0 (or a batch too large for the
 // in-kernel numbering of the chunks) asks for the same number of chunks for every sequence instead.
 spark::DecodePlan plan_of(const spark_desc *d)
@@ -63,7 +63,7 @@ spark::DecodePlan plan_of(const spark_desc *d)
     // at once, and every further round costs a block's fixed start-up and merge latency: then only sequences
     // well above the average length are cut.
     if ((int64_t)d->batch * d->n_kv_heads >= 256) chunk *= 2;
-    if (chunk < 8) chunk = 8;
+    if (chunk < 4) chunk = 4;     // one tile per wavefront: below that a block's start-up outweighs its work
     p.chunk_tiles = (int)chunk;
     p.fixed_splits = 0;
     if (d->n_splits > 0) {
