@@ -159,7 +159,7 @@ def main() -> int:
     # Streaming-read yardstick on this machine: the library's plain read kernel over one V copy
     # (also the kernel of known size that scales the HBM byte counters of a profiler run).
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
-    probe_blocks = 1536
+    probe_blocks = 512      # two blocks per compute unit: the fastest plain read on this part (more are slower)
     for c in range(ncopy):
         spark.probe_read(vs[c], sink, probe_blocks)
     torch.cuda.synchronize()
