@@ -15,7 +15,7 @@ import torch
 import oracle
 import workloads as wl
 import paper_2508_15212_amd as spark
-from tests.gpu_util import run_gpu_case
+from tests.gpu_util import make_desc, run_gpu_case, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -196,3 +196,20 @@ def test_batch_between_64_and_256_sequences():
     lens = tuple(int(x) for x in rng.integers(0, 200, size=150))
     w = wl.small(name="batch150", batch=150, n_q_heads=4, n_kv_heads=2, keep=26, seqlens=lens, seed=122)
     _run(w)
+
+
+def test_batch_of_empty_sequences_gives_zero_output():
+    """No cached token at all: prune launches nothing, decode still writes every output row (zeros)."""
+    w = wl.small(name="allempty", batch=2, n_q_heads=4, n_kv_heads=2, keep=26, seqlens=(0, 0), seed=1)
+    t = wl.generate(w)
+    desc = make_desc(w)
+    desc.k_head_stride = desc.v_head_stride = w.head_dim        # (zero tokens: any valid stride)
+    dq = to_dev(t.q)
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.zeros(max(spark.packed_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    k1 = torch.zeros(256, dtype=torch.int16, device="cuda")          # valid pointers; no row is ever read
+    spark.prune(desc, k1, to_dev(t.qwin), dcu, packed)
+    out = torch.full((w.batch, w.n_q_heads, w.head_dim), 7.0, dtype=torch.float32, device="cuda")
+    spark.decode_attn(desc, dq, packed, k1, dcu, out, spark.new_decode_workspace(desc))
+    torch.cuda.synchronize()
+    assert np.all(out.cpu().numpy() == 0)
