@@ -112,7 +112,6 @@ __device__ __forceinline__ float wave_sum(float x)
 
 // device-scope (all XCDs) relaxed store / load of one float
 __device__ __forceinline__ void st_agent(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-__device__ __forceinline__ float ld_agent(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ uint32_t u4c(const uint4 &v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -811,113 +810,53 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     }
     __syncthreads();
     if (!last_flag) return;
+    // Each thread owns two adjacent output channels of one head and folds the partial states with the
+    // running-maximum rule; per round it has sixteen partials' (m, l) pairs and accumulator pairs in flight,
+    // all 8-byte device-scope loads, so a pair with up to sixteen partials needs one round trip.
     constexpr int NTH = kDecodeWaves * 64;
-    if (nmerge <= 256) {
-        // The (m, l) pairs of all partials go to LDS first (one 8-byte device-scope load each); then each
-        // thread owns two adjacent output channels of one head and folds the partials' accumulators with
-        // sixteen 8-byte loads in flight.  (The per-wavefront buffers are free: every thread passed the
-        // barrier above after its last read of them.)
-        float2 *mlsh = reinterpret_cast<float2 *>(&wbuf[0][0]);     // [G][nmerge]
-        static_assert(sizeof(wbuf) >= (size_t)G * 256 * sizeof(float2), "LDS reuse");
-        for (int idx = tid; idx < G * nmerge; idx += NTH) {
-            const int g = idx / nmerge, i = idx % nmerge;
-            const int64_t slot = slot_of(h * G + g, i);
-            const uint64_t raw = __hip_atomic_load(reinterpret_cast<const uint64_t *>(P.part_ml + slot * 2),
-                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            mlsh[idx] = make_float2(__uint_as_float((uint32_t)raw), __uint_as_float((uint32_t)(raw >> 32)));
-        }
-        __syncthreads();
-        for (int e = tid; e < G * (SPARK_D / 2); e += NTH) {
-            const int g = e / (SPARK_D / 2), c2 = e % (SPARK_D / 2);
-            const float2 *mlg = mlsh + g * nmerge;
-            float M = -INFINITY;
-            for (int i = 0; i < nmerge; ++i) M = fmaxf(M, mlg[i].x);
-            const float Ms = (M == -INFINITY) ? 0.0f : M;
-            const int64_t bq = (int64_t)b * P.Hq + h * G + g;
-            const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + 2 * c2);
-            float Lsum = 0.0f, A0 = 0.0f, A1 = 0.0f;
-            for (int i0 = 0; i0 < nmerge; i0 += 16) {
-                uint64_t av[16];
+    for (int e = tid; e < G * (SPARK_D / 2); e += NTH) {
+        const int g = e / (SPARK_D / 2), c2 = e % (SPARK_D / 2);
+        const int qh = h * G + g;
+        const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + 2 * c2);
+        const uint64_t *pm = reinterpret_cast<const uint64_t *>(P.part_ml);
+        float M = -INFINITY, Lsum = 0.0f, A0 = 0.0f, A1 = 0.0f;
+        for (int i0 = 0; i0 < nmerge; i0 += 16) {
+            uint64_t av[16], mv[16];
 #pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    const int i = (i0 + k < nmerge) ? (i0 + k) : (nmerge - 1);
-                    av[k] = __hip_atomic_load(pa + slot_of(h * G + g, i) * (SPARK_D / 2), __ATOMIC_RELAXED,
-                                              __HIP_MEMORY_SCOPE_AGENT);
-                }
+            for (int k = 0; k < 16; ++k) {
+                const int i = (i0 + k < nmerge) ? (i0 + k) : (nmerge - 1);
+                const int64_t slot = slot_of(qh, i);
+                mv[k] = __hip_atomic_load(pm + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                av[k] = __hip_atomic_load(pa + slot * (SPARK_D / 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            float Mn = M;
 #pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    if (i0 + k < nmerge) {
-                        const float2 mlv = mlg[i0 + k];
-                        const float f = fast_exp2(mlv.x - Ms);      // m = -inf -> 0
-                        Lsum = fmaf(mlv.y, f, Lsum);
-                        A0 = fmaf(__uint_as_float((uint32_t)av[k]), f, A0);
-                        A1 = fmaf(__uint_as_float((uint32_t)(av[k] >> 32)), f, A1);
-                    }
+            for (int k = 0; k < 16; ++k)
+                if (i0 + k < nmerge) Mn = fmaxf(Mn, __uint_as_float((uint32_t)mv[k]));
+            const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
+            const float fo = fast_exp2(M - Ms);               // M = -inf -> 0
+            Lsum *= fo;
+            A0 *= fo;
+            A1 *= fo;
+            M = Mn;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                if (i0 + k < nmerge) {
+                    const float f = fast_exp2(__uint_as_float((uint32_t)mv[k]) - Ms);
+                    Lsum = fmaf(__uint_as_float((uint32_t)(mv[k] >> 32)), f, Lsum);
+                    A0 = fmaf(__uint_as_float((uint32_t)av[k]), f, A0);
+                    A1 = fmaf(__uint_as_float((uint32_t)(av[k] >> 32)), f, A1);
                 }
             }
-            const float o0 = (Lsum > 0.0f) ? (A0 / Lsum) : 0.0f, o1 = (Lsum > 0.0f) ? (A1 / Lsum) : 0.0f;
-            if (P.out_f32) {
-                reinterpret_cast<float2 *>(P.out)[bq * (SPARK_D / 2) + c2] = make_float2(o0, o1);
-            } else {
-                const uint32_t packed2 = (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o0) |
-                                         ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o1) << 16);
-                reinterpret_cast<uint32_t *>(P.out)[bq * (SPARK_D / 2) + c2] = packed2;
-            }
         }
-        return;
-    }
-    // More than 256 partials: each thread owns output elements (g, ch) and folds the partial states one by
-    // one with the running-maximum rule, eight splits' loads in flight at a time, two elements at once.
-    for (int idx0 = tid; idx0 < G * SPARK_D; idx0 += 2 * NTH) {
-        float M[2], Lsum[2], A[2];
-        int qh[2];
-        int64_t bq[2];
-        int ch[2];
-        bool on[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int idx = idx0 + u * NTH;
-            on[u] = idx < G * SPARK_D;
-            const int g = on[u] ? idx / SPARK_D : 0;
-            ch[u] = idx % SPARK_D;
-            qh[u] = h * G + g;
-            bq[u] = (int64_t)b * P.Hq + qh[u];
-            M[u] = -INFINITY; Lsum[u] = 0.0f; A[u] = 0.0f;
-        }
-        for (int i0 = 0; i0 < nmerge; i0 += 8) {
-            float mi[2][8], li[2][8], ai[2][8];
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const int i = (i0 + k < nmerge) ? (i0 + k) : (nmerge - 1);
-                    const int64_t slot = slot_of(qh[u], i);
-                    mi[u][k] = ld_agent(P.part_ml + slot * 2);
-                    li[u][k] = ld_agent(P.part_ml + slot * 2 + 1);
-                    ai[u][k] = ld_agent(P.part_acc + slot * SPARK_D + ch[u]);
-                }
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    if (i0 + k < nmerge) {
-                        const float Mn = fmaxf(M[u], mi[u][k]);
-                        const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
-                        const float fo = fast_exp2(M[u] - Ms), fn = fast_exp2(mi[u][k] - Ms);
-                        Lsum[u] = fmaf(Lsum[u], fo, li[u][k] * fn);
-                        A[u] = fmaf(A[u], fo, ai[u][k] * fn);
-                        M[u] = Mn;
-                    }
-                }
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            if (!on[u]) continue;
-            const float o = (Lsum[u] > 0.0f) ? (A[u] / Lsum[u]) : 0.0f;
-            if (P.out_f32)
-                reinterpret_cast<float *>(P.out)[bq[u] * SPARK_D + ch[u]] = o;
-            else
-                reinterpret_cast<uint16_t *>(P.out)[bq[u] * SPARK_D + ch[u]] = __builtin_bit_cast(uint16_t, (__bf16)o);
+        const int64_t bq = (int64_t)b * P.Hq + qh;
+        const float o0 = (Lsum > 0.0f) ? (A0 / Lsum) : 0.0f, o1 = (Lsum > 0.0f) ? (A1 / Lsum) : 0.0f;
+        if (P.out_f32) {
+            reinterpret_cast<float2 *>(P.out)[bq * (SPARK_D / 2) + c2] = make_float2(o0, o1);
+        } else {
+            const uint32_t packed2 = (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o0) |
+                                     ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o1) << 16);
+            reinterpret_cast<uint32_t *>(P.out)[bq * (SPARK_D / 2) + c2] = packed2;
         }
     }
 }
