@@ -180,6 +180,18 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     const int64_t wt = (int64_t)blockIdx.x * kPruneWaves + wave;
     const int64_t full_tiles = L.total_tokens / SPARK_TILE_TOKENS;
     if (wt >= (FULL ? full_tiles : 1) * L.n_kv_heads) return;   // whole wavefront leaves; no block barrier is used
+    if (VALUES && wt == 0 && (FULL || full_tiles == 0)) {
+        // header of a value cache (the key cache's is written with the channel weights): first wavefront of
+        // whichever launch comes first
+        uint32_t v = 0;
+        if (lane == 0) v = SPARK_MAGIC;
+        if (lane == 1) v = (uint32_t)L.T;
+        if (lane == 4) v = (uint32_t)L.n_kv_heads;
+        if (lane == 5) v = (uint32_t)L.total_tokens;
+        if (lane == 6) v = (uint32_t)L.ndw;
+        if (lane == 7) v = 1u;   // value cache
+        reinterpret_cast<uint32_t *>(packed)[lane] = v;
+    }
     const int h = FULL ? (int)(wt / full_tiles) : (int)wt;
     const int64_t tile = FULL ? wt % full_tiles : full_tiles;
     const int T = L.T;
@@ -540,19 +552,6 @@ hipError_t launch_tiles(const uint16_t *x, int64_t tok_stride, int64_t head_stri
                   : launch(&spark_prune_kernel<0, false, VALUES>, tail_waves);
 }
 
-__global__ void spark_values_header_kernel(uint8_t *packed, SparkLayout L)
-{
-    const int j = threadIdx.x;
-    uint32_t v = 0;
-    if (j == 0) v = SPARK_MAGIC;
-    if (j == 1) v = (uint32_t)L.T;
-    if (j == 4) v = (uint32_t)L.n_kv_heads;
-    if (j == 5) v = (uint32_t)L.total_tokens;
-    if (j == 6) v = (uint32_t)L.ndw;
-    if (j == 7) v = 1u;   // value cache
-    reinterpret_cast<uint32_t *>(packed)[j] = v;
-}
-
 }  // namespace
 
 hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
@@ -569,9 +568,6 @@ hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_
 hipError_t launch_prune_values(const uint16_t *v, int64_t v_tok_stride, int64_t v_head_stride, uint8_t *packed,
                                const SparkLayout &L, hipStream_t st)
 {
-    hipLaunchKernelGGL(spark_values_header_kernel, dim3(1), dim3(64), 0, st, packed, L);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     return launch_tiles<true>(v, v_tok_stride, v_head_stride, nullptr, packed, L, st);
 }
 
