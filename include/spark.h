@@ -51,7 +51,7 @@ typedef enum { SPARK_OUT_BF16 = 0, SPARK_OUT_F32 = 1 } spark_out_dtype;
 
 /* Problem description shared by all calls (plain data, host memory). */
 typedef struct spark_desc {
-    int32_t batch;            /* B >= 1 */
+    int32_t batch;            /* 1 <= B <= 2^18 */
     int32_t n_q_heads;        /* Hq, a multiple of n_kv_heads; Hq/Hkv in {1,2,4,8,16} */
     int32_t n_kv_heads;       /* Hkv >= 1 */
     int32_t head_dim;         /* D, must be 128 */
@@ -60,7 +60,7 @@ typedef struct spark_desc {
     int32_t window;           /* W >= 1: observation-window length (spark_prune only) */
     int32_t pack_dtype;       /* spark_pack_dtype: storage of the kept key entries */
     int32_t out_dtype;        /* spark_out_dtype: element type of spark_decode_attn's output */
-    int64_t total_tokens;     /* sum of sequence lengths, < 2^31 */
+    int64_t total_tokens;     /* sum of sequence lengths, <= 2^31 - 256 */
     int64_t k_token_stride, k_head_stride;    /* dense K (spark_prune only) */
     int64_t v_token_stride, v_head_stride;    /* dense V (spark_decode_attn only) */
     float   softmax_scale;    /* 0 => 1/sqrt(head_dim) */

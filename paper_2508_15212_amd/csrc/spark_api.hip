@@ -15,7 +15,9 @@ bool desc_ok(const spark_desc *d, spark_status *why)
     *why = SPARK_ERR_INVALID_ARG;
     if (!d) return false;
     if (d->batch < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1) return false;
-    if (d->total_tokens < 0 || d->total_tokens >= (int64_t)1 << 31) return false;
+    // token and tile indices are 32-bit in the kernels (a tile's last row index must still fit), block counts too
+    if (d->total_tokens < 0 || d->total_tokens > ((int64_t)1 << 31) - 256) return false;
+    if (d->batch > (1 << 18)) return false;
     if (d->keep < 1 || d->keep > d->head_dim) return false;
     if (d->n_q_heads % d->n_kv_heads) return false;
     if (d->n_splits < 0 || d->n_splits > 4096) return false;

@@ -120,3 +120,9 @@ def test_value_cache_and_tail_entry_points_check_their_arguments_on_the_host():
     assert lib.spark_decode_attn_tail(ctypes.byref(_desc()), A, A, A, A, A, A, A, A, A, ws_t, None) == 1   # capacity 0
     assert lib.spark_decode_attn_tail(ctypes.byref(dt), A, A, A, A, A, A, A, A, A, ws_t - 1, None) == 3
     assert spark.packed_bytes(_desc(tail_capacity=-1)) == 0
+
+
+def test_size_limits_of_the_description():
+    assert spark.packed_bytes(_desc(batch=1, total_tokens=(1 << 31) - 256)) > 0
+    assert spark.packed_bytes(_desc(batch=1, total_tokens=(1 << 31) - 255)) == 0
+    assert spark.packed_bytes(_desc(batch=(1 << 18) + 1)) == 0
