@@ -31,7 +31,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per decode launch from rocprofv3 counters (FETCH_SIZE x 2.000 calibration + WRITE_SIZE),
 # per workload; measured once and recorded in profiles/decode_prune_cfg2_hbm_traffic.md.
-MEASURED_DECODE_TRAFFIC_BYTES = {("cfg2_llama8b_b8_32k_keep26", "bf16"): 2 * 336620 * 1024 + 1232 * 1024}
+MEASURED_DECODE_TRAFFIC_BYTES = {("cfg2_llama8b_b8_32k_keep26", "bf16"): 2 * 336613 * 1024 + 1232 * 1024}
 
 
 def main() -> int:
