@@ -42,6 +42,8 @@ def lib() -> ctypes.CDLL:
         _lib.oracle_max_threads.restype = ctypes.c_int
         _lib.oracle_prune.restype = ctypes.c_int
         _lib.oracle_prune_values.restype = ctypes.c_int
+        _lib.oracle_uniform.restype = ctypes.c_double
+        _lib.oracle_mix32.restype = ctypes.c_uint32
     return _lib
 
 
@@ -202,6 +204,49 @@ def decode_literal(q, pr: Pruned, v, layout, cu, scale=None, want_probs=False):
 def decode_fused(q, pr: Pruned, v, layout, cu, scale=None):
     """Algebraically identical form with the recovery term factored out."""
     return _decode("fused", q, pr, v, layout, cu, scale, False)
+
+
+GAUSSIAN, EXPONENTIAL = 1, 2
+
+
+def row_stats(k: np.ndarray, layout: str, a32: np.ndarray, cu: np.ndarray):
+    """All-channel saliency statistics per (token, KV head): (mu float32, sigma float32), each [total, Hkv]."""
+    k, ts, hs, total, hkv, d = _strided(k, layout)
+    cu = _c(cu, np.int32)
+    a32 = _c(a32, np.float32)
+    mu = np.empty((total, hkv), np.float32)
+    sigma = np.empty((total, hkv), np.float32)
+    lib().oracle_row_stats(_p(k), ctypes.c_int64(ts), ctypes.c_int64(hs), _p(a32), _p(cu), cu.shape[0] - 1, hkv, d,
+                           _p(mu), _p(sigma))
+    return mu, sigma
+
+
+def mix32(x: int) -> int:
+    return int(lib().oracle_mix32(ctypes.c_uint32(x & 0xFFFFFFFF)))
+
+
+def uniform(seed: int, n: int, h: int, c: int) -> float:
+    return float(lib().oracle_uniform(ctypes.c_uint32(seed & 0xFFFFFFFF), ctypes.c_uint32((seed >> 32) & 0xFFFFFFFF),
+                                      ctypes.c_uint32(n), ctypes.c_uint32(h), ctypes.c_uint32(c)))
+
+
+def decode_sampled(kind: int, seed: int, q, pr: Pruned, mu_all, sigma, v, layout, cu, scale=None, want_ktilde=False):
+    """Decode with the Gaussian (1) or Exponential (2) recovery function; seed is a 64-bit integer."""
+    q = _c(q, np.uint16)
+    b, hq, d = q.shape
+    v, ts, hs, total, hkv, dv = _strided(v, layout)
+    assert dv == d == pr.D and pr.codes is None
+    cu = _c(cu, np.int32)
+    mu_all, sigma = _c(mu_all, np.float32), _c(sigma, np.float32)
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    out = np.empty((b, hq, d), np.float64)
+    kt = np.zeros((total, hkv, d), np.float64) if want_ktilde else None
+    lib().oracle_decode_sampled(int(kind), ctypes.c_uint32(seed & 0xFFFFFFFF), ctypes.c_uint32((seed >> 32) & 0xFFFFFFFF),
+                                _p(q), _p(pr.mask), _p(pr.kept), _p(mu_all), _p(sigma), _p(pr.a32), _p(v),
+                                ctypes.c_int64(ts), ctypes.c_int64(hs), _p(cu), b, hq, hkv, d, pr.T,
+                                ctypes.c_double(scale), _p(out), _p(kt))
+    return (out, kt) if want_ktilde else out
 
 
 def decode_literal_tail(q, pr: Pruned, v, layout, cu, tail_k, tail_v, tail_len, scale=None):

@@ -27,7 +27,10 @@
  * window-scale invariance, and the invariants listed in tests/test_oracle_pins.py; the
  * value-cache functions by brute-force subset optimality, a second hand-worked case and
  * an independent masked-matrix product; the appended-token decode by a third hand-worked
- * case, dense attention on the concatenated cache (keep-all) and the empty-tail identity.  No function in this file is "parity unpinned".
+ * case, dense attention on the concatenated cache (keep-all) and the empty-tail identity; the
+ * sampled recovery by the invertibility and the statistics of its generator, the sigma = 0
+ * reduction to the degenerate function, sample means, and a plain softmax attention over the
+ * exported rebuilt keys.  No function in this file is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -432,6 +435,145 @@ void oracle_decode_fused(const uint16_t *q, const uint32_t *mask, const uint16_t
                              v_tok_stride, D, out + ((int64_t)b * Hq + g) * D, NULL);
         free(s);
         free(r);
+    }
+}
+
+/* ------------------------------------------------------------- sampled recovery */
+
+/*
+ * Per-token statistics of the saliency over ALL channels, App. "Caching Pruned Channel
+ * Statistics": for every (token n, KV head h), with w_j = a32[b,h,j] * |K[n,h,j]| (the same
+ * binary32 product the selection compares),
+ *     mu    = (1/D) sum_j w_j
+ *     sigma = sqrt( (1/D) sum_j (w_j - mu)^2 )          (population standard deviation)
+ * in double, each rounded once to binary32 for storage.  mu32, sigma32 [total,Hkv].
+ */
+void oracle_row_stats(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride,
+                      const float *a32, const int32_t *cu, int B, int Hkv, int D, float *mu32,
+                      float *sigma32)
+{
+    const int64_t total = cu[B];
+    int64_t n;
+#pragma omp parallel for schedule(static)
+    for (n = 0; n < total; ++n) {
+        const int b = seq_of_token(cu, B, n);
+        for (int h = 0; h < Hkv; ++h) {
+            const uint16_t *krow = k + n * k_tok_stride + (int64_t)h * k_head_stride;
+            const float *a = a32 + ((int64_t)b * Hkv + h) * D;
+            double w[1024], s = 0.0;
+            for (int j = 0; j < D; ++j) {
+                volatile float prod = a[j] * fabsf(bf16_bits_to_f32(krow[j]));
+                w[j] = (double)prod;
+                s += w[j];
+            }
+            const double mu = s / (double)D;
+            double ss = 0.0;
+            for (int j = 0; j < D; ++j) ss += (w[j] - mu) * (w[j] - mu);
+            mu32[n * Hkv + h] = (float)mu;
+            sigma32[n * Hkv + h] = (float)sqrt(ss / (double)D);
+        }
+    }
+}
+
+/*
+ * Random numbers of the sampled recovery functions.  The paper does not say how or when the
+ * samples are drawn; here they are a pure function of (seed, token n, KV head h, counter c),
+ * so a decode step can be repeated and both implementations can produce the same variates:
+ *     mix(x):  x ^= x >> 16;  x *= 0x85EBCA6B;  x ^= x >> 13;  x *= 0xC2B2AE35;  x ^= x >> 16
+ *              (the 32-bit finalizer of MurmurHash3, a bijection of the 32-bit words)
+ *     base   = mix( mix( mix(n) + seed_lo ) + h * 0x9E3779B9 + seed_hi )
+ *     x_c    = mix( base + c * 0x9E3779B9 )
+ *     u_c    = ( (x_c >> 8) + 0.5 ) / 2^24            in (0, 1), 24 bits
+ */
+static uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x85EBCA6Bu;
+    x ^= x >> 13;
+    x *= 0xC2B2AE35u;
+    x ^= x >> 16;
+    return x;
+}
+
+uint32_t oracle_mix32(uint32_t x) { return mix32(x); }
+
+double oracle_uniform(uint32_t seed_lo, uint32_t seed_hi, uint32_t n, uint32_t h, uint32_t c)
+{
+    const uint32_t base = mix32(mix32(mix32(n) + seed_lo) + h * 0x9E3779B9u + seed_hi);
+    const uint32_t x = mix32(base + c * 0x9E3779B9u);
+    return ((double)(x >> 8) + 0.5) / 16777216.0;
+}
+
+/*
+ * Sampled saliency of pruned channel j of row (n, h), Sec. "SparK", "Channel Recovery":
+ *   kind 1, Gaussian:     w~ = mu + sigma * z_j,  z from the Box-Muller transform of the pair
+ *                         (u_{2m}, u_{2m+1}) for channels j = 2m, 2m+1:
+ *                         z_{2m} = sqrt(-2 ln u_{2m}) cos(2 pi u_{2m+1}),  z_{2m+1} = ... sin(...)
+ *   kind 2, Exponential:  w~ = -mu * ln(u_j)        (rate 1/mu, i.e. mean mu)
+ * mu, sigma are the all-channel statistics above.  A Gaussian sample may be negative; the
+ * paper does not clamp it and neither does this.
+ */
+static double sampled_saliency(int kind, double mu, double sigma, uint32_t seed_lo,
+                               uint32_t seed_hi, uint32_t n, uint32_t h, int j)
+{
+    const double two_pi = 6.283185307179586476925286766559;
+    if (kind == 1) {
+        const int m = j >> 1;
+        const double u1 = oracle_uniform(seed_lo, seed_hi, n, h, (uint32_t)(2 * m));
+        const double u2 = oracle_uniform(seed_lo, seed_hi, n, h, (uint32_t)(2 * m + 1));
+        const double r = sqrt(-2.0 * log(u1));
+        const double z = (j & 1) ? r * sin(two_pi * u2) : r * cos(two_pi * u2);
+        return mu + sigma * z;
+    }
+    return -mu * log(oracle_uniform(seed_lo, seed_hi, n, h, (uint32_t)j));
+}
+
+/*
+ * Decode attention with a sampled recovery function (literal form): pruned entry (n, j) is
+ * rebuilt as  ktilde = w~ / a_j  (0 if a_j == 0) with w~ drawn as above, kept entries are
+ * copied back, then Eq. (4).  kind: 1 Gaussian, 2 Exponential.  mu_all32, sigma32 from
+ * oracle_row_stats.  ktilde_out (may be NULL) [total,Hkv,D] double receives the rebuilt keys.
+ * Other arguments as oracle_decode_literal.
+ */
+void oracle_decode_sampled(int kind, uint32_t seed_lo, uint32_t seed_hi, const uint16_t *q,
+                           const uint32_t *mask, const uint16_t *kept_bf16, const float *mu_all32,
+                           const float *sigma32, const float *a32, const uint16_t *v,
+                           int64_t v_tok_stride, int64_t v_head_stride, const int32_t *cu, int B,
+                           int Hq, int Hkv, int D, int T, double softmax_scale, double *out,
+                           double *ktilde_out)
+{
+    const int G = Hq / Hkv;
+    const int MW = (D + 31) / 32;
+    int bg;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (bg = 0; bg < B * Hq; ++bg) {
+        const int b = bg / Hq, g = bg % Hq, h = g / G;
+        const int64_t n0 = cu[b], S = cu[b + 1] - cu[b];
+        const float *a = a32 + ((int64_t)b * Hkv + h) * D;
+        double *s = (double *)malloc(sizeof(double) * (size_t)(S > 0 ? S : 1));
+        double *ktilde = (double *)malloc(sizeof(double) * (size_t)D);
+        for (int64_t t = 0; t < S; ++t) {
+            const int64_t row = (n0 + t) * Hkv + h;
+            int c = 0;
+            for (int j = 0; j < D; ++j) {
+                if (mask[row * MW + j / 32] >> (j % 32) & 1u)
+                    ktilde[j] = bf16_bits_to_f64(kept_bf16[row * T + c++]);
+                else if (a[j] != 0.0f)
+                    ktilde[j] = sampled_saliency(kind, (double)mu_all32[row], (double)sigma32[row], seed_lo,
+                                                 seed_hi, (uint32_t)(n0 + t), (uint32_t)h, j) / (double)a[j];
+                else
+                    ktilde[j] = 0.0;
+                if (ktilde_out && g % G == 0) ktilde_out[row * D + j] = ktilde[j];
+            }
+            double dot = 0.0;
+            for (int j = 0; j < D; ++j)
+                dot += bf16_bits_to_f64(q[((int64_t)b * Hq + g) * D + j]) * ktilde[j];
+            s[t] = softmax_scale * dot;
+        }
+        softmax_weighted_sum(s, S, v + n0 * v_tok_stride + (int64_t)h * v_head_stride,
+                             v_tok_stride, D, out + ((int64_t)b * Hq + g) * D, NULL);
+        free(s);
+        free(ktilde);
     }
 }
 

@@ -528,3 +528,115 @@ def test_tail_empty_is_plain_decode_and_tail_only_is_dense_attention():
     ref = oracle.dense_attn(t0.q, np.ascontiguousarray(tk[:w0.batch].reshape(-1, w0.n_kv_heads, w0.head_dim)),
                             np.ascontiguousarray(tv[:w0.batch].reshape(-1, w0.n_kv_heads, w0.head_dim)), "NHD", cu5)
     assert np.allclose(got, ref, rtol=0, atol=1e-13)
+
+
+# ------------------------------------------------------------------ sampled recovery pins
+
+def _unmix32(y):
+    """Inverse of the 32-bit mixer, derived independently: undo each xor-shift, multiply by the modular
+    inverse of each odd constant."""
+    M = 0xFFFFFFFF
+    y ^= y >> 16
+    y = (y * pow(0xC2B2AE35, -1, 1 << 32)) & M
+    y ^= (y >> 13) ^ (y >> 26)
+    y = (y * pow(0x85EBCA6B, -1, 1 << 32)) & M
+    y ^= y >> 16
+    return y
+
+
+def test_generator_is_a_bijective_mixer_and_its_uniforms_behave():
+    rng = np.random.default_rng(31)
+    for x in [0, 1, 2, 0xFFFFFFFF] + [int(v) for v in rng.integers(0, 1 << 32, size=200)]:
+        assert _unmix32(oracle.mix32(x)) == x
+    assert oracle.mix32(0) == 0
+    # uniforms: in (0,1), on the 24-bit grid offset by half a step, deterministic, sensitive to every argument
+    u = np.array([[oracle.uniform(1234567890123, n, 1, c) for c in range(128)] for n in range(400)])
+    assert u.min() > 0.0 and u.max() < 1.0
+    assert np.all((u * (1 << 24) - 0.5) == np.round(u * (1 << 24) - 0.5))
+    assert oracle.uniform(7, 3, 1, 5) == oracle.uniform(7, 3, 1, 5)
+    base = oracle.uniform(7, 3, 1, 5)
+    assert len({base, oracle.uniform(8, 3, 1, 5), oracle.uniform(7 + (1 << 32), 3, 1, 5), oracle.uniform(7, 4, 1, 5),
+                oracle.uniform(7, 3, 2, 5), oracle.uniform(7, 3, 1, 6)}) == 6
+    flat = u.reshape(-1)                                       # 51,200 draws
+    assert abs(flat.mean() - 0.5) < 0.005 and abs(flat.var() - 1.0 / 12.0) < 0.002
+    assert abs(np.corrcoef(u[:, :-1].reshape(-1), u[:, 1:].reshape(-1))[0, 1]) < 0.02     # neighbouring counters
+    assert abs(np.corrcoef(u[:-1].reshape(-1), u[1:].reshape(-1))[0, 1]) < 0.02           # neighbouring tokens
+    hist = np.histogram(flat, bins=16, range=(0, 1))[0]
+    assert hist.min() > 0.9 * flat.size / 16 and hist.max() < 1.1 * flat.size / 16
+
+
+def _sampled_setup(seed, T=26):
+    w, t = _random_small(seed, Hq=8, Hkv=2, T=T)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep, want_w=True)
+    mu, sigma = oracle.row_stats(t.k, t.layout, a32, t.cu)
+    return w, t, a32, pr, mu, sigma
+
+
+def test_row_statistics_are_mean_and_population_std_of_the_saliency():
+    w, t, a32, pr, mu, sigma = _sampled_setup(41)
+    wf = pr.w.astype(np.float64)                               # [total,Hkv,D], the compared products
+    assert np.allclose(mu, wf.mean(-1), rtol=1e-7, atol=0)
+    assert np.allclose(sigma, wf.std(-1), rtol=1e-6, atol=0)   # numpy's std is the population one
+    # the mean of the pruned set lies below the all-channel mean (the largest entries were kept)
+    assert np.all(pr.mu64 <= mu.astype(np.float64) * (1 + 1e-6))
+
+
+@pytest.mark.parametrize("kind", [oracle.GAUSSIAN, oracle.EXPONENTIAL])
+def test_sampled_decode_is_plain_attention_over_the_exported_rebuilt_keys(kind):
+    w, t, a32, pr, mu, sigma = _sampled_setup(42)
+    out, kt = oracle.decode_sampled(kind, 99, t.q, pr, mu, sigma, t.v, t.layout, t.cu, want_ktilde=True)
+    bits = np.unpackbits(pr.mask.view(np.uint8), axis=-1, bitorder="little").astype(bool)
+    kf = fb(t.k).transpose(1, 0, 2).astype(np.float64)         # [total,Hkv,D]
+    assert np.array_equal(kt[bits], kf[bits])                  # kept entries are the original ones
+    qf, vf = fb(t.q).astype(np.float64), fb(t.v).transpose(1, 0, 2).astype(np.float64)
+    G = w.n_q_heads // w.n_kv_heads
+    for b in range(w.batch):
+        n0, n1 = int(t.cu[b]), int(t.cu[b + 1])
+        for g in range(w.n_q_heads):
+            s = kt[n0:n1, g // G, :] @ qf[b, g] / math.sqrt(w.head_dim)
+            p = np.exp(s - s.max())
+            p /= p.sum()
+            assert np.allclose(out[b, g], p @ vf[n0:n1, g // G, :], rtol=0, atol=1e-12)
+    # another seed gives other pruned entries, the same kept ones
+    _, kt2 = oracle.decode_sampled(kind, 100, t.q, pr, mu, sigma, t.v, t.layout, t.cu, want_ktilde=True)
+    assert np.array_equal(kt2[bits], kt[bits]) and not np.array_equal(kt2[~bits], kt[~bits])
+
+
+@pytest.mark.parametrize("kind", [oracle.GAUSSIAN, oracle.EXPONENTIAL])
+def test_sampled_entries_have_the_moments_of_their_distribution(kind):
+    """Rebuilt pruned entries times a are the sampled saliencies: Gaussian N(mu, sigma^2), Exponential with
+    mean mu (hence standard deviation mu), per row; checked through standardised samples over many rows."""
+    w, t, a32, pr, mu, sigma = _sampled_setup(43)
+    _, kt = oracle.decode_sampled(kind, 7, t.q, pr, mu, sigma, t.v, t.layout, t.cu, want_ktilde=True)
+    bits = np.unpackbits(pr.mask.view(np.uint8), axis=-1, bitorder="little").astype(bool)
+    cu = np.asarray(t.cu)
+    seq = np.searchsorted(cu, np.arange(w.total), side="right") - 1
+    a_rows = a32[seq].astype(np.float64)                       # [total,Hkv,D]
+    wt = kt * a_rows                                           # sampled saliency where pruned and a != 0
+    sel = (~bits) & (a_rows != 0)
+    m, sd = mu.astype(np.float64)[..., None], sigma.astype(np.float64)[..., None]
+    if kind == oracle.GAUSSIAN:
+        z = ((wt - m) / sd)[sel]
+        assert abs(z.mean()) < 0.02 and abs(z.std() - 1.0) < 0.02
+        assert abs(((z ** 3).mean())) < 0.05 and abs((z ** 4).mean() - 3.0) < 0.15
+        assert (wt[sel] < 0).any()                             # not clamped
+    else:
+        e = (wt / m)[sel]
+        assert e.min() > 0 and abs(e.mean() - 1.0) < 0.02 and abs(e.std() - 1.0) < 0.03
+        assert abs(np.mean(e > math.log(2.0)) - 0.5) < 0.01    # median of the unit exponential
+
+
+def test_gaussian_recovery_with_zero_spread_is_the_degenerate_recovery_at_the_row_mean():
+    """Rows whose saliencies are all equal have sigma = 0 and mu = mu_pruned, so the Gaussian recovery
+    function returns mu for every pruned entry: exactly the degenerate function."""
+    w, t = _random_small(44, Hq=4, Hkv=2, T=26)
+    rng = np.random.default_rng(44)
+    t.k = bf(rng.choice([-2.0, 2.0], size=t.k.shape).astype(np.float32))     # |k| constant
+    t.qwin = bf(np.ones(t.qwin.shape, np.float32))                           # a constant (= 1)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    mu, sigma = oracle.row_stats(t.k, t.layout, a32, t.cu)
+    assert np.all(sigma == 0) and np.array_equal(mu, pr.mu32)
+    got = oracle.decode_sampled(oracle.GAUSSIAN, 5, t.q, pr, mu, sigma, t.v, t.layout, t.cu)
+    assert np.allclose(got, oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu), rtol=0, atol=1e-14)
