@@ -48,6 +48,7 @@ typedef enum {
 
 typedef enum { SPARK_PACK_BF16 = 0, SPARK_PACK_INT8 = 1 } spark_pack_dtype;
 typedef enum { SPARK_OUT_BF16 = 0, SPARK_OUT_F32 = 1 } spark_out_dtype;
+typedef enum { SPARK_RECOVER_GAUSSIAN = 1, SPARK_RECOVER_EXPONENTIAL = 2 } spark_recovery;
 
 /* Problem description shared by all calls (plain data, host memory). */
 typedef struct spark_desc {
@@ -70,6 +71,9 @@ typedef struct spark_desc {
                                  query, its init and the calls. */
     int32_t keep_v;           /* T_v in [1, D]: channels kept per (token, KV head) of the VALUE cache, used by
                                  the *_values entry points only; 0 where values stay dense */
+    int32_t stats;            /* 1: spark_prune also stores, per (token, KV head), the mean and the standard
+                                 deviation of the saliency over all channels (8 bytes more per row; needed by
+                                 spark_decode_attn_sampled; bf16 storage only); 0: not stored */
     int32_t tail_capacity;    /* rows per sequence in the appended-token buffers of spark_decode_attn_tail;
                                  0 elsewhere.  Enters the decode workspace size: keep it the same for the
                                  workspace query, its init and the calls. */
@@ -160,6 +164,39 @@ spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const
 spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *mask_out,
                           void *vals_out, float *mu_out, float *scale_out, float *a_out,
                           void *hip_stream);
+
+/*
+ * One decode step with a SAMPLED recovery function.
+ * [Sec. "SparK", "Channel Recovery": a saliency w~ is sampled for every pruned entry from the cached
+ *  statistics and the key entry is back-computed as w~ / a; Gaussian: w~ ~ N(mu, sigma^2); Exponential:
+ *  w~ ~ Exp(1/mu); App. "Caching Pruned Channel Statistics": mu, sigma over all channels of the token]
+ *
+ *   ktilde[n,h,j] = K[n,h,j] if kept, else w~[n,h,j] / a[b,h,j]  (0 if a == 0); then scores, softmax, P V
+ *   as in spark_decode_attn.
+ * The paper does not say how the samples are drawn.  Here they are a pure function of (seed, n, h, j):
+ *   mix(x): x ^= x >> 16; x *= 0x85EBCA6B; x ^= x >> 13; x *= 0xC2B2AE35; x ^= x >> 16   (32-bit words)
+ *   base = mix(mix(mix(n) + seed_lo) + h * 0x9E3779B9 + seed_hi),  x_c = mix(base + c * 0x9E3779B9),
+ *   u_c  = ((x_c >> 9) + 0.5) / 2^23
+ *   Gaussian, channels 2m, 2m+1:  w~ = mu + sigma * sqrt(-2 ln u_2m) * {cos, sin}(2 pi u_(2m+1))
+ *   Exponential, channel j:        w~ = -mu * ln u_j
+ * so a call with the same seed repeats, and a caller that wants fresh samples per step changes the seed.
+ * A Gaussian sample may be negative (it is not clamped).
+ *
+ *   packed    written by spark_prune with desc->stats = 1 (bf16 storage)
+ *   recovery  spark_recovery
+ *   seed      64 bits: seed_lo = low word, seed_hi = high word
+ * Other arguments as spark_decode_attn.  This variant draws 128 - keep variates per (token, KV head) and is
+ * bound by arithmetic, not by memory.
+ */
+spark_status spark_decode_attn_sampled(const spark_desc *desc, const void *q_bf16, const void *packed,
+                                       const void *v_bf16, const int32_t *cu_seqlens, void *out,
+                                       void *workspace, size_t workspace_bytes, int32_t recovery,
+                                       uint64_t seed, void *hip_stream);
+
+/* Export of the per-row statistics of a cache written with desc->stats = 1 (parity tests, debugging):
+ *   mu_all_out, sigma_out  float [total_tokens, n_kv_heads]; either may be NULL. */
+spark_status spark_unpack_stats(const spark_desc *desc, const void *packed, float *mu_all_out,
+                                float *sigma_out, void *hip_stream);
 
 /*
  * One decode step when tokens have been appended after prefill.

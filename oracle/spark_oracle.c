@@ -483,7 +483,7 @@ void oracle_row_stats(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_st
  *              (the 32-bit finalizer of MurmurHash3, a bijection of the 32-bit words)
  *     base   = mix( mix( mix(n) + seed_lo ) + h * 0x9E3779B9 + seed_hi )
  *     x_c    = mix( base + c * 0x9E3779B9 )
- *     u_c    = ( (x_c >> 8) + 0.5 ) / 2^24            in (0, 1), 24 bits
+ *     u_c    = ( (x_c >> 9) + 0.5 ) / 2^23            in (0, 1), 23 bits (exact in binary32 too)
  */
 static uint32_t mix32(uint32_t x)
 {
@@ -501,7 +501,7 @@ double oracle_uniform(uint32_t seed_lo, uint32_t seed_hi, uint32_t n, uint32_t h
 {
     const uint32_t base = mix32(mix32(mix32(n) + seed_lo) + h * 0x9E3779B9u + seed_hi);
     const uint32_t x = mix32(base + c * 0x9E3779B9u);
-    return ((double)(x >> 8) + 0.5) / 16777216.0;
+    return ((double)(x >> 9) + 0.5) / 8388608.0;
 }
 
 /*

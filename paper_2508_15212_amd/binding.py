@@ -15,12 +15,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libspark_hip.so")
 
 PACK_BF16, PACK_INT8 = 0, 1
+RECOVER_GAUSSIAN, RECOVER_EXPONENTIAL = 1, 2
 OUT_BF16, OUT_F32 = 0, 1
 
 EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspace", "spark_decode_workspace_init", "spark_decode_splits",
            "spark_prune", "spark_decode_attn", "spark_unpack", "spark_probe_read", "spark_status_string",
            "spark_packed_values_bytes", "spark_prune_values", "spark_unpack_values", "spark_decode_attn_values", "spark_decode_attn_tail",
-           "spark_decode_attn_values_tail"]
+           "spark_decode_attn_values_tail", "spark_decode_attn_sampled", "spark_unpack_stats"]
 
 
 class SparkError(RuntimeError):
@@ -37,7 +38,7 @@ class SparkDesc(ctypes.Structure):
         ("k_token_stride", ctypes.c_int64), ("k_head_stride", ctypes.c_int64),
         ("v_token_stride", ctypes.c_int64), ("v_head_stride", ctypes.c_int64),
         ("softmax_scale", ctypes.c_float), ("n_splits", ctypes.c_int32),
-        ("keep_v", ctypes.c_int32), ("tail_capacity", ctypes.c_int32),
+        ("keep_v", ctypes.c_int32), ("stats", ctypes.c_int32), ("tail_capacity", ctypes.c_int32),
     ]
 
 
@@ -85,6 +86,11 @@ def load() -> ctypes.CDLL:
     lib.spark_decode_attn_tail.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.spark_decode_attn_values_tail.restype = ctypes.c_int
     lib.spark_decode_attn_values_tail.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.spark_decode_attn_sampled.restype = ctypes.c_int
+    lib.spark_decode_attn_sampled.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, ctypes.c_int32,
+                                              ctypes.c_uint64, vp]
+    lib.spark_unpack_stats.restype = ctypes.c_int
+    lib.spark_unpack_stats.argtypes = [dp, vp, vp, vp, vp]
     lib.spark_unpack_values.restype = ctypes.c_int
     lib.spark_unpack_values.argtypes = [dp, vp, vp, vp, vp]
     lib.spark_probe_read.restype = ctypes.c_int
@@ -183,6 +189,19 @@ def decode_attn_values_tail(desc: SparkDesc, q: torch.Tensor, packed: torch.Tens
                                               _ptr(tail_k), _ptr(tail_v), _ptr(tail_len), _ptr(out), _ptr(workspace),
                                               workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "spark_decode_attn_values_tail")
+
+
+def decode_attn_sampled(desc: SparkDesc, q: torch.Tensor, packed: torch.Tensor, v: torch.Tensor, cu: torch.Tensor,
+                        out: torch.Tensor, workspace: torch.Tensor, recovery: int, seed: int) -> None:
+    rc = load().spark_decode_attn_sampled(ctypes.byref(desc), _ptr(q), _ptr(packed), _ptr(v), _ptr(cu), _ptr(out),
+                                          _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                          int(recovery), ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF), _stream())
+    _check(rc, "spark_decode_attn_sampled")
+
+
+def unpack_stats(desc: SparkDesc, packed: torch.Tensor, mu_all=None, sigma=None) -> None:
+    rc = load().spark_unpack_stats(ctypes.byref(desc), _ptr(packed), _ptr(mu_all), _ptr(sigma), _stream())
+    _check(rc, "spark_unpack_stats")
 
 
 def unpack_values(desc: SparkDesc, packed_v: torch.Tensor, mask=None, vals=None) -> None:

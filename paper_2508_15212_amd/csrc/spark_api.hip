@@ -23,19 +23,22 @@ bool desc_ok(const spark_desc *d, spark_status *why)
     if (d->n_splits < 0 || d->n_splits > 4096) return false;
     if (d->keep_v < 0 || d->keep_v > d->head_dim) return false;
     if (d->tail_capacity < 0 || d->tail_capacity > (1 << 20)) return false;
+    if (d->stats != 0 && d->stats != 1) return false;
     *why = SPARK_ERR_UNSUPPORTED;
     if (d->head_dim != SPARK_D) return false;
     const int G = d->n_q_heads / d->n_kv_heads;
     if (!(G == 1 || G == 2 || G == 4 || G == 8 || G == 16)) return false;
     if (d->pack_dtype != SPARK_PACK_BF16 && d->pack_dtype != SPARK_PACK_INT8) return false;
     if (d->out_dtype != SPARK_OUT_BF16 && d->out_dtype != SPARK_OUT_F32) return false;
+    if (d->stats && d->pack_dtype != SPARK_PACK_BF16) return false;
     *why = SPARK_OK;
     return true;
 }
 
 SparkLayout layout_of(const spark_desc *d)
 {
-    return spark_make_layout(d->keep, d->pack_dtype == SPARK_PACK_INT8, d->batch, d->n_kv_heads, d->total_tokens);
+    return spark_make_layout(d->keep, d->pack_dtype == SPARK_PACK_INT8, d->batch, d->n_kv_heads, d->total_tokens,
+                             d->stats);
 }
 
 SparkLayout values_layout_of(const spark_desc *d)
@@ -243,7 +246,7 @@ spark_status spark_unpack_values(const spark_desc *desc, const void *packed_v, u
     if (!desc_ok(desc, &why)) return why;
     if (desc->keep_v < 1 || !packed_v) return SPARK_ERR_INVALID_ARG;
     const hipError_t e = spark::launch_unpack(static_cast<const uint8_t *>(packed_v), values_layout_of(desc), mask_out,
-                                              vals_out, nullptr, nullptr, nullptr, static_cast<hipStream_t>(hip_stream));
+                                              vals_out, nullptr, nullptr, nullptr, nullptr, nullptr, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }
 
@@ -252,7 +255,8 @@ namespace {
 spark_status decode_common(const spark_desc *desc, const void *q_bf16, const void *packed, const void *v_bf16,
                            const void *packed_v, const int32_t *cu_seqlens, void *out, void *workspace,
                            size_t workspace_bytes, void *hip_stream, const void *tail_k = nullptr,
-                           const void *tail_v = nullptr, const int32_t *tail_len = nullptr)
+                           const void *tail_v = nullptr, const int32_t *tail_len = nullptr, int rec = 0,
+                           uint64_t seed = 0)
 {
     spark_status why;
     if (!desc_ok(desc, &why)) return why;
@@ -288,7 +292,7 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
         static_cast<const uint8_t *>(packed_v), packed_v ? &Lv : nullptr, cu_seqlens, part_acc, part_ml, counters,
         desc->n_q_heads, plan, scale, L, out, desc->out_dtype == SPARK_OUT_F32,
         static_cast<const uint16_t *>(tail_k), static_cast<const uint16_t *>(tail_v), tail_len,
-        desc->tail_capacity, static_cast<hipStream_t>(hip_stream));
+        desc->tail_capacity, rec, seed, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }
 
@@ -301,6 +305,29 @@ spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const
     if (!v_bf16) return SPARK_ERR_INVALID_ARG;
     return decode_common(desc, q_bf16, packed, v_bf16, nullptr, cu_seqlens, out, workspace, workspace_bytes,
                          hip_stream);
+}
+
+spark_status spark_decode_attn_sampled(const spark_desc *desc, const void *q_bf16, const void *packed,
+                                       const void *v_bf16, const int32_t *cu_seqlens, void *out, void *workspace,
+                                       size_t workspace_bytes, int32_t recovery, uint64_t seed, void *hip_stream)
+{
+    if (!v_bf16) return SPARK_ERR_INVALID_ARG;
+    if (recovery != SPARK_RECOVER_GAUSSIAN && recovery != SPARK_RECOVER_EXPONENTIAL) return SPARK_ERR_INVALID_ARG;
+    if (desc && !desc->stats) return SPARK_ERR_INVALID_ARG;     // the cache must carry the all-channel statistics
+    return decode_common(desc, q_bf16, packed, v_bf16, nullptr, cu_seqlens, out, workspace, workspace_bytes,
+                         hip_stream, nullptr, nullptr, nullptr, recovery, seed);
+}
+
+spark_status spark_unpack_stats(const spark_desc *desc, const void *packed, float *mu_all_out, float *sigma_out,
+                                void *hip_stream)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!packed || !desc->stats) return SPARK_ERR_INVALID_ARG;
+    const hipError_t e = spark::launch_unpack(static_cast<const uint8_t *>(packed), layout_of(desc), nullptr, nullptr,
+                                              nullptr, nullptr, nullptr, mu_all_out, sigma_out,
+                                              static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }
 
 spark_status spark_decode_attn_tail(const spark_desc *desc, const void *q_bf16, const void *packed, const void *v_bf16,
@@ -341,7 +368,7 @@ spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *
     if (!packed) return SPARK_ERR_INVALID_ARG;
     const SparkLayout L = layout_of(desc);
     const hipError_t e = spark::launch_unpack(static_cast<const uint8_t *>(packed), L, mask_out, vals_out, mu_out,
-                                              scale_out, a_out, static_cast<hipStream_t>(hip_stream));
+                                              scale_out, a_out, nullptr, nullptr, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }
 

@@ -22,7 +22,7 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
                               const int32_t *cu, float *part_acc, float *part_ml,
                               uint32_t *counters, int Hq, const DecodePlan &plan, float softmax_scale, const SparkLayout &L,
                               void *out, int out_f32, const uint16_t *tail_k, const uint16_t *tail_v,
-                              const int32_t *tail_len, int tail_cap, hipStream_t st)
+                              const int32_t *tail_len, int tail_cap, int rec, uint64_t seed, hipStream_t st)
 {
     DecodeParams P;
     P.q = q;
@@ -50,6 +50,9 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.tail_v = tail_v;
     P.tail_len = tail_len;
     P.tail_cap = tail_cap;
+    P.rec = rec;
+    P.seed_lo = (uint32_t)seed;
+    P.seed_hi = (uint32_t)(seed >> 32);
     P.scale_log2 = softmax_scale * 1.44269504088896340736f;
     P.L = L;
     const int G = P.Hq / P.Hkv;

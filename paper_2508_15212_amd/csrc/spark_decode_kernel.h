@@ -66,6 +66,8 @@ struct DecodeParams {
     const uint16_t *tail_k, *tail_v;   // appended never-pruned rows [B, tail_cap, Hkv, 128] bf16, or NULL
     const int32_t *tail_len;           // [B]
     int tail_cap;
+    int rec;                           // 0: degenerate recovery; 1 Gaussian, 2 Exponential (sampled)
+    uint32_t seed_lo, seed_hi;         // seed of the sampled recovery
     float scale_log2;        // softmax scale * log2(e)
     SparkLayout L;
 };
@@ -297,7 +299,10 @@ constexpr int decode_min_blocks(int, int) { return 2; }
 #define NT_LOAD(p) __builtin_nontemporal_load(p)
 // TVC: 0 = dense values; > 0 = packed values with that many kept channels per row (row held in registers);
 // -1 = packed values, any count (row words read from memory as they are needed).
-template <int G, int TCT, int INT8, int TVC>
+// REC: 0 = degenerate recovery (mu / a, folded into the score sum); 1 / 2 = Gaussian / Exponential recovery:
+// a saliency is drawn for every pruned entry from the row's all-channel statistics with a counter-based
+// generator keyed by (seed, token, head, channel), so the run can be repeated and checked.
+template <int G, int TCT, int INT8, int TVC, int REC = 0>
 __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void spark_decode_kernel(DecodeParams P)
 {
     constexpr bool PV = (TVC != 0);             // packed value cache
@@ -526,7 +531,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
 
         uint32_t (&r)[NR] = rn;
         // ---- scores, lane = token
-        const float mu = __uint_as_float(r[4]);
+        const float mu = REC ? 0.0f : __uint_as_float(r[4]);   // sampled recovery: no mean term
         float s[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) s[g] = 0.0f;
@@ -587,8 +592,47 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                 for (int i = 0; i < T; ++i) {
                     const int per = INT8 ? 4 : 2;
                     if (i % per == 0)
-                        vw = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, VAL0 + i / per));
+                        vw = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, L.val0 + i / per));
                     entry(i, vw);
+                }
+            }
+        }
+        if constexpr (REC != 0) {
+            // ---- sampled recovery: every pruned entry j adds q_gj * w~_j / a_j
+            constexpr uint32_t kGold = 0x9E3779B9u;
+            auto mix = [](uint32_t x) {
+                x ^= x >> 16; x *= 0x85EBCA6Bu; x ^= x >> 13; x *= 0xC2B2AE35u; x ^= x >> 16;
+                return x;
+            };
+            const uint32_t base = mix(mix(mix((uint32_t)n_lane) + P.seed_lo) + (uint32_t)h * kGold + P.seed_hi);
+            auto unif = [&](uint32_t c) {   // ((x >> 9) + 0.5) / 2^23: exact in float32
+                return ((float)(mix(base + c * kGold) >> 9) + 0.5f) * (1.0f / 8388608.0f);
+            };
+            const float mu_a = __uint_as_float(r[5]);
+            const float sg = __uint_as_float(*reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, 6)));
+            constexpr float kLn2 = 0.69314718055994530942f;
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd) {
+                uint32_t mw = r[wd];
+#pragma unroll 2
+                for (int pp = 0; pp < 16; ++pp) {
+                    const int j = 32 * wd + 2 * pp;
+                    const float u1 = unif((uint32_t)j), u2 = unif((uint32_t)j + 1u);
+                    float w0, w1;
+                    if (REC == 1) {   // Box-Muller pair for channels j, j + 1
+                        const float rr = __builtin_sqrtf(-2.0f * kLn2 * __builtin_amdgcn_logf(u1));
+                        w0 = fmaf(sg, rr * __builtin_amdgcn_cosf(u2), mu_a);    // v_cos / v_sin take revolutions
+                        w1 = fmaf(sg, rr * __builtin_amdgcn_sinf(u2), mu_a);
+                    } else {          // rate 1 / mu
+                        w0 = -mu_a * kLn2 * __builtin_amdgcn_logf(u1);
+                        w1 = -mu_a * kLn2 * __builtin_amdgcn_logf(u2);
+                    }
+                    const float *e0 = &qtab[j * GP], *e1 = &qtab[(j + 1) * GP];
+                    const float t0 = (mw & 1u) ? 0.0f : e0[G] * w0;
+                    const float t1 = (mw & 2u) ? 0.0f : e1[G] * w1;
+                    mw >>= 2;
+#pragma unroll
+                    for (int g = 0; g < G; ++g) s[g] = fmaf(e1[g], t1, fmaf(e0[g], t0, s[g]));
                 }
             }
         }
@@ -863,10 +907,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
 
 // ---------------------------------------------------------------- host-side launch
 
-template <int G, int TCT, int INT8, int TVC>
+template <int G, int TCT, int INT8, int TVC, int REC = 0>
 static hipError_t launch_one(const DecodeParams &P, int nblocks, hipStream_t st)
 {
-    hipLaunchKernelGGL((spark_decode_kernel<G, TCT, INT8, TVC>), dim3(nblocks), dim3(kDecodeWaves * 64), 0, st, P);
+    hipLaunchKernelGGL((spark_decode_kernel<G, TCT, INT8, TVC, REC>), dim3(nblocks), dim3(kDecodeWaves * 64), 0, st, P);
     return hipGetLastError();
 }
 
@@ -887,7 +931,10 @@ static hipError_t launch_pv(const DecodeParams &P, int nblocks, hipStream_t st)
 template <int G>
 hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
 {
-    const int T = P.L.T;
+    // rows that carry the all-channel statistics are longer: only the any-length instantiations read them
+    const int T = P.L.stats ? -1 : P.L.T;
+    if (P.rec == 1) return launch_one<G, 0, 0, 0, 1>(P, nblocks, st);
+    if (P.rec == 2) return launch_one<G, 0, 0, 0, 2>(P, nblocks, st);
     if (P.packed_v) {
         if (P.L.int8) return hipErrorInvalidValue;   // (the host rejects this combination before it gets here)
         if (T == 26) return launch_pv<G, 26>(P, nblocks, st);

@@ -25,7 +25,8 @@ hipError_t launch_prune_values(const uint16_t *v, int64_t v_tok_stride, int64_t 
                                const SparkLayout &L, hipStream_t st);
 
 hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *mask_out, void *vals_out,
-                         float *mu_out, float *scale_out, float *a_out, hipStream_t st);
+                         float *mu_out, float *scale_out, float *a_out, float *mu_all_out, float *sigma_out,
+                         hipStream_t st);
 
 // q [B,Hq,128] bf16; the caller splits the workspace into part_acc / part_ml / counters.
 // Values are either dense (v, strides; packed_v = NULL) or a packed value cache (packed_v, Lv; v = NULL).
@@ -36,7 +37,7 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
                               const int32_t *cu, float *part_acc, float *part_ml,
                               uint32_t *counters, int Hq, const DecodePlan &plan, float softmax_scale, const SparkLayout &L,
                               void *out, int out_f32, const uint16_t *tail_k, const uint16_t *tail_v,
-                              const int32_t *tail_len, int tail_cap, hipStream_t st);
+                              const int32_t *tail_len, int tail_cap, int rec, uint64_t seed, hipStream_t st);
 
 hipError_t launch_zero_counters(uint32_t *counters, int n, hipStream_t st);
 

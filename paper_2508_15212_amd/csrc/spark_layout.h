@@ -7,6 +7,7 @@
 //   bf16 storage : [ m0 m1 m2 m3 | mu | v0 v1 ... v(nv-1) | pad ]   nv = ceil(T/2)
 //   int8 storage : [ m0 m1 m2 m3 | mu | scale | c0 ... c(nv-1) | pad ]   nv = ceil(T/4)
 //   value cache  : [ m0 m1 m2 m3 | v0 v1 ... v(nv-1) | pad ]        (pruned entries are dropped: no statistic)
+//   bf16 + stats : [ m0 m1 m2 m3 | mu | mu_all | sigma_all | v0 ... v(nv-1) | pad ]   (for the sampled recovery functions)
 //
 // m0..m3 is the 128-bit channel mask (bit j%32 of word j/32 = channel j kept), mu the
 // mean saliency of the pruned channels, v* the kept entries in ascending channel order
@@ -39,6 +40,7 @@ struct SparkLayout {
     int32_t T;            // kept channels per row
     int32_t int8;         // 1 = int8 codes + scale
     int32_t values;       // 1 = packed VALUE cache: rows carry no mu word and there is no a / 1/a section
+    int32_t stats;        // 1 = rows also carry the mean and standard deviation of the saliency over all channels
     int32_t nv;           // value words per row
     int32_t val0;         // index of the first value word in a row
     int32_t ndw;          // words per row (even)
@@ -55,14 +57,15 @@ struct SparkLayout {
 };
 
 static inline SPARK_HD SparkLayout spark_make_layout(int T, int int8, int batch, int n_kv_heads,
-                                                     int64_t total_tokens)
+                                                     int64_t total_tokens, int stats = 0)
 {
     SparkLayout L;
     L.T = T;
     L.int8 = int8;
     L.values = 0;
+    L.stats = stats;
     L.nv = int8 ? (T + 3) / 4 : (T + 1) / 2;
-    L.val0 = int8 ? 6 : 5;
+    L.val0 = int8 ? 6 : (stats ? 7 : 5);
     int ndw = L.val0 + L.nv;
     L.ndw = (ndw + 1) & ~1;
     L.nq = L.ndw / 4;

@@ -19,6 +19,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "spark_kernels.h"
 #include "spark_layout.h"
 
@@ -156,6 +158,32 @@ __device__ __forceinline__ float fold_pair(float A, float B, bool hi)
     return stay + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(go), CTRL, 0xF, 0xF, true));
 }
 
+// Sum over the 64 lanes, returned wave-uniform (same moves as the prefix sum; lane 63 ends with the total).
+__device__ __forceinline__ float wave_total_f32(float v)
+{
+    auto step = [&](auto ctrl, auto rmask) {
+        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value,
+                                                        decltype(rmask)::value, 0xF, false));
+    };
+    step(std::integral_constant<int, 0x111>{}, std::integral_constant<int, 0xF>{});
+    step(std::integral_constant<int, 0x112>{}, std::integral_constant<int, 0xF>{});
+    step(std::integral_constant<int, 0x114>{}, std::integral_constant<int, 0xF>{});
+    step(std::integral_constant<int, 0x118>{}, std::integral_constant<int, 0xF>{});
+    step(std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xA>{});
+    step(std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xC>{});
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+// One wave-uniform value into lane `lane_id` of a register.
+__device__ __forceinline__ void write_lane1(uint32_t &a, uint32_t va, int lane_id)
+{
+    asm("s_mov_b32 m0, %2\n\t"
+        "v_writelane_b32 %0, %1, m0"
+        : "+v"(a)
+        : "s"(va), "s"(lane_id)
+        : "m0");
+}
+
 __device__ __forceinline__ void prune_lds_sync()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -165,13 +193,16 @@ __device__ __forceinline__ void prune_lds_sync()
 
 // FULL: the launch covers the tiles that hold all 64 tokens (the first total_tokens / 64 of every head);
 // otherwise it covers the one partly filled last tile of every head, one wavefront each.
+// MODE: 0 = bf16 kept entries, 1 = int8 codes + scale, 2 = bf16 plus the all-channel mean and standard
+// deviation of the row's saliencies (App. "Caching Pruned Channel Statistics", for the sampled recovery).
 // VALUES: the rows are value-cache rows (App. "Pruning Value Cache Channels"): the score of a channel is
 // |v| itself, there is no channel weight, no sequence bookkeeping and no statistic of the pruned set.
-template <int INT8, bool FULL, bool VALUES>
+template <int MODE, bool FULL, bool VALUES>
 __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     const uint16_t *__restrict__ k, int64_t k_tok_stride, int64_t k_head_stride,
     const int32_t *__restrict__ cu, uint8_t *__restrict__ packed, SparkLayout L)
 {
+    constexpr bool INT8 = (MODE == 1), STATS = (MODE == 2);
     extern __shared__ __align__(16) uint8_t smem[];
     const int lane = threadIdx.x & 63;
     // the wavefront index is the same in all 64 lanes; saying so keeps everything derived from it
@@ -254,6 +285,8 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     // lane t collects, for token t, the ballots of kept even channels (e) and kept odd channels (o)
     uint32_t e_lo = 0, e_hi = 0, o_lo = 0, o_hi = 0;
     float mureg = 0.0f;                                     // lane t: sum of pruned saliencies
+    uint32_t muall = 0;                                     // lane t: mean saliency over all channels (bits)
+    float sqreg = 0.0f;                                     // lane t: sum of squared deviations from it
 
     // Rows are fetched a block ahead: while one block of PF rows is searched the next is in flight,
     // in two register sets that swap roles.
@@ -285,8 +318,8 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
 
     // searches and stages the PF rows held in x (tokens tb .. tb+PF-1); returns their pruned-saliency
     // partials folded into one register (token tb + u in the lanes with l & 7 == u)
-    auto do_block = [&](const uint32_t (&x)[PF], int tb) __attribute__((always_inline)) -> float {
-        float ps[PF];
+    auto do_block = [&](const uint32_t (&x)[PF], int tb) __attribute__((always_inline)) -> float2 {
+        float ps[PF], qs[PF];
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int t = tb + u;
@@ -390,30 +423,52 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
             write_lane4(e_lo, e_hi, o_lo, o_hi, (uint32_t)kb0, (uint32_t)(kb0 >> 32), (uint32_t)kb1,
                         (uint32_t)(kb1 >> 32), t);
             ps[u] = VALUES ? 0.0f : (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
+            qs[u] = 0.0f;
+            if constexpr (STATS) {
+                // mean over all 128 channels now (wave sum), squared deviations folded with the rest
+                const float mrow = wave_total_f32(w0 + w1) * (1.0f / (float)SPARK_D);
+                write_lane1(muall, (uint32_t)__builtin_amdgcn_readfirstlane(__float_as_int(mrow)), t);
+                const float d0 = w0 - mrow, d1 = w1 - mrow;
+                qs[u] = fmaf(d0, d0, d1 * d1);
+            }
         }
-        if constexpr (VALUES) return 0.0f;
+        if constexpr (VALUES) return make_float2(0.0f, 0.0f);
+        float q07 = 0.0f;
+        if constexpr (STATS) {
+            const float g01 = fold_pair<0xB1>(qs[0], qs[1], lane & 1);
+            const float g23 = fold_pair<0xB1>(qs[2], qs[3], lane & 1);
+            const float g45 = fold_pair<0xB1>(qs[4], qs[5], lane & 1);
+            const float g67 = fold_pair<0xB1>(qs[6], qs[7], lane & 1);
+            q07 = fold_pair<0x124>(fold_pair<0x4E>(g01, g23, lane & 2), fold_pair<0x4E>(g45, g67, lane & 2), lane & 4);
+        }
         const float f01 = fold_pair<0xB1>(ps[0], ps[1], lane & 1);     // quad_perm [1,0,3,2]
         const float f23 = fold_pair<0xB1>(ps[2], ps[3], lane & 1);
         const float f45 = fold_pair<0xB1>(ps[4], ps[5], lane & 1);
         const float f67 = fold_pair<0xB1>(ps[6], ps[7], lane & 1);
         const float f03 = fold_pair<0x4E>(f01, f23, lane & 2);         // quad_perm [2,3,0,1]
         const float f47 = fold_pair<0x4E>(f45, f67, lane & 2);
-        return fold_pair<0x124>(f03, f47, lane & 4);                   // row_ror 4
+        return make_float2(fold_pair<0x124>(f03, f47, lane & 4), q07);   // row_ror 4
     };
 
     // Every one of the 64 rows is processed; rows past the last token repeat the last one and are
     // overwritten by the epilogue.
     for (int tb = 0; tb < SPARK_TILE_TOKENS; tb += 2 * PF) {
         load_block(xb, tb + PF);
-        const float fa = do_block(xa, tb);
+        const float2 fa = do_block(xa, tb);
         if (tb + 2 * PF < SPARK_TILE_TOKENS) load_block(xa, tb + 2 * PF);
-        const float fb = do_block(xb, tb + PF);
+        const float2 fb = do_block(xb, tb + PF);
         if constexpr (!VALUES) {
             // pruned-saliency sums of these 16 tokens: pair the two blocks, finish across the four rows
-            float s = fold_pair<0x128>(fa, fb, lane & 8);                  // row_ror 8
+            float s = fold_pair<0x128>(fa.x, fb.x, lane & 8);              // row_ror 8
             s += __shfl_xor(s, 16);
             s += __shfl_xor(s, 32);
             if ((lane >> 4) == (tb >> 4)) mureg = s;
+            if constexpr (STATS) {
+                float s2 = fold_pair<0x128>(fa.y, fb.y, lane & 8);
+                s2 += __shfl_xor(s2, 16);
+                s2 += __shfl_xor(s2, 32);
+                if ((lane >> 4) == (tb >> 4)) sqreg = s2;
+            }
         }
     }
 
@@ -433,8 +488,12 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     row[2] = valid ? (spread16(e_hi) | (spread16(o_hi) << 1)) : low_bits(T - 64);
     row[3] = valid ? (spread16(e_hi >> 16) | (spread16(o_hi >> 16) << 1)) : low_bits(T - 96);
     if (!VALUES) row[4] = __float_as_uint(mu);
+    if (STATS) {
+        row[5] = valid ? muall : 0u;
+        row[6] = valid ? __float_as_uint(sqrtf(sqreg * (1.0f / (float)SPARK_D))) : 0u;
+    }
     if (!valid) {
-        for (int d = VALUES ? 4 : 5; d < sw; ++d) row[d] = 0u;
+        for (int d = VALUES ? 4 : (STATS ? 7 : 5); d < sw; ++d) row[d] = 0u;
     } else {
         const int vend = L.val0 + (T + 1) / 2;               // one past the last staged bf16 word
         if (T & 1) row[vend - 1] &= 0xFFFFu;                 // unused upper half of the last word
@@ -491,7 +550,7 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
 // one thread per (token, KV head) row
 __global__ void spark_unpack_kernel(const uint8_t *__restrict__ packed, SparkLayout L,
                                     uint32_t *mask_out, void *vals_out, float *mu_out,
-                                    float *scale_out, float *a_out)
+                                    float *scale_out, float *a_out, float *mu_all_out, float *sigma_out)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t rows = L.total_tokens * L.n_kv_heads;
@@ -508,6 +567,10 @@ __global__ void spark_unpack_kernel(const uint8_t *__restrict__ packed, SparkLay
     if (mask_out)
         for (int m = 0; m < 4; ++m) mask_out[idx * 4 + m] = word(m);
     if (mu_out && !L.values) mu_out[idx] = __uint_as_float(word(4));
+    if (L.stats) {
+        if (mu_all_out) mu_all_out[idx] = __uint_as_float(word(5));
+        if (sigma_out) sigma_out[idx] = __uint_as_float(word(6));
+    }
     if (L.int8) {
         if (scale_out) scale_out[idx] = __uint_as_float(word(5));
         if (vals_out) {
@@ -545,11 +608,16 @@ hipError_t launch_tiles(const uint16_t *x, int64_t tok_stride, int64_t head_stri
     };
     const int64_t full_waves = (L.total_tokens / SPARK_TILE_TOKENS) * L.n_kv_heads;
     const int64_t tail_waves = (L.total_tokens % SPARK_TILE_TOKENS) ? L.n_kv_heads : 0;
-    hipError_t e = L.int8 ? launch(&spark_prune_kernel<1, true, VALUES>, full_waves)
-                          : launch(&spark_prune_kernel<0, true, VALUES>, full_waves);
-    if (e != hipSuccess) return e;
-    return L.int8 ? launch(&spark_prune_kernel<1, false, VALUES>, tail_waves)
-                  : launch(&spark_prune_kernel<0, false, VALUES>, tail_waves);
+    if (VALUES || (!L.int8 && !L.stats)) {
+        const hipError_t e = launch(&spark_prune_kernel<0, true, VALUES>, full_waves);
+        return e != hipSuccess ? e : launch(&spark_prune_kernel<0, false, VALUES>, tail_waves);
+    }
+    if (L.int8) {
+        const hipError_t e = launch(&spark_prune_kernel<1, true, false>, full_waves);
+        return e != hipSuccess ? e : launch(&spark_prune_kernel<1, false, false>, tail_waves);
+    }
+    const hipError_t e = launch(&spark_prune_kernel<2, true, false>, full_waves);
+    return e != hipSuccess ? e : launch(&spark_prune_kernel<2, false, false>, tail_waves);
 }
 
 }  // namespace
@@ -572,14 +640,15 @@ hipError_t launch_prune_values(const uint16_t *v, int64_t v_tok_stride, int64_t 
 }
 
 hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *mask_out, void *vals_out,
-                         float *mu_out, float *scale_out, float *a_out, hipStream_t st)
+                         float *mu_out, float *scale_out, float *a_out, float *mu_all_out, float *sigma_out,
+                         hipStream_t st)
 {
     int64_t n = L.total_tokens * L.n_kv_heads;
     const int64_t na = (int64_t)L.batch * L.n_kv_heads * SPARK_D;
     if (a_out && na > n) n = na;
     if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(spark_unpack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed, L,
-                       mask_out, vals_out, mu_out, scale_out, a_out);
+                       mask_out, vals_out, mu_out, scale_out, a_out, mu_all_out, sigma_out);
     return hipGetLastError();
 }
 

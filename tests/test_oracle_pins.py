@@ -549,10 +549,10 @@ def test_generator_is_a_bijective_mixer_and_its_uniforms_behave():
     for x in [0, 1, 2, 0xFFFFFFFF] + [int(v) for v in rng.integers(0, 1 << 32, size=200)]:
         assert _unmix32(oracle.mix32(x)) == x
     assert oracle.mix32(0) == 0
-    # uniforms: in (0,1), on the 24-bit grid offset by half a step, deterministic, sensitive to every argument
+    # uniforms: in (0,1), on the 23-bit grid offset by half a step, deterministic, sensitive to every argument
     u = np.array([[oracle.uniform(1234567890123, n, 1, c) for c in range(128)] for n in range(400)])
     assert u.min() > 0.0 and u.max() < 1.0
-    assert np.all((u * (1 << 24) - 0.5) == np.round(u * (1 << 24) - 0.5))
+    assert np.all((u * (1 << 23) - 0.5) == np.round(u * (1 << 23) - 0.5))
     assert oracle.uniform(7, 3, 1, 5) == oracle.uniform(7, 3, 1, 5)
     base = oracle.uniform(7, 3, 1, 5)
     assert len({base, oracle.uniform(8, 3, 1, 5), oracle.uniform(7 + (1 << 32), 3, 1, 5), oracle.uniform(7, 4, 1, 5),
