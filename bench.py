@@ -44,6 +44,8 @@ def main() -> int:
     ap.add_argument("--int8", action="store_true", help="int8 storage of the kept entries")
     ap.add_argument("--keep-v", type=int, default=0,
                     help="also prune the value cache to this many channels per row (0 = values stay dense)")
+    ap.add_argument("--recovery", choices=["degenerate", "gaussian", "exponential"], default="degenerate",
+                    help="recovery function at decode (the sampled ones store two more statistics per row)")
     ap.add_argument("--tail", type=int, default=0,
                     help="appended never-pruned rows per sequence (decode through spark_decode_attn_tail)")
     ap.add_argument("--splits", type=int, default=0)
@@ -91,6 +93,13 @@ def main() -> int:
     Tv = args.keep_v
     ntail = args.tail
     desc.tail_capacity = ntail
+    rec = {"degenerate": 0, "gaussian": spark.RECOVER_GAUSSIAN, "exponential": spark.RECOVER_EXPONENTIAL}[args.recovery]
+    desc.stats = 1 if rec else 0
+    rec_seed = 0x5EED0000 + w.seed
+    if rec and (Tv or ntail or args.int8):
+        print("bench.py: --recovery gaussian/exponential is timed on its own (no --keep-v / --tail / --int8)",
+              file=sys.stderr)
+        return 2
     if ntail and Tv:
         print("bench.py: --tail and --keep-v are separate entry points; pick one", file=sys.stderr)
         return 2
@@ -123,7 +132,9 @@ def main() -> int:
         tail_len = torch.from_numpy(tail_len_np).cuda()
 
     def decode(c, d=desc, o=out):
-        if ntail:
+        if rec:
+            spark.decode_attn_sampled(d, q, packs[c], vs[c], cu, o, ws, rec, rec_seed)
+        elif ntail:
             spark.decode_attn_tail(d, q, packs[c], vs[c], cu, tail_k, tail_v, tail_len, o, ws)
         elif Tv:
             spark.decode_attn_values(d, q, packs[c], packvs[c], cu, o, ws)
@@ -191,6 +202,8 @@ def main() -> int:
     row_bytes = (pbytes - 256 - 2 * ((w.batch * hkv * D * 4 + 255) // 256 * 256)) / (
         hkv * ((total + 63) // 64) * 64)
     k_row = (T + 16 + 4 + 4) if args.int8 else (2 * T + 16 + 4)      # kept entries + mask + mu (+ scale)
+    if rec:
+        k_row += 8                                                    # all-channel mean and standard deviation
     v_row = (2 * Tv + 16) if Tv else 2 * D                            # kept entries + mask, or the dense row
     dec_alg_bytes = rows * (k_row + v_row)                            # packed K row + V row
     dec_alg_bytes += w.batch * ntail * hkv * 4 * D                    # appended rows: dense K and V
@@ -220,6 +233,7 @@ def main() -> int:
             "workload": w.name, "batch": w.batch, "n_q_heads": hq, "n_kv_heads": hkv, "head_dim": D,
             "context": int(w.seqlens.max()), "total_tokens": total, "keep": T, "window": w.window,
             "pack": "int8" if args.int8 else "bf16", "keep_v": Tv if Tv else None, "tail_rows_per_sequence": ntail if ntail else None,
+            "recovery": args.recovery,
             "splits": spark.decode_splits(desc),
             "input_copies_rotated": ncopy, "seed": w.seed, "step": ("spark_prune + spark_prune_values + spark_decode_attn_values" if Tv
                                                               else "spark_prune + spark_decode_attn_tail" if ntail
@@ -237,7 +251,7 @@ def main() -> int:
                      "frac": round(kern_gbs / HBM_PEAK_GBS, 4),
                      "kernel_us": round(kern_us, 2),
                      "traffic": MEASURED_DECODE_TRAFFIC_BYTES.get((w.name, "int8" if args.int8 else "bf16"))
-                     if not (args.keep or Tv or ntail) else None,
+                     if not (args.keep or Tv or ntail or rec) else None,
                      "algorithmic_bytes": dec_alg_bytes,
                      "kernel": "spark_decode_kernel, HIP events around %d back-to-back launches" % args.steps},
         "stream_read_ceiling": {"GBps": round(probe_gbs, 1), "us": round(probe_us, 2),
@@ -262,6 +276,10 @@ def main() -> int:
             pv = oracle.prune_values(t.v, t.layout, Tv)
             t1 = time.perf_counter()
             ref = oracle.decode_literal(t.q, pr, oracle.expand_values(pv), "NHD", t.cu)
+        elif rec:
+            mu_all, sigma_all = oracle.row_stats(t.k, t.layout, a32, t.cu)
+            t1 = time.perf_counter()
+            ref = oracle.decode_sampled(rec, rec_seed, t.q, pr, mu_all, sigma_all, t.v, t.layout, t.cu)
         elif ntail:
             ref = oracle.decode_literal_tail(t.q, pr, t.v, t.layout, t.cu, tail_k_np, tail_v_np, tail_len_np)
         else:
