@@ -126,3 +126,22 @@ def test_size_limits_of_the_description():
     assert spark.packed_bytes(_desc(batch=1, total_tokens=(1 << 31) - 256)) > 0
     assert spark.packed_bytes(_desc(batch=1, total_tokens=(1 << 31) - 255)) == 0
     assert spark.packed_bytes(_desc(batch=(1 << 18) + 1)) == 0
+
+
+def test_statistics_rows_and_sampled_decode_arguments():
+    lib = spark.load()
+    A = 0x7F0000000000
+    rows = 8 * 32768 * 8
+    ds = _desc(stats=1)
+    assert spark.packed_bytes(ds) == 256 + 2 * 8 * 8 * 128 * 4 + rows * 80      # 72 + mean + standard deviation
+    assert spark.packed_bytes(_desc(stats=1, pack_dtype=spark.PACK_INT8)) == 0  # bf16 storage only
+    assert spark.packed_bytes(_desc(stats=2)) == 0
+    ws = spark.decode_workspace_bytes(ds)
+    u64 = ctypes.c_uint64(1)
+    assert lib.spark_decode_attn_sampled(ctypes.byref(_desc()), A, A, A, A, A, A, ws, 1, u64, None) == 1   # no stats
+    assert lib.spark_decode_attn_sampled(ctypes.byref(ds), A, A, A, A, A, A, ws, 0, u64, None) == 1        # bad kind
+    assert lib.spark_decode_attn_sampled(ctypes.byref(ds), A, A, A, A, A, A, ws, 3, u64, None) == 1
+    assert lib.spark_decode_attn_sampled(ctypes.byref(ds), A, A, None, A, A, A, ws, 1, u64, None) == 1
+    assert lib.spark_decode_attn_sampled(ctypes.byref(ds), A, A, A, A, A, A, ws - 1, 1, u64, None) == 3
+    assert lib.spark_unpack_stats(ctypes.byref(_desc()), A, A, A, None) == 1
+    assert lib.spark_unpack_stats(ctypes.byref(ds), None, A, A, None) == 1
