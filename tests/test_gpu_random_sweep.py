@@ -1,6 +1,6 @@
 """Seeded sweep over random small problem shapes: group size, head count, kept channels, ragged lengths
-(empty sequences included), layout, forced or library-chosen blocks per sequence, optional value pruning
-and optional appended rows, each checked against the CPU oracle (masks and kept entries bit for bit,
+(empty sequences included), layout, forced or library-chosen blocks per sequence, optional value pruning,
+optional appended rows, optional statistics rows with a sampled recovery function, each checked against the CPU oracle (masks and kept entries bit for bit,
 decode output max |err| <= 1e-2, mean |err| <= 1e-3)."""
 import numpy as np
 import pytest
@@ -24,10 +24,13 @@ def _one_case(rng, idx):
     n_splits = int(rng.choice([0, 0, 1, 2, 5]))
     Tv = int(rng.choice([0, 0, 26, 38, 64, 90]))
     cap = int(rng.choice([0, 0, 3, 70, 300]))
+    stats = int(rng.choice([0, 0, 1]))            # rows that also carry the all-channel mean / standard deviation
+    rec = int(rng.choice([0, 1, 2])) if (stats and not Tv and not cap) else 0
     w = wl.small(name=f"sweep{idx}", batch=batch, n_q_heads=G * hkv, n_kv_heads=hkv, keep=T, seqlens=lens,
                  seed=1000 + idx)
     t = wl.generate(w)
-    tag = f"case {idx}: G={G} Hkv={hkv} lens={lens} T={T} {layout} splits={n_splits} Tv={Tv} cap={cap}"
+    tag = (f"case {idx}: G={G} Hkv={hkv} lens={lens} T={T} {layout} splits={n_splits} Tv={Tv} cap={cap} "
+           f"stats={stats} rec={rec}")
     print(tag, flush=True)
     _, _, a32 = oracle.window_stat(t.qwin, hkv)
     pr = oracle.prune(t.k, t.layout, a32, t.cu, T)
@@ -35,7 +38,10 @@ def _one_case(rng, idx):
     if Tv:
         pv = oracle.prune_values(t.v, t.layout, Tv)
         v_for_oracle, v_layout = oracle.expand_values(pv), "NHD"
-    if cap:
+    if rec:
+        mu_all, sigma_all = oracle.row_stats(t.k, t.layout, a32, t.cu)
+        ref = oracle.decode_sampled(rec, 77 + idx, t.q, pr, mu_all, sigma_all, t.v, t.layout, t.cu)
+    elif cap:
         tk = wl.f32_to_bf16_bits(rng.standard_normal((batch, cap, hkv, 128)).astype(np.float32))
         tv = wl.f32_to_bf16_bits(rng.standard_normal((batch, cap, hkv, 128)).astype(np.float32))
         tl = rng.integers(0, cap + 1, size=batch).astype(np.int32)
@@ -48,7 +54,7 @@ def _one_case(rng, idx):
         k = np.ascontiguousarray(k.transpose(1, 0, 2))
         v = np.ascontiguousarray(v.transpose(1, 0, 2))
     desc = make_desc(w, layout, n_splits=n_splits)
-    desc.keep_v, desc.tail_capacity = Tv, cap
+    desc.keep_v, desc.tail_capacity, desc.stats = Tv, cap, stats
     if w.total == 0:                       # no rows: any valid stride
         desc.k_head_stride = desc.v_head_stride = desc.k_token_stride = desc.v_token_stride = 128
     dk = to_dev(k) if w.total else torch.zeros(256, dtype=torch.int16, device="cuda")
@@ -77,6 +83,8 @@ def _one_case(rng, idx):
                                           torch.from_numpy(tl).cuda(), out, ws)
         else:
             spark.decode_attn_values(desc, dq, packed, packed_v, dcu, out, ws)
+    elif rec:
+        spark.decode_attn_sampled(desc, dq, packed, dv, dcu, out, ws, rec, 77 + idx)
     elif cap:
         spark.decode_attn_tail(desc, dq, packed, dv, dcu, to_dev(tk), to_dev(tv), torch.from_numpy(tl).cuda(), out, ws)
     else:
@@ -90,5 +98,5 @@ def _one_case(rng, idx):
 
 def test_random_shapes_against_the_oracle():
     rng = np.random.default_rng(20250815)
-    for idx in range(160):
+    for idx in range(240):
         _one_case(rng, idx)
