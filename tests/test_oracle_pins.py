@@ -492,7 +492,7 @@ def _random_tail(w, seed, cap):
 def test_tail_keep_all_is_dense_attention_on_the_concatenated_cache():
     w, t = _random_small(21, Hq=8, Hkv=2, T=128)
     tk, tv, tl = _random_tail(w, 21, cap=9)
-    tl[0] = 9
+    tl[:] = (9, 4)                                                        # full buffer, partly filled buffer
     _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
     pr = oracle.prune(t.k, t.layout, a32, t.cu, w.head_dim)               # T = D: nothing pruned
     got = oracle.decode_literal_tail(t.q, pr, t.v, t.layout, t.cu, tk, tv, tl)
@@ -640,3 +640,33 @@ def test_gaussian_recovery_with_zero_spread_is_the_degenerate_recovery_at_the_ro
     assert np.all(sigma == 0) and np.array_equal(mu, pr.mu32)
     got = oracle.decode_sampled(oracle.GAUSSIAN, 5, t.q, pr, mu, sigma, t.v, t.layout, t.cu)
     assert np.allclose(got, oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu), rtol=0, atol=1e-14)
+
+
+def test_gaussian_pairs_are_the_box_muller_transform_of_their_two_uniforms():
+    """Channels 2m, 2m+1 share one radius and one angle: z0^2 + z1^2 = -2 ln u_(2m) and the angle of
+    (z0, z1) is 2 pi u_(2m+1); so the two samples of a pair are uncorrelated, not copies."""
+    w, t, a32, pr, mu, sigma = _sampled_setup(45)
+    seed = 0xABCDEF0123
+    _, kt = oracle.decode_sampled(oracle.GAUSSIAN, seed, t.q, pr, mu, sigma, t.v, t.layout, t.cu, want_ktilde=True)
+    bits = np.unpackbits(pr.mask.view(np.uint8), axis=-1, bitorder="little").astype(bool)
+    cu = np.asarray(t.cu)
+    checked = 0
+    z0s, z1s = [], []
+    for n in range(0, w.total, 7):
+        b = int(np.searchsorted(cu, n, side="right") - 1)
+        for h in range(w.n_kv_heads):
+            for m in range(64):
+                j = 2 * m
+                if bits[n, h, j] or bits[n, h, j + 1] or a32[b, h, j] == 0 or a32[b, h, j + 1] == 0:
+                    continue
+                z0 = (kt[n, h, j] * float(a32[b, h, j]) - float(mu[n, h])) / float(sigma[n, h])
+                z1 = (kt[n, h, j + 1] * float(a32[b, h, j + 1]) - float(mu[n, h])) / float(sigma[n, h])
+                u1, u2 = oracle.uniform(seed, n, h, j), oracle.uniform(seed, n, h, j + 1)
+                assert z0 * z0 + z1 * z1 == pytest.approx(-2.0 * math.log(u1), rel=1e-9)
+                ang = math.atan2(z1, z0) % (2 * math.pi)
+                assert min(abs(ang - 2 * math.pi * u2), 2 * math.pi - abs(ang - 2 * math.pi * u2)) < 1e-7
+                z0s.append(z0)
+                z1s.append(z1)
+                checked += 1
+    assert checked > 500
+    assert abs(np.corrcoef(z0s, z1s)[0, 1]) < 0.1
