@@ -217,9 +217,9 @@ def main() -> int:
     prune_gbs = prune_alg_bytes / (prune_us * 1e-6) / 1e9 if prune_us > 0 else 0.0
 
     result = {
-        "metric": "decode-attn us/step + achieved HBM GB/s (% peak) at 32K ctx, 80% prune",
+        "metric": "decode-attn \u00b5s/step + achieved HBM GB/s (% peak) at 32K ctx, 80% prune",
         "value": round(dec_us, 2),
-        "unit": "us/step (decode attention)",
+        "unit": "\u00b5s/step (decode attention)",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
