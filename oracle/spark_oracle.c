@@ -200,7 +200,10 @@ int oracle_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride,
  *     amax = max_i |khat_i|;  scale = amax / 127  (binary32 division)
  *     code_i = clamp(round-to-nearest-even(khat_i / scale), -127, 127), all 0 if scale == 0
  * Both divisions are single binary32 operations so the integer code is decided in the
- * same precision on the CPU and on the GPU.
+ * same precision on the CPU and on the GPU.  (With an absmax scale |khat_i / scale| never
+ * exceeds 127 by more than the rounding of the two divisions, which round-to-nearest
+ * brings back to 127, so the clamp never changes a value; it is kept as a statement of
+ * the code range.)
  */
 void oracle_quant_int8(const uint16_t *kept, int64_t rows, int T, int8_t *codes, float *scale)
 {
