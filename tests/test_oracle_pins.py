@@ -565,6 +565,57 @@ def test_generator_is_a_bijective_mixer_and_its_uniforms_behave():
     assert hist.min() > 0.9 * flat.size / 16 and hist.max() < 1.1 * flat.size / 16
 
 
+def _header_generator_text():
+    with open(os.path.join(os.path.dirname(HERE), "include", "spark.h")) as fh:
+        return fh.read()
+
+
+def _uniform_from_the_header(seed, n, h, c):
+    """The generator exactly as include/spark.h words it, in Python integers (no oracle call):
+    mix(x): x ^= x >> 16; x *= 0x85EBCA6B; x ^= x >> 13; x *= 0xC2B2AE35; x ^= x >> 16 on 32-bit words,
+    base = mix(mix(mix(n) + seed_lo) + h * 0x9E3779B9 + seed_hi), x_c = mix(base + c * 0x9E3779B9),
+    u_c = ((x_c >> 9) + 0.5) / 2^23.  Returns (x_c, u_c as an exact fraction numerator over 2^24)."""
+    M = 0xFFFFFFFF
+
+    def mix(x):
+        x &= M
+        x ^= x >> 16
+        x = (x * 0x85EBCA6B) & M
+        x ^= x >> 13
+        x = (x * 0xC2B2AE35) & M
+        x ^= x >> 16
+        return x
+
+    seed_lo, seed_hi = seed & M, (seed >> 32) & M
+    base = mix((mix((mix(n) + seed_lo) & M) + h * 0x9E3779B9 + seed_hi) & M)
+    x = mix((base + c * 0x9E3779B9) & M)
+    return x, 2 * (x >> 9) + 1          # u = (2 * (x >> 9) + 1) / 2^24
+
+
+def test_generator_known_answers_from_the_header_text():
+    """Holds the oracle's uniforms to the generator written out in include/spark.h: the composition (which
+    word is added where, the stride of the counter, the order of the three mixes) is recomputed here with
+    Python integers for a spread of arguments and must agree exactly, bit for bit."""
+    text = _header_generator_text()
+    for token in ("0x85EBCA6B", "0xC2B2AE35", "0x9E3779B9", "x >> 16", "x >> 13", "(x_c >> 9) + 0.5"):
+        assert token in text, f"the header no longer states {token}"
+    # the mixer alone, two values computed by hand from the five steps (x = 1 and x = 0xFFFFFFFF)
+    assert oracle.mix32(1) == 0x514E28B7 and oracle.mix32(0xFFFFFFFF) == 0x81F16F39
+    rng = np.random.default_rng(77)
+    cases = [(0, 0, 0, 0), (1, 0, 0, 0), (0, 1, 0, 0), (0, 0, 1, 0), (0, 0, 0, 1), (1 << 32, 0, 0, 0),
+             (0xFFFFFFFFFFFFFFFF, 0xFFFFFFFF, 7, 127), (0x5EED0002, 2097151, 7, 101)]
+    cases += [(int(rng.integers(0, 1 << 63)), int(rng.integers(0, 1 << 31)), int(rng.integers(0, 64)),
+               int(rng.integers(0, 128))) for _ in range(300)]
+    for seed, n, h, c in cases:
+        x, num = _uniform_from_the_header(seed, n, h, c)
+        u = oracle.uniform(seed, n, h, c)
+        assert u * (1 << 24) == num, (seed, n, h, c, x)
+    # neighbouring counters, heads and tokens are separated by the stated strides, not by some other constant
+    x0, _ = _uniform_from_the_header(123, 5, 1, 0)
+    x1, _ = _uniform_from_the_header(123, 5, 1, 1)
+    assert x0 != x1 and _unmix32(x1) == (_unmix32(x0) + 0x9E3779B9) & 0xFFFFFFFF
+
+
 def _sampled_setup(seed, T=26):
     w, t = _random_small(seed, Hq=8, Hkv=2, T=T)
     _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
