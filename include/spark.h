@@ -22,8 +22,9 @@
  *     exceptions, no global state; calls on distinct streams and buffers are thread safe.
  *   - bfloat16 tensors are raw 16-bit patterns.  Channel stride is 1 everywhere; token and
  *     head strides are in ELEMENTS: K[n,h,j] = k[n*k_token_stride + h*k_head_stride + j]
- *     for global token n in [0,total_tokens), likewise V.  Rows must be 16-byte aligned
- *     (strides multiples of 8, base pointers 16-byte aligned).
+ *     for global token n in [0,total_tokens), likewise V.  Rows of K and V must be 16-byte
+ *     aligned (strides multiples of 8, base pointers 16-byte aligned; checked); q and the window
+ *     queries need 2-byte alignment only.
  *   - Sequences are ragged: cu_seqlens[b] .. cu_seqlens[b+1] are the global token indices
  *     of batch element b (int32 [batch+1], cu_seqlens[0] = 0, cu_seqlens[batch] =
  *     total_tokens).  Query head g reads KV head g / (n_q_heads / n_kv_heads).
@@ -43,7 +44,8 @@ typedef enum {
     SPARK_ERR_INVALID_ARG = 1,      /* NULL pointer, non-positive size, bad stride/alignment */
     SPARK_ERR_UNSUPPORTED = 2,      /* head_dim != 128, group size not in {1,2,4,8,16}, token stride of K above 2^24 */
     SPARK_ERR_WORKSPACE_TOO_SMALL = 3,
-    SPARK_ERR_HIP = 4               /* the HIP runtime reported an error at launch */
+    SPARK_ERR_HIP = 4,              /* the HIP runtime reported an error at launch */
+    SPARK_ERR_MISMATCH = 5          /* spark_check_packed: the cache was not written for this description */
 } spark_status;
 
 typedef enum { SPARK_PACK_BF16 = 0, SPARK_PACK_INT8 = 1 } spark_pack_dtype;
@@ -88,11 +90,13 @@ size_t spark_prune_workspace(const spark_desc *desc);
 size_t spark_decode_workspace(const spark_desc *desc);
 
 /*
- * Prepares a decode workspace: zeroes the per-(batch, KV head) arrival counters at its end.
- * Call once after allocating (or overwriting) the workspace and whenever batch, n_q_heads,
- * n_kv_heads or the split count change; spark_decode_attn leaves the counters zeroed, so one
- * workspace serves any number of successive calls on one stream.  Two calls that overlap in
- * time need two workspaces.
+ * Prepares a decode workspace: zeroes the per-(batch, KV head) arrival counters, which sit at its
+ * start (batch * n_kv_heads 32-bit words, at a position that does not depend on token counts,
+ * split counts or tail capacity; the partial softmax states follow).  Call once after allocating
+ * (or overwriting) the workspace and whenever batch or n_kv_heads change; spark_decode_attn leaves
+ * the counters zeroed, so one workspace that is large enough serves any number of successive calls
+ * on one stream, also for descriptions that differ in total_tokens, n_splits or tail_capacity.
+ * Two calls that overlap in time need two workspaces.
  */
 spark_status spark_decode_workspace_init(const spark_desc *desc, void *workspace,
                                          size_t workspace_bytes, void *hip_stream);
@@ -164,6 +168,19 @@ spark_status spark_decode_attn(const spark_desc *desc, const void *q_bf16, const
 spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *mask_out,
                           void *vals_out, float *mu_out, float *scale_out, float *a_out,
                           void *hip_stream);
+
+/*
+ * Debugging aid: does this packed cache belong to this description?  The decode and unpack calls
+ * trust the description they are given (they read rows at the stride it implies and cannot report a
+ * mismatch without a device-to-host round trip); this call makes that round trip.  It copies the
+ * cache's 64-byte header to the host, WAITS for `hip_stream`, and compares magic word, kept-channel
+ * count, storage type, statistics flag, batch, n_kv_heads, total_tokens and row length with what
+ * `desc` implies.  `is_value_cache` = 0 checks a key cache written by spark_prune (against keep,
+ * pack_dtype, stats), 1 a value cache written by spark_prune_values (against keep_v).
+ * Returns SPARK_OK, SPARK_ERR_MISMATCH, or the usual argument / runtime errors.  Not a hot path.
+ */
+spark_status spark_check_packed(const spark_desc *desc, const void *packed, int32_t is_value_cache,
+                                void *hip_stream);
 
 /*
  * One decode step with a SAMPLED recovery function.
@@ -268,14 +285,6 @@ spark_status spark_decode_attn_values_tail(const spark_desc *desc, const void *q
  */
 spark_status spark_unpack_values(const spark_desc *desc, const void *packed_v, uint32_t *mask_out,
                                  void *vals_out, void *hip_stream);
-
-/*
- * Measurement aid, not part of the method: reads `bytes` (a multiple of 16) from `src` once with
- * 16-byte loads from n_blocks blocks of 256 threads and discards them.  Its time is the
- * streaming-read ceiling the decode kernel is compared with.  `sink` is 4 writable bytes.
- */
-spark_status spark_probe_read(const void *src, size_t bytes, void *sink, int32_t n_blocks,
-                              void *hip_stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char *spark_status_string(spark_status status);

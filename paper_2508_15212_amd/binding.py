@@ -17,11 +17,12 @@ _LIB_PATH = os.path.join(_HERE, "libspark_hip.so")
 PACK_BF16, PACK_INT8 = 0, 1
 RECOVER_GAUSSIAN, RECOVER_EXPONENTIAL = 1, 2
 OUT_BF16, OUT_F32 = 0, 1
+ERR_MISMATCH = 5
 
 EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspace", "spark_decode_workspace_init", "spark_decode_splits",
            "spark_prune", "spark_decode_attn", "spark_unpack", "spark_probe_read", "spark_status_string",
            "spark_packed_values_bytes", "spark_prune_values", "spark_unpack_values", "spark_decode_attn_values", "spark_decode_attn_tail",
-           "spark_decode_attn_values_tail", "spark_decode_attn_sampled", "spark_unpack_stats"]
+           "spark_decode_attn_values_tail", "spark_decode_attn_sampled", "spark_unpack_stats", "spark_check_packed"]
 
 
 class SparkError(RuntimeError):
@@ -93,6 +94,8 @@ def load() -> ctypes.CDLL:
     lib.spark_unpack_stats.argtypes = [dp, vp, vp, vp, vp]
     lib.spark_unpack_values.restype = ctypes.c_int
     lib.spark_unpack_values.argtypes = [dp, vp, vp, vp, vp]
+    lib.spark_check_packed.restype = ctypes.c_int
+    lib.spark_check_packed.argtypes = [dp, vp, ctypes.c_int32, vp]
     lib.spark_probe_read.restype = ctypes.c_int
     lib.spark_probe_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, vp]
     lib.spark_status_string.restype = ctypes.c_char_p
@@ -215,7 +218,15 @@ def unpack(desc: SparkDesc, packed: torch.Tensor, mask=None, vals=None, mu=None,
     _check(rc, "spark_unpack")
 
 
+def check_packed(desc: SparkDesc, packed: torch.Tensor, is_value_cache: bool = False) -> int:
+    """spark_check_packed: status code (0 = the cache matches the description, 5 = mismatch); synchronises."""
+    rc = int(load().spark_check_packed(ctypes.byref(desc), _ptr(packed), 1 if is_value_cache else 0, _stream()))
+    if rc not in (0, ERR_MISMATCH):
+        _check(rc, "spark_check_packed")
+    return rc
+
+
 def probe_read(src: torch.Tensor, sink: torch.Tensor, n_blocks: int) -> None:
-    """spark_probe_read: stream `src` once (measurement aid)."""
+    """spark_probe_read (include/spark_bench.h): stream `src` once (measurement aid)."""
     rc = load().spark_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), n_blocks, _stream())
     _check(rc, "spark_probe_read")

@@ -103,44 +103,16 @@ size_t partial_slots(const spark_desc *d)
     return (size_t)p.nchunk_max * d->n_q_heads + (size_t)d->batch * d->n_q_heads * p.tail_slots;
 }
 
-// Streaming-read yardstick: every lane pulls 16-byte words grid-stride (non-temporal, as the decode
-// kernel does) and folds them into one value that is stored only to keep the loads alive.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-__global__ __launch_bounds__(256) void spark_probe_read_kernel(const u32x4 *__restrict__ src, size_t n16,
-                                                               uint32_t *__restrict__ sink)
-{
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    uint32_t acc = 0;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride),
-                    c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
-        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
-    }
-    for (; i < n16; i += stride) {
-        const u32x4 a = __builtin_nontemporal_load(src + i);
-        acc ^= a.x ^ a.y ^ a.z ^ a.w;
-    }
-    if (acc == 0x9E3779B9u) sink[0] = acc;
-}
-
+// The arrival counters sit at the START of the workspace, so their position depends on batch and n_kv_heads
+// only and not on how a call cuts its sequences into blocks; the partial states follow at a 256-byte boundary.
 size_t counter_bytes(const spark_desc *d)
 {
-    return (((size_t)d->batch * d->n_kv_heads * sizeof(uint32_t)) + 15) & ~(size_t)15;
+    return (((size_t)d->batch * d->n_kv_heads * sizeof(uint32_t)) + 255) & ~(size_t)255;
 }
 
 }  // namespace
 
 extern "C" {
-
-spark_status spark_probe_read(const void *src, size_t bytes, void *sink, int32_t n_blocks, void *hip_stream)
-{
-    if (!src || !sink || bytes < 16 || n_blocks < 1 || !aligned(src, 16) || !aligned(sink, 4))
-        return SPARK_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(spark_probe_read_kernel, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<const u32x4 *>(src), bytes / 16, static_cast<uint32_t *>(sink));
-    return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
-}
 
 const char *spark_status_string(spark_status s)
 {
@@ -150,6 +122,7 @@ const char *spark_status_string(spark_status s)
         case SPARK_ERR_UNSUPPORTED: return "unsupported configuration";
         case SPARK_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case SPARK_ERR_HIP: return "HIP runtime error";
+        case SPARK_ERR_MISMATCH: return "packed cache does not match the description";
     }
     return "unknown status";
 }
@@ -189,8 +162,7 @@ spark_status spark_decode_workspace_init(const spark_desc *desc, void *workspace
     if (!desc_ok(desc, &why)) return why;
     if (!workspace || !aligned(workspace, 16)) return SPARK_ERR_INVALID_ARG;
     if (workspace_bytes < spark_decode_workspace(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
-    const size_t slots = partial_slots(desc);
-    uint32_t *counters = reinterpret_cast<uint32_t *>(static_cast<float *>(workspace) + slots * (SPARK_D + 2));
+    uint32_t *counters = static_cast<uint32_t *>(workspace);
     const hipError_t e = spark::launch_zero_counters(counters, desc->batch * desc->n_kv_heads,
                                                      static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
@@ -209,7 +181,7 @@ spark_status spark_prune(const spark_desc *desc, const void *k_bf16, const void 
     if (!strides_ok(desc->k_token_stride, desc->k_head_stride)) return SPARK_ERR_INVALID_ARG;
     // the prune kernel addresses the 64 rows of a tile with 32-bit byte offsets from the tile's first row
     if (desc->k_token_stride > ((int64_t)1 << 24)) return SPARK_ERR_UNSUPPORTED;
-    if (!aligned(k_bf16, 2) || !aligned(qwin_bf16, 2) || !aligned(packed_out, 256)) return SPARK_ERR_INVALID_ARG;
+    if (!aligned(k_bf16, 16) || !aligned(qwin_bf16, 2) || !aligned(packed_out, 256)) return SPARK_ERR_INVALID_ARG;
     const SparkLayout L = layout_of(desc);
     const hipError_t e = spark::launch_prune(static_cast<const uint16_t *>(k_bf16), desc->k_token_stride,
                                              desc->k_head_stride, static_cast<const uint16_t *>(qwin_bf16),
@@ -232,7 +204,7 @@ spark_status spark_prune_values(const spark_desc *desc, const void *v_bf16, void
     if (desc->keep_v < 1 || !v_bf16 || !packed_v_out) return SPARK_ERR_INVALID_ARG;
     if (!strides_ok(desc->v_token_stride, desc->v_head_stride)) return SPARK_ERR_INVALID_ARG;
     if (desc->v_token_stride > ((int64_t)1 << 24)) return SPARK_ERR_UNSUPPORTED;
-    if (!aligned(v_bf16, 2) || !aligned(packed_v_out, 256)) return SPARK_ERR_INVALID_ARG;
+    if (!aligned(v_bf16, 16) || !aligned(packed_v_out, 256)) return SPARK_ERR_INVALID_ARG;
     const hipError_t e = spark::launch_prune_values(static_cast<const uint16_t *>(v_bf16), desc->v_token_stride,
                                                     desc->v_head_stride, static_cast<uint8_t *>(packed_v_out),
                                                     values_layout_of(desc), static_cast<hipStream_t>(hip_stream));
@@ -282,9 +254,9 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
     if (packed_v) Lv = values_layout_of(desc);
     const spark::DecodePlan plan = plan_of(desc);
     const size_t slots = partial_slots(desc);
-    float *part_acc = static_cast<float *>(workspace);
+    uint32_t *counters = static_cast<uint32_t *>(workspace);
+    float *part_acc = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counter_bytes(desc));
     float *part_ml = part_acc + slots * SPARK_D;
-    uint32_t *counters = reinterpret_cast<uint32_t *>(part_ml + slots * 2);
     const float scale = desc->softmax_scale != 0.0f ? desc->softmax_scale : 1.0f / sqrtf((float)SPARK_D);
     const hipError_t e = spark::launch_decode_attn(
         static_cast<const uint16_t *>(q_bf16), static_cast<const uint8_t *>(packed),
@@ -370,6 +342,25 @@ spark_status spark_unpack(const spark_desc *desc, const void *packed, uint32_t *
     const hipError_t e = spark::launch_unpack(static_cast<const uint8_t *>(packed), L, mask_out, vals_out, mu_out,
                                               scale_out, a_out, nullptr, nullptr, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
+}
+
+spark_status spark_check_packed(const spark_desc *desc, const void *packed, int32_t is_value_cache, void *hip_stream)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!packed || !aligned(packed, 256)) return SPARK_ERR_INVALID_ARG;
+    if (is_value_cache && desc->keep_v < 1) return SPARK_ERR_INVALID_ARG;
+    uint32_t hdr[16];
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (hipMemcpyAsync(hdr, packed, sizeof hdr, hipMemcpyDeviceToHost, st) != hipSuccess) return SPARK_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return SPARK_ERR_HIP;
+    const SparkLayout L = is_value_cache ? values_layout_of(desc) : layout_of(desc);
+    // header words: magic, T, int8, batch, Hkv, total_tokens, words per row, value-cache flag, statistics flag
+    const uint32_t want[9] = {SPARK_MAGIC, (uint32_t)L.T, (uint32_t)L.int8, (uint32_t)L.batch, (uint32_t)L.n_kv_heads,
+                              (uint32_t)L.total_tokens, (uint32_t)L.ndw, is_value_cache ? 1u : 0u, (uint32_t)L.stats};
+    for (int i = 0; i < 9; ++i)
+        if (hdr[i] != want[i]) return SPARK_ERR_MISMATCH;
+    return SPARK_OK;
 }
 
 }  // extern "C"

@@ -77,6 +77,7 @@ __global__ __launch_bounds__(8 * SPARK_D) void spark_window_stat_kernel(const ui
         if (j == 4) v = (uint32_t)L.n_kv_heads;
         if (j == 5) v = (uint32_t)L.total_tokens;
         if (j == 6) v = (uint32_t)L.ndw;
+        if (j == 8) v = (uint32_t)L.stats;      // (word 7 = 0: a key cache)
         hdr[j] = v;
     }
 }

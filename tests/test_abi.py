@@ -11,9 +11,17 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
+    names = set()
+    for header in ("spark.h", "spark_bench.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(spark_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_the_method_header_holds_no_measurement_aid():
     text = open(os.path.join(ROOT, "include", "spark.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(spark_[a-z_0-9]+)\s*\(", text)))
+    assert "spark_probe_read" not in text
 
 
 def test_library_exports_every_declared_symbol():
@@ -45,7 +53,9 @@ def test_size_queries_follow_the_layout():
     assert ns == 8                          # 4096 tiles x 8 heads / 512 blocks = chunks of 64 tiles; 512 / 64
     # slots: one per (chunk, q head) for at most (4096 + 2 * 8) // 64 + 8 + 1 = 73 chunks, plus one spare per
     # (batch, q head) for appended rows; 130 floats per slot; then the 8 * 8 arrival counters
-    assert spark.decode_workspace_bytes(d) == (73 * 32 + 8 * 32 * 1) * 130 * 4 + 8 * 8 * 4
+    # (the counters come first, padded to 256 bytes, so their place depends on batch and KV heads only)
+    assert spark.decode_workspace_bytes(d) == (73 * 32 + 8 * 32 * 1) * 130 * 4 + 256
+    assert spark.decode_workspace_bytes(_desc(batch=64, total_tokens=64 * 2048)) % 256 == 0
     assert spark.decode_splits(_desc(n_splits=7)) == 7
     # partial last tile is padded to 64 tokens
     assert spark.packed_bytes(_desc(batch=1, total_tokens=65)) == 256 + 2 * 8 * 128 * 4 + 2 * 64 * 8 * 72
@@ -88,6 +98,16 @@ def test_alignment_strides_and_workspace_are_checked_before_any_launch():
     assert lib.spark_prune(ctypes.byref(_desc(window=0)), A, A, A, A, None, 0, None) == 1
     assert lib.spark_probe_read(None, 1024, A, 4, None) == 1
     assert lib.spark_probe_read(A, 8, A, 4, None) == 1
+    # K and V base pointers must be 16-byte aligned (the kernels issue 4- and 16-byte row loads)
+    assert lib.spark_prune(ctypes.byref(d), A + 2, A, A, A, None, 0, None) == 1
+    assert lib.spark_prune(ctypes.byref(d), A + 8, A, A, A, None, 0, None) == 1
+    assert lib.spark_prune_values(ctypes.byref(_desc(keep_v=64)), A + 4, A, None) == 1
+    # the cache checker rejects bad arguments before it copies anything
+    assert lib.spark_check_packed(ctypes.byref(d), None, 0, None) == 1
+    assert lib.spark_check_packed(ctypes.byref(d), A + 64, 0, None) == 1
+    assert lib.spark_check_packed(ctypes.byref(d), A, 1, None) == 1          # keep_v = 0: there is no value cache
+    assert lib.spark_check_packed(ctypes.byref(_desc(head_dim=64)), A, 0, None) == 2
+    assert lib.spark_status_string(5) == b"packed cache does not match the description"
 
 
 def test_value_cache_and_tail_entry_points_check_their_arguments_on_the_host():
@@ -112,7 +132,7 @@ def test_value_cache_and_tail_entry_points_check_their_arguments_on_the_host():
     assert lib.spark_unpack_values(ctypes.byref(d), None, None, None, None) == 1
     # appended rows: capacity enters the workspace size (one spare slot per 256 rows)
     dt = _desc(tail_capacity=600)
-    assert spark.decode_workspace_bytes(dt) == (73 * 32 + 8 * 32 * 3) * 130 * 4 + 8 * 8 * 4
+    assert spark.decode_workspace_bytes(dt) == (73 * 32 + 8 * 32 * 3) * 130 * 4 + 256
     ws_t = spark.decode_workspace_bytes(dt)
     assert lib.spark_decode_attn_tail(ctypes.byref(dt), A, A, A, A, None, A, A, A, A, ws_t, None) == 1
     assert lib.spark_decode_attn_tail(ctypes.byref(dt), A, A, A, A, A, None, A, A, A, ws_t, None) == 1

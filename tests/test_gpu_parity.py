@@ -213,3 +213,51 @@ def test_batch_of_empty_sequences_gives_zero_output():
     spark.decode_attn(desc, dq, packed, k1, dcu, out, spark.new_decode_workspace(desc))
     torch.cuda.synchronize()
     assert np.all(out.cpu().numpy() == 0)
+
+
+def test_one_workspace_serves_descriptions_of_different_total_length():
+    """The arrival counters sit at the start of the workspace, so a workspace prepared once serves batches of
+    other total lengths (other block counts, other partial-state positions) with the same batch and KV heads."""
+    ws_desc = make_desc(wl.small(name="wsbig", seqlens=(5000, 3000), seed=71))
+    ws = torch.empty(2 * spark.decode_workspace_bytes(ws_desc), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xA5)                                   # garbage everywhere ...
+    spark.decode_workspace_init(ws_desc, ws)         # ... except what the init call prepares
+    for seqlens, seed in (((5000, 3000), 71), ((130, 77), 72), ((2500, 900), 73), ((64, 64), 74), ((5000, 3000), 71)):
+        w = wl.small(name=f"ws{seqlens[0]}", seqlens=seqlens, seed=seed)
+        t = wl.generate(w)
+        a32, pr, ref = _oracle_all(w, t)
+        res = run_gpu_case(w, t, want_unpack=False, want_bf16=False)      # fresh workspace: the reference run
+        desc = res["desc"]
+        assert spark.decode_workspace_bytes(desc) <= ws.numel()
+        dk, dv, dqw, dq, dcu = res["dev"]
+        out = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+        spark.decode_attn(desc, dq, res["packed"], dv, dcu, out, ws)
+        got = out.cpu().numpy()
+        assert np.array_equal(got, res["out_f32"]), seqlens
+        err = np.abs(got.astype(np.float64) - ref)
+        assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+
+
+def test_check_packed_tells_matching_from_foreign_caches():
+    w = wl.small(name="chk", seqlens=(200, 77), seed=75)
+    t = wl.generate(w)
+    res = run_gpu_case(w, t, want_unpack=False, want_bf16=False)
+    desc, packed = res["desc"], res["packed"]
+    assert spark.check_packed(desc, packed) == 0
+    for field, val in (("keep", 27), ("pack_dtype", spark.PACK_INT8), ("stats", 1), ("total_tokens", w.total + 1),
+                       ("n_kv_heads", 1), ("batch", 3)):
+        d2 = spark.SparkDesc.from_buffer_copy(desc)
+        setattr(d2, field, val)
+        if field == "n_kv_heads":
+            d2.n_q_heads = 4
+        assert spark.check_packed(d2, packed) == spark.ERR_MISMATCH, field
+    # a value cache is told apart from a key cache, and checked against keep_v
+    dv_desc = spark.SparkDesc.from_buffer_copy(desc)
+    dv_desc.keep_v = 64
+    packed_v = torch.empty(spark.packed_values_bytes(dv_desc), dtype=torch.uint8, device="cuda")
+    spark.prune_values(dv_desc, res["dev"][1], packed_v)
+    assert spark.check_packed(dv_desc, packed_v, True) == 0
+    assert spark.check_packed(dv_desc, packed_v, False) == spark.ERR_MISMATCH
+    assert spark.check_packed(dv_desc, packed, True) == spark.ERR_MISMATCH
+    dv_desc.keep_v = 38
+    assert spark.check_packed(dv_desc, packed_v, True) == spark.ERR_MISMATCH
