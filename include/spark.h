@@ -286,6 +286,22 @@ spark_status spark_decode_attn_values_tail(const spark_desc *desc, const void *q
 spark_status spark_unpack_values(const spark_desc *desc, const void *packed_v, uint32_t *mask_out,
                                  void *vals_out, void *hip_stream);
 
+/*
+ * spark_decode_attn for callers that can neither allocate device memory nor hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result
+ * as spark_decode_attn, without the workspace: split partials and arrival counters live in an array of
+ * SPARK_STATIC_WORKSPACE_BYTES inside the library's device image (one copy per GPU, held until the process
+ * ends).  The call allocates nothing, frees nothing and prepares the array itself (no init call).
+ *   - SPARK_ERR_WORKSPACE_TOO_SMALL if spark_decode_workspace(desc) exceeds SPARK_STATIC_WORKSPACE_BYTES
+ *     (all five benchmark shapes fit; the largest needs 2.7 MB);
+ *   - the first call on a GPU looks the array's address up (hipGetSymbolAddress): make it outside a capture;
+ *   - every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (two streams) race.
+ */
+#define SPARK_STATIC_WORKSPACE_BYTES (4u << 20)
+spark_status spark_decode_attn_static(const spark_desc *desc, const void *q_bf16, const void *packed,
+                                      const void *v_bf16, const int32_t *cu_seqlens, void *out,
+                                      void *hip_stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *spark_status_string(spark_status status);
 

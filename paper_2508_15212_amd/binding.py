@@ -22,7 +22,8 @@ ERR_MISMATCH = 5
 EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspace", "spark_decode_workspace_init", "spark_decode_splits",
            "spark_prune", "spark_decode_attn", "spark_unpack", "spark_probe_read", "spark_status_string",
            "spark_packed_values_bytes", "spark_prune_values", "spark_unpack_values", "spark_decode_attn_values", "spark_decode_attn_tail",
-           "spark_decode_attn_values_tail", "spark_decode_attn_sampled", "spark_unpack_stats", "spark_check_packed"]
+           "spark_decode_attn_values_tail", "spark_decode_attn_sampled", "spark_unpack_stats", "spark_check_packed",
+           "spark_decode_attn_static"]
 
 
 class SparkError(RuntimeError):
@@ -94,6 +95,8 @@ def load() -> ctypes.CDLL:
     lib.spark_unpack_stats.argtypes = [dp, vp, vp, vp, vp]
     lib.spark_unpack_values.restype = ctypes.c_int
     lib.spark_unpack_values.argtypes = [dp, vp, vp, vp, vp]
+    lib.spark_decode_attn_static.restype = ctypes.c_int
+    lib.spark_decode_attn_static.argtypes = [dp, vp, vp, vp, vp, vp, vp]
     lib.spark_check_packed.restype = ctypes.c_int
     lib.spark_check_packed.argtypes = [dp, vp, ctypes.c_int32, vp]
     lib.spark_probe_read.restype = ctypes.c_int
@@ -156,6 +159,17 @@ def decode_attn(desc: SparkDesc, q: torch.Tensor, packed: torch.Tensor, v: torch
     rc = load().spark_decode_attn(ctypes.byref(desc), _ptr(q), _ptr(packed), _ptr(v), _ptr(cu), _ptr(out),
                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "spark_decode_attn")
+
+
+STATIC_WORKSPACE_BYTES = 4 << 20
+
+
+def decode_attn_static(desc: SparkDesc, q: torch.Tensor, packed: torch.Tensor, v: torch.Tensor, cu: torch.Tensor,
+                       out: torch.Tensor) -> None:
+    """spark_decode_attn_static: decode with the library's own per-GPU scratch array (no workspace argument)."""
+    rc = load().spark_decode_attn_static(ctypes.byref(desc), _ptr(q), _ptr(packed), _ptr(v), _ptr(cu), _ptr(out),
+                                         _stream())
+    _check(rc, "spark_decode_attn_static")
 
 
 def packed_values_bytes(desc: SparkDesc) -> int:

@@ -4,6 +4,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/spark.h"
 #include "spark_kernels.h"
 #include "spark_layout.h"
@@ -361,6 +363,52 @@ spark_status spark_check_packed(const spark_desc *desc, const void *packed, int3
     for (int i = 0; i < 9; ++i)
         if (hdr[i] != want[i]) return SPARK_ERR_MISMATCH;
     return SPARK_OK;
+}
+
+// ---------------------------------------------------------------- decode without a caller-provided workspace
+
+// Split partials and arrival counters of spark_decode_attn_static: one array per GPU, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; kernels get the looked-up address.
+static __device__ __align__(256) unsigned char scratch[SPARK_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];      // device address of `scratch` on each GPU, looked up on first use
+std::mutex g_scratch_mutex;
+
+// address of this GPU's copy of the array (the current device's), or nullptr after a runtime error
+void *scratch_address()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+spark_status spark_decode_attn_static(const spark_desc *desc, const void *q_bf16, const void *packed,
+                                      const void *v_bf16, const int32_t *cu_seqlens, void *out, void *hip_stream)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!v_bf16) return SPARK_ERR_INVALID_ARG;
+    const size_t need = spark_decode_workspace(desc);
+    if (need > (size_t)SPARK_STATIC_WORKSPACE_BYTES) return SPARK_ERR_WORKSPACE_TOO_SMALL;
+    void *ws = scratch_address();
+    if (!ws) return SPARK_ERR_HIP;
+    // the array keeps whatever the last call on this GPU left: the counters must start at zero (a small fill
+    // kernel, not a memset node, so the call can be captured into a graph); partial states are written before
+    // they are read
+    if (spark::launch_zero_counters(static_cast<uint32_t *>(ws), desc->batch * desc->n_kv_heads,
+                                    static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return SPARK_ERR_HIP;
+    return decode_common(desc, q_bf16, packed, v_bf16, nullptr, cu_seqlens, out, ws, SPARK_STATIC_WORKSPACE_BYTES,
+                         hip_stream);
 }
 
 }  // extern "C"
