@@ -21,13 +21,14 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build(verbose: bool = False, jobs: int | None = None) -> str:
+def build(verbose: bool = False, jobs: int | None = None, extra_flags: list[str] | None = None,
+          out: str | None = None) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     jobs = jobs or min(len(SOURCES), os.cpu_count() or 1, 16)
     with tempfile.TemporaryDirectory(prefix="spark_build_") as tmp:
         def compile_one(src: str):
             obj = os.path.join(tmp, src.replace(".hip", ".o"))
-            res = subprocess.run([hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj],
+            res = subprocess.run([hipcc] + FLAGS + (extra_flags or []) + ["-c", os.path.join(CSRC, src), "-o", obj],
                                  capture_output=True, text=True)
             return src, obj, res
 
@@ -40,13 +41,13 @@ def build(verbose: bool = False, jobs: int | None = None) -> str:
         if failed:
             raise RuntimeError("hipcc failed compiling " + ", ".join(r[0] for r in failed))
         link = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + [r[1] for r in results] +
-                              ["-o", LIB], capture_output=True, text=True)
+                              ["-o", out or LIB], capture_output=True, text=True)
         if verbose or link.returncode != 0:
             print(link.stdout)
             print(link.stderr)
         if link.returncode != 0:
             raise RuntimeError("hipcc failed linking libspark_hip.so")
-    return LIB
+    return out or LIB
 
 
 if __name__ == "__main__":

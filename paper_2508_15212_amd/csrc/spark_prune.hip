@@ -85,7 +85,46 @@ __global__ __launch_bounds__(8 * SPARK_D) void spark_window_stat_kernel(const ui
 // ---------------------------------------------------------------- top-T selection + pack
 
 constexpr int kPruneWaves = 4;      // wavefronts per block, one tile each
-constexpr int kHistBins = 64;       // one 64-bin digit histogram per wavefront (+ 64 spare words)
+constexpr int kHistBins = 128;      // digit bins of the counting pass, one 32-bit word per bin: 16 that collect the
+                                    // keys above the window, then 112 = 3.5 octaves x 32 digits
+constexpr int kOverBins = 16;
+constexpr int kHistWords = kHistBins + 64;  // per wavefront: the bins, then one spare word per lane
+constexpr int kBatch = 4;           // rows whose counting passes share the bins (one byte of every word each)
+
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+// LDS byte address of a pointer into shared memory, and back
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+__device__ __forceinline__ lds_u32 *lds_word(uint32_t byte_address) { return (lds_u32 *)(uintptr_t)byte_address; }
+
+// a * b + c with a, b taken as signed 24-bit numbers (one instruction; b is a small constant here)
+template <int B>
+__device__ __forceinline__ int mad_i24(int a, int c)
+{
+    int r;
+    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "n"(B), "s"(c));
+    return r;
+}
+// lanes whose byte R of x is >= y (wave-uniform), as a wave mask (one instruction: the compare selects the byte itself)
+template <int R>
+__device__ __forceinline__ uint64_t ballot_byte_ge(uint32_t x, uint32_t y)
+{
+    uint64_t m;
+    if constexpr (R == 0) asm("v_cmp_ge_u32_sdwa %0, %1, %2 src0_sel:BYTE_0 src1_sel:DWORD" : "=s"(m) : "v"(x), "s"(y));
+    if constexpr (R == 1) asm("v_cmp_ge_u32_sdwa %0, %1, %2 src0_sel:BYTE_1 src1_sel:DWORD" : "=s"(m) : "v"(x), "s"(y));
+    if constexpr (R == 2) asm("v_cmp_ge_u32_sdwa %0, %1, %2 src0_sel:BYTE_2 src1_sel:DWORD" : "=s"(m) : "v"(x), "s"(y));
+    if constexpr (R == 3) asm("v_cmp_ge_u32_sdwa %0, %1, %2 src0_sel:BYTE_3 src1_sel:DWORD" : "=s"(m) : "v"(x), "s"(y));
+    return m;
+}
+// x clamped to [lo, hi] (one instruction; lo <= hi)
+__device__ __forceinline__ int clamp_i32(int x, int lo, int hi)
+{
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo), "v"(hi));
+    return r;
+}
 
 // words per token in the LDS staging row: mask, mu, (scale), then T bf16 values
 __host__ __device__ inline int spark_stage_words(const SparkLayout &L)
@@ -95,10 +134,20 @@ __host__ __device__ inline int spark_stage_words(const SparkLayout &L)
     return (w + 1) & ~1;
 }
 
+// Rows a wavefront stages in LDS before it writes them out (a whole tile of 64, or 32, or 16): the largest that
+// leaves room for at least five wavefronts per SIMD (20 per compute unit of 160 KB), since the search is a
+// chain of dependent cross-lane steps that needs other wavefronts to fill its gaps.
+__host__ inline int spark_prune_rows_per_flush(const SparkLayout &L)
+{
+    for (int rows = SPARK_TILE_TOKENS; rows > 16; rows /= 2)
+        if ((size_t)rows * spark_stage_words(L) * 4 + kHistWords * 4 <= 7000) return rows;
+    return 16;
+}
+
 __host__ inline size_t spark_prune_lds_bytes(const SparkLayout &L)
 {
     return (size_t)kPruneWaves *
-           ((size_t)SPARK_TILE_TOKENS * spark_stage_words(L) * 4 + 2 * kHistBins * 4);
+           ((size_t)spark_prune_rows_per_flush(L) * spark_stage_words(L) * 4 + kHistWords * 4);
 }
 
 // bits 0..15 of x spread to the even bit positions of a 32-bit word
@@ -131,20 +180,67 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
     return v;
 }
 
-// Four wave-uniform values into lane `lane_id` (wave-uniform) of four registers; the other lanes
-// keep theirs.  (The lane selector of v_writelane travels in M0 because the value is a scalar
-// register already.)
-__device__ __forceinline__ void write_lane4(uint32_t &a, uint32_t &b, uint32_t &c, uint32_t &d, uint32_t va,
-                                            uint32_t vb, uint32_t vc, uint32_t vd, int lane_id)
+// One searched row goes to its staging place.  kb0 / kb1: wave masks of the lanes whose first / second value is
+// kept; pos0: number of kept values in front of this lane's first one; row_a: LDS byte address of the row's
+// first value slot (wave-uniform).  The lane's kept values are stored to their slots (16 bits each), and the
+// two masks are filed in the registers (em, om) of the lane named by the one-hot `lane_bit`.
+// The stores run under the keep masks and the two 64-bit moves under `lane_bit`; the execution mask is set
+// back to all lanes afterwards: the kernel has wave-uniform control flow only, every lane is active here.
+#ifndef SPARK_PRUNE_STAGE_VARIANT
+#define SPARK_PRUNE_STAGE_VARIANT 2
+#endif
+__device__ __forceinline__ void stage_row(int pos0, uint32_t xx, uint64_t kb0, uint64_t kb1, uint32_t row_a,
+                                          uint64_t lane_bit, uint32_t dump_a, uint64_t &em, uint64_t &om)
 {
+#if SPARK_PRUNE_STAGE_VARIANT == 2
+    uint32_t a0, a1;
+    asm volatile(
+        "v_addc_co_u32 %[a1], vcc, 0, %[pos], %[kb0]\n\t"      // slot of the second value: + 1 if the first is kept
+        "v_lshl_add_u32 %[a0], %[pos], 1, %[row]\n\t"
+        "v_lshl_add_u32 %[a1], %[a1], 1, %[row]\n\t"
+        "s_mov_b64 exec, %[kb0]\n\t"
+        "ds_write_b16 %[a0], %[x]\n\t"
+        "s_mov_b64 exec, %[kb1]\n\t"
+        "ds_write_b16_d16_hi %[a1], %[x]\n\t"
+        "s_mov_b64 exec, %[bit]\n\t"
+        "v_mov_b64 %[e], %[kb0]\n\t"
+        "v_mov_b64 %[o], %[kb1]\n\t"
+        "s_mov_b64 exec, -1"
+        : [e] "+v"(em), [o] "+v"(om), [a0] "=&v"(a0), [a1] "=&v"(a1)
+        : [kb0] "s"(kb0), [kb1] "s"(kb1), [bit] "s"(lane_bit), [pos] "v"(pos0), [row] "s"(row_a), [x] "v"(xx)
+        : "memory", "vcc");
+    (void)dump_a;
+#else
+    // every lane stores; a pruned value goes to the lane's spare word instead of masking lanes off
+    const bool keep0 = __builtin_amdgcn_inverse_ballot_w64(kb0);
+    const bool keep1 = __builtin_amdgcn_inverse_ballot_w64(kb1);
+    const uint32_t a0 = row_a + 2u * (uint32_t)pos0, a1 = a0 + (keep0 ? 2u : 0u);
+    typedef __attribute__((address_space(3))) uint16_t lds_u16;
+    *(lds_u16 *)(uintptr_t)(keep0 ? a0 : dump_a) = (uint16_t)xx;
+    *(lds_u16 *)(uintptr_t)(keep1 ? a1 : dump_a) = (uint16_t)(xx >> 16);
+#if SPARK_PRUNE_STAGE_VARIANT == 1
+    asm volatile(
+        "s_mov_b64 exec, %[bit]\n\t"
+        "v_mov_b64 %[e], %[kb0]\n\t"
+        "v_mov_b64 %[o], %[kb1]\n\t"
+        "s_mov_b64 exec, -1"
+        : [e] "+v"(em), [o] "+v"(om)
+        : [kb0] "s"(kb0), [kb1] "s"(kb1), [bit] "s"(lane_bit));
+#else
+    const int lane_id = __builtin_ctzll(lane_bit);
+    uint32_t e_lo = (uint32_t)em, e_hi = (uint32_t)(em >> 32), o_lo = (uint32_t)om, o_hi = (uint32_t)(om >> 32);
     asm("s_mov_b32 m0, %8\n\t"
         "v_writelane_b32 %0, %4, m0\n\t"
         "v_writelane_b32 %1, %5, m0\n\t"
         "v_writelane_b32 %2, %6, m0\n\t"
         "v_writelane_b32 %3, %7, m0"
-        : "+v"(a), "+v"(b), "+v"(c), "+v"(d)
-        : "s"(va), "s"(vb), "s"(vc), "s"(vd), "s"(lane_id)
+        : "+v"(e_lo), "+v"(e_hi), "+v"(o_lo), "+v"(o_hi)
+        : "s"((uint32_t)kb0), "s"((uint32_t)(kb0 >> 32)), "s"((uint32_t)kb1), "s"((uint32_t)(kb1 >> 32)), "s"(lane_id)
         : "m0");
+    em = ((uint64_t)e_hi << 32) | e_lo;
+    om = ((uint64_t)o_hi << 32) | o_lo;
+#endif
+#endif
 }
 
 // Pairwise step of a transposing reduction.  A and B hold one partial per lane for two tokens;
@@ -199,9 +295,9 @@ __device__ __forceinline__ void prune_lds_sync()
 // VALUES: the rows are value-cache rows (App. "Pruning Value Cache Channels"): the score of a channel is
 // |v| itself, there is no channel weight, no sequence bookkeeping and no statistic of the pruned set.
 template <int MODE, bool FULL, bool VALUES>
-__global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
+__global__ __launch_bounds__(kPruneWaves * 64, MODE == 2 ? 6 : 7) void spark_prune_kernel(
     const uint16_t *__restrict__ k, int64_t k_tok_stride, int64_t k_head_stride,
-    const int32_t *__restrict__ cu, uint8_t *__restrict__ packed, SparkLayout L)
+    const int32_t *__restrict__ cu, uint8_t *__restrict__ packed, SparkLayout L, int rows_per_flush)
 {
     constexpr bool INT8 = (MODE == 1), STATS = (MODE == 2);
     extern __shared__ __align__(16) uint8_t smem[];
@@ -230,8 +326,8 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     const int B = L.batch;
     const int sw = spark_stage_words(L);
     uint32_t *stage = reinterpret_cast<uint32_t *>(smem) +
-                      (size_t)wave * (SPARK_TILE_TOKENS * sw + 2 * kHistBins);
-    uint32_t *hist = stage + SPARK_TILE_TOKENS * sw;
+                      (size_t)wave * (rows_per_flush * sw + kHistWords);
+    uint32_t *hist = stage + rows_per_flush * sw;        // [0, 128) bins, [128, 192) spare
     uint16_t *stage16 = reinterpret_cast<uint16_t *>(stage);
 
     const float2 *a_all = reinterpret_cast<const float2 *>(packed + L.off_a);
@@ -283,8 +379,8 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
         }
     };
 
-    // lane t collects, for token t, the ballots of kept even channels (e) and kept odd channels (o)
-    uint32_t e_lo = 0, e_hi = 0, o_lo = 0, o_hi = 0;
+    // lane t collects, for token t, the ballots of kept even channels (em) and kept odd channels (om)
+    uint64_t em = 0, om = 0;
     float mureg = 0.0f;                                     // lane t: sum of pruned saliencies
     uint32_t muall = 0;                                     // lane t: mean saliency over all channels (bits)
     float sqreg = 0.0f;                                     // lane t: sum of squared deviations from it
@@ -295,15 +391,20 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
     load_block(xa, 0);
 
     // T-th largest key of a row.  The search is most-significant-bit first on the float32 bit pattern:
-    // keep a prefix p such that at least T keys are >= p and try to extend it; a probe is two wave
-    // ballots and two scalar popcounts.  Two shortcuts settle the top 14 bits: the exponent E (largest
-    // with at least T keys >= 2^E) is found by stepping from the previous row's -- rows of one head
-    // rarely differ by more than an octave -- and the next six bits by one counting pass (lanes add
-    // their keys' digits to a 64-bin LDS histogram stored highest digit first, lane l reads bin l, a
-    // wave prefix sum turns that into "keys with digit >= d", a ballot finds the digit where the count
-    // reaches what is still needed).  The search stops as soon as exactly T keys are >= p.
-    int E;
-    {   // first row: E by bisection over the 256 exponents
+    // keep a prefix p such that at least T keys are >= p and extend it until exactly T keys are >= p (or all
+    // 31 bits are fixed: a tie at the cut).  A probe of one candidate is two wave ballots and two scalar
+    // popcounts.  The top 13 bits (exponent and five mantissa bits = the DIGIT of a key) are settled by one
+    // counting pass: a window of 112 digits (3.5 octaves) is centred on the digit found for the row before
+    // (rows of one head rarely differ by more than an octave or two); every lane adds its
+    // two keys' digits to LDS bins, highest digit first, keys above the window into sixteen bins in front of
+    // it (spread by lane) and keys below it into a per-lane spare word, so no lane is masked off and nothing
+    // piles up on one address.  Lane l reads bins l and 64 + l, wave prefix sums turn them into "keys with
+    // digit >= the bin's", and one ballot per row finds the bin where the count reaches T.  Four rows share a
+    // pass: row r counts in byte r of every bin (a bin holds at most 128 keys), so zeroing, reading and the
+    // prefix sums are paid once per four rows.  A row whose T-th key lies outside the window repeats the pass
+    // alone with the window moved; its exponent is found by bisection if that fails as well.
+    int D;    // digit (exponent and five mantissa bits) of the T-th key of the row before
+    {   // first row: the exponent by bisection over the 256 exponents
         const uint32_t xx = xa[0];
         const uint32_t key0 = __float_as_uint(__fmul_rn(a01.x, fabsf(__uint_as_float(xx << 16))));
         const uint32_t key1 = __float_as_uint(__fmul_rn(a01.y, fabsf(__uint_as_float(xx & 0xFFFF0000u))));
@@ -314,18 +415,68 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
             const int c = __popcll(__ballot(key0 >= x)) + __popcll(__ballot(key1 >= x));
             if (c >= T) lo = mid; else hi = mid;
         }
-        E = lo;
+        D = (lo << 5) + 16;
     }
+    const uint32_t bins_a = lds_address(hist);                                   // byte address of bin 0 (wave-uniform)
+    const int lo_clamp = (int)(bins_a + 4u * (lane & (kOverBins - 1)));          // where a key far above the window counts
+    const int hi_clamp = (int)(bins_a + 4u * kHistBins + 4u * lane);             // this lane's spare word, past the bins
+    lds_u32 *const my_bin = lds_word(bins_a + 4u * lane);                        // bins l and 64 + l
+    const uint32_t dump_a = lds_address(hist + kHistBins + lane);     // where pruned values go
+    const uint32_t row_a0 = lds_address(stage16 + L.val0 * 2);
+    uint32_t row_a = row_a0;                                          // LDS byte address of the current row's first value slot
+    const uint32_t row_step = (uint32_t)sw * 4u;
+    const uint32_t Tv = (uint32_t)T;
 
-    // searches and stages the PF rows held in x (tokens tb .. tb+PF-1); returns their pruned-saliency
-    // partials folded into one register (token tb + u in the lanes with l & 7 == u)
-    auto do_block = [&](const uint32_t (&x)[PF], int tb) __attribute__((always_inline)) -> float2 {
-        float ps[PF], qs[PF];
+    // One counting pass.  key0 / key1 [NR]: the rows' keys; topd: digit of bin kOverBins (the window's highest).
+    // Leaves in (sA, sB) the counts of keys with digit >= the digit of bins l and 64 + l, row r in byte r.
+    auto count_pass = [&](auto nr_tag, const uint32_t *k0, const uint32_t *k1, const int topd, uint32_t &sA,
+                          uint32_t &sB) __attribute__((always_inline)) {
+        constexpr int NR = decltype(nr_tag)::value;
+        my_bin[0] = 0u;
+        my_bin[64] = 0u;
+        prune_lds_sync();
+        // byte address of the bin of digit d: bins_a + 4 * (kOverBins + topd - d)
+        const int top_a = (int)bins_a + 4 * (kOverBins + topd);
 #pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            const int t = tb + u;
-            const uint32_t xx = x[u];
-            if (!VALUES && __builtin_expect(t >= seq_end_t, 0)) {    // rare: the tile crosses into the next non-empty sequence
+        for (int r = 0; r < NR; ++r) {
+            const int a0 = clamp_i32(mad_i24<-4>((int)(k0[r] >> 18), top_a), lo_clamp, hi_clamp);
+            const int a1 = clamp_i32(mad_i24<-4>((int)(k1[r] >> 18), top_a), lo_clamp, hi_clamp);
+            __hip_atomic_fetch_add(lds_word((uint32_t)a0), 1u << (8 * r), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            __hip_atomic_fetch_add(lds_word((uint32_t)a1), 1u << (8 * r), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        }
+        prune_lds_sync();
+        const uint32_t hA = my_bin[0], hB = my_bin[64];
+        prune_lds_sync();
+        sA = wave_inclusive_sum(hA);
+        sB = wave_inclusive_sum(hB) + (uint32_t)__builtin_amdgcn_readlane((int)sA, 63);   // (bytes cannot carry: <= 128 keys)
+    };
+    // Where row R's count reaches T: bin index (>= kOverBins) and the count there; -1 if T or more keys lie
+    // above the window, -2 if fewer than T keys lie in or above it.
+    auto crossing = [&](auto r_tag, const uint32_t sA, const uint32_t sB, int &cnt) __attribute__((always_inline)) -> int {
+        constexpr int R = decltype(r_tag)::value;
+        const uint64_t rA = ballot_byte_ge<R>(sA, Tv);
+        if (rA != 0) {
+            const int l = __builtin_ctzll(rA);
+            cnt = (int)(((uint32_t)__builtin_amdgcn_readlane((int)sA, l) >> (8 * R)) & 0xFFu);
+            return l >= kOverBins ? l : -1;
+        }
+        const uint64_t rB = ballot_byte_ge<R>(sB, Tv);
+        if (__builtin_expect(rB == 0, 0)) return -2;
+        const int l = __builtin_ctzll(rB);
+        cnt = (int)(((uint32_t)__builtin_amdgcn_readlane((int)sB, l) >> (8 * R)) & 0xFFu);
+        return 64 + l;
+    };
+
+    // searches and stages rows u0 .. u0+3 of the block held in x (tokens tb+u0 ..); leaves their pruned-saliency
+    // partials in ps (and, with statistics, the squared deviations in qs)
+    auto do_batch = [&](const uint32_t (&x)[PF], const int u0, const int tb, float (&ps)[PF],
+                        float (&qs)[PF]) __attribute__((always_inline)) {
+        uint32_t key0[kBatch], key1[kBatch];
+        // ---- saliency: one float32 multiply, never fused
+        auto first_stage = [&](const int r, const bool may_cross) __attribute__((always_inline)) {
+            const int t = tb + u0 + r;
+            const uint32_t xx = x[u0 + r];
+            if (!VALUES && may_cross && t >= seq_end_t) {    // the tile crosses into the next non-empty sequence
                 if (t < nvalid) {
                     do {
                         ++b;
@@ -337,73 +488,122 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
                 }
             }
-            // saliency: one float32 multiply, never fused
-            const float w0 = __fmul_rn(a01.x, fabsf(__uint_as_float(xx << 16)));
-            const float w1 = __fmul_rn(a01.y, fabsf(__uint_as_float(xx & 0xFFFF0000u)));
-            const uint32_t key0 = __float_as_uint(w0), key1 = __float_as_uint(w1);
-            auto count_ge = [&](uint32_t x) {
-                return __popcll(__ballot(key0 >= x)) + __popcll(__ballot(key1 >= x));
-            };
-
-            // exponent: in the common case the previous row's E still has (keys >= 2^E) >= T > above1
-            int above1 = count_ge(((uint32_t)E + 1u) << 23);      // keys with exponent > E
-            while (__builtin_expect(above1 >= T, 0)) {            // step up (2^256 is above every key)
-                ++E;
-                above1 = count_ge(((uint32_t)E + 1u) << 23);
-            }
-            // next six bits: counting pass over the keys whose exponent is E; the others land in a
-            // spare word (bins 64..127) that is never read.  If the octave turns out to hold fewer
-            // keys than are still needed, all of it counts as "above" and the pass moves one octave
-            // down (octave 0 ends this: it holds every key not above it).
-            uint32_t s2;
-            uint64_t reached;
-            for (;;) {
-                hist[lane] = 0u;
-                prune_lds_sync();
-                {
-                    const uint32_t top = ((uint32_t)E << 6) | 63u;
-                    const uint32_t d0 = top - (key0 >> 17), d1 = top - (key1 >> 17);
-                    const uint32_t spare = (uint32_t)(kHistBins + lane);   // one spare word per lane: no pile-up
-                    atomicAdd(&hist[d0 < spare ? d0 : spare], 1u);
-                    atomicAdd(&hist[d1 < spare ? d1 : spare], 1u);
+            key0[r] = __float_as_uint(__fmul_rn(a01.x, fabsf(__uint_as_float(xx << 16))));
+            key1[r] = __float_as_uint(__fmul_rn(a01.y, fabsf(__uint_as_float(xx & 0xFFFF0000u))));
+        };
+        if (!VALUES && __builtin_expect(tb + u0 + kBatch - 1 >= seq_end_t, 0)) {
+#pragma unroll
+            for (int r = 0; r < kBatch; ++r) first_stage(r, true);
+        } else {
+#pragma unroll
+            for (int r = 0; r < kBatch; ++r) first_stage(r, false);
+        }
+        // ---- counting pass: exponent and five mantissa bits, four rows at once
+        uint32_t pfx[kBatch];
+        int geq[kBatch];
+        uint32_t miss_up = 0, miss_down = 0;
+        const int topd = D + 56;                  // the window's highest digit: the window is centred on D
+        {
+            uint32_t sA, sB;
+            count_pass(std::integral_constant<int, kBatch>{}, key0, key1, topd, sA, sB);
+            auto locate = [&](auto r_tag) __attribute__((always_inline)) {
+                constexpr int R = decltype(r_tag)::value;
+                int cnt = 0;
+                const int bin = crossing(r_tag, sA, sB, cnt);
+                geq[R] = cnt;
+                pfx[R] = (uint32_t)(topd + kOverBins - bin) << 18;
+                if (__builtin_expect(bin < 0, 0)) {
+                    if (bin == -1) miss_up |= 1u << R; else miss_down |= 1u << R;
                 }
-                prune_lds_sync();
-                s2 = wave_inclusive_sum(hist[lane]);              // keys in octave E with digit >= 63 - lane
-                prune_lds_sync();
-                reached = __ballot(s2 >= (uint32_t)(T - above1)); // T - above1 >= 1
-                if (__builtin_expect(reached != 0, 1)) break;
-                above1 += __builtin_amdgcn_readlane((int)s2, 63);
-                --E;
+            };
+            locate(std::integral_constant<int, 0>{});
+            locate(std::integral_constant<int, 1>{});
+            locate(std::integral_constant<int, 2>{});
+            locate(std::integral_constant<int, 3>{});
+        }
+        // rows whose T-th key lies outside the window: one at a time, window moved by three octaves; if that is
+        // not enough either, the exponent by bisection (a window whose top octave is that one cannot miss)
+        uint32_t miss = miss_up | miss_down;
+        while (__builtin_expect(miss != 0, 0)) {
+            const int r = __builtin_ctz(miss);
+            miss &= miss - 1;
+            // (values, not references, are selected: the four rows' registers stay registers)
+            auto pick = [&](auto v0, auto v1, auto v2, auto v3) { return r == 0 ? v0 : (r == 1 ? v1 : (r == 2 ? v2 : v3)); };
+            const uint32_t k0[1] = {pick(key0[0], key0[1], key0[2], key0[3])};
+            const uint32_t k1[1] = {pick(key1[0], key1[1], key1[2], key1[3])};
+            int td = topd + (((miss_up >> r) & 1u) ? 96 : -96);
+            uint32_t P = 0;
+            int GE = 0;
+            for (int round = 0;; ++round) {
+                uint32_t sA, sB;
+                count_pass(std::integral_constant<int, 1>{}, k0, k1, td, sA, sB);
+                int cnt = 0;
+                const int bin = crossing(std::integral_constant<int, 0>{}, sA, sB, cnt);
+                if (bin >= 0) {
+                    GE = cnt;
+                    P = (uint32_t)(td + kOverBins - bin) << 18;
+                    break;
+                }
+                if (round == 2) {   // cannot happen for keys below 2^31 (finite input); never spin
+                    GE = T;
+                    P = 0x7F800000u;
+                    break;
+                }
+                int lo = 0, hi = 256;   // at least T keys are >= lo << 23, fewer are >= hi << 23
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    const uint32_t v = (uint32_t)mid << 23;
+                    const int c = __popcll(__ballot(k0[0] >= v)) + __popcll(__ballot(k1[0] >= v));
+                    if (c >= T) lo = mid; else hi = mid;
+                }
+                td = ((lo + 1) << 5) - 1;     // the T-th key has exponent lo: the window's first octave
             }
-            const int l2 = __builtin_ctzll(reached);
-            const int ge = above1 + __builtin_amdgcn_readlane((int)s2, l2);   // keys >= p
-            uint32_t p = ((uint32_t)E << 23) | ((uint32_t)(63 - l2) << 17);
-            int tied = 0;
-            if (ge != T) {
-                // remaining 17 bits (a probe is 2 vector compares and ~8 scalar instructions, with
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                pfx[i] = (r == i) ? P : pfx[i];
+                geq[i] = (r == i) ? GE : geq[i];
+            }
+        }
+        D = (int)(pfx[kBatch - 1] >> 18);
+        // ---- the rest of each row
+#pragma unroll
+        for (int r = 0; r < kBatch; ++r) {
+            const int u = u0 + r, t = tb + u;
+            const uint32_t xx = x[u];
+            const uint32_t k0 = key0[r], k1 = key1[r];
+            const float w0 = __uint_as_float(k0), w1 = __uint_as_float(k1);
+            uint32_t p = (uint32_t)__builtin_amdgcn_readfirstlane((int)pfx[r]);
+            uint64_t kb0, kb1;
+            int c = __builtin_amdgcn_readfirstlane(geq[r]);      // keys >= p (at least T)
+            if (__builtin_expect(c == T, 1)) {
+                kb0 = __ballot(k0 >= p);
+                kb1 = __ballot(k1 >= p);
+            } else {
+                // remaining 18 bits (a probe is 2 vector compares and a few scalar instructions, with
                 // the candidate and the prefix held in scalar registers)
-                tied = 1;
-                uint32_t bit = 1u << 16;
+                uint32_t bit = 1u << 17;
 #pragma nounroll
                 do {
                     const uint32_t cand = p | bit;
-                    const int c = count_ge(cand);
-                    p = (c >= T) ? cand : p;
-                    if (c == T) { tied = 0; break; }
+                    const int cc = __popcll(__ballot(k0 >= cand)) + __popcll(__ballot(k1 >= cand));
+                    const bool up = cc >= T;
+                    p = up ? cand : p;
+                    c = up ? cc : c;
                     bit >>= 1;
-                } while (bit != (VALUES ? (1u << 15) : 0u));   // |v| of a bf16 entry has no bits below 16
-            }
-            // exactly T keys are >= p, unless p is the T-th largest value and it is tied
-            uint64_t kb0 = __ballot(key0 >= p), kb1 = __ballot(key1 >= p);
-            if (__builtin_expect(tied, 0)) {
-                const bool eq0 = (key0 == p), eq1 = (key1 == p);
-                const uint64_t q0 = __ballot(eq0), q1 = __ballot(eq1);
-                const int need = T - __popcll(__ballot(key0 > p)) - __popcll(__ballot(key1 > p));
-                // tied channels below 2l: both halves of every lower lane; below 2l+1: plus own even
-                const int r0 = mbcnt64(q0) + mbcnt64(q1);
-                const int r1 = r0 + (eq0 ? 1 : 0);
-                kb0 = __ballot((key0 > p) || (eq0 && r0 < need));   // lower channel first
-                kb1 = __ballot((key1 > p) || (eq1 && r1 < need));
+                } while (c != T && bit != (VALUES ? (1u << 15) : 0u));   // |v| of a bf16 entry has no bits below 16
+                kb0 = __ballot(k0 >= p);
+                kb1 = __ballot(k1 >= p);
+                if (__builtin_expect(c != T, 0)) {
+                    // all bits fixed and still more than T keys >= p: p is the T-th largest value and it is tied
+                    const bool eq0 = (k0 == p), eq1 = (k1 == p);
+                    const uint64_t q0 = __ballot(eq0), q1 = __ballot(eq1);
+                    const int need = T - __popcll(__ballot(k0 > p)) - __popcll(__ballot(k1 > p));
+                    // tied channels below 2l: both halves of every lower lane; below 2l+1: plus own even
+                    const int r0 = mbcnt64(q0) + mbcnt64(q1);
+                    const int r1 = r0 + (eq0 ? 1 : 0);
+                    kb0 = __ballot((k0 > p) || (eq0 && r0 < need));   // lower channel first
+                    kb1 = __ballot((k1 > p) || (eq1 && r1 < need));
+                }
             }
             const bool keep0 = __builtin_amdgcn_inverse_ballot_w64(kb0);
             const bool keep1 = __builtin_amdgcn_inverse_ballot_w64(kb1);
@@ -413,16 +613,8 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                 __builtin_amdgcn_mbcnt_lo((uint32_t)kb1,
                                           __builtin_amdgcn_mbcnt_hi((uint32_t)(kb0 >> 32),
                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)kb0, 0))));
-            const int pos1 = pos0 + (keep0 ? 1 : 0);
-            uint16_t *vrow = stage16 + (size_t)t * sw * 2 + L.val0 * 2;
-            // every lane stores; a pruned value goes to the lane's spare word instead of masking
-            // lanes off around the store
-            uint16_t *dump = reinterpret_cast<uint16_t *>(hist + kHistBins + lane);
-            *(keep0 ? vrow + pos0 : dump) = (uint16_t)xx;
-            *(keep1 ? vrow + pos1 : dump) = (uint16_t)(xx >> 16);
-            // lane t keeps the ballots of token t
-            write_lane4(e_lo, e_hi, o_lo, o_hi, (uint32_t)kb0, (uint32_t)(kb0 >> 32), (uint32_t)kb1,
-                        (uint32_t)(kb1 >> 32), t);
+            stage_row(pos0, xx, kb0, kb1, row_a, 1ull << t, dump_a, em, om);
+            row_a += row_step;
             ps[u] = VALUES ? 0.0f : (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
             qs[u] = 0.0f;
             if constexpr (STATS) {
@@ -433,6 +625,14 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                 qs[u] = fmaf(d0, d0, d1 * d1);
             }
         }
+    };
+
+    // the PF rows held in x (tokens tb .. tb+PF-1); returns their pruned-saliency partials folded into one
+    // register (token tb + u in the lanes with l & 7 == u)
+    auto do_block = [&](const uint32_t (&x)[PF], int tb) __attribute__((always_inline)) -> float2 {
+        float ps[PF], qs[PF];
+#pragma unroll
+        for (int u0 = 0; u0 < PF; u0 += kBatch) do_batch(x, u0, tb, ps, qs);
         if constexpr (VALUES) return make_float2(0.0f, 0.0f);
         float q07 = 0.0f;
         if constexpr (STATS) {
@@ -449,6 +649,86 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
         const float f03 = fold_pair<0x4E>(f01, f23, lane & 2);         // quad_perm [2,3,0,1]
         const float f47 = fold_pair<0x4E>(f45, f67, lane & 2);
         return make_float2(fold_pair<0x124>(f03, f47, lane & 4), q07);   // row_ror 4
+    };
+
+    // ---- rows t0 .. t0 + rows_per_flush - 1 leave the staging area, lane = token (the other lanes idle)
+    uint8_t *const tile_out = packed + L.off_tiles + ((int64_t)h * L.n_tiles + tile) * L.tile_bytes;
+    auto flush = [&](const int t0) __attribute__((always_inline)) {
+        prune_lds_sync();
+        // (the lane number is taken afresh here so that nothing of this rarely run part is computed ahead
+        // of the row loop and kept in registers across it)
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        if (ln >= t0 && ln < t0 + rows_per_flush) {
+            const bool valid = ln < nvalid;
+            uint32_t *row = stage + (size_t)(ln - t0) * sw;
+            const float mu = (!VALUES && valid && T < SPARK_D) ? (mureg / (float)(SPARK_D - T)) : 0.0f;
+            // channel-ordered mask: bit 2l of the row = even ballot bit l, bit 2l+1 = odd ballot bit l.
+            // Rows past the last token carry a well-formed mask (channels 0..T-1) and zero values, so a
+            // reader that walks exactly T bits never runs off the mask.
+            auto low_bits = [](int n) { return n <= 0 ? 0u : (n >= 32 ? 0xFFFFFFFFu : ((1u << n) - 1u)); };
+            const uint32_t e_lo = (uint32_t)em, e_hi = (uint32_t)(em >> 32), o_lo = (uint32_t)om, o_hi = (uint32_t)(om >> 32);
+            row[0] = valid ? (spread16(e_lo) | (spread16(o_lo) << 1)) : low_bits(T);
+            row[1] = valid ? (spread16(e_lo >> 16) | (spread16(o_lo >> 16) << 1)) : low_bits(T - 32);
+            row[2] = valid ? (spread16(e_hi) | (spread16(o_hi) << 1)) : low_bits(T - 64);
+            row[3] = valid ? (spread16(e_hi >> 16) | (spread16(o_hi >> 16) << 1)) : low_bits(T - 96);
+            if (!VALUES) row[4] = __float_as_uint(mu);
+            if (STATS) {
+                row[5] = valid ? muall : 0u;
+                row[6] = valid ? __float_as_uint(sqrtf(sqreg * (1.0f / (float)SPARK_D))) : 0u;
+            }
+            if (!valid) {
+                for (int d = VALUES ? 4 : (STATS ? 7 : 5); d < sw; ++d) row[d] = 0u;
+            } else {
+                const int vend = L.val0 + (T + 1) / 2;               // one past the last staged bf16 word
+                if (T & 1) row[vend - 1] &= 0xFFFFu;                 // unused upper half of the last word
+                for (int d = vend; d < sw; ++d) row[d] = 0u;
+                if (INT8) {
+                    // absmax scale and round-to-nearest-even codes, decided in float32
+                    auto val = [&](int i) {
+                        return bf16_bits_to_float((row[L.val0 + (i >> 1)] >> (16 * (i & 1))) & 0xFFFFu);
+                    };
+                    float amax = 0.0f;
+                    for (int i = 0; i < T; ++i) amax = fmaxf(amax, fabsf(val(i)));
+                    const float scale = __fdiv_rn(amax, 127.0f);
+                    row[5] = __float_as_uint(scale);
+                    for (int c = 0; c < L.nv; ++c) {
+                        uint32_t word = 0;
+                        for (int e = 0; e < 4; ++e) {
+                            const int i = 4 * c + e;
+                            int code = 0;
+                            if (i < T && scale != 0.0f) {
+                                float qf = rintf(__fdiv_rn(val(i), scale));
+                                qf = fminf(fmaxf(qf, -127.0f), 127.0f);
+                                code = (int)qf;
+                            }
+                            word |= ((uint32_t)code & 0xFFu) << (8 * e);
+                        }
+                        row[L.val0 + c] = word;   // never ahead of the bf16 words still to be read
+                    }
+                    for (int d = L.val0 + L.nv; d < L.ndw; ++d) row[d] = 0u;
+                }
+            }
+            // ---- coalesced tile write: section q holds words 4q..4q+3 of every token
+            // (written once, read by another kernel much later: non-temporal, like the loads)
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            for (int q = 0; q < L.nq; ++q) {
+                u32x4 v;
+                v.x = row[4 * q + 0];
+                v.y = row[4 * q + 1];
+                v.z = row[4 * q + 2];
+                v.w = row[4 * q + 3];
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(tile_out + (size_t)q * 1024 + ln * 16));
+            }
+            if (L.tail2) {
+                u32x2 v;
+                v.x = row[4 * L.nq + 0];
+                v.y = row[4 * L.nq + 1];
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(tile_out + (size_t)L.nq * 1024 + ln * 8));
+            }
+        }
+        prune_lds_sync();      // the staging rows are reused
     };
 
     // Every one of the 64 rows is processed; rows past the last token repeat the last one and are
@@ -471,80 +751,13 @@ __global__ __launch_bounds__(kPruneWaves * 64) void spark_prune_kernel(
                 if ((lane >> 4) == (tb >> 4)) sqreg = s2;
             }
         }
-    }
-
-    // ---- row epilogue, lane = token
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const bool valid = lane < nvalid;
-    uint32_t *row = stage + (size_t)lane * sw;
-    const float mu = (!VALUES && valid && T < SPARK_D) ? (mureg / (float)(SPARK_D - T)) : 0.0f;
-    // channel-ordered mask: bit 2l of the row = even ballot bit l, bit 2l+1 = odd ballot bit l.
-    // Rows past the last token carry a well-formed mask (channels 0..T-1) and zero values, so a
-    // reader that walks exactly T bits never runs off the mask.
-    auto low_bits = [](int n) { return n <= 0 ? 0u : (n >= 32 ? 0xFFFFFFFFu : ((1u << n) - 1u)); };
-    row[0] = valid ? (spread16(e_lo) | (spread16(o_lo) << 1)) : low_bits(T);
-    row[1] = valid ? (spread16(e_lo >> 16) | (spread16(o_lo >> 16) << 1)) : low_bits(T - 32);
-    row[2] = valid ? (spread16(e_hi) | (spread16(o_hi) << 1)) : low_bits(T - 64);
-    row[3] = valid ? (spread16(e_hi >> 16) | (spread16(o_hi >> 16) << 1)) : low_bits(T - 96);
-    if (!VALUES) row[4] = __float_as_uint(mu);
-    if (STATS) {
-        row[5] = valid ? muall : 0u;
-        row[6] = valid ? __float_as_uint(sqrtf(sqreg * (1.0f / (float)SPARK_D))) : 0u;
-    }
-    if (!valid) {
-        for (int d = VALUES ? 4 : (STATS ? 7 : 5); d < sw; ++d) row[d] = 0u;
-    } else {
-        const int vend = L.val0 + (T + 1) / 2;               // one past the last staged bf16 word
-        if (T & 1) row[vend - 1] &= 0xFFFFu;                 // unused upper half of the last word
-        for (int d = vend; d < sw; ++d) row[d] = 0u;
-        if (INT8) {
-            // absmax scale and round-to-nearest-even codes, decided in float32
-            auto val = [&](int i) {
-                return bf16_bits_to_float((row[L.val0 + (i >> 1)] >> (16 * (i & 1))) & 0xFFFFu);
-            };
-            float amax = 0.0f;
-            for (int i = 0; i < T; ++i) amax = fmaxf(amax, fabsf(val(i)));
-            const float scale = __fdiv_rn(amax, 127.0f);
-            row[5] = __float_as_uint(scale);
-            for (int c = 0; c < L.nv; ++c) {
-                uint32_t word = 0;
-                for (int e = 0; e < 4; ++e) {
-                    const int i = 4 * c + e;
-                    int code = 0;
-                    if (i < T && scale != 0.0f) {
-                        float qf = rintf(__fdiv_rn(val(i), scale));
-                        qf = fminf(fmaxf(qf, -127.0f), 127.0f);
-                        code = (int)qf;
-                    }
-                    word |= ((uint32_t)code & 0xFFu) << (8 * e);
-                }
-                row[L.val0 + c] = word;   // never ahead of the bf16 words still to be read
-            }
-            for (int d = L.val0 + L.nv; d < L.ndw; ++d) row[d] = 0u;
+        if (((tb + 2 * PF) & (rows_per_flush - 1)) == 0) {
+            flush(tb + 2 * PF - rows_per_flush);
+            row_a = row_a0;
         }
     }
-    // ---- coalesced tile write: section q holds words 4q..4q+3 of every token
-    uint8_t *tile_out = packed + L.off_tiles + ((int64_t)h * L.n_tiles + tile) * L.tile_bytes;
-    // (written once, read by another kernel much later: non-temporal, like the loads)
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-    for (int q = 0; q < L.nq; ++q) {
-        u32x4 v;
-        v.x = row[4 * q + 0];
-        v.y = row[4 * q + 1];
-        v.z = row[4 * q + 2];
-        v.w = row[4 * q + 3];
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(tile_out + (size_t)q * 1024 + lane * 16));
-    }
-    if (L.tail2) {
-        u32x2 v;
-        v.x = row[4 * L.nq + 0];
-        v.y = row[4 * L.nq + 1];
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(tile_out + (size_t)L.nq * 1024 + lane * 8));
-    }
 }
+
 
 // ---------------------------------------------------------------- canonical export
 
@@ -604,7 +817,7 @@ hipError_t launch_tiles(const uint16_t *x, int64_t tok_stride, int64_t head_stri
         }
         const int nblocks = (int)((waves + kPruneWaves - 1) / kPruneWaves);
         hipLaunchKernelGGL(kern, dim3(nblocks), dim3(kPruneWaves * 64), lds, st, x, tok_stride, head_stride, cu,
-                           packed, L);
+                           packed, L, spark_prune_rows_per_flush(L));
         return hipGetLastError();
     };
     const int64_t full_waves = (L.total_tokens / SPARK_TILE_TOKENS) * L.n_kv_heads;
