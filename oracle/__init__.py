@@ -42,6 +42,7 @@ def lib() -> ctypes.CDLL:
         _lib.oracle_max_threads.restype = ctypes.c_int
         _lib.oracle_prune.restype = ctypes.c_int
         _lib.oracle_prune_values.restype = ctypes.c_int
+        _lib.oracle_prune_topp.restype = ctypes.c_int
         _lib.oracle_uniform.restype = ctypes.c_double
         _lib.oracle_mix32.restype = ctypes.c_uint32
     return _lib
@@ -102,6 +103,7 @@ class Pruned:
     D: int
     codes: np.ndarray | None = None   # int8 [total, Hkv, T]   (int8 storage variant)
     scale: np.ndarray | None = None   # float32 [total, Hkv]
+    count: np.ndarray | None = None   # int32 [total, Hkv]  kept channels per row (top-p variant; else T everywhere)
 
     def near_ties(self, rel=1e-6) -> int:
         return int(np.count_nonzero(self.gap < rel))
@@ -128,6 +130,32 @@ def prune(k: np.ndarray, layout: str, a32: np.ndarray, cu: np.ndarray, T: int,
     if rc != 0:
         raise ValueError("oracle_prune: bad arguments")
     return Pruned(mask, kept, mu64, mu32, gap, a32, w, int(T), d)
+
+
+def prune_topp(k: np.ndarray, layout: str, a32: np.ndarray, cu: np.ndarray, p_bp: int = 9900) -> Pruned:
+    """The top-p variant: per (token, KV head) the fewest most salient channels whose saliencies reach
+    p_bp / 10000 of the row total.  Returns a Pruned whose `kept` is [total, Hkv, D] (the first count[row]
+    entries of a row are used) and whose `count` holds the per-row numbers; T = D is the row stride, so the
+    decode functions take it as it is."""
+    k, ts, hs, total, hkv, d = _strided(k, layout)
+    cu = _c(cu, np.int32)
+    b = cu.shape[0] - 1
+    assert int(cu[-1]) == total and int(cu[0]) == 0
+    a32 = _c(a32, np.float32)
+    assert a32.shape == (b, hkv, d)
+    mw = (d + 31) // 32
+    mask = np.empty((total, hkv, mw), np.uint32)
+    kept = np.empty((total, hkv, d), np.uint16)
+    count = np.empty((total, hkv), np.int32)
+    mu64 = np.empty((total, hkv), np.float64)
+    mu32 = np.empty((total, hkv), np.float32)
+    rc = lib().oracle_prune_topp(_p(k), ctypes.c_int64(ts), ctypes.c_int64(hs), _p(a32), _p(cu), b, hkv, d,
+                                 int(p_bp), _p(mask), _p(kept), _p(count), _p(mu64), _p(mu32))
+    if rc != 0:
+        raise ValueError("oracle_prune_topp: bad arguments")
+    pr = Pruned(mask, kept, mu64, mu32, np.full((total, hkv), np.inf), a32, None, d, d)
+    pr.count = count
+    return pr
 
 
 def quant_int8(pr: Pruned) -> Pruned:

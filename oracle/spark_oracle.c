@@ -30,7 +30,9 @@
  * case, dense attention on the concatenated cache (keep-all) and the empty-tail identity; the
  * sampled recovery by the invertibility and the statistics of its generator, the sigma = 0
  * reduction to the degenerate function, sample means, and a plain softmax attention over the
- * exported rebuilt keys.  No function in this file is "parity unpinned".
+ * exported rebuilt keys; the top-p variant by exact rational arithmetic over every prefix of tiny
+ * rows, the one-dominant-channel, equal-saliency and p = 100 % cases and the prefix property.  No
+ * function in this file is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -227,6 +229,103 @@ void oracle_quant_int8(const uint16_t *kept, int64_t rows, int T, int8_t *codes,
             codes[r * T + i] = (int8_t)rq;
         }
     }
+}
+
+/*
+ * The top-p variant, Sec. "Adaptive Variants of SparK" (and the "Ablation study on variants" table):
+ * no fixed number of channels; per (token, KV head) the FEWEST most salient channels are kept
+ * whose saliencies together reach a fraction p (99 % in the paper) of the row's total saliency.
+ *
+ *   w[j]   = a32[b,h,j] * |K[n,h,j]|                 the same binary32 product as in oracle_prune
+ *   order  = channels by w descending, equal w by ascending j (stable), as in oracle_prune
+ *   m      = the smallest m >= 1 with  sum_{i<m} w[order[i]]  >=  p * sum_j w[j]
+ *   kept   = order[0..m);  mask, kept entries (ascending channel), count m
+ *   mu     = mean of w over the D-m pruned channels (0 when m == D), as in oracle_prune
+ *
+ * Reading: the count m is an integer decided by sums, and a floating-point sum depends on the
+ * order of its terms, which a parallel implementation cannot follow.  The decision is therefore
+ * taken in exact integer arithmetic: every w of the row is expressed in units of the last place of
+ * the row's LARGEST saliency, rounded down,
+ *     ulp = 2^(E-150),  E = max(1, biased exponent of max_j w[j]);   q[j] = floor(w[j] / ulp) < 2^24,
+ * p is a whole number of basis points (9900 for 99 %), and the rule is
+ *     m = the smallest m >= 1 with  10000 * sum_{i<m} q[order[i]]  >=  p_bp * sum_j q[j].
+ * The sums are below 2^31 and the products below 2^45: exact in 64-bit integers, in any order.  Rounding
+ * down loses less than 128 units of 2^-23 of the largest element over a whole row, four orders of
+ * magnitude below the 1 % the rule cuts at.  An all-zero row keeps one channel (m >= 1; channel 0).
+ *
+ * mask [total,Hkv,ceil(D/32)]; kept [total,Hkv,D] (first m entries of a row used, the rest 0);
+ * count [total,Hkv]; mu64, mu32 [total,Hkv].  Returns 0, or -1 on bad arguments.
+ */
+int oracle_prune_topp(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride,
+                      const float *a32, const int32_t *cu, int B, int Hkv, int D, int p_bp,
+                      uint32_t *mask, uint16_t *kept, int32_t *count, double *mu64, float *mu32)
+{
+    if (D < 1 || D > 128 || p_bp < 1 || p_bp > 10000 || B < 1 || Hkv < 1) return -1;
+    const int MW = (D + 31) / 32;
+    const int64_t total = cu[B];
+    int64_t n;
+#pragma omp parallel for schedule(static)
+    for (n = 0; n < total; ++n) {
+        const int b = seq_of_token(cu, B, n);
+        float w[128];
+        int order[128];
+        int64_t q[128];
+        for (int h = 0; h < Hkv; ++h) {
+            const uint16_t *krow = k + n * k_tok_stride + (int64_t)h * k_head_stride;
+            const float *a = a32 + ((int64_t)b * Hkv + h) * D;
+            const int64_t row = n * Hkv + h;
+            for (int j = 0; j < D; ++j) {
+                volatile float prod = a[j] * fabsf(bf16_bits_to_f32(krow[j]));
+                w[j] = prod;
+            }
+            for (int j = 0; j < D; ++j) {   /* stable: w descending, ties by index */
+                int pos = j;
+                while (pos > 0 && w[order[pos - 1]] < w[j]) {
+                    order[pos] = order[pos - 1];
+                    --pos;
+                }
+                order[pos] = j;
+            }
+            /* saliencies in units of the last place of the largest one, rounded down */
+            int emax = 1;
+            for (int j = 0; j < D; ++j) {
+                uint32_t bits;
+                memcpy(&bits, &w[j], sizeof bits);
+                const int e = (int)((bits >> 23) & 0xFF);
+                if (e > emax) emax = e;
+            }
+            int64_t S = 0;
+            for (int j = 0; j < D; ++j) {
+                uint32_t bits;
+                memcpy(&bits, &w[j], sizeof bits);
+                const int e = (int)((bits >> 23) & 0xFF);
+                const int64_t mant = (int64_t)(bits & 0x7FFFFFu) | (e ? 0x800000 : 0);   /* w = mant * 2^(max(e,1)-150) */
+                const int shift = emax - (e ? e : 1);
+                q[j] = (shift < 24) ? (mant >> shift) : 0;
+                S += q[j];
+            }
+            int m = 0;
+            int64_t G = 0;
+            do {
+                G += q[order[m]];
+                ++m;
+            } while (m < D && 10000 * G < (int64_t)p_bp * S);
+            for (int mw = 0; mw < MW; ++mw) mask[row * MW + mw] = 0u;
+            for (int i = 0; i < m; ++i) mask[row * MW + order[i] / 32] |= (1u << (order[i] % 32));
+            int c = 0;
+            for (int j = 0; j < D; ++j)
+                kept[row * D + j] = 0;
+            for (int j = 0; j < D; ++j)
+                if (mask[row * MW + j / 32] >> (j % 32) & 1u) kept[row * D + c++] = krow[j];
+            count[row] = m;
+            double s = 0.0;
+            for (int i = m; i < D; ++i) s += (double)w[order[i]];
+            const double mu = (m < D) ? s / (double)(D - m) : 0.0;
+            mu64[row] = mu;
+            mu32[row] = (float)mu;
+        }
+    }
+    return 0;
 }
 
 /* ------------------------------------------------------------- value cache */

@@ -721,3 +721,132 @@ def test_gaussian_pairs_are_the_box_muller_transform_of_their_two_uniforms():
                 checked += 1
     assert checked > 500
     assert abs(np.corrcoef(z0s, z1s)[0, 1]) < 0.1
+
+
+# ------------------------------------------------------------------ top-p variant pins
+
+def _topp_rows(k_rows, a_row, p_bp=9900):
+    """Runs the oracle's top-p pruning on hand-made rows: k_rows [S, D] floats (bf16-exact), a_row [D] floats that
+    are exact as the mean |window query| of a one-query window.  Returns the Pruned and the float32 saliencies."""
+    k_rows = np.asarray(k_rows, np.float32)
+    S, D = k_rows.shape
+    qwin = _bits(np.asarray(a_row, np.float32).reshape(1, 1, 1, D))
+    _, _, a32 = oracle.window_stat(qwin, 1)
+    assert np.array_equal(a32.reshape(-1), np.asarray(a_row, np.float32))
+    k = _bits(k_rows.reshape(S, 1, D))
+    pr = oracle.prune_topp(k, "NHD", a32, np.array([0, S], np.int32), p_bp)
+    w = (a32.reshape(1, D) * np.abs(k_rows)).astype(np.float32)      # one float32 multiply per entry
+    return pr, w
+
+
+def test_topp_count_is_the_shortest_prefix_by_exact_rational_arithmetic():
+    """Brute force over every prefix length of tiny rows, in exact fractions of the float32 saliencies (not the
+    oracle's integer units): the kept count is the first m whose m largest saliencies reach 99 % of the total,
+    no shorter prefix does, and the kept set is the m largest with ties to the lower channel."""
+    from fractions import Fraction
+    rng = np.random.default_rng(91)
+    checked = 0
+    for D in (3, 5, 8, 10):
+        for trial in range(40):
+            a_row = _q(rng.uniform(0.25, 4.0, size=D))
+            k_rows = _q(rng.standard_normal((6, D)) * rng.choice([1.0, 8.0, 0.01], size=(1, D)))
+            pr, w = _topp_rows(k_rows, a_row)
+            for t in range(k_rows.shape[0]):
+                ws = [Fraction(float(x)) for x in w[t]]
+                order = sorted(range(D), key=lambda j: (-ws[j], j))
+                tot = sum(ws)
+                cum, m = Fraction(0), 0
+                margins = []
+                while True:
+                    cum += ws[order[m]]
+                    m += 1
+                    margins.append(abs(cum - Fraction(99, 100) * tot))
+                    if cum >= Fraction(99, 100) * tot or m == D:
+                        break
+                if tot > 0 and min(margins) < Fraction(1, 10**5) * tot:
+                    continue          # (a prefix sum within 1e-5 of the cut: the integer units may decide either way)
+                assert int(pr.count[t, 0]) == m, (D, trial, t)
+                assert _kept_channels(pr.mask[t, 0], D) == sorted(order[:m])
+                assert np.array_equal(fb(pr.kept[t, 0, :m]), k_rows[t, sorted(order[:m])])
+                assert np.all(pr.kept[t, 0, m:] == 0)
+                pruned = [ws[j] for j in order[m:]]
+                want_mu = float(sum(pruned) / len(pruned)) if pruned else 0.0
+                assert pr.mu64[t, 0] == pytest.approx(want_mu, rel=1e-12, abs=0)
+                checked += 1
+    assert checked > 600
+
+
+def _q(x):
+    """Round to bfloat16-representable float32 values."""
+    return fb(bf(np.asarray(x, np.float32)))
+
+
+def test_topp_special_rows():
+    D = 128
+    ones = np.ones(D, np.float32)
+    # one dominant channel: 99.5 % of the total sits in channel 17 -> one channel kept
+    k = np.full((1, D), 1.0, np.float32)
+    k[0, 17] = 32768.0            # 32768 / (32768 + 127) = 0.9961
+    pr, _ = _topp_rows(k, ones)
+    assert pr.count[0, 0] == 1 and _kept_channels(pr.mask[0, 0], D) == [17]
+    # ... just below 99 %: the dominant one plus as many equal small ones (lowest channels) as it takes
+    k[0, 17] = 8192.0             # 8192 / 8319 = 0.9847;  (8192 + n) >= 0.99 * 8319 = 8235.81  ->  n = 44
+    pr, _ = _topp_rows(k, ones)
+    assert pr.count[0, 0] == 45
+    assert _kept_channels(pr.mask[0, 0], D) == sorted([17] + list(range(0, 17)) + list(range(18, 45)))
+    # equal saliencies: ceil(0.99 * 128) = 127 channels, the lowest ones
+    pr, _ = _topp_rows(np.full((1, D), 3.0, np.float32), ones)
+    assert pr.count[0, 0] == 127 and _kept_channels(pr.mask[0, 0], D) == list(range(127))
+    assert pr.mu64[0, 0] == 3.0
+    # p = 100 %: every channel with a saliency that counts; zero channels are dropped, and mu is then 0
+    k = np.zeros((1, D), np.float32)
+    k[0, 5:50] = np.linspace(1, 2, 45, dtype=np.float32)
+    pr, _ = _topp_rows(_q(k), ones, p_bp=10000)
+    assert pr.count[0, 0] == 45 and _kept_channels(pr.mask[0, 0], D) == list(range(5, 50))
+    assert pr.mu64[0, 0] == 0.0
+    # an all-zero row keeps exactly one channel, the first
+    pr, _ = _topp_rows(np.zeros((2, D), np.float32), ones)
+    assert np.all(pr.count == 1) and _kept_channels(pr.mask[1, 0], D) == [0]
+    # a smaller p keeps fewer: counts are monotone in p
+    rng = np.random.default_rng(92)
+    k = _q(rng.standard_normal((20, D)))
+    a = _q(rng.uniform(0.5, 2.0, size=D))
+    counts = [_topp_rows(k, a, p_bp)[0].count[:, 0] for p_bp in (5000, 9000, 9900, 9990, 10000)]
+    for lo, hi in zip(counts[:-1], counts[1:]):
+        assert np.all(lo <= hi)
+    assert np.all(counts[-1] == D) or np.any(np.abs(k) == 0)
+
+
+def test_topp_prefix_property_and_decode_on_random_data():
+    """On benchmark-like rows: the kept saliencies reach 99 % of the total and would not without the smallest kept
+    one (float64 sums, with a margin for the integer units); the kept set is a top set; decode over the rebuilt
+    keys is the literal recovery followed by Eq. (4), and a row that keeps everything reproduces dense attention."""
+    w, t = _random_small(61, Hq=8, Hkv=2, T=26)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune_topp(t.k, t.layout, a32, t.cu, 9900)
+    full = oracle.prune(t.k, t.layout, a32, t.cu, w.head_dim, want_w=True)      # (for the saliencies w)
+    wf = full.w.astype(np.float64)
+    bits = np.unpackbits(pr.mask.view(np.uint8), axis=-1, bitorder="little").astype(bool)
+    assert np.array_equal(bits.sum(-1), pr.count)
+    tot = wf.sum(-1)
+    kept_sum = (wf * bits).sum(-1)
+    smallest_kept = np.where(bits, wf, np.inf).min(-1)
+    largest_pruned = np.where(~bits, wf, -np.inf).max(-1)
+    assert np.all(kept_sum >= 0.99 * tot * (1 - 1e-5))
+    assert np.all((kept_sum - smallest_kept < 0.99 * tot * (1 + 1e-5)) | (pr.count == 1))
+    assert np.all(smallest_kept >= largest_pruned)
+    # the same count selected with the fixed-count rule gives the same set (the top-p set is a top-T set)
+    for n in range(0, w.total, 17):
+        for h in range(w.n_kv_heads):
+            T_row = int(pr.count[n, h])
+            one = oracle.prune(np.ascontiguousarray(t.k[:, n:n + 1]), t.layout, a32[:1] if n < t.cu[1] else a32[1:2],
+                               np.array([0, 1], np.int32), T_row)
+            assert np.array_equal(one.mask[0, h], pr.mask[n, h])
+            assert one.mu64[0, h] == pr.mu64[n, h]
+    # decode: literal form == factored form; at p = 100 % (every row keeps all non-zero channels) == dense attention
+    out = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
+    assert np.allclose(oracle.decode_fused(t.q, pr, t.v, t.layout, t.cu), out, rtol=0, atol=1e-12)
+    allp = oracle.prune_topp(t.k, t.layout, a32, t.cu, 10000)
+    if np.all(allp.count == w.head_dim):
+        assert np.allclose(oracle.decode_literal(t.q, allp, t.v, t.layout, t.cu),
+                           oracle.dense_attn(t.q, t.k, t.v, t.layout, t.cu), rtol=0, atol=1e-13)
