@@ -46,6 +46,9 @@ def main() -> int:
                     help="also prune the value cache to this many channels per row (0 = values stay dense)")
     ap.add_argument("--recovery", choices=["degenerate", "gaussian", "exponential"], default="degenerate",
                     help="recovery function at decode (the sampled ones store two more statistics per row)")
+    ap.add_argument("--top-p", type=int, default=0,
+                    help="the top-p variant: keep per row the fewest channels holding this many basis points of the "
+                         "row's saliency (9900 = 99 %%); prune through spark_prune_topp, decode through spark_decode_attn_topp")
     ap.add_argument("--tail", type=int, default=0,
                     help="appended never-pruned rows per sequence (decode through spark_decode_attn_tail)")
     ap.add_argument("--splits", type=int, default=0)
@@ -103,6 +106,10 @@ def main() -> int:
     if ntail and Tv:
         print("bench.py: --tail and --keep-v are separate entry points; pick one", file=sys.stderr)
         return 2
+    topp = args.top_p
+    if topp and (Tv or ntail or rec or args.int8 or args.keep):
+        print("bench.py: --top-p is timed on its own (no --keep / --keep-v / --tail / --recovery / --int8)", file=sys.stderr)
+        return 2
 
     ncopy = max(1, args.copies)
     k0, v0 = dev(t.k), dev(t.v)
@@ -110,7 +117,7 @@ def main() -> int:
     vs = [v0] + [v0.clone() for _ in range(ncopy - 1)]
     qwin, q = dev(t.qwin), dev(t.q)
     cu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
-    pbytes = spark.packed_bytes(desc)
+    pbytes = spark.packed_topp_bytes(desc) if topp else spark.packed_bytes(desc)
     packs = [torch.empty(pbytes, dtype=torch.uint8, device="cuda") for _ in range(ncopy)]
     packvs = ([torch.empty(spark.packed_values_bytes(desc), dtype=torch.uint8, device="cuda") for _ in range(ncopy)]
               if Tv else None)
@@ -118,6 +125,9 @@ def main() -> int:
     out = torch.empty((w.batch, hq, D), dtype=torch.bfloat16, device="cuda")
 
     def prune_all(c):
+        if topp:
+            spark.prune_topp(desc, ks[c], qwin, cu, topp, packs[c])
+            return
         spark.prune(desc, ks[c], qwin, cu, packs[c])
         if Tv:
             spark.prune_values(desc, vs[c], packvs[c])
@@ -132,7 +142,9 @@ def main() -> int:
         tail_len = torch.from_numpy(tail_len_np).cuda()
 
     def decode(c, d=desc, o=out):
-        if rec:
+        if topp:
+            spark.decode_attn_topp(d, q, packs[c], vs[c], cu, o, ws)
+        elif rec:
             spark.decode_attn_sampled(d, q, packs[c], vs[c], cu, o, ws, rec, rec_seed)
         elif ntail:
             spark.decode_attn_tail(d, q, packs[c], vs[c], cu, tail_k, tail_v, tail_len, o, ws)
@@ -202,6 +214,14 @@ def main() -> int:
     row_bytes = (pbytes - 256 - 2 * ((w.batch * hkv * D * 4 + 255) // 256 * 256)) / (
         hkv * ((total + 63) // 64) * 64)
     k_row = (T + 16 + 4 + 4) if args.int8 else (2 * T + 16 + 4)      # kept entries + mask + mu (+ scale)
+    mean_kept = None
+    if topp:
+        # rows of 24 bytes (mask, mu, count) plus the kept entries, every row rounded up to a whole 4-byte word
+        cnt = torch.empty((total, hkv), dtype=torch.int32, device="cuda")
+        spark.unpack_topp(desc, packs[0], None, cnt, None, None, None)
+        mean_kept = float(cnt.float().mean().item())
+        k_row = 24 + 4.0 * float(((cnt + 1) // 2).float().mean().item())
+        row_bytes = k_row
     if rec:
         k_row += 8                                                    # all-channel mean and standard deviation
     v_row = (2 * Tv + 16) if Tv else 2 * D                            # kept entries + mask, or the dense row
@@ -233,9 +253,11 @@ def main() -> int:
             "workload": w.name, "batch": w.batch, "n_q_heads": hq, "n_kv_heads": hkv, "head_dim": D,
             "context": int(w.seqlens.max()), "total_tokens": total, "keep": T, "window": w.window,
             "pack": "int8" if args.int8 else "bf16", "keep_v": Tv if Tv else None, "tail_rows_per_sequence": ntail if ntail else None,
-            "recovery": args.recovery,
+            "recovery": args.recovery, "top_p_basis_points": topp if topp else None,
+            "mean_kept_per_row": mean_kept,
             "splits": spark.decode_splits(desc),
             "input_copies_rotated": ncopy, "seed": w.seed, "step": ("spark_prune + spark_prune_values + spark_decode_attn_values" if Tv
+                                                              else "spark_prune_topp + spark_decode_attn_topp" if topp
                                                               else "spark_prune + spark_decode_attn_tail" if ntail
                                                               else "spark_prune + spark_decode_attn"),
         },
@@ -251,7 +273,7 @@ def main() -> int:
                      "frac": round(kern_gbs / HBM_PEAK_GBS, 4),
                      "kernel_us": round(kern_us, 2),
                      "traffic": MEASURED_DECODE_TRAFFIC_BYTES.get((w.name, "int8" if args.int8 else "bf16"))
-                     if not (args.keep or Tv or ntail or rec) else None,
+                     if not (args.keep or Tv or ntail or rec or topp) else None,
                      "algorithmic_bytes": dec_alg_bytes,
                      "kernel": "spark_decode_kernel, HIP events around %d back-to-back launches" % args.steps},
         "stream_read_ceiling": {"GBps": round(probe_gbs, 1), "us": round(probe_us, 2),
@@ -268,7 +290,7 @@ def main() -> int:
         threads = oracle.max_threads()
         t0 = time.perf_counter()
         _, _, a32 = oracle.window_stat(t.qwin, hkv)
-        pr = oracle.prune(t.k, t.layout, a32, t.cu, T)
+        pr = oracle.prune_topp(t.k, t.layout, a32, t.cu, topp) if topp else oracle.prune(t.k, t.layout, a32, t.cu, T)
         if args.int8:
             pr = oracle.quant_int8(pr)
         t1 = time.perf_counter()
@@ -293,7 +315,10 @@ def main() -> int:
         # the oracle's result is at hand: compare the last GPU step against it
         c = (args.steps - 1) % ncopy if args.steps > 0 else 0
         mask = torch.empty((total, hkv, 4), dtype=torch.int32, device="cuda")
-        spark.unpack(desc, packs[c], mask, None, None, None, None)
+        if topp:
+            spark.unpack_topp(desc, packs[c], mask, None, None, None, None)
+        else:
+            spark.unpack(desc, packs[c], mask, None, None, None, None)
         desc32 = spark.SparkDesc.from_buffer_copy(desc)
         desc32.out_dtype = spark.OUT_F32
         out32 = torch.empty((w.batch, hq, D), dtype=torch.float32, device="cuda")

@@ -287,6 +287,52 @@ spark_status spark_unpack_values(const spark_desc *desc, const void *packed_v, u
                                  void *vals_out, void *hip_stream);
 
 /*
+ * The top-p variant of the pruning: no fixed number of channels per row.
+ * [Sec. "Adaptive Variants of SparK", table "Ablation study on variants": per token, the fewest most salient
+ *  channels whose saliencies together account for 99 % of the row's total saliency are kept]
+ *
+ *   w[n,h,j]   as in spark_prune (one float32 multiply); order: w descending, equal w lower channel first
+ *   count(n,h) = the smallest m >= 1 whose m most salient channels hold at least p of the row's saliency
+ *   kept, mask, mu (mean of w over the 128 - count pruned channels, 0 if none) as in spark_prune
+ * The count is an integer decided by sums, so the decision is taken in integers, which any summation order
+ * reproduces: every w of a row is expressed in units of the last place of the row's largest saliency, rounded
+ * down (q < 2^24), p is given in basis points, and count = the smallest m >= 1 with
+ *   10000 * (sum of the m largest q)  >=  p_basis_points * (sum of all q).
+ * An all-zero row keeps one channel (channel 0).
+ *
+ *   p_basis_points  1 .. 10000 (9900 = the paper's 99 %)
+ *   packed_out      spark_packed_topp_bytes(desc) bytes, 256-byte aligned: sized for the worst case (every row
+ *                   keeps all 128 channels); rows are 24 bytes (mask, mu, count) plus two bytes per kept entry
+ *                   in a value stream, and only the used part of the stream is written or ever read
+ * Uses batch, head counts, window, total_tokens and the k strides of `desc`; desc->keep is not used;
+ * bf16 storage only (SPARK_ERR_UNSUPPORTED for SPARK_PACK_INT8 or stats).  Other arguments as spark_prune.
+ */
+size_t spark_packed_topp_bytes(const spark_desc *desc);
+spark_status spark_prune_topp(const spark_desc *desc, const void *k_bf16, const void *qwin_bf16,
+                              const int32_t *cu_seqlens, int32_t p_basis_points, void *packed_out,
+                              void *hip_stream);
+
+/*
+ * One decode step over a cache written by spark_prune_topp: scores, softmax and output exactly as in
+ * spark_decode_attn (degenerate recovery mu / a for the pruned entries of every row), with every row walked to
+ * its own count.  Arguments, workspace and split count as spark_decode_attn.
+ */
+spark_status spark_decode_attn_topp(const spark_desc *desc, const void *q_bf16, const void *packed,
+                                    const void *v_bf16, const int32_t *cu_seqlens, void *out,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Canonical export of a top-p cache (parity tests and debugging).  Any output may be NULL.
+ *   mask_out   uint32 [total_tokens, n_kv_heads, 4]
+ *   count_out  int32  [total_tokens, n_kv_heads]        kept channels of the row
+ *   vals_out   uint16 [total_tokens, n_kv_heads, 128]   kept entries (bf16 bits), ascending channel, then zeros
+ *   mu_out     float  [total_tokens, n_kv_heads];   a_out float [batch, n_kv_heads, 128]
+ */
+spark_status spark_unpack_topp(const spark_desc *desc, const void *packed, uint32_t *mask_out,
+                               int32_t *count_out, void *vals_out, float *mu_out, float *a_out,
+                               void *hip_stream);
+
+/*
  * spark_decode_attn for callers that can neither allocate device memory nor hand over a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result
  * as spark_decode_attn, without the workspace: split partials and arrival counters live in an array of

@@ -23,7 +23,8 @@ EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspac
            "spark_prune", "spark_decode_attn", "spark_unpack", "spark_probe_read", "spark_status_string",
            "spark_packed_values_bytes", "spark_prune_values", "spark_unpack_values", "spark_decode_attn_values", "spark_decode_attn_tail",
            "spark_decode_attn_values_tail", "spark_decode_attn_sampled", "spark_unpack_stats", "spark_check_packed",
-           "spark_decode_attn_static"]
+           "spark_decode_attn_static", "spark_packed_topp_bytes", "spark_prune_topp", "spark_decode_attn_topp",
+           "spark_unpack_topp"]
 
 
 class SparkError(RuntimeError):
@@ -97,6 +98,14 @@ def load() -> ctypes.CDLL:
     lib.spark_unpack_values.argtypes = [dp, vp, vp, vp, vp]
     lib.spark_decode_attn_static.restype = ctypes.c_int
     lib.spark_decode_attn_static.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+    lib.spark_packed_topp_bytes.restype = ctypes.c_size_t
+    lib.spark_packed_topp_bytes.argtypes = [dp]
+    lib.spark_prune_topp.restype = ctypes.c_int
+    lib.spark_prune_topp.argtypes = [dp, vp, vp, vp, ctypes.c_int32, vp, vp]
+    lib.spark_decode_attn_topp.restype = ctypes.c_int
+    lib.spark_decode_attn_topp.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.spark_unpack_topp.restype = ctypes.c_int
+    lib.spark_unpack_topp.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp]
     lib.spark_check_packed.restype = ctypes.c_int
     lib.spark_check_packed.argtypes = [dp, vp, ctypes.c_int32, vp]
     lib.spark_probe_read.restype = ctypes.c_int
@@ -170,6 +179,31 @@ def decode_attn_static(desc: SparkDesc, q: torch.Tensor, packed: torch.Tensor, v
     rc = load().spark_decode_attn_static(ctypes.byref(desc), _ptr(q), _ptr(packed), _ptr(v), _ptr(cu), _ptr(out),
                                          _stream())
     _check(rc, "spark_decode_attn_static")
+
+
+def packed_topp_bytes(desc: SparkDesc) -> int:
+    return int(load().spark_packed_topp_bytes(ctypes.byref(desc)))
+
+
+def prune_topp(desc: SparkDesc, k: torch.Tensor, qwin: torch.Tensor, cu: torch.Tensor, p_basis_points: int,
+               packed: torch.Tensor) -> None:
+    """spark_prune_topp: the variant that keeps, per row, the fewest channels holding p of the row's saliency."""
+    rc = load().spark_prune_topp(ctypes.byref(desc), _ptr(k), _ptr(qwin), _ptr(cu), int(p_basis_points), _ptr(packed),
+                                 _stream())
+    _check(rc, "spark_prune_topp")
+
+
+def decode_attn_topp(desc: SparkDesc, q: torch.Tensor, packed: torch.Tensor, v: torch.Tensor, cu: torch.Tensor,
+                     out: torch.Tensor, workspace: torch.Tensor) -> None:
+    rc = load().spark_decode_attn_topp(ctypes.byref(desc), _ptr(q), _ptr(packed), _ptr(v), _ptr(cu), _ptr(out),
+                                       _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "spark_decode_attn_topp")
+
+
+def unpack_topp(desc: SparkDesc, packed: torch.Tensor, mask=None, count=None, vals=None, mu=None, a=None) -> None:
+    rc = load().spark_unpack_topp(ctypes.byref(desc), _ptr(packed), _ptr(mask), _ptr(count), _ptr(vals), _ptr(mu),
+                                  _ptr(a), _stream())
+    _check(rc, "spark_unpack_topp")
 
 
 def packed_values_bytes(desc: SparkDesc) -> int:

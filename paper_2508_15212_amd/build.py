@@ -14,7 +14,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspark_hip.so")
-SOURCES = ["spark_api.hip", "spark_bench.hip", "spark_prune.hip", "spark_decode.hip", "spark_decode_g1.hip", "spark_decode_g2.hip",
+SOURCES = ["spark_api.hip", "spark_bench.hip", "spark_prune.hip", "spark_topp.hip", "spark_decode.hip", "spark_decode_g1.hip", "spark_decode_g2.hip",
            "spark_decode_g4.hip", "spark_decode_g8.hip", "spark_decode_g16.hip"]
 # packed-FP32 instructions are switched off for every device function of this library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

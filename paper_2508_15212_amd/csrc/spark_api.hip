@@ -43,6 +43,11 @@ SparkLayout layout_of(const spark_desc *d)
                              d->stats);
 }
 
+SparkLayout topp_layout_of(const spark_desc *d)
+{
+    return spark_make_topp_layout(d->batch, d->n_kv_heads, d->total_tokens);
+}
+
 SparkLayout values_layout_of(const spark_desc *d)
 {
     return spark_make_values_layout(d->keep_v, d->n_kv_heads, d->total_tokens);
@@ -230,7 +235,7 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
                            const void *packed_v, const int32_t *cu_seqlens, void *out, void *workspace,
                            size_t workspace_bytes, void *hip_stream, const void *tail_k = nullptr,
                            const void *tail_v = nullptr, const int32_t *tail_len = nullptr, int rec = 0,
-                           uint64_t seed = 0)
+                           uint64_t seed = 0, bool topp = false)
 {
     spark_status why;
     if (!desc_ok(desc, &why)) return why;
@@ -251,7 +256,7 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
         if (!aligned(tail_k, 16) || !aligned(tail_v, 16) || !aligned(tail_len, 4)) return SPARK_ERR_INVALID_ARG;
     }
     if (workspace_bytes < spark_decode_workspace(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
-    const SparkLayout L = layout_of(desc);
+    const SparkLayout L = topp ? topp_layout_of(desc) : layout_of(desc);
     SparkLayout Lv = L;
     if (packed_v) Lv = values_layout_of(desc);
     const spark::DecodePlan plan = plan_of(desc);
@@ -363,6 +368,57 @@ spark_status spark_check_packed(const spark_desc *desc, const void *packed, int3
     for (int i = 0; i < 9; ++i)
         if (hdr[i] != want[i]) return SPARK_ERR_MISMATCH;
     return SPARK_OK;
+}
+
+// ---------------------------------------------------------------- the top-p variant
+
+size_t spark_packed_topp_bytes(const spark_desc *desc)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return 0;
+    return (size_t)topp_layout_of(desc).total_bytes;
+}
+
+spark_status spark_prune_topp(const spark_desc *desc, const void *k_bf16, const void *qwin_bf16,
+                              const int32_t *cu_seqlens, int32_t p_basis_points, void *packed_out, void *hip_stream)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!k_bf16 || !qwin_bf16 || !cu_seqlens || !packed_out) return SPARK_ERR_INVALID_ARG;
+    if (desc->window < 1 || p_basis_points < 1 || p_basis_points > 10000) return SPARK_ERR_INVALID_ARG;
+    if (!strides_ok(desc->k_token_stride, desc->k_head_stride)) return SPARK_ERR_INVALID_ARG;
+    if (desc->pack_dtype != SPARK_PACK_BF16 || desc->stats) return SPARK_ERR_UNSUPPORTED;
+    if (!aligned(k_bf16, 16) || !aligned(qwin_bf16, 2) || !aligned(packed_out, 256)) return SPARK_ERR_INVALID_ARG;
+    const SparkLayout L = topp_layout_of(desc);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = spark::launch_window_stat(static_cast<const uint16_t *>(qwin_bf16), static_cast<uint8_t *>(packed_out), L,
+                                             desc->n_q_heads, desc->window, st);
+    if (e == hipSuccess)
+        e = spark::launch_prune_topp(static_cast<const uint16_t *>(k_bf16), desc->k_token_stride, desc->k_head_stride,
+                                     cu_seqlens, static_cast<uint8_t *>(packed_out), L, p_basis_points, st);
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
+}
+
+spark_status spark_decode_attn_topp(const spark_desc *desc, const void *q_bf16, const void *packed, const void *v_bf16,
+                                    const int32_t *cu_seqlens, void *out, void *workspace, size_t workspace_bytes,
+                                    void *hip_stream)
+{
+    if (!v_bf16) return SPARK_ERR_INVALID_ARG;
+    if (desc && (desc->pack_dtype != SPARK_PACK_BF16 || desc->stats)) return SPARK_ERR_UNSUPPORTED;
+    return decode_common(desc, q_bf16, packed, v_bf16, nullptr, cu_seqlens, out, workspace, workspace_bytes, hip_stream,
+                         nullptr, nullptr, nullptr, 0, 0, true);
+}
+
+spark_status spark_unpack_topp(const spark_desc *desc, const void *packed, uint32_t *mask_out, int32_t *count_out,
+                               void *vals_out, float *mu_out, float *a_out, void *hip_stream)
+{
+    spark_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!packed) return SPARK_ERR_INVALID_ARG;
+    const hipError_t e = spark::launch_unpack_topp(static_cast<const uint8_t *>(packed), topp_layout_of(desc), mask_out,
+                                                   count_out, static_cast<uint16_t *>(vals_out), mu_out, a_out,
+                                                   static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
 }
 
 // ---------------------------------------------------------------- decode without a caller-provided workspace

@@ -302,9 +302,13 @@ constexpr int decode_min_blocks(int, int) { return 2; }
 // REC: 0 = degenerate recovery (mu / a, folded into the score sum); 1 / 2 = Gaussian / Exponential recovery:
 // a saliency is drawn for every pruned entry from the row's all-channel statistics with a counter-based
 // generator keyed by (seed, token, head, channel), so the run can be repeated and checked.
-template <int G, int TCT, int INT8, int TVC, int REC = 0>
+// VAR: rows keep a per-row number of channels (the top-p variant, Sec. "Adaptive Variants of SparK"): the row's
+// count sits in its sixth word and the kept entries in the head's value stream, located through the tile
+// directory and a wave prefix sum of the lower tokens' lengths.
+template <int G, int TCT, int INT8, int TVC, int REC = 0, int VAR = 0>
 __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void spark_decode_kernel(DecodeParams P)
 {
+    static_assert(!VAR || (TCT == 0 && INT8 == 0 && TVC == 0 && REC == 0), "variable-length rows: any-length bf16 path only");
     constexpr bool PV = (TVC != 0);             // packed value cache
     constexpr int NVW = PV ? (TVC > 0 ? (((4 + (TVC + 1) / 2) + 1) & ~1) : 4) : 1;   // value-row words in registers
     // LDS row stride (words) of a parked value row: >= the row, and = 4 mod 8 so that 16-byte row writes of
@@ -587,6 +591,31 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
 #pragma unroll
                             for (int g = 0; g < G; ++g) s[g] = fmaf(ev[u][g], d, s[g]);
                         }
+                }
+            } else if constexpr (VAR) {
+                // this row's kept entries: words [before, before + (count + 1) / 2) of the tile's part of the stream
+                const uint32_t cnt = r[5] < (uint32_t)SPARK_D ? r[5] : (uint32_t)SPARK_D;     // (bounds the walk whatever the cache holds)
+                const uint32_t words = (cnt + 1u) >> 1;
+                const uint32_t before = (uint32_t)wave_inclusive_sum_i32((int)words) - words;
+                const uint32_t *vsrc = reinterpret_cast<const uint32_t *>(P.packed + L.off_vals) + (int64_t)h * L.vals_head_words +
+                                       reinterpret_cast<const uint32_t *>(P.packed + L.off_dir)[(int64_t)h * (L.n_tiles + 1) + tile] + before;
+                int tmax = (int)cnt;
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) { const int y = __shfl_xor(tmax, o); tmax = tmax > y ? tmax : y; }
+                tmax = __builtin_amdgcn_readfirstlane(tmax);
+                for (int i = 0; i < tmax; ++i) {
+                    const bool on = (uint32_t)i < cnt;            // lanes whose row is shorter idle through the rest
+                    if ((i & 1) == 0) vw = on ? vsrc[i >> 1] : 0u;
+                    // (as next_channel, but defined when the row's bits have run out: an idle lane reads some entry)
+                    const bool sw = (i == clo);
+                    cur = sw ? upper : cur;
+                    jb = sw ? 64 : jb;
+                    const int j = (__builtin_ctzll((unsigned long long)cur | (1ull << 63)) + jb) & (SPARK_D - 1);
+                    cur &= cur - 1;
+                    const float *e = &qtab[j * GP];
+                    const float d = on ? fmaf(-mu, e[G], kept_value(i, vw)) : 0.0f;
+#pragma unroll
+                    for (int g = 0; g < G; ++g) s[g] = fmaf(e[g], d, s[g]);
                 }
             } else {
                 for (int i = 0; i < T; ++i) {
@@ -907,10 +936,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
 
 // ---------------------------------------------------------------- host-side launch
 
-template <int G, int TCT, int INT8, int TVC, int REC = 0>
+template <int G, int TCT, int INT8, int TVC, int REC = 0, int VAR = 0>
 static hipError_t launch_one(const DecodeParams &P, int nblocks, hipStream_t st)
 {
-    hipLaunchKernelGGL((spark_decode_kernel<G, TCT, INT8, TVC, REC>), dim3(nblocks), dim3(kDecodeWaves * 64), 0, st, P);
+    hipLaunchKernelGGL((spark_decode_kernel<G, TCT, INT8, TVC, REC, VAR>), dim3(nblocks), dim3(kDecodeWaves * 64), 0, st, P);
     return hipGetLastError();
 }
 
@@ -933,6 +962,7 @@ hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
 {
     // rows that carry the all-channel statistics are longer: only the any-length instantiations read them
     const int T = P.L.stats ? -1 : P.L.T;
+    if (P.L.topp) return launch_one<G, 0, 0, 0, 0, 1>(P, nblocks, st);
     if (P.rec == 1) return launch_one<G, 0, 0, 0, 1>(P, nblocks, st);
     if (P.rec == 2) return launch_one<G, 0, 0, 0, 2>(P, nblocks, st);
     if (P.packed_v) {

@@ -41,4 +41,13 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
 
 hipError_t launch_zero_counters(uint32_t *counters, int n, hipStream_t st);
 
+// channel weights a, 1/a (and the key cache's header) alone
+hipError_t launch_window_stat(const uint16_t *qwin, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st);
+
+// top-p variant (L from spark_make_topp_layout; the channel weights must have been written before)
+hipError_t launch_prune_topp(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const int32_t *cu,
+                             uint8_t *packed, const SparkLayout &L, int p_bp, hipStream_t st);
+hipError_t launch_unpack_topp(const uint8_t *packed, const SparkLayout &L, uint32_t *mask_out, int32_t *count_out,
+                              uint16_t *vals_out, float *mu_out, float *a_out, hipStream_t st);
+
 }  // namespace spark

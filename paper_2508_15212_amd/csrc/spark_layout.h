@@ -8,6 +8,7 @@
 //   int8 storage : [ m0 m1 m2 m3 | mu | scale | c0 ... c(nv-1) | pad ]   nv = ceil(T/4)
 //   value cache  : [ m0 m1 m2 m3 | v0 v1 ... v(nv-1) | pad ]        (pruned entries are dropped: no statistic)
 //   bf16 + stats : [ m0 m1 m2 m3 | mu | mu_all | sigma_all | v0 ... v(nv-1) | pad ]   (for the sampled recovery functions)
+//   top-p rows   : [ m0 m1 m2 m3 | mu | count ]        the kept entries live in a value stream, see below
 //
 // m0..m3 is the 128-bit channel mask (bit j%32 of word j/32 = channel j kept), mu the
 // mean saliency of the pruned channels, v* the kept entries in ascending channel order
@@ -22,6 +23,14 @@
 //
 // with nq = ndw/4 full 16-byte sections.  Tiles are ordered [KV head][tile index]; the
 // tile index of global token n is n/64, so a tile may straddle two sequences.
+//
+// The top-p variant keeps a different number of channels in every row.  Its tiles hold only the fixed part of
+// the rows (24 bytes: mask, mu, count); the kept entries of a KV head form one VALUE STREAM of 32-bit words:
+// tile by tile, inside a tile token by token, every row rounded up to a whole word (two bf16 per word, the
+// lower channel in the low half, an unused upper half 0).  A DIRECTORY uint32 [Hkv][n_tiles + 1] gives the
+// word offset of every tile in its head's stream (an exclusive prefix sum; the last entry is the head's
+// length).  The stream is sized for the worst case (every row keeps all 128 channels); only its used part
+// is ever read.
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
@@ -54,6 +63,12 @@ struct SparkLayout {
     int64_t off_inva;     // float [batch][Hkv][128]   1/a, 0 where a == 0
     int64_t off_tiles;    // tiles [Hkv][n_tiles]
     int64_t total_bytes;
+    // top-p variant only
+    int32_t topp;         // 1 = rows keep a per-row number of channels (values in the stream)
+    int32_t pad_;
+    int64_t off_dir;      // uint32 [Hkv][n_tiles + 1]
+    int64_t off_vals;     // value streams [Hkv][vals_head_words] 32-bit words
+    int64_t vals_head_words;   // capacity of one head's stream: n_tiles * 64 rows * 64 words
 };
 
 static inline SPARK_HD SparkLayout spark_make_layout(int T, int int8, int batch, int n_kv_heads,
@@ -81,6 +96,30 @@ static inline SPARK_HD SparkLayout spark_make_layout(int T, int int8, int batch,
     L.off_inva = L.off_a + apad;
     L.off_tiles = L.off_inva + apad;
     L.total_bytes = L.off_tiles + (int64_t)n_kv_heads * L.n_tiles * L.tile_bytes;
+    L.topp = 0;
+    L.pad_ = 0;
+    L.off_dir = L.off_vals = L.vals_head_words = 0;
+    return L;
+}
+
+// Top-p cache: rows [ m0 m1 m2 m3 | mu | count ] in the tiles, then the directory and the value streams.
+static inline SPARK_HD SparkLayout spark_make_topp_layout(int batch, int n_kv_heads, int64_t total_tokens)
+{
+    SparkLayout L = spark_make_layout(SPARK_D, 0, batch, n_kv_heads, total_tokens);
+    L.topp = 1;
+    L.T = 0;              // no fixed count
+    L.nv = 0;
+    L.val0 = 6;
+    L.ndw = 6;
+    L.nq = 1;
+    L.tail2 = 1;
+    L.tile_bytes = SPARK_TILE_TOKENS * 4 * L.ndw;
+    const int64_t tiles_end = L.off_tiles + (int64_t)n_kv_heads * L.n_tiles * L.tile_bytes;
+    L.off_dir = (tiles_end + 255) & ~(int64_t)255;
+    const int64_t dir_bytes = (int64_t)n_kv_heads * (L.n_tiles + 1) * 4;
+    L.off_vals = (L.off_dir + dir_bytes + 255) & ~(int64_t)255;
+    L.vals_head_words = L.n_tiles * SPARK_TILE_TOKENS * (SPARK_D / 2);
+    L.total_bytes = L.off_vals + (int64_t)n_kv_heads * L.vals_head_words * 4;
     return L;
 }
 

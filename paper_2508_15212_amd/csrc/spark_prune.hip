@@ -23,10 +23,9 @@
 
 #include "spark_kernels.h"
 #include "spark_layout.h"
+#include "spark_wave.h"
 
 namespace spark {
-
-__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
 // ---------------------------------------------------------------- window statistic
 
@@ -150,36 +149,6 @@ __host__ inline size_t spark_prune_lds_bytes(const SparkLayout &L)
            ((size_t)spark_prune_rows_per_flush(L) * spark_stage_words(L) * 4 + kHistWords * 4);
 }
 
-// bits 0..15 of x spread to the even bit positions of a 32-bit word
-__device__ __forceinline__ uint32_t spread16(uint32_t x)
-{
-    x &= 0xFFFFu;
-    x = (x | (x << 8)) & 0x00FF00FFu;
-    x = (x | (x << 4)) & 0x0F0F0F0Fu;
-    x = (x | (x << 2)) & 0x33333333u;
-    x = (x | (x << 1)) & 0x55555555u;
-    return x;
-}
-
-__device__ __forceinline__ int mbcnt64(uint64_t m)   // set bits of m below this lane
-{
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
-}
-
-// Inclusive prefix sum over the 64 lanes (lane l gets x_0 + ... + x_l) with data-parallel-primitive
-// moves: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of row 0 / 2 is added
-// to row 1 / 3 and the last lane of row 1 to rows 2 and 3.  Lanes with no source add 0.
-__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
-{
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);   // row_shr 1
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);   // row_shr 2
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);   // row_shr 4
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);   // row_shr 8
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);   // row_bcast 15 -> rows 1, 3
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);   // row_bcast 31 -> rows 2, 3
-    return v;
-}
-
 // One searched row goes to its staging place.  kb0 / kb1: wave masks of the lanes whose first / second value is
 // kept; pos0: number of kept values in front of this lane's first one; row_a: LDS byte address of the row's
 // first value slot (wave-uniform).  The lane's kept values are stored to their slots (16 bits each), and the
@@ -253,39 +222,6 @@ __device__ __forceinline__ float fold_pair(float A, float B, bool hi)
 {
     const float stay = hi ? B : A, go = hi ? A : B;
     return stay + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(go), CTRL, 0xF, 0xF, true));
-}
-
-// Sum over the 64 lanes, returned wave-uniform (same moves as the prefix sum; lane 63 ends with the total).
-__device__ __forceinline__ float wave_total_f32(float v)
-{
-    auto step = [&](auto ctrl, auto rmask) {
-        v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value,
-                                                        decltype(rmask)::value, 0xF, false));
-    };
-    step(std::integral_constant<int, 0x111>{}, std::integral_constant<int, 0xF>{});
-    step(std::integral_constant<int, 0x112>{}, std::integral_constant<int, 0xF>{});
-    step(std::integral_constant<int, 0x114>{}, std::integral_constant<int, 0xF>{});
-    step(std::integral_constant<int, 0x118>{}, std::integral_constant<int, 0xF>{});
-    step(std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xA>{});
-    step(std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xC>{});
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
-}
-
-// One wave-uniform value into lane `lane_id` of a register.
-__device__ __forceinline__ void write_lane1(uint32_t &a, uint32_t va, int lane_id)
-{
-    asm("s_mov_b32 m0, %2\n\t"
-        "v_writelane_b32 %0, %1, m0"
-        : "+v"(a)
-        : "s"(va), "s"(lane_id)
-        : "m0");
-}
-
-__device__ __forceinline__ void prune_lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // FULL: the launch covers the tiles that hold all 64 tokens (the first total_tokens / 64 of every head);
@@ -836,13 +772,18 @@ hipError_t launch_tiles(const uint16_t *x, int64_t tok_stride, int64_t head_stri
 
 }  // namespace
 
-hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
-                        const int32_t *cu, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st)
+hipError_t launch_window_stat(const uint16_t *qwin, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st)
 {
     hipLaunchKernelGGL(spark_window_stat_kernel, dim3(L.batch * L.n_kv_heads),
                        dim3(((Hq / L.n_kv_heads) < 8 ? (Hq / L.n_kv_heads) : 8) * SPARK_D), 0, st, qwin, Hq,
                        L.n_kv_heads, W, packed, L);
-    hipError_t e = hipGetLastError();
+    return hipGetLastError();
+}
+
+hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
+                        const int32_t *cu, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st)
+{
+    const hipError_t e = launch_window_stat(qwin, packed, L, Hq, W, st);
     if (e != hipSuccess) return e;
     return launch_tiles<false>(k, k_tok_stride, k_head_stride, cu, packed, L, st);
 }

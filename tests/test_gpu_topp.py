@@ -1,0 +1,106 @@
+"""GPU parity for the top-p variant (per row, the fewest channels that hold p of the row's saliency): per-row
+counts, masks and kept entries bit-exact against the CPU oracle (both sides decide the count in the same integer
+arithmetic), mu to 1e-5 relative, decode output within the decode tolerance; small ragged shapes, the special
+rows (one dominant channel, equal saliencies, zero rows, ties at the cut) and the 32K benchmark shape."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_2508_15212_amd as spark
+from tests.gpu_util import make_desc, to_dev
+
+pytestmark = pytest.mark.gpu
+MAX_ABS, MEAN_ABS = 1e-2, 1e-3
+
+
+def _run(w, t, p_bp=9900, layout="HND", decode=True, n_splits=0):
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune_topp(t.k, t.layout, a32, t.cu, p_bp)
+    k, v = t.k, t.v
+    if layout == "NHD":
+        k = np.ascontiguousarray(k.transpose(1, 0, 2))
+        v = np.ascontiguousarray(v.transpose(1, 0, 2))
+    desc = make_desc(w, layout, n_splits=n_splits)
+    dk, dv, dq = to_dev(k), to_dev(v), to_dev(t.q)
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.zeros(max(spark.packed_topp_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    spark.prune_topp(desc, dk, to_dev(t.qwin), dcu, p_bp, packed)
+    total, hkv, D = w.total, w.n_kv_heads, w.head_dim
+    mask = torch.empty((total, hkv, 4), dtype=torch.int32, device="cuda")
+    count = torch.empty((total, hkv), dtype=torch.int32, device="cuda")
+    vals = torch.empty((total, hkv, D), dtype=torch.int16, device="cuda")
+    mu = torch.empty((total, hkv), dtype=torch.float32, device="cuda")
+    a = torch.empty((w.batch, hkv, D), dtype=torch.float32, device="cuda")
+    spark.unpack_topp(desc, packed, mask, count, vals, mu, a)
+    torch.cuda.synchronize()
+    cnt = count.cpu().numpy()
+    print(f"{w.name}: rows={total * hkv} p={p_bp / 100:.2f}% kept per row: mean {cnt.mean():.1f} min {cnt.min()} max {cnt.max()}")
+    assert np.array_equal(a.cpu().numpy(), a32)
+    assert np.array_equal(cnt, pr.count), "per-row counts differ"
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), pr.mask), "kept-channel sets differ"
+    assert np.array_equal(vals.cpu().numpy().view(np.uint16), pr.kept), "kept entries differ"
+    assert np.allclose(mu.cpu().numpy(), pr.mu32, rtol=1e-5, atol=1e-30)
+    if decode:
+        out = torch.empty((w.batch, w.n_q_heads, D), dtype=torch.float32, device="cuda")
+        spark.decode_attn_topp(desc, dq, packed, dv, dcu, out, spark.new_decode_workspace(desc))
+        ref = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
+        err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+        print(f"   decode max|err|={err.max():.3e} mean|err|={err.mean():.3e}")
+        assert np.all(np.isfinite(out.cpu().numpy()))
+        assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+    return pr
+
+
+@pytest.mark.parametrize("p_bp", [9900, 9000, 5000, 10000, 1])
+def test_small_ragged(p_bp):
+    w = wl.small(name=f"topp{p_bp}", seqlens=(200, 77), seed=300 + p_bp % 97)
+    _run(w, wl.generate(w), p_bp)
+
+
+@pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 2), (4, 2), (8, 1), (16, 1)])
+def test_group_sizes(G, Hkv):
+    w = wl.small(name=f"toppG{G}", n_q_heads=G * Hkv, n_kv_heads=Hkv, seqlens=(130, 321), seed=310 + G)
+    _run(w, wl.generate(w))
+
+
+def test_token_major_layout_and_split_counts():
+    w = wl.small(name="toppNHD", seqlens=(700, 64, 1), seed=321, batch=3)
+    t = wl.generate(w)
+    _run(w, t, layout="NHD")
+    for ns in (1, 3, 7):
+        _run(w, t, n_splits=ns)
+
+
+def test_empty_and_single_token_sequences():
+    w = wl.small(name="toppempty", batch=5, seqlens=(0, 1, 130, 0, 64), seed=322)
+    _run(w, wl.generate(w))
+
+
+def test_special_rows():
+    """One dominant channel, equal saliencies (ties at the cut: lowest channels win), zero rows, heavy outliers."""
+    w = wl.small(name="toppspecial", batch=1, n_q_heads=4, n_kv_heads=1, seqlens=(192,), seed=323)
+    t = wl.generate(w)
+    k = wl.bf16_bits_to_f32(t.k).copy()            # [1, 192, 128]
+    k[0, 0] = 1.0
+    k[0, 0, 17] = 32768.0                          # dominant
+    k[0, 1] = 3.0                                  # all equal (given equal channel weights below)
+    k[0, 2] = 0.0                                  # zero row
+    k[0, 3] = 0.0
+    k[0, 3, 100] = -2.0                            # a single non-zero entry
+    k[0, 4, :64] = 1.0                             # two plateaus: ties inside the cut
+    k[0, 4, 64:] = 0.5
+    k[0, 5] *= 1e-30                               # tiny row
+    k[0, 6] *= 1e30                                # huge row
+    t.k = wl.f32_to_bf16_bits(k)
+    t.qwin = wl.f32_to_bf16_bits(np.ones(t.qwin.shape, np.float32))      # a = 1 everywhere
+    pr = _run(w, t)
+    assert pr.count[0, 0] == 1 and pr.count[1, 0] == 127 and pr.count[2, 0] == 1 and pr.count[3, 0] == 1
+    _run(w, t, p_bp=10000)
+
+
+def test_config2_size():
+    """The 32K benchmark shape (2.1 M rows): every count, mask and kept entry checked, decode checked."""
+    w = wl.config(2)
+    _run(w, wl.generate(w))
