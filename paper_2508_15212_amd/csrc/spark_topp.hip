@@ -239,39 +239,50 @@ __global__ __launch_bounds__(256) void spark_topp_scan_kernel(uint8_t *__restric
     }
 }
 
-// One wavefront per tile, lane = token.
+// One wavefront per tile.  Lane = token reads the fixed parts (mask, count) and numbers the rows' places in the
+// stream (a wave prefix sum of their lengths); then token by token the wavefront reads the dense key row as
+// spark_topp_select_kernel did (lane l = channels 2l, 2l+1) and every lane stores its kept entries at the slots
+// the mask gives them, so loads and stores both run over contiguous bytes.
 __global__ __launch_bounds__(kWaves * 64) void spark_topp_pack_kernel(const uint16_t *__restrict__ k, int64_t k_tok_stride,
                                                                       int64_t k_head_stride, uint8_t *__restrict__ packed,
                                                                       SparkLayout L)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t wt = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    const int64_t wt = (int64_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wt >= L.n_tiles * L.n_kv_heads) return;
     const int h = (int)(wt / L.n_tiles);
     const int64_t tile = wt % L.n_tiles;
-    const int64_t n = tile * SPARK_TILE_TOKENS + lane;
+    const int64_t n0 = tile * SPARK_TILE_TOKENS;
+    const int64_t left = L.total_tokens - n0;
+    const int nvalid = left < SPARK_TILE_TOKENS ? (int)left : SPARK_TILE_TOKENS;
     const uint8_t *tp = packed + L.off_tiles + ((int64_t)h * L.n_tiles + tile) * L.tile_bytes;
     const uint4 mk = *reinterpret_cast<const uint4 *>(tp + lane * 16);
     const uint32_t cnt = *reinterpret_cast<const uint32_t *>(tp + 1024 + lane * 8 + 4);
     const uint32_t words = (cnt + 1u) / 2u;
     const uint32_t before = wave_inclusive_sum(words) - words;       // words of the lower tokens of this tile
     const uint32_t base = reinterpret_cast<const uint32_t *>(packed + L.off_dir)[(int64_t)h * (L.n_tiles + 1) + tile];
-    uint32_t *dst = reinterpret_cast<uint32_t *>(packed + L.off_vals) + (int64_t)h * L.vals_head_words + base + before;
-    if (cnt == 0) return;      // (rows past the last token)
-    const uint16_t *krow = k + n * k_tok_stride + (int64_t)h * k_head_stride;
-    uint64_t cur = ((uint64_t)mk.y << 32) | mk.x;
-    const uint64_t upper = ((uint64_t)mk.w << 32) | mk.z;
-    int jb = 0;
-    auto next_value = [&]() -> uint32_t {
-        if (cur == 0ull) { cur = upper; jb = 64; }
-        const int j = (__builtin_ctzll(cur | (1ull << 63)) + jb) & (SPARK_D - 1);
-        cur &= cur - 1;
-        return (uint32_t)krow[j];
-    };
-    for (uint32_t i = 0; i < cnt; i += 2) {
-        const uint32_t lo = next_value();
-        const uint32_t hi = (i + 1 < cnt) ? next_value() : 0u;
-        dst[i >> 1] = lo | (hi << 16);
+    uint16_t *dst_tile = reinterpret_cast<uint16_t *>(reinterpret_cast<uint32_t *>(packed + L.off_vals) +
+                                                     (int64_t)h * L.vals_head_words + base);
+    const uint16_t *kbase = k + n0 * k_tok_stride + (int64_t)h * k_head_stride + 2 * lane;
+    // this lane's two channels are bits 2l, 2l+1 of the 128-bit mask: bits sh, sh+1 of its lower or upper half
+    const int sh = (2 * lane) & 63;
+    const uint64_t below = (1ull << sh) - 1ull;
+    uint32_t xnext = *reinterpret_cast<const uint32_t *>(kbase);
+    for (int t = 0; t < nvalid; ++t) {
+        const uint32_t xx = xnext;
+        if (t + 1 < nvalid) xnext = *reinterpret_cast<const uint32_t *>(kbase + (int64_t)(t + 1) * k_tok_stride);
+        const uint64_t lo = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mk.y, t) << 32) |
+                            (uint32_t)__builtin_amdgcn_readlane((int)mk.x, t);
+        const uint64_t hi = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mk.w, t) << 32) |
+                            (uint32_t)__builtin_amdgcn_readlane((int)mk.z, t);
+        const uint32_t cnt_t = (uint32_t)__builtin_amdgcn_readlane((int)cnt, t);
+        uint16_t *dst = dst_tile + 2 * (size_t)(uint32_t)__builtin_amdgcn_readlane((int)before, t);
+        const uint64_t mine = lane < 32 ? lo : hi;
+        const uint32_t slot0 = (lane < 32 ? 0u : (uint32_t)__popcll(lo)) + (uint32_t)__popcll(mine & below);
+        const bool keep0 = (mine >> sh) & 1ull, keep1 = (mine >> (sh + 1)) & 1ull;
+        if (keep0) dst[slot0] = (uint16_t)xx;
+        if (keep1) dst[slot0 + (keep0 ? 1u : 0u)] = (uint16_t)(xx >> 16);
+        if (lane == 0 && (cnt_t & 1u)) dst[cnt_t] = 0;      // the unused half of the row's last word
     }
 }
 
