@@ -25,6 +25,12 @@
  *     for global token n in [0,total_tokens), likewise V.  Rows of K and V must be 16-byte
  *     aligned (strides multiples of 8, base pointers 16-byte aligned; checked); q and the window
  *     queries need 2-byte alignment only.
+ *   - Inputs are expected to be FINITE.  Infinities and NaNs in K, V, q or the window queries are not
+ *     detected.  Every loop in the library is bounded whatever the bits are, so a call with such input
+ *     completes without fault; but the mask, kept entries and statistic of a row that contains one (of
+ *     every row of a sequence whose window queries contain one) are unspecified, and so is every output
+ *     row computed from such a row (it may be NaN).  Rows and sequences without such entries are not
+ *     affected: sequences and KV heads are independent.
  *   - Sequences are ragged: cu_seqlens[b] .. cu_seqlens[b+1] are the global token indices
  *     of batch element b (int32 [batch+1], cu_seqlens[0] = 0, cu_seqlens[batch] =
  *     total_tokens).  Query head g reads KV head g / (n_q_heads / n_kv_heads).

@@ -875,7 +875,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     // and only then is the block's arrival counted.  That orders partials before the count
     // without a device-wide cache write-back.  atomicInc wraps at the number of arrivals - 1, which leaves the
     // counter at zero for the next call.
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have completed
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);   // this thread's stores have been acknowledged
     __syncthreads();
     if (tid == 0) {
         const uint32_t old = atomicInc(&P.counters[bh], (uint32_t)(nmerge - 1));

@@ -7,6 +7,12 @@
 
 namespace spark {
 
+// Immediate of s_waitcnt on gfx9-family parts: vmcnt in bits [3:0] and [15:14] (vector memory loads AND stores
+// of this wavefront still outstanding), expcnt in bits [6:4], lgkmcnt in bits [11:8] (LDS, scalar memory).  A
+// field left at its maximum does not wait.  This one waits for vmcnt == 0 only: every global load has returned
+// and every global store of the wavefront has been acknowledged by the memory system.
+constexpr int kWaitVmcnt0 = (0 << 0) | (0 << 14) | (7 << 4) | (15 << 8);      // = 0x0F70
+
 struct DecodeParams;
 
 // How the decode grid cuts sequences into blocks (chosen on the host from the description alone).

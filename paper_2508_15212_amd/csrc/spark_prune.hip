@@ -421,7 +421,7 @@ __global__ __launch_bounds__(kPruneWaves * 64, MODE == 2 ? 6 : 7) void spark_pru
                     a01 = a_all[((int64_t)b * L.n_kv_heads + h) * (SPARK_D / 2) + lane];
                     // finish this load here, inside the rare branch: otherwise the wait for it
                     // lands after the join and drains the prefetched K rows on every token
-                    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+                    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
                 }
             }
             key0[r] = __float_as_uint(__fmul_rn(a01.x, fabsf(__uint_as_float(xx << 16))));

@@ -135,3 +135,69 @@ def test_config2_with_128_appended_rows():
     err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
     print(f"{w.name} + appended rows {tl.tolist()}: decode max|err|={err.max():.3e} mean|err|={err.mean():.3e}")
     assert err.max() <= 1e-2 and err.mean() <= 1e-3
+
+
+@pytest.mark.parametrize("kind", [spark.RECOVER_GAUSSIAN, spark.RECOVER_EXPONENTIAL])
+def test_config2_sampled_recovery(kind):
+    """The sampled recovery functions at the 32K benchmark shape: statistics rows (mean and standard deviation of
+    every row's saliencies to 1e-5), masks bit-exact, decode against the oracle's draw of the same seed."""
+    import torch
+    from tests.gpu_util import make_desc, to_dev
+    w, t = _tensors(2)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    mu, sigma = oracle.row_stats(t.k, t.layout, a32, t.cu)
+    desc = make_desc(w)
+    desc.stats = 1
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.empty(spark.packed_bytes(desc), dtype=torch.uint8, device="cuda")
+    spark.prune(desc, to_dev(t.k), to_dev(t.qwin), dcu, packed)
+    mask = torch.empty((w.total, w.n_kv_heads, 4), dtype=torch.int32, device="cuda")
+    mua = torch.empty((w.total, w.n_kv_heads), dtype=torch.float32, device="cuda")
+    sg = torch.empty_like(mua)
+    spark.unpack(desc, packed, mask, None, None, None, None)
+    spark.unpack_stats(desc, packed, mua, sg)
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), pr.mask)
+    assert np.allclose(mua.cpu().numpy(), mu, rtol=1e-5, atol=1e-30)
+    assert np.allclose(sg.cpu().numpy(), sigma, rtol=1e-5, atol=1e-6 * np.abs(mu).max())
+    del mask, mua, sg
+    seed = 0x5EED00000000 + kind
+    ref = oracle.decode_sampled(kind, seed, t.q, pr, mu, sigma, t.v, t.layout, t.cu)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    spark.decode_attn_sampled(desc, to_dev(t.q), packed, to_dev(t.v), dcu, out, spark.new_decode_workspace(desc), kind, seed)
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    print(f"{w.name} sampled recovery {kind}: decode max|err|={err.max():.3e} mean|err|={err.mean():.3e}")
+    assert err.max() <= 1e-2 and err.mean() <= 1e-3
+
+
+def test_config2_decode_replayed_500_times_on_one_workspace():
+    """The split merge (partial states written with device-scope stores, counted at an arrival counter, folded by the
+    block that arrives last) replayed on ONE workspace: 500 launches rotating over four query sets, every output
+    compared bit for bit with the first output of the same query set; stops at the first mismatch."""
+    import torch
+    from tests.gpu_util import make_desc, to_dev
+    w, t = _tensors(2)
+    desc = make_desc(w, out_dtype=spark.OUT_F32)
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.empty(spark.packed_bytes(desc), dtype=torch.uint8, device="cuda")
+    spark.prune(desc, to_dev(t.k), to_dev(t.qwin), dcu, packed)
+    dv = to_dev(t.v)
+    rng = np.random.default_rng(9)
+    qs = [to_dev(t.q)] + [to_dev(wl.f32_to_bf16_bits(rng.standard_normal(t.q.shape).astype(np.float32))) for _ in range(3)]
+    ws = spark.new_decode_workspace(desc)
+    first = [None] * len(qs)
+    outs = [torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda") for _ in range(8)]
+    for i in range(500):
+        j = i % len(qs)
+        o = outs[i % len(outs)]
+        spark.decode_attn(desc, qs[j], packed, dv, dcu, o, ws)
+        if first[j] is None:
+            first[j] = o.clone()
+        elif i % 8 == 7 or i == 499:      # (check in groups so that launches really run back to back)
+            for back in range(min(8, i + 1)):
+                ii = i - back
+                assert torch.equal(outs[ii % len(outs)], first[ii % len(qs)]), f"replay {ii} differs from its first run"
+    torch.cuda.synchronize()
+    ref = oracle.decode_literal(t.q, oracle.prune(t.k, t.layout, oracle.window_stat(t.qwin, w.n_kv_heads)[2], t.cu, w.keep),
+                                t.v, t.layout, t.cu)
+    assert np.abs(first[0].cpu().numpy().astype(np.float64) - ref).max() <= 1e-2

@@ -261,3 +261,36 @@ def test_check_packed_tells_matching_from_foreign_caches():
     assert spark.check_packed(dv_desc, packed, True) == spark.ERR_MISMATCH
     dv_desc.keep_v = 38
     assert spark.check_packed(dv_desc, packed_v, True) == spark.ERR_MISMATCH
+
+
+def test_non_finite_entries_stay_inside_their_sequence_and_head():
+    """Inputs are expected to be finite; Inf / NaN entries are not detected.  The contract: the call completes, and
+    rows, sequences and KV heads that hold no such entry are not affected."""
+    w = wl.small(name="nonfinite", batch=4, n_q_heads=8, n_kv_heads=2, seqlens=(150, 260, 90, 200), seed=88)
+    t = wl.generate(w)
+    cu = np.asarray(t.cu)
+    inf, nan = np.uint16(0x7F80), np.uint16(0x7FC1)
+    # sequence 1, KV head 0: scattered Inf / -Inf / NaN key entries, one row full of NaN, one full of Inf
+    for n, j, bits in ((cu[1] + 3, 5, inf), (cu[1] + 3, 77, np.uint16(0xFF80)), (cu[1] + 64, 0, nan), (cu[1] + 65, 127, nan)):
+        t.k[0, n, j] = bits
+    t.k[0, cu[1] + 100, :] = nan
+    t.k[0, cu[1] + 101, :] = inf
+    # sequence 3: a NaN and an Inf among the window queries of q head 5 (KV head 1)
+    t.qwin[3, 5, 2, 10] = nan
+    t.qwin[3, 5, 3, 11] = inf
+    res = run_gpu_case(w, t, want_bf16=False)          # completes (every search loop is bounded)
+    a32, pr, ref = _oracle_all(w, t)
+    bad_rows = np.zeros((w.total, w.n_kv_heads), bool)
+    bad_rows[cu[1]:cu[2], 0] = ~np.isfinite(wl.bf16_bits_to_f32(t.k[0, cu[1]:cu[2]])).all(-1)
+    bad_rows[cu[3]:cu[4], 1] = True
+    good = ~bad_rows
+    assert np.array_equal(res["mask"][good], pr.mask[good]), "a clean row changed"
+    assert np.array_equal(res["vals"][good], pr.kept[good])
+    assert np.allclose(res["mu"][good], pr.mu32[good], rtol=1e-5, atol=1e-30)
+    G = w.n_q_heads // w.n_kv_heads
+    clean_out = np.ones((w.batch, w.n_q_heads), bool)
+    clean_out[1, 0:G] = False             # q heads of KV head 0 in sequence 1
+    clean_out[3, G:2 * G] = False         # q heads of KV head 1 in sequence 3
+    err = np.abs(res["out_f32"].astype(np.float64) - ref)[clean_out]
+    assert np.all(np.isfinite(res["out_f32"][clean_out]))
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
