@@ -269,8 +269,9 @@ spark_status spark_prune_values(const spark_desc *desc, const void *v_bf16, void
  *   out[b,g,:] = sum_n softmax_n(s[g,:])[n] * Vtilde[n,h,:],  Vtilde[n,h,j] = V[n,h,j] if kept_v else 0
  *
  * Arguments as spark_decode_attn, with `packed_v` (written by spark_prune_values with the same
- * n_kv_heads / keep_v / total_tokens) in place of the dense values; desc->pack_dtype must be
- * SPARK_PACK_BF16.  Workspace and split count are those of spark_decode_attn.
+ * n_kv_heads / keep_v / total_tokens) in place of the dense values; the kept key entries may be stored
+ * as bf16 or as int8 codes (desc->pack_dtype), the kept value entries are always bf16.  Workspace and split
+ * count are those of spark_decode_attn.
  */
 spark_status spark_decode_attn_values(const spark_desc *desc, const void *q_bf16, const void *packed,
                                       const void *packed_v, const int32_t *cu_seqlens, void *out,

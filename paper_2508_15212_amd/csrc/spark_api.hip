@@ -242,7 +242,6 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
     if (!q_bf16 || !packed || !cu_seqlens || !out || !workspace) return SPARK_ERR_INVALID_ARG;
     if (packed_v) {
         if (desc->keep_v < 1) return SPARK_ERR_INVALID_ARG;
-        if (desc->pack_dtype != SPARK_PACK_BF16) return SPARK_ERR_UNSUPPORTED;
         if (!aligned(packed_v, 256)) return SPARK_ERR_INVALID_ARG;
     } else {
         if (!v_bf16) return SPARK_ERR_INVALID_ARG;

@@ -944,14 +944,14 @@ static hipError_t launch_one(const DecodeParams &P, int nblocks, hipStream_t st)
 }
 
 // packed values: row lengths 64 / 38 / 26 with the row in registers, anything else generic
-template <int G, int TCT>
+template <int G, int TCT, int INT8 = 0>
 static hipError_t launch_pv(const DecodeParams &P, int nblocks, hipStream_t st)
 {
     switch (P.Lv.T) {
-        case 64: return launch_one<G, TCT, 0, 64>(P, nblocks, st);
-        case 38: return launch_one<G, TCT, 0, 38>(P, nblocks, st);
-        case 26: return launch_one<G, TCT, 0, 26>(P, nblocks, st);
-        default: return launch_one<G, TCT, 0, -1>(P, nblocks, st);
+        case 64: return launch_one<G, TCT, INT8, 64>(P, nblocks, st);
+        case 38: return launch_one<G, TCT, INT8, 38>(P, nblocks, st);
+        case 26: return launch_one<G, TCT, INT8, 26>(P, nblocks, st);
+        default: return launch_one<G, TCT, INT8, -1>(P, nblocks, st);
     }
 }
 
@@ -966,7 +966,7 @@ hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
     if (P.rec == 1) return launch_one<G, 0, 0, 0, 1>(P, nblocks, st);
     if (P.rec == 2) return launch_one<G, 0, 0, 0, 2>(P, nblocks, st);
     if (P.packed_v) {
-        if (P.L.int8) return hipErrorInvalidValue;   // (the host rejects this combination before it gets here)
+        if (P.L.int8) return T == 26 ? launch_pv<G, 26, 1>(P, nblocks, st) : launch_pv<G, 0, 1>(P, nblocks, st);
         if (T == 26) return launch_pv<G, 26>(P, nblocks, st);
         if (T == 64) return launch_pv<G, 64>(P, nblocks, st);
         return launch_pv<G, 0>(P, nblocks, st);

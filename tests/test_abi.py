@@ -127,8 +127,6 @@ def test_value_cache_and_tail_entry_points_check_their_arguments_on_the_host():
     assert lib.spark_prune_values(ctypes.byref(_desc(keep_v=64, v_token_stride=1 << 25)), A, A, None) == 2
     assert lib.spark_decode_attn_values(ctypes.byref(d), A, A, None, A, A, A, ok_ws, None) == 1
     assert lib.spark_decode_attn_values(ctypes.byref(_desc()), A, A, A, A, A, A, ok_ws, None) == 1
-    assert lib.spark_decode_attn_values(ctypes.byref(_desc(keep_v=64, pack_dtype=spark.PACK_INT8)), A, A, A, A, A, A,
-                                        ok_ws, None) == 2
     assert lib.spark_unpack_values(ctypes.byref(d), None, None, None, None) == 1
     # appended rows: capacity enters the workspace size (one spare slot per 256 rows)
     dt = _desc(tail_capacity=600)

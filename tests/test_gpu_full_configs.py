@@ -201,3 +201,29 @@ def test_config2_decode_replayed_500_times_on_one_workspace():
     ref = oracle.decode_literal(t.q, oracle.prune(t.k, t.layout, oracle.window_stat(t.qwin, w.n_kv_heads)[2], t.cu, w.keep),
                                 t.v, t.layout, t.cu)
     assert np.abs(first[0].cpu().numpy().astype(np.float64) - ref).max() <= 1e-2
+
+
+def test_config5_int8_keys_with_pruned_values_keep64():
+    """The Qwen-shaped workload with int8 key entries and the value cache pruned to 64 channels per row."""
+    import torch
+    from tests.gpu_util import make_desc, to_dev
+    w, t = _tensors(5)
+    Tv = 64
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.quant_int8(oracle.prune(t.k, t.layout, a32, t.cu, w.keep))
+    pv = oracle.prune_values(t.v, t.layout, Tv)
+    ref = oracle.decode_literal(t.q, pr, oracle.expand_values(pv), "NHD", t.cu)
+    desc = make_desc(w, pack=spark.PACK_INT8)
+    desc.keep_v = Tv
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.empty(spark.packed_bytes(desc), dtype=torch.uint8, device="cuda")
+    packed_v = torch.empty(spark.packed_values_bytes(desc), dtype=torch.uint8, device="cuda")
+    dv = to_dev(t.v)
+    spark.prune(desc, to_dev(t.k), to_dev(t.qwin), dcu, packed)
+    spark.prune_values(desc, dv, packed_v)
+    del dv
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    spark.decode_attn_values(desc, to_dev(t.q), packed, packed_v, dcu, out, spark.new_decode_workspace(desc))
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    print(f"{w.name} int8 keys + Tv={Tv}: decode max|err|={err.max():.3e} mean|err|={err.mean():.3e}")
+    assert err.max() <= 1e-2 and err.mean() <= 1e-3

@@ -14,7 +14,7 @@ from tests.gpu_util import make_desc, to_dev
 pytestmark = pytest.mark.gpu
 
 
-def _one_case(rng, idx):
+def _one_case(rng, idx, int8=False):
     G = int(rng.choice([1, 2, 4, 8, 16]))
     hkv = int(rng.integers(1, 4))
     batch = int(rng.integers(1, 6))
@@ -25,15 +25,19 @@ def _one_case(rng, idx):
     Tv = int(rng.choice([0, 0, 26, 38, 64, 90]))
     cap = int(rng.choice([0, 0, 3, 70, 300]))
     stats = int(rng.choice([0, 0, 1]))            # rows that also carry the all-channel mean / standard deviation
+    if int8:
+        stats = 0                                 # (statistics rows are bf16 storage only)
     rec = int(rng.choice([0, 1, 2])) if (stats and not Tv and not cap) else 0
     w = wl.small(name=f"sweep{idx}", batch=batch, n_q_heads=G * hkv, n_kv_heads=hkv, keep=T, seqlens=lens,
                  seed=1000 + idx)
     t = wl.generate(w)
     tag = (f"case {idx}: G={G} Hkv={hkv} lens={lens} T={T} {layout} splits={n_splits} Tv={Tv} cap={cap} "
-           f"stats={stats} rec={rec}")
+           f"stats={stats} rec={rec} int8={int(int8)}")
     print(tag, flush=True)
     _, _, a32 = oracle.window_stat(t.qwin, hkv)
     pr = oracle.prune(t.k, t.layout, a32, t.cu, T)
+    if int8:
+        pr = oracle.quant_int8(pr)
     v_for_oracle, v_layout = t.v, t.layout
     if Tv:
         pv = oracle.prune_values(t.v, t.layout, Tv)
@@ -53,7 +57,7 @@ def _one_case(rng, idx):
     if layout == "NHD":
         k = np.ascontiguousarray(k.transpose(1, 0, 2))
         v = np.ascontiguousarray(v.transpose(1, 0, 2))
-    desc = make_desc(w, layout, n_splits=n_splits)
+    desc = make_desc(w, layout, pack=spark.PACK_INT8 if int8 else spark.PACK_BF16, n_splits=n_splits)
     desc.keep_v, desc.tail_capacity, desc.stats = Tv, cap, stats
     if w.total == 0:                       # no rows: any valid stride
         desc.k_head_stride = desc.v_head_stride = desc.k_token_stride = desc.v_token_stride = 128
@@ -64,10 +68,13 @@ def _one_case(rng, idx):
     spark.prune(desc, dk, to_dev(t.qwin), dcu, packed)
     if w.total:
         mask = torch.empty((w.total, hkv, 4), dtype=torch.int32, device="cuda")
-        vals = torch.empty((w.total, hkv, T), dtype=torch.int16, device="cuda")
+        vals = torch.empty((w.total, hkv, T), dtype=torch.int8 if int8 else torch.int16, device="cuda")
         spark.unpack(desc, packed, mask, vals, None, None, None)
         assert np.array_equal(mask.cpu().numpy().view(np.uint32), pr.mask), tag
-        assert np.array_equal(vals.cpu().numpy().view(np.uint16), pr.kept), tag
+        if int8:
+            assert np.array_equal(vals.cpu().numpy(), pr.codes), tag
+        else:
+            assert np.array_equal(vals.cpu().numpy().view(np.uint16), pr.kept), tag
     ws = spark.new_decode_workspace(desc)
     out = torch.full((batch, G * hkv, 128), float("nan"), dtype=torch.float32, device="cuda")
     dq = to_dev(t.q)
@@ -100,3 +107,11 @@ def test_random_shapes_against_the_oracle():
     rng = np.random.default_rng(20250815)
     for idx in range(240):
         _one_case(rng, idx)
+
+
+def test_random_shapes_with_int8_key_storage():
+    """The same sweep with the kept key entries stored as int8 codes (also together with pruned values and with
+    appended rows)."""
+    rng = np.random.default_rng(20250816)
+    for idx in range(80):
+        _one_case(rng, 5000 + idx, int8=True)

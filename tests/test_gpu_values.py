@@ -57,11 +57,13 @@ def test_value_selection_layouts_ties_zero_rows(layout):
 MAX_ABS, MEAN_ABS = 1e-2, 1e-3
 
 
-def _decode_kv_case(w, Tv, t=None, n_splits=0, layout="HND"):
+def _decode_kv_case(w, Tv, t=None, n_splits=0, layout="HND", int8=False):
     """prune keys, prune values, decode over both packed caches; compare with the oracle."""
     t = wl.generate(w) if t is None else t
     _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
     pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    if int8:
+        pr = oracle.quant_int8(pr)
     pv = oracle.prune_values(t.v, t.layout, Tv)
     ref = oracle.decode_literal(t.q, pr, oracle.expand_values(pv), "NHD", t.cu)
 
@@ -69,6 +71,8 @@ def _decode_kv_case(w, Tv, t=None, n_splits=0, layout="HND"):
     desc, packed_v, mask_v, vals_v = _prune_values_gpu(w, t.v, Tv, layout)
     assert np.array_equal(mask_v, pv.mask) and np.array_equal(vals_v, pv.kept)
     desc.n_splits = n_splits
+    if int8:
+        desc.pack_dtype = spark.PACK_INT8
     dk, dqw, dq = to_dev(k), to_dev(t.qwin), to_dev(t.q)
     dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
     packed = torch.empty(max(spark.packed_bytes(desc), 256), dtype=torch.uint8, device="cuda")
@@ -117,3 +121,12 @@ def test_keep_all_values_equals_dense_value_decode():
     got, _ = _decode_kv_case(w, 128, t=t)
     dense = run_gpu_case(w, t, want_unpack=False, want_bf16=False)["out_f32"]
     assert np.abs(got - dense).max() < 1e-5
+
+
+@pytest.mark.parametrize("T,Tv", [(26, 64), (26, 26), (26, 100), (64, 64), (38, 38), (1, 5)])
+def test_int8_keys_with_pruned_values(T, Tv):
+    """Kept key entries stored as int8 codes with a per-row scale, kept value entries as bf16."""
+    _decode_kv_case(wl.small(name=f"kv_int8_{T}_{Tv}", keep=T, seqlens=(130, 321), seed=390 + T + Tv), Tv, int8=True)
+    if T == 26 and Tv == 64:
+        _decode_kv_case(wl.small(name="kv_int8_g8", n_q_heads=16, n_kv_heads=2, keep=26, seqlens=(257, 64), seed=399), 64,
+                        int8=True)
