@@ -224,24 +224,24 @@ __device__ __forceinline__ float fold_pair(float A, float B, bool hi)
     return stay + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(go), CTRL, 0xF, 0xF, true));
 }
 
-// FULL: the launch covers the tiles that hold all 64 tokens (the first total_tokens / 64 of every head);
-// otherwise it covers the one partly filled last tile of every head, one wavefront each.
+// One tile by one wavefront.  FULL: wavefront number wt (over tiles, then heads) of those that take the tiles which
+// hold all 64 tokens (the first total_tokens / 64 of every head); otherwise wt = the KV head whose partly filled
+// last tile this wavefront takes.  Two instantiations, so that the hot one carries no bounds logic.
 // MODE: 0 = bf16 kept entries, 1 = int8 codes + scale, 2 = bf16 plus the all-channel mean and standard
 // deviation of the row's saliencies (App. "Caching Pruned Channel Statistics", for the sampled recovery).
 // VALUES: the rows are value-cache rows (App. "Pruning Value Cache Channels"): the score of a channel is
 // |v| itself, there is no channel weight, no sequence bookkeeping and no statistic of the pruned set.
+#ifndef SPARK_PRUNE_MIN_WAVES
+#define SPARK_PRUNE_MIN_WAVES (MODE == 2 ? 6 : 7)
+#endif
 template <int MODE, bool FULL, bool VALUES>
-__global__ __launch_bounds__(kPruneWaves * 64, MODE == 2 ? 6 : 7) void spark_prune_kernel(
-    const uint16_t *__restrict__ k, int64_t k_tok_stride, int64_t k_head_stride,
-    const int32_t *__restrict__ cu, uint8_t *__restrict__ packed, SparkLayout L, int rows_per_flush)
+__device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64_t k_tok_stride, int64_t k_head_stride,
+                                           const int32_t *__restrict__ cu, uint8_t *__restrict__ packed,
+                                           const SparkLayout &L, const int rows_per_flush, const int wave, const int64_t wt)
 {
     constexpr bool INT8 = (MODE == 1), STATS = (MODE == 2);
     extern __shared__ __align__(16) uint8_t smem[];
     const int lane = threadIdx.x & 63;
-    // the wavefront index is the same in all 64 lanes; saying so keeps everything derived from it
-    // (tile, token loop, search state) in scalar registers
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t wt = (int64_t)blockIdx.x * kPruneWaves + wave;
     const int64_t full_tiles = L.total_tokens / SPARK_TILE_TOKENS;
     if (wt >= (FULL ? full_tiles : 1) * L.n_kv_heads) return;   // whole wavefront leaves; no block barrier is used
     if (VALUES && wt == 0 && (FULL || full_tiles == 0)) {
@@ -695,6 +695,27 @@ __global__ __launch_bounds__(kPruneWaves * 64, MODE == 2 ? 6 : 7) void spark_pru
 }
 
 
+// One launch for a whole cache: the first tail_blocks blocks take the heads' partly filled last tiles (few
+// wavefronts, each a long serial chain of rows: they start first and run beside the rest), the other blocks the
+// tiles that hold 64 tokens.  Blocks are four independent wavefronts; nothing synchronises across them.
+// (WITH_TAIL = false: the token count is a multiple of 64, there are no partly filled tiles, and the kernel holds
+// the one instantiation only, which the register allocator then treats a little better.)
+template <int MODE, bool VALUES, bool WITH_TAIL>
+__global__ __launch_bounds__(kPruneWaves * 64, SPARK_PRUNE_MIN_WAVES) void spark_prune_kernel(
+    const uint16_t *__restrict__ k, int64_t k_tok_stride, int64_t k_head_stride,
+    const int32_t *__restrict__ cu, uint8_t *__restrict__ packed, SparkLayout L, int rows_per_flush, int tail_blocks)
+{
+    // the wavefront index is the same in all 64 lanes; saying so keeps everything derived from it
+    // (tile, token loop, search state) in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (WITH_TAIL && (int)blockIdx.x < tail_blocks)
+        prune_tile<MODE, false, VALUES>(k, k_tok_stride, k_head_stride, cu, packed, L, rows_per_flush, wave,
+                                        (int64_t)blockIdx.x * kPruneWaves + wave);
+    else
+        prune_tile<MODE, true, VALUES>(k, k_tok_stride, k_head_stride, cu, packed, L, rows_per_flush, wave,
+                                       (int64_t)((int)blockIdx.x - tail_blocks) * kPruneWaves + wave);
+}
+
 // ---------------------------------------------------------------- canonical export
 
 // one thread per (token, KV head) row
@@ -738,36 +759,35 @@ __global__ void spark_unpack_kernel(const uint8_t *__restrict__ packed, SparkLay
 
 namespace {
 
-// the tiles that hold 64 tokens, then (if the token count is not a multiple of 64) each head's last tile
+// every tile of the cache in one launch
 template <bool VALUES>
 hipError_t launch_tiles(const uint16_t *x, int64_t tok_stride, int64_t head_stride, const int32_t *cu,
                         uint8_t *packed, const SparkLayout &L, hipStream_t st)
 {
     const size_t lds = spark_prune_lds_bytes(L);
-    auto launch = [&](auto kern, int64_t waves) -> hipError_t {
-        if (waves == 0) return hipSuccess;
+    const int64_t full_waves = (L.total_tokens / SPARK_TILE_TOKENS) * L.n_kv_heads;
+    const int64_t tail_waves = (L.total_tokens % SPARK_TILE_TOKENS) ? L.n_kv_heads : 0;
+    const int tail_blocks = (int)((tail_waves + kPruneWaves - 1) / kPruneWaves);
+    const int64_t nblocks = tail_blocks + (full_waves + kPruneWaves - 1) / kPruneWaves;
+    if (nblocks == 0) return hipSuccess;
+    auto launch = [&](auto kern) -> hipError_t {
         if (lds > 48 * 1024) {
             hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e2 != hipSuccess) return e2;
         }
-        const int nblocks = (int)((waves + kPruneWaves - 1) / kPruneWaves);
-        hipLaunchKernelGGL(kern, dim3(nblocks), dim3(kPruneWaves * 64), lds, st, x, tok_stride, head_stride, cu,
-                           packed, L, spark_prune_rows_per_flush(L));
+        hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(kPruneWaves * 64), lds, st, x, tok_stride, head_stride, cu,
+                           packed, L, spark_prune_rows_per_flush(L), tail_blocks);
         return hipGetLastError();
     };
-    const int64_t full_waves = (L.total_tokens / SPARK_TILE_TOKENS) * L.n_kv_heads;
-    const int64_t tail_waves = (L.total_tokens % SPARK_TILE_TOKENS) ? L.n_kv_heads : 0;
-    if (VALUES || (!L.int8 && !L.stats)) {
-        const hipError_t e = launch(&spark_prune_kernel<0, true, VALUES>, full_waves);
-        return e != hipSuccess ? e : launch(&spark_prune_kernel<0, false, VALUES>, tail_waves);
+    if (tail_blocks == 0) {
+        if (VALUES || (!L.int8 && !L.stats)) return launch(&spark_prune_kernel<0, VALUES, false>);
+        if (L.int8) return launch(&spark_prune_kernel<1, false, false>);
+        return launch(&spark_prune_kernel<2, false, false>);
     }
-    if (L.int8) {
-        const hipError_t e = launch(&spark_prune_kernel<1, true, false>, full_waves);
-        return e != hipSuccess ? e : launch(&spark_prune_kernel<1, false, false>, tail_waves);
-    }
-    const hipError_t e = launch(&spark_prune_kernel<2, true, false>, full_waves);
-    return e != hipSuccess ? e : launch(&spark_prune_kernel<2, false, false>, tail_waves);
+    if (VALUES || (!L.int8 && !L.stats)) return launch(&spark_prune_kernel<0, VALUES, true>);
+    if (L.int8) return launch(&spark_prune_kernel<1, false, true>);
+    return launch(&spark_prune_kernel<2, false, true>);
 }
 
 }  // namespace
