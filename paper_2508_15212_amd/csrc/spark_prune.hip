@@ -125,6 +125,44 @@ __device__ __forceinline__ int clamp_i32(int x, int lo, int hi)
     return r;
 }
 
+// The search below the digit, one bit per step from bit 17 down to bit LAST.  On entry at least T keys are >= p and
+// c (> T) of them are counted; every step tries p with one more bit set and keeps it if T or more keys are still
+// >= it.  Ends as soon as exactly T keys are >= p, or after bit LAST (then p is the T-th largest key and it is
+// tied).  p, c and the bit live in scalar registers; a step is two vector compares, nine scalar instructions and
+// two branches (written out because the compiler's version of the loop condition costs six scalar instructions
+// more, and the scalar unit is what bounds this kernel).  Leaves in kb0 / kb1 the wave masks of the keys >= p
+// (taken here, in the same block, so that this rarely run path shares no code with the usual one).
+template <uint32_t LAST>
+__device__ __forceinline__ void probe_bits(uint32_t k0, uint32_t k1, uint32_t Tv, uint32_t &p, uint32_t &c,
+                                           uint64_t &kb0, uint64_t &kb1)
+{
+    uint32_t bit = 1u << 17, cand, n0, n1;
+    uint64_t m1;
+    asm volatile(
+        "1:\n\t"
+        "s_or_b32 %[cand], %[p], %[bit]\n\t"
+        "v_cmp_le_u32_e32 vcc, %[cand], %[k0]\n\t"
+        "v_cmp_le_u32_e64 %[m1], %[cand], %[k1]\n\t"
+        "s_bcnt1_i32_b64 %[n0], vcc\n\t"
+        "s_bcnt1_i32_b64 %[n1], %[m1]\n\t"
+        "s_add_i32 %[n0], %[n0], %[n1]\n\t"
+        "s_cmp_lt_u32 %[n0], %[T]\n\t"
+        "s_cselect_b32 %[p], %[p], %[cand]\n\t"
+        "s_cselect_b32 %[c], %[c], %[n0]\n\t"
+        "s_cmp_eq_u32 %[c], %[T]\n\t"
+        "s_cbranch_scc1 2f\n\t"
+        "s_lshr_b32 %[bit], %[bit], 1\n\t"          // (sets the condition code to "result not zero")
+        "s_cmp_ge_u32 %[bit], %[last]\n\t"
+        "s_cbranch_scc1 1b\n\t"
+        "2:\n\t"
+        "v_cmp_le_u32_e64 %[kb0], %[p], %[k0]\n\t"
+        "v_cmp_le_u32_e64 %[kb1], %[p], %[k1]"
+        : [p] "+s"(p), [c] "+s"(c), [bit] "+s"(bit), [cand] "=&s"(cand), [n0] "=&s"(n0), [n1] "=&s"(n1), [m1] "=&s"(m1),
+          [kb0] "=&s"(kb0), [kb1] "=&s"(kb1)
+        : [k0] "v"(k0), [k1] "v"(k1), [T] "s"(Tv), [last] "n"(LAST)
+        : "vcc", "scc");
+}
+
 // words per token in the LDS staging row: mask, mu, (scale), then T bf16 values
 __host__ __device__ inline int spark_stage_words(const SparkLayout &L)
 {
@@ -317,6 +355,7 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
 
     // lane t collects, for token t, the ballots of kept even channels (em) and kept odd channels (om)
     uint64_t em = 0, om = 0;
+    uint64_t tok_bit = 1;                                   // one-hot: the lane of the row being searched
     float mureg = 0.0f;                                     // lane t: sum of pruned saliencies
     uint32_t muall = 0;                                     // lane t: mean saliency over all channels (bits)
     float sqreg = 0.0f;                                     // lane t: sum of squared deviations from it
@@ -386,21 +425,28 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
         sA = wave_inclusive_sum(hA);
         sB = wave_inclusive_sum(hB) + (uint32_t)__builtin_amdgcn_readlane((int)sA, 63);   // (bytes cannot carry: <= 128 keys)
     };
-    // Where row R's count reaches T: bin index (>= kOverBins) and the count there; -1 if T or more keys lie
-    // above the window, -2 if fewer than T keys lie in or above it.
-    auto crossing = [&](auto r_tag, const uint32_t sA, const uint32_t sB, int &cnt) __attribute__((always_inline)) -> int {
+    // Where row R's count reaches T.  Returns the 13-bit prefix of the T-th key, shifted to its place (topS = the
+    // window's highest digit plus kOverBins, shifted likewise), and in cnt the number of keys >= that prefix;
+    // sets bit R of miss_up if T or more keys lie above the window, of miss_down if fewer than T keys lie in or
+    // above it.  (The usual case, a crossing in the lower 64 bins, is six scalar instructions.)
+    auto crossing = [&](auto r_tag, const uint32_t sA, const uint32_t sB, const uint32_t topS, const uint32_t topS_low,
+                        int &cnt, uint32_t &miss_up, uint32_t &miss_down) __attribute__((always_inline)) -> uint32_t {
         constexpr int R = decltype(r_tag)::value;
         const uint64_t rA = ballot_byte_ge<R>(sA, Tv);
         if (rA != 0) {
             const int l = __builtin_ctzll(rA);
             cnt = (int)(((uint32_t)__builtin_amdgcn_readlane((int)sA, l) >> (8 * R)) & 0xFFu);
-            return l >= kOverBins ? l : -1;
+            if (__builtin_expect(l < kOverBins, 0)) miss_up |= 1u << R;
+            return topS - ((uint32_t)l << 18);
         }
         const uint64_t rB = ballot_byte_ge<R>(sB, Tv);
-        if (__builtin_expect(rB == 0, 0)) return -2;
+        if (__builtin_expect(rB == 0, 0)) {
+            miss_down |= 1u << R;
+            return 0u;
+        }
         const int l = __builtin_ctzll(rB);
         cnt = (int)(((uint32_t)__builtin_amdgcn_readlane((int)sB, l) >> (8 * R)) & 0xFFu);
-        return 64 + l;
+        return topS_low - ((uint32_t)l << 18);
     };
 
     // searches and stages rows u0 .. u0+3 of the block held in x (tokens tb+u0 ..); leaves their pruned-saliency
@@ -442,15 +488,14 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
         {
             uint32_t sA, sB;
             count_pass(std::integral_constant<int, kBatch>{}, key0, key1, topd, sA, sB);
+            const uint32_t topS = (uint32_t)(topd + kOverBins) << 18;
+            uint32_t topS_low = topS - (64u << 18);     // the same for the lower 64 bins
+            asm volatile("" : "+s"(topS_low));          // (kept as a value of its own: one subtraction per row less)
             auto locate = [&](auto r_tag) __attribute__((always_inline)) {
                 constexpr int R = decltype(r_tag)::value;
                 int cnt = 0;
-                const int bin = crossing(r_tag, sA, sB, cnt);
+                pfx[R] = crossing(r_tag, sA, sB, topS, topS_low, cnt, miss_up, miss_down);
                 geq[R] = cnt;
-                pfx[R] = (uint32_t)(topd + kOverBins - bin) << 18;
-                if (__builtin_expect(bin < 0, 0)) {
-                    if (bin == -1) miss_up |= 1u << R; else miss_down |= 1u << R;
-                }
             };
             locate(std::integral_constant<int, 0>{});
             locate(std::integral_constant<int, 1>{});
@@ -474,10 +519,12 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
                 uint32_t sA, sB;
                 count_pass(std::integral_constant<int, 1>{}, k0, k1, td, sA, sB);
                 int cnt = 0;
-                const int bin = crossing(std::integral_constant<int, 0>{}, sA, sB, cnt);
-                if (bin >= 0) {
+                uint32_t up = 0, down = 0;
+                const uint32_t pre = crossing(std::integral_constant<int, 0>{}, sA, sB, (uint32_t)(td + kOverBins) << 18,
+                                              (uint32_t)(td + kOverBins - 64) << 18, cnt, up, down);
+                if ((up | down) == 0) {
                     GE = cnt;
-                    P = (uint32_t)(td + kOverBins - bin) << 18;
+                    P = pre;
                     break;
                 }
                 if (round == 2) {   // cannot happen for keys below 2^31 (finite input); never spin
@@ -509,27 +556,16 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
             const uint32_t k0 = key0[r], k1 = key1[r];
             const float w0 = __uint_as_float(k0), w1 = __uint_as_float(k1);
             uint32_t p = (uint32_t)__builtin_amdgcn_readfirstlane((int)pfx[r]);
-            uint64_t kb0, kb1;
-            int c = __builtin_amdgcn_readfirstlane(geq[r]);      // keys >= p (at least T)
-            if (__builtin_expect(c == T, 1)) {
-                kb0 = __ballot(k0 >= p);
-                kb1 = __ballot(k1 >= p);
-            } else {
-                // remaining 18 bits (a probe is 2 vector compares and a few scalar instructions, with
-                // the candidate and the prefix held in scalar registers)
-                uint32_t bit = 1u << 17;
-#pragma nounroll
-                do {
-                    const uint32_t cand = p | bit;
-                    const int cc = __popcll(__ballot(k0 >= cand)) + __popcll(__ballot(k1 >= cand));
-                    const bool up = cc >= T;
-                    p = up ? cand : p;
-                    c = up ? cc : c;
-                    bit >>= 1;
-                } while (c != T && bit != (VALUES ? (1u << 15) : 0u));   // |v| of a bf16 entry has no bits below 16
-                kb0 = __ballot(k0 >= p);
-                kb1 = __ballot(k1 >= p);
-                if (__builtin_expect(c != T, 0)) {
+            uint32_t c = (uint32_t)__builtin_amdgcn_readfirstlane(geq[r]);      // keys >= p (at least T)
+            // the usual case first: the digit's bin ends exactly at T keys (taken unconditionally: a plain
+            // if-then compiles to one compare and one branch, an if-else here does not)
+            uint64_t kb0 = __ballot(k0 >= p);
+            uint64_t kb1 = __ballot(k1 >= p);
+            if (__builtin_expect(c != Tv, 0)) {
+                // remaining 18 bits: the digit's bin did not end exactly at T keys (|v| of a bf16 entry has no bits
+                // below 16)
+                probe_bits<(VALUES ? (1u << 16) : 1u)>(k0, k1, Tv, p, c, kb0, kb1);
+                if (__builtin_expect(c != Tv, 0)) {
                     // all bits fixed and still more than T keys >= p: p is the T-th largest value and it is tied
                     const bool eq0 = (k0 == p), eq1 = (k1 == p);
                     const uint64_t q0 = __ballot(eq0), q1 = __ballot(eq1);
@@ -549,7 +585,8 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
                 __builtin_amdgcn_mbcnt_lo((uint32_t)kb1,
                                           __builtin_amdgcn_mbcnt_hi((uint32_t)(kb0 >> 32),
                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)kb0, 0))));
-            stage_row(pos0, xx, kb0, kb1, row_a, 1ull << t, dump_a, em, om);
+            stage_row(pos0, xx, kb0, kb1, row_a, tok_bit, dump_a, em, om);
+            tok_bit <<= 1;
             row_a += row_step;
             ps[u] = VALUES ? 0.0f : (keep0 ? 0.0f : w0) + (keep1 ? 0.0f : w1);
             qs[u] = 0.0f;
