@@ -73,6 +73,10 @@ struct DecodeParams {
 };
 
 constexpr int kDecodeWaves = 4;
+#ifndef SPARK_MERGE_BATCH
+#define SPARK_MERGE_BATCH 16
+#endif
+constexpr int kMergeBatch = SPARK_MERGE_BATCH;   // partial states a merging thread has in flight at a time
 
 __device__ __forceinline__ void wave_lds_sync()
 {
@@ -884,8 +888,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     __syncthreads();
     if (!last_flag) return;
     // Each thread owns two adjacent output channels of one head and folds the partial states with the
-    // running-maximum rule; per round it has sixteen partials' (m, l) pairs and accumulator pairs in flight,
-    // all 8-byte device-scope loads, so a pair with up to sixteen partials needs one round trip.
+    // running-maximum rule; per round it has kMergeBatch partials' (m, l) pairs and accumulator pairs in flight,
+    // all 8-byte device-scope loads (the accumulators of the main loop are dead here, so the registers are there):
+    // a pair with up to kMergeBatch partials needs one round trip.  (32 at a time was measured: one microsecond
+    // less with 64 partials, nothing otherwise.)
     constexpr int NTH = kDecodeWaves * 64;
     for (int e = tid; e < G * (SPARK_D / 2); e += NTH) {
         const int g = e / (SPARK_D / 2), c2 = e % (SPARK_D / 2);
@@ -893,10 +899,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + 2 * c2);
         const uint64_t *pm = reinterpret_cast<const uint64_t *>(P.part_ml);
         float M = -INFINITY, Lsum = 0.0f, A0 = 0.0f, A1 = 0.0f;
-        for (int i0 = 0; i0 < nmerge; i0 += 16) {
-            uint64_t av[16], mv[16];
+        for (int i0 = 0; i0 < nmerge; i0 += kMergeBatch) {
+            uint64_t av[kMergeBatch], mv[kMergeBatch];
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
+            for (int k = 0; k < kMergeBatch; ++k) {
                 const int i = (i0 + k < nmerge) ? (i0 + k) : (nmerge - 1);
                 const int64_t slot = slot_of(qh, i);
                 mv[k] = __hip_atomic_load(pm + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -904,7 +910,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             }
             float Mn = M;
 #pragma unroll
-            for (int k = 0; k < 16; ++k)
+            for (int k = 0; k < kMergeBatch; ++k)
                 if (i0 + k < nmerge) Mn = fmaxf(Mn, __uint_as_float((uint32_t)mv[k]));
             const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
             const float fo = fast_exp2(M - Ms);               // M = -inf -> 0
@@ -913,7 +919,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             A1 *= fo;
             M = Mn;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
+            for (int k = 0; k < kMergeBatch; ++k) {
                 if (i0 + k < nmerge) {
                     const float f = fast_exp2(__uint_as_float((uint32_t)mv[k]) - Ms);
                     Lsum = fmaf(__uint_as_float((uint32_t)(mv[k] >> 32)), f, Lsum);

@@ -83,7 +83,10 @@ __global__ __launch_bounds__(8 * SPARK_D) void spark_window_stat_kernel(const ui
 
 // ---------------------------------------------------------------- top-T selection + pack
 
-constexpr int kPruneWaves = 4;      // wavefronts per block, one tile each
+#ifndef SPARK_PRUNE_WAVES
+#define SPARK_PRUNE_WAVES 4
+#endif
+constexpr int kPruneWaves = SPARK_PRUNE_WAVES;      // wavefronts per block, one tile each
 constexpr int kHistBins = 128;      // digit bins of the counting pass, one 32-bit word per bin: 16 that collect the
                                     // keys above the window, then 112 = 3.5 octaves x 32 digits
 constexpr int kOverBins = 16;

@@ -163,3 +163,14 @@ def test_statistics_rows_and_sampled_decode_arguments():
     assert lib.spark_decode_attn_sampled(ctypes.byref(ds), A, A, A, A, A, A, ws - 1, 1, u64, None) == 3
     assert lib.spark_unpack_stats(ctypes.byref(_desc()), A, A, A, None) == 1
     assert lib.spark_unpack_stats(ctypes.byref(ds), None, A, A, None) == 1
+
+
+def test_bench_traffic_table_names_profile_files_that_hold_the_figures():
+    # every stored HBM-traffic figure of bench.py comes out of the profile summary the table names
+    import bench
+    assert bench.TRAFFIC_PROFILES
+    for (workload, pack), rel in bench.TRAFFIC_PROFILES.items():
+        assert os.path.exists(os.path.join(ROOT, rel)), rel
+        nbytes, src = bench.measured_traffic(workload, pack)
+        assert src == rel and nbytes is not None and nbytes > 0, (workload, pack)
+    assert bench.measured_traffic("no_such_workload", "bf16") == (None, None)
