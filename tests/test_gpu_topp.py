@@ -93,11 +93,19 @@ def test_special_rows():
     k[0, 4, 64:] = 0.5
     k[0, 5] *= 1e-30                               # tiny row
     k[0, 6] *= 1e30                                # huge row
+    k[0, 7] = 0.0                                  # saliencies of exactly one unit in the last place of the largest
+    k[0, 7, 40] = 1.0
+    k[0, 7, [3, 77, 101]] = 2.0 ** -23
+    k[0, 8] = 0.0                                  # ... and of half a unit (rounded down to nothing)
+    k[0, 8, 40] = 1.0
+    k[0, 8, [3, 77, 101]] = 2.0 ** -24
     t.k = wl.f32_to_bf16_bits(k)
     t.qwin = wl.f32_to_bf16_bits(np.ones(t.qwin.shape, np.float32))      # a = 1 everywhere
     pr = _run(w, t)
     assert pr.count[0, 0] == 1 and pr.count[1, 0] == 127 and pr.count[2, 0] == 1 and pr.count[3, 0] == 1
-    _run(w, t, p_bp=10000)
+    pr = _run(w, t, p_bp=10000)
+    assert pr.count[7, 0] == 4 and pr.count[8, 0] == 1
+    _run(w, t, p_bp=9999)
 
 
 def test_config2_size():

@@ -804,6 +804,20 @@ def test_topp_special_rows():
     pr, _ = _topp_rows(_q(k), ones, p_bp=10000)
     assert pr.count[0, 0] == 45 and _kept_channels(pr.mask[0, 0], D) == list(range(5, 50))
     assert pr.mu64[0, 0] == 0.0
+    # the unit is the last place of the row's largest saliency, no coarser: three saliencies of exactly one unit
+    # (2^-23 beside 1.0) count at p = 100 % (total 2^23 + 3 units: all four channels are needed), and at 99.99 %
+    # the largest alone is enough (need = ceil(0.9999 * (2^23 + 3)) <= 2^23)
+    k = np.zeros((1, D), np.float32)
+    k[0, 40] = 1.0
+    k[0, [3, 77, 101]] = 2.0 ** -23
+    pr, _ = _topp_rows(k, ones, p_bp=10000)
+    assert pr.count[0, 0] == 4 and _kept_channels(pr.mask[0, 0], D) == [3, 40, 77, 101]
+    pr, _ = _topp_rows(k, ones, p_bp=9999)
+    assert pr.count[0, 0] == 1 and _kept_channels(pr.mask[0, 0], D) == [40]
+    # ... and no finer: half a unit is rounded down to nothing (2^-24 beside 1.0 never counts)
+    k[0, [3, 77, 101]] = 2.0 ** -24
+    pr, _ = _topp_rows(k, ones, p_bp=10000)
+    assert pr.count[0, 0] == 1 and _kept_channels(pr.mask[0, 0], D) == [40]
     # an all-zero row keeps exactly one channel, the first
     pr, _ = _topp_rows(np.zeros((2, D), np.float32), ones)
     assert np.all(pr.count == 1) and _kept_channels(pr.mask[1, 0], D) == [0]
