@@ -24,7 +24,7 @@ EXPORTS = ["spark_packed_bytes", "spark_prune_workspace", "spark_decode_workspac
            "spark_packed_values_bytes", "spark_prune_values", "spark_unpack_values", "spark_decode_attn_values", "spark_decode_attn_tail",
            "spark_decode_attn_values_tail", "spark_decode_attn_sampled", "spark_unpack_stats", "spark_check_packed",
            "spark_decode_attn_static", "spark_packed_topp_bytes", "spark_prune_topp", "spark_decode_attn_topp",
-           "spark_unpack_topp"]
+           "spark_unpack_topp", "spark_decode_timeline"]
 
 
 class SparkError(RuntimeError):
@@ -110,6 +110,8 @@ def load() -> ctypes.CDLL:
     lib.spark_check_packed.argtypes = [dp, vp, ctypes.c_int32, vp]
     lib.spark_probe_read.restype = ctypes.c_int
     lib.spark_probe_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int32, vp]
+    lib.spark_decode_timeline.restype = ctypes.c_int
+    lib.spark_decode_timeline.argtypes = [vp, ctypes.c_size_t]
     lib.spark_status_string.restype = ctypes.c_char_p
     lib.spark_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -272,6 +274,16 @@ def check_packed(desc: SparkDesc, packed: torch.Tensor, is_value_cache: bool = F
     if rc not in (0, ERR_MISMATCH):
         _check(rc, "spark_check_packed")
     return rc
+
+
+def decode_timeline(buffer) -> None:
+    """spark_decode_timeline (include/spark_bench.h): later decode launches file eight int64 words per block into
+    `buffer` (an int64 device tensor the caller keeps alive); None switches the aid off."""
+    if buffer is None:
+        rc = load().spark_decode_timeline(None, 0)
+    else:
+        rc = load().spark_decode_timeline(_ptr(buffer), buffer.numel() * buffer.element_size())
+    _check(rc, "spark_decode_timeline")
 
 
 def probe_read(src: torch.Tensor, sink: torch.Tensor, n_blocks: int) -> None:

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/spark_bench.h"
+#include "spark_kernels.h"
 
 namespace {
 
@@ -40,4 +41,11 @@ extern "C" spark_status spark_probe_read(const void *src, size_t bytes, void *si
     hipLaunchKernelGGL(spark_probe_read_kernel, dim3(n_blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        static_cast<const u32x4 *>(src), bytes / 16, static_cast<uint32_t *>(sink));
     return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_HIP;
+}
+
+extern "C" spark_status spark_decode_timeline(void *device_buffer, size_t bytes)
+{
+    if (device_buffer && (!aligned(device_buffer, 8) || bytes < 64)) return SPARK_ERR_INVALID_ARG;
+    spark::set_decode_timeline(static_cast<unsigned long long *>(device_buffer), device_buffer ? bytes / 64 : 0);
+    return SPARK_OK;
 }

@@ -17,6 +17,18 @@ __global__ void spark_zero_kernel(uint32_t *p, int n)
     if (i < n) p[i] = 0u;
 }
 
+// Timeline buffer of the measurement aid spark_decode_timeline (process-wide; NULL = off)
+namespace {
+unsigned long long *g_timeline = nullptr;
+size_t g_timeline_blocks = 0;
+}  // namespace
+
+void set_decode_timeline(unsigned long long *device_words, size_t blocks)
+{
+    g_timeline = device_words;
+    g_timeline_blocks = device_words ? blocks : 0;
+}
+
 hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const uint16_t *v, int64_t v_tok_stride,
                               int64_t v_head_stride, const uint8_t *packed_v, const SparkLayout *Lv,
                               const int32_t *cu, float *part_acc, float *part_ml,
@@ -57,6 +69,7 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.L = L;
     const int G = P.Hq / P.Hkv;
     const int nblocks = P.Hkv * (P.nchunk_max + L.batch * P.ntail);
+    P.trace = (g_timeline != nullptr && (size_t)nblocks <= g_timeline_blocks) ? g_timeline : nullptr;
     switch (G) {
         case 1: return launch_g<1>(P, nblocks, st);
         case 2: return launch_g<2>(P, nblocks, st);

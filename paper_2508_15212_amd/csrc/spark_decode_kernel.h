@@ -49,6 +49,7 @@ struct DecodeParams {
     float *part_acc;         // [slots][128]   partial softmax states, see slot numbering below
     float *part_ml;          // [slots][2]     (m in log2 units, l)
     uint32_t *counters;      // [B*Hkv] arrival counters, zero between calls
+    unsigned long long *trace;   // NULL, or eight 64-bit words per block of the grid for the timeline (see stamp())
     void *out;               // [B, Hq, 128] bf16 or float32
     int out_f32;
     int Hq, Hkv;
@@ -301,6 +302,14 @@ constexpr int decode_min_blocks(int, int) { return 2; }
 // The cache is read once per step: the streaming loads carry the non-temporal hint so they do not
 // displace each other in the L2 / memory-side cache (measured: 129 us -> 118 us on the 32K workload).
 #define NT_LOAD(p) __builtin_nontemporal_load(p)
+// Timeline of a launch (a measurement aid, off unless a buffer has been given through spark_decode_timeline):
+// thread 0 of every block files the 100 MHz wall clock at five points - word 0 entry, 1 start of streaming,
+// 2 end of streaming (wavefront 0), 3 partial stored, 4 exit - and, with word 5, its tile count, 6 the
+// hardware ids (XCC id << 32 | HW_ID), 7 whether it merged its (batch, KV head) pair.
+__device__ __forceinline__ void stamp(const DecodeParams &P, int word, unsigned long long value)
+{
+    if (P.trace != nullptr && threadIdx.x == 0) P.trace[(size_t)blockIdx.x * 8 + word] = value;
+}
 // TVC: 0 = dense values; > 0 = packed values with that many kept channels per row (row held in registers);
 // -1 = packed values, any count (row words read from memory as they are needed).
 // REC: 0 = degenerate recovery (mu / a, folded into the score sum); 1 / 2 = Gaussian / Exponential recovery:
@@ -345,6 +354,12 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep tile addressing scalar
+    if (P.trace != nullptr) {
+        stamp(P, 0, wall_clock64());
+        stamp(P, 6, ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11)) << 32) |     // XCC_ID
+                        (unsigned long long)__builtin_amdgcn_s_getreg(4 | (31 << 11)));              // HW_ID
+        stamp(P, 7, 0ull);
+    }
     const SparkLayout &L = P.L;
     const int T = TCT ? TCT : L.T;
     // blocks [0, nchunk_max * Hkv) are (global chunk, KV head) pairs; when rows have been appended after
@@ -529,6 +544,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     for (int g = 0; g < G; ++g) R[g] = Rsh[g];
 
 
+    if (P.trace != nullptr) { stamp(P, 1, wall_clock64()); stamp(P, 5, (unsigned long long)nts); }
     for (; kidx < nts; kidx += kDecodeWaves) {
         tile = tile_of(kidx);
         const uint8_t *tp = tiles + (int64_t)tile * L.tile_bytes;
@@ -824,6 +840,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         }
     }
 
+    if (P.trace != nullptr) stamp(P, 2, wall_clock64());
     // ---- merge the 4 wavefronts, write the split partial
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -871,6 +888,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         }
     }
     }   // sequence split
+    if (P.trace != nullptr) { const unsigned long long now = wall_clock64(); stamp(P, 3, now); stamp(P, 4, now); }
     if (nmerge == 1) return;   // (block-uniform)
 
     // ---- the last block of this (batch, KV head) to get here merges the splits.
@@ -886,6 +904,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         last_flag = (old == (uint32_t)(nmerge - 1));
     }
     __syncthreads();
+    if (P.trace != nullptr) stamp(P, 4, wall_clock64());
     if (!last_flag) return;
     // Each thread owns two adjacent output channels of one head and folds the partial states with the
     // running-maximum rule; per round it has kMergeBatch partials' (m, l) pairs and accumulator pairs in flight,
@@ -938,6 +957,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             reinterpret_cast<uint32_t *>(P.out)[bq * (SPARK_D / 2) + c2] = packed2;
         }
     }
+    if (P.trace != nullptr) { stamp(P, 4, wall_clock64()); stamp(P, 7, 1ull); }
 }
 
 // ---------------------------------------------------------------- host-side launch

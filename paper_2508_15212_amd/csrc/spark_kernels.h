@@ -23,6 +23,10 @@ struct DecodePlan {
     int tail_slots;     // partial slots reserved per (batch, q head) for appended rows
 };
 
+// measurement aid: later decode launches of this process file eight 64-bit words per block into `device_words`
+// (room for `blocks` blocks; launches with more blocks file nothing); NULL switches it off
+void set_decode_timeline(unsigned long long *device_words, size_t blocks);
+
 hipError_t launch_prune(const uint16_t *k, int64_t k_tok_stride, int64_t k_head_stride, const uint16_t *qwin,
                         const int32_t *cu, uint8_t *packed, const SparkLayout &L, int Hq, int W, hipStream_t st);
 

@@ -174,3 +174,11 @@ def test_bench_traffic_table_names_profile_files_that_hold_the_figures():
         nbytes, src = bench.measured_traffic(workload, pack)
         assert src == rel and nbytes is not None and nbytes > 0, (workload, pack)
     assert bench.measured_traffic("no_such_workload", "bf16") == (None, None)
+
+
+def test_timeline_aid_checks_its_buffer_on_the_host():
+    lib = spark.load()
+    assert lib.spark_decode_timeline(None, 0) == 0                       # off
+    assert lib.spark_decode_timeline(0x7F0000000004, 4096) == 1          # misaligned
+    assert lib.spark_decode_timeline(0x7F0000000000, 32) == 1            # no room for one block
+    assert lib.spark_decode_timeline(None, 0) == 0

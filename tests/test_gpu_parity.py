@@ -294,3 +294,39 @@ def test_non_finite_entries_stay_inside_their_sequence_and_head():
     err = np.abs(res["out_f32"].astype(np.float64) - ref)[clean_out]
     assert np.all(np.isfinite(res["out_f32"][clean_out]))
     assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+
+
+def test_timeline_aid_changes_no_result_and_files_ordered_stamps():
+    """The measurement aid of include/spark_bench.h: with a buffer given, every working block files five ordered
+    wall-clock stamps and exactly one block per (batch, KV head) reports the merge; the output is bit for bit
+    the one computed without it; a buffer too small for the grid files nothing."""
+    w = wl.small(name="tline", seqlens=(5000, 3000, 0, 700), batch=4, seed=76)
+    t = wl.generate(w)
+    res = run_gpu_case(w, t, want_unpack=False, want_bf16=False)
+    desc = res["desc"]
+    dk, dv, dqw, dq, dcu = res["dev"]
+    ws = spark.new_decode_workspace(desc)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    buf = torch.zeros(4096 * 8, dtype=torch.int64, device="cuda")
+    spark.decode_timeline(buf)
+    try:
+        spark.decode_attn(desc, dq, res["packed"], dv, dcu, out, ws)
+        torch.cuda.synchronize()
+        tr = buf.cpu().numpy().reshape(-1, 8)
+        small = torch.zeros(8, dtype=torch.int64, device="cuda")       # room for one block only
+        spark.decode_timeline(small)
+        spark.decode_attn(desc, dq, res["packed"], dv, dcu, out, ws)
+        torch.cuda.synchronize()
+        assert not small.cpu().numpy().any()
+    finally:
+        spark.decode_timeline(None)
+    assert np.array_equal(out.cpu().numpy(), res["out_f32"])
+    work = tr[(tr[:, 0] != 0) & (tr[:, 4] != 0)]
+    assert len(work) >= w.batch * w.n_kv_heads
+    assert np.all(work[:, 0] <= work[:, 1]) and np.all(work[:, 1] <= work[:, 2])
+    assert np.all(work[:, 2] <= work[:, 3]) and np.all(work[:, 3] <= work[:, 4])
+    assert (work[:, 4] - work[:, 0]).max() < 100 * 1000 * 100          # under 100 ms in 10 ns ticks
+    tiles = sum((int(t.cu[i + 1]) - 1) // 64 - int(t.cu[i]) // 64 + 1 for i in range(w.batch) if t.cu[i + 1] > t.cu[i])
+    assert work[:, 5].sum() == tiles * w.n_kv_heads
+    # pairs cut into several blocks are merged by exactly one of them
+    assert 0 < (work[:, 7] == 1).sum() <= w.batch * w.n_kv_heads
