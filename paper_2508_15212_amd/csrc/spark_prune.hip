@@ -9,13 +9,14 @@
 //                             as float32 together with 1/a (G*128 threads per (b, h)).
 //   spark_prune_kernel        one wavefront per tile (64 tokens of one KV head).  For each
 //                             token the 128 saliencies sit two per lane (channels 2l, 2l+1);
-//                             the T-th largest is found by a most-significant-bit-first
-//                             search on the float32 bit pattern where every probe is two
-//                             wave ballots and two scalar popcounts; the kept set is then a
-//                             pair of 64-bit ballots = the channel mask, and a prefix
-//                             popcount (mbcnt) gives each kept value its slot in the packed
-//                             row.  Rows are staged in LDS and the finished tile is written
-//                             with lane = token, coalesced.
+//                             the T-th largest is found on the float32 bit pattern, most
+//                             significant bits first: the top 13 bits by a counting pass over
+//                             LDS bins that four rows share, the rest (for the rows that need
+//                             it) by probes of two wave ballots and two scalar popcounts each.
+//                             The kept set is then a pair of 64-bit ballots = the channel
+//                             mask, and a prefix popcount (mbcnt) gives each kept value its
+//                             slot in the packed row.  Rows are staged in LDS and written out
+//                             with lane = token, coalesced, every 64, 32 or 16 rows.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
