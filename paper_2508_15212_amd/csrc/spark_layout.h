@@ -119,7 +119,8 @@ static inline SPARK_HD SparkLayout spark_make_topp_layout(int batch, int n_kv_he
     const int64_t dir_bytes = (int64_t)n_kv_heads * (L.n_tiles + 1) * 4;
     L.off_vals = (L.off_dir + dir_bytes + 255) & ~(int64_t)255;
     L.vals_head_words = L.n_tiles * SPARK_TILE_TOKENS * (SPARK_D / 2);
-    L.total_bytes = L.off_vals + (int64_t)n_kv_heads * L.vals_head_words * 4;
+    // (256 bytes of padding behind the last stream: a reader may fetch whole 16-byte groups of a row's words)
+    L.total_bytes = L.off_vals + (int64_t)n_kv_heads * L.vals_head_words * 4 + 256;
     return L;
 }
 
