@@ -32,15 +32,23 @@ namespace {
 
 constexpr int kWaves = 4;     // wavefronts per block, one tile each
 
-// Maximum over the 64 lanes, wave-uniform.
+// Maximum over the 64 lanes, wave-uniform.  Data-parallel-primitive moves: two quad permutes and two row rotates
+// leave each row of 16 lanes holding its row maximum, two row broadcasts fold the four rows into lane 63.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_max_u32_step(uint32_t x)
+{
+    const uint32_t y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, ROW_MASK, 0xF, false);
+    return x > y ? x : y;
+}
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        const uint32_t y = (uint32_t)__shfl_xor((int)v, o);
-        v = v > y ? v : y;
-    }
-    return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
+    v = dpp_max_u32_step<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v = dpp_max_u32_step<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v = dpp_max_u32_step<0x124, 0xF>(v);   // row_ror 4
+    v = dpp_max_u32_step<0x128, 0xF>(v);   // row_ror 8
+    v = dpp_max_u32_step<0x142, 0xA>(v);   // row_bcast 15 into rows 1 and 3
+    v = dpp_max_u32_step<0x143, 0xC>(v);   // row_bcast 31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
 // a saliency (float32 bits, sign clear) in units of 2^(emax - 150), rounded down; emax >= 1
@@ -110,7 +118,9 @@ __global__ __launch_bounds__(kWaves * 64) void spark_topp_select_kernel(
         emax = emax < 1 ? 1 : emax;
         const uint32_t q0 = quantise(k0, emax), q1 = quantise(k1, emax);
         const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_sum(q0 + q1), 63);
-        const uint32_t need = (uint32_t)(((uint64_t)total * (uint32_t)p_bp + 9999u) / 10000u);
+        // need = ceil(total * p / 10000) without a 64-bit division: total = 10000 A + B, B * p < 2^27
+        const uint32_t tA = total / 10000u, tB = total - tA * 10000u;
+        const uint32_t need = tA * (uint32_t)p_bp + (tB * (uint32_t)p_bp + 9999u) / 10000u;
 
         uint64_t kb0, kb1;
         if (need == 0) {
@@ -121,7 +131,7 @@ __global__ __launch_bounds__(kWaves * 64) void spark_topp_select_kernel(
             // radix selection on sums: theta = the largest bit pattern with sum{q : key >= theta} >= need
             uint32_t theta = 0;      // the bits fixed so far
             uint32_t above = 0;      // sum of q over the keys above every pattern that starts with theta's fixed bits
-            auto level = [&](const int sh, const int nbits) __attribute__((always_inline)) {
+            auto level = [&](const int sh, const int nbits) __attribute__((always_inline)) -> bool {
                 // undecided keys agree with theta above bit sh + nbits; their next digit is (key >> sh) & (2^nbits - 1).
                 // Bins are laid out highest digit first, so lane l reads the bin of digit top - l.
                 const uint32_t top = (theta >> sh) | ((1u << nbits) - 1u);
@@ -138,13 +148,15 @@ __global__ __launch_bounds__(kWaves * 64) void spark_topp_select_kernel(
                 const int l2 = __builtin_ctzll(reached);
                 if (l2 > 0) above += (uint32_t)__builtin_amdgcn_readlane((int)c, l2 - 1);
                 theta |= (((1u << nbits) - 1u) - (uint32_t)l2) << sh;
+                // If one key alone starts with the bits fixed so far, it is the smallest kept one: the levels
+                // below would only spell out its remaining bits.  (Usual after two or three levels.)
+                const uint64_t in0 = __ballot((k0 >> sh) == (theta >> sh)), in1 = __ballot((k1 >> sh) == (theta >> sh));
+                if (__popcll(in0) + __popcll(in1) != 1) return false;
+                theta = in0 ? (uint32_t)__builtin_amdgcn_readlane((int)k0, __builtin_ctzll(in0))
+                            : (uint32_t)__builtin_amdgcn_readlane((int)k1, __builtin_ctzll(in1 | (1ull << 63)));
+                return true;
             };
-            level(25, 6);
-            level(19, 6);
-            level(13, 6);
-            level(7, 6);
-            level(1, 6);
-            level(0, 1);
+            if (!level(25, 6) && !level(19, 6) && !level(13, 6) && !level(7, 6) && !level(1, 6)) level(0, 1);
             // `above` is now the sum over the keys > theta; the keys == theta (each worth q_theta) fill the rest,
             // lowest channels first
             const bool eq0 = (k0 == theta), eq1 = (k1 == theta);
