@@ -14,11 +14,14 @@
 //                             bit pattern of the smallest kept saliency is fixed six bits at a time, each level
 //                             adding the q of the still undecided keys to 64 LDS bins by their next digit; a wave
 //                             prefix sum over the bins (highest digit first) and one ballot give the digit at
-//                             which the running sum reaches `need`.  Writes the rows' fixed part (mask, mean
+//                             which the running sum reaches `need`; the levels end as soon as one key alone
+//                             starts with the bits fixed so far.  Writes the rows' fixed part (mask, mean
 //                             saliency of the pruned channels, count) and the tile's length in the value stream.
 //   spark_topp_scan_kernel    exclusive prefix sum of the tile lengths of every KV head: the directory.
-//   spark_topp_pack_kernel    lane = token: walks its mask and copies the kept entries from the dense keys into
-//                             the value stream at the place the directory and the counts of the lower tokens give.
+//   spark_topp_pack_kernel    one wavefront per row: reads the dense key row with one coalesced load; every lane
+//                             finds the slots of its two channels from popcounts of the row's mask and stores its
+//                             kept entries into the value stream at the place the directory and the counts of
+//                             the tile's lower tokens give.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
