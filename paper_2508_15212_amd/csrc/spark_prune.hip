@@ -661,26 +661,41 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
                 if (T & 1) row[vend - 1] &= 0xFFFFu;                 // unused upper half of the last word
                 for (int d = vend; d < sw; ++d) row[d] = 0u;
                 if (INT8) {
-                    // absmax scale and round-to-nearest-even codes, decided in float32
-                    auto val = [&](int i) {
-                        return bf16_bits_to_float((row[L.val0 + (i >> 1)] >> (16 * (i & 1))) & 0xFFFFu);
-                    };
+                    // absmax scale and round-to-nearest-even codes, decided in float32.  The staged bf16 words
+                    // are read two at a time (four values; val0 is even, rows are 8-byte aligned, and the words
+                    // behind the last kept value are zero up to the row's end).
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    const u32x2 *vals2 = reinterpret_cast<const u32x2 *>(row + L.val0);
+                    const int nquad = (T + 3) / 4;
                     float amax = 0.0f;
-                    for (int i = 0; i < T; ++i) amax = fmaxf(amax, fabsf(val(i)));
+                    for (int c = 0; c < nquad; ++c) {
+                        const u32x2 w = vals2[c];
+                        amax = fmaxf(fmaxf(amax, fabsf(bf16_bits_to_float(w.x & 0xFFFFu))), fabsf(bf16_bits_to_float(w.x >> 16)));
+                        amax = fmaxf(fmaxf(amax, fabsf(bf16_bits_to_float(w.y & 0xFFFFu))), fabsf(bf16_bits_to_float(w.y >> 16)));
+                    }
                     const float scale = __fdiv_rn(amax, 127.0f);
                     row[5] = __float_as_uint(scale);
-                    for (int c = 0; c < L.nv; ++c) {
+                    // The code is rint(fl32(v / scale)).  The exact division costs ten instructions a value, so the
+                    // integer is first taken from v times an approximate reciprocal: that product and the exactly
+                    // rounded quotient both lie within 3.1e-5 of v / scale (|v / scale| <= 127, reciprocal to one
+                    // unit in the last place, two roundings), so unless the product comes within 6e-5 of a half
+                    // integer the two round to the same integer; otherwise (and when the reciprocal is not
+                    // finite) the lane divides exactly.
+                    const float rs = __builtin_amdgcn_rcpf(scale);
+                    auto code_of = [&](uint32_t bits) -> uint32_t {
+                        const float v = bf16_bits_to_float(bits);
+                        const float qa = v * rs;
+                        float qf = rintf(qa);
+                        if (!(fabsf(qa - qf) < 0.5f - 6e-5f)) qf = rintf(__fdiv_rn(v, scale));
+                        // (|v| <= amax and scale = fl32(amax / 127), so |qf| <= 127 already: no clamp is needed)
+                        return (uint32_t)(int)qf & 0xFFu;
+                    };
+                    for (int c = 0; c < nquad; ++c) {
+                        const u32x2 w = vals2[c];      // values 4c .. 4c+3 (zero bits past the T-th: code 0)
                         uint32_t word = 0;
-                        for (int e = 0; e < 4; ++e) {
-                            const int i = 4 * c + e;
-                            int code = 0;
-                            if (i < T && scale != 0.0f) {
-                                float qf = rintf(__fdiv_rn(val(i), scale));
-                                qf = fminf(fmaxf(qf, -127.0f), 127.0f);
-                                code = (int)qf;
-                            }
-                            word |= ((uint32_t)code & 0xFFu) << (8 * e);
-                        }
+                        if (scale != 0.0f)
+                            word = code_of(w.x & 0xFFFFu) | (code_of(w.x >> 16) << 8) | (code_of(w.y & 0xFFFFu) << 16) |
+                                   (code_of(w.y >> 16) << 24);
                         row[L.val0 + c] = word;   // never ahead of the bf16 words still to be read
                     }
                     for (int d = L.val0 + L.nv; d < L.ndw; ++d) row[d] = 0u;
