@@ -330,3 +330,10 @@ def test_timeline_aid_changes_no_result_and_files_ordered_stamps():
     assert work[:, 5].sum() == tiles * w.n_kv_heads
     # pairs cut into several blocks are merged by exactly one of them
     assert 0 < (work[:, 7] == 1).sum() <= w.batch * w.n_kv_heads
+
+
+def test_profile_summaries_that_bench_reads_are_present_on_this_box():
+    """bench.py takes roofline.traffic from a profile summary: the file has to travel with the tree."""
+    import bench
+    nbytes, src = bench.measured_traffic("cfg2_llama8b_b8_32k_keep26", "bf16")
+    assert src == "profiles/decode_prune_cfg2_hbm_traffic.md" and nbytes and 0.9 < nbytes / 687865856 < 1.1
