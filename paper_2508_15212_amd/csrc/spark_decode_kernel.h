@@ -324,9 +324,12 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     static_assert(!VAR || (TCT == 0 && INT8 == 0 && TVC == 0 && REC == 0), "variable-length rows: any-length bf16 path only");
     constexpr bool PV = (TVC != 0);             // packed value cache
     constexpr int NVW = PV ? (TVC > 0 ? (((4 + (TVC + 1) / 2) + 1) & ~1) : 4) : 1;   // value-row words in registers
-    // LDS row stride (words) of a parked value row: >= the row, and = 4 mod 8 so that 16-byte row writes of
-    // consecutive tokens fall on different banks; a row kept whole in registers is NVW words, the longest is 68
-    constexpr int RSV = PV ? (TVC > 0 ? 8 * ((NVW + 3) / 8) + 4 : 68) : 1;
+    // LDS row stride (words) of a parked value row.  A row kept whole in registers (NVW words) is parked word by
+    // word at an ODD stride: the four tokens whose windows a wavefront reads together then start in banks of both
+    // parities (with an even stride the window offsets, which advance by about two words per group, fell on even
+    // banks only: 104 instead of 113 us at 26 kept value channels on the 32K shape, no change at 64).  Rows of any
+    // length are read from memory in 16-byte pieces and keep a stride that is 4 mod 8; the longest is 68 words.
+    constexpr int RSV = PV ? (TVC > 0 ? (NVW | 1) : 68) : 1;
     // floats per table entry: G queries, 1/a, pad -- a multiple of 4 (16-byte gathers) that is 4 mod 8, so
     // that the entries of different channels start in all eight 16-byte bank groups, not in half of them
     constexpr int GP = 8 * ((G + 1 + 3) / 8) + 4;
@@ -344,10 +347,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     constexpr int WBUF = (PV && RAW_BYTES > RED_BYTES) ? RAW_BYTES : RED_BYTES;
     __shared__ __align__(16) uint8_t wbuf[kDecodeWaves][WBUF];
     // packed values: per token 16 x {kept entries before the group, the group's mask byte}; the selector
-    // table (12 words per entry, 6 used: the odd stride spreads the entries over the LDS banks)
-    constexpr int LUTW = 12;
+    // table in two arrays (four words and two words per entry, each read with one aligned access: either array's
+    // entries then tile all 32 banks; one array of 12-word entries left half the banks idle on the short read)
     __shared__ __align__(16) uint32_t vmeta[PV ? kDecodeWaves : 1][PV ? SPARK_TILE_TOKENS * 8 : 1];
-    __shared__ __align__(16) uint32_t vlut[PV ? 256 * LUTW : 1];
+    __shared__ __align__(16) uint32_t vlut[PV ? 256 * 4 : 1];
+    __shared__ __align__(16) uint32_t vlutb[PV ? 256 * 2 : 1];
     __shared__ float red_m[kDecodeWaves][G], red_l[kDecodeWaves][G];
     __shared__ int last_flag;
 
@@ -517,9 +521,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             }
             rnk += on ? 1 : 0;
         }
-        u32x4 lo4 = {sel[0], sel[1], sel[2], sel[3]}, hi4 = {sel[4], sel[5], 0u, 0u};
-        *reinterpret_cast<u32x4 *>(&vlut[tid * LUTW]) = lo4;
-        *reinterpret_cast<u32x4 *>(&vlut[tid * LUTW + 4]) = hi4;
+        u32x4 lo4 = {sel[0], sel[1], sel[2], sel[3]};
+        *reinterpret_cast<u32x4 *>(&vlut[tid * 4]) = lo4;
+        vlutb[tid * 2] = sel[4];
+        vlutb[tid * 2 + 1] = sel[5];
     }
     // ---- per-step query prep: table {q_g[j] * scale * log2e, 1/a[j]} and R_g
     if (tid < SPARK_D) {
@@ -761,10 +766,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             uint32_t mk[4];
             if (TVC > 0) {
 #pragma unroll
-                for (int qd = 0; qd < NVW / 4; ++qd) {
-                    u32x4 x = {vrow[4 * qd], vrow[4 * qd + 1], vrow[4 * qd + 2], vrow[4 * qd + 3]};
-                    *reinterpret_cast<u32x4 *>(&raw[lane * RSV + 4 * qd]) = x;
-                }
+                for (int d = 0; d < 4 * (NVW / 4); ++d) raw[lane * RSV + d] = vrow[d];    // (word stores: the stride is odd)
                 if (NVW % 4) {
                     raw[lane * RSV + 4 * (NVW / 4)] = vrow[4 * (NVW / 4)];
                     raw[lane * RSV + 4 * (NVW / 4) + 1] = vrow[4 * (NVW / 4) + 1];
@@ -824,8 +826,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                             const uint32_t q1 = __builtin_amdgcn_alignbit(d2, d1, sh);
                             const uint32_t q2 = __builtin_amdgcn_alignbit(d3, d2, sh);
                             const uint32_t q3 = __builtin_amdgcn_alignbit(d4, d3, sh);
-                            const u32x4 sa = *reinterpret_cast<const u32x4 *>(&vlut[byte * LUTW]);
-                            const uint2 sb = *reinterpret_cast<const uint2 *>(&vlut[byte * LUTW + 4]);
+                            const u32x4 sa = *reinterpret_cast<const u32x4 *>(&vlut[byte * 4]);
+                            const uint2 sb = *reinterpret_cast<const uint2 *>(&vlutb[byte * 2]);
                             vr[ks][i].x = __builtin_amdgcn_perm(q1, q0, sa.x);
                             vr[ks][i].y = __builtin_amdgcn_perm(q1, q0, sa.y);
                             vr[ks][i].z = __builtin_amdgcn_perm(q1, q0, sa.z) | __builtin_amdgcn_perm(q3, q2, sa.w);
