@@ -74,10 +74,6 @@ struct DecodeParams {
 };
 
 constexpr int kDecodeWaves = 4;
-#ifndef SPARK_MERGE_BATCH
-#define SPARK_MERGE_BATCH 16
-#endif
-constexpr int kMergeBatch = SPARK_MERGE_BATCH;   // partial states a merging thread has in flight at a time
 
 __device__ __forceinline__ void wave_lds_sync()
 {
@@ -940,44 +936,58 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     __syncthreads();
     if (P.trace != nullptr) stamp(P, 4, wall_clock64());
     if (!last_flag) return;
-    // Each thread owns two adjacent output channels of one head and folds the partial states with the
-    // running-maximum rule; per round it has kMergeBatch partials' (m, l) pairs and accumulator pairs in flight,
-    // all 8-byte device-scope loads (the accumulators of the main loop are dead here, so the registers are there):
-    // a pair with up to kMergeBatch partials needs one round trip.  (32 at a time was measured: one microsecond
-    // less with 64 partials, nothing otherwise.)
+    // A wavefront takes one query head per pass, its lane l the output channels 2l, 2l+1.  Up to 64 partial states
+    // are folded per round with the running-maximum rule: lane i fetches the (m, l) pair of partial i - one 8-byte
+    // load per lane, the pair's factor exp2(m_i - M) is then handed out by readlane - while every lane fetches
+    // its accumulator pair of all the partials (64 independent 8-byte loads in flight; the accumulators of the
+    // main loop are dead here, so the registers are there).  All loads are device-scope.  A (batch, KV head)
+    // pair with up to 64 partials is merged in one memory round trip.
     constexpr int NTH = kDecodeWaves * 64;
-    for (int e = tid; e < G * (SPARK_D / 2); e += NTH) {
-        const int g = e / (SPARK_D / 2), c2 = e % (SPARK_D / 2);
+    for (int e0 = wave * 64; e0 < G * (SPARK_D / 2); e0 += NTH) {
+        const int g = e0 / (SPARK_D / 2), c2 = lane;      // (g is wave-uniform)
         const int qh = h * G + g;
         const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + 2 * c2);
         const uint64_t *pm = reinterpret_cast<const uint64_t *>(P.part_ml);
         float M = -INFINITY, Lsum = 0.0f, A0 = 0.0f, A1 = 0.0f;
-        for (int i0 = 0; i0 < nmerge; i0 += kMergeBatch) {
-            uint64_t av[kMergeBatch], mv[kMergeBatch];
-#pragma unroll
-            for (int k = 0; k < kMergeBatch; ++k) {
-                const int i = (i0 + k < nmerge) ? (i0 + k) : (nmerge - 1);
-                const int64_t slot = slot_of(qh, i);
-                mv[k] = __hip_atomic_load(pm + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                av[k] = __hip_atomic_load(pa + slot * (SPARK_D / 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int i0 = 0; i0 < nmerge; i0 += 64) {
+            const int n = (nmerge - i0 < 64) ? nmerge - i0 : 64;
+            float mi = -INFINITY, li = 0.0f;
+            if (lane < n) {
+                const uint64_t ml = __hip_atomic_load(pm + slot_of(qh, i0 + lane), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                mi = __uint_as_float((uint32_t)ml);
+                li = __uint_as_float((uint32_t)(ml >> 32));
             }
-            float Mn = M;
+            uint64_t av[64];
 #pragma unroll
-            for (int k = 0; k < kMergeBatch; ++k)
-                if (i0 + k < nmerge) Mn = fmaxf(Mn, __uint_as_float((uint32_t)mv[k]));
+            for (int k0 = 0; k0 < 64; k0 += 8) {
+                if (k0 < n) {                                      // (wave-uniform: whole groups of eight are skipped)
+#pragma unroll
+                    for (int k = k0; k < k0 + 8; ++k) {
+                        const int i = i0 + ((k < n) ? k : n - 1);  // (past the batch: some valid slot, its factor is 0)
+                        av[k] = __hip_atomic_load(pa + slot_of(qh, i) * (SPARK_D / 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                } else {
+#pragma unroll
+                    for (int k = k0; k < k0 + 8; ++k) av[k] = 0ull;
+                }
+            }
+            const float Mn = fmaxf(M, wave_max(mi));
             const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
             const float fo = fast_exp2(M - Ms);               // M = -inf -> 0
-            Lsum *= fo;
+            M = Mn;
+            const float fi = fast_exp2(mi - Ms);              // lane i: factor of partial i0 + i (0 past the batch)
+            Lsum = fmaf(Lsum, fo, wave_sum(li * fi));
             A0 *= fo;
             A1 *= fo;
-            M = Mn;
 #pragma unroll
-            for (int k = 0; k < kMergeBatch; ++k) {
-                if (i0 + k < nmerge) {
-                    const float f = fast_exp2(__uint_as_float((uint32_t)mv[k]) - Ms);
-                    Lsum = fmaf(__uint_as_float((uint32_t)(mv[k] >> 32)), f, Lsum);
-                    A0 = fmaf(__uint_as_float((uint32_t)av[k]), f, A0);
-                    A1 = fmaf(__uint_as_float((uint32_t)(av[k] >> 32)), f, A1);
+            for (int k0 = 0; k0 < 64; k0 += 8) {
+                if (k0 < n) {
+#pragma unroll
+                    for (int k = k0; k < k0 + 8; ++k) {
+                        const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fi), k));
+                        A0 = fmaf(__uint_as_float((uint32_t)av[k]), f, A0);
+                        A1 = fmaf(__uint_as_float((uint32_t)(av[k] >> 32)), f, A1);
+                    }
                 }
             }
         }
