@@ -263,7 +263,7 @@ def decode_sampled(kind: int, seed: int, q, pr: Pruned, mu_all, sigma, v, layout
     q = _c(q, np.uint16)
     b, hq, d = q.shape
     v, ts, hs, total, hkv, dv = _strided(v, layout)
-    assert dv == d == pr.D and pr.codes is None
+    assert dv == d == pr.D
     cu = _c(cu, np.int32)
     mu_all, sigma = _c(mu_all, np.float32), _c(sigma, np.float32)
     if scale is None:
@@ -271,7 +271,7 @@ def decode_sampled(kind: int, seed: int, q, pr: Pruned, mu_all, sigma, v, layout
     out = np.empty((b, hq, d), np.float64)
     kt = np.zeros((total, hkv, d), np.float64) if want_ktilde else None
     lib().oracle_decode_sampled(int(kind), ctypes.c_uint32(seed & 0xFFFFFFFF), ctypes.c_uint32((seed >> 32) & 0xFFFFFFFF),
-                                _p(q), _p(pr.mask), _p(pr.kept), _p(mu_all), _p(sigma), _p(pr.a32), _p(v),
+                                _p(q), _p(pr.mask), _p(pr.kept), _p(pr.codes), _p(pr.scale), _p(mu_all), _p(sigma), _p(pr.a32), _p(v),
                                 ctypes.c_int64(ts), ctypes.c_int64(hs), _p(cu), b, hq, hkv, d, pr.T,
                                 ctypes.c_double(scale), _p(out), _p(kt))
     return (out, kt) if want_ktilde else out

@@ -635,10 +635,13 @@ static double sampled_saliency(int kind, double mu, double sigma, uint32_t seed_
  * rebuilt as  ktilde = w~ / a_j  (0 if a_j == 0) with w~ drawn as above, kept entries are
  * copied back, then Eq. (4).  kind: 1 Gaussian, 2 Exponential.  mu_all32, sigma32 from
  * oracle_row_stats.  ktilde_out (may be NULL) [total,Hkv,D] double receives the rebuilt keys.
- * Other arguments as oracle_decode_literal.
+ * Kept entries as in oracle_decode_literal: the original bf16 bits, or code * scale when the
+ * int8 storage variant is in use (codes != NULL); the statistics are those of the saliencies
+ * before quantisation either way.  Other arguments as oracle_decode_literal.
  */
 void oracle_decode_sampled(int kind, uint32_t seed_lo, uint32_t seed_hi, const uint16_t *q,
-                           const uint32_t *mask, const uint16_t *kept_bf16, const float *mu_all32,
+                           const uint32_t *mask, const uint16_t *kept_bf16, const int8_t *codes,
+                           const float *scale, const float *mu_all32,
                            const float *sigma32, const float *a32, const uint16_t *v,
                            int64_t v_tok_stride, int64_t v_head_stride, const int32_t *cu, int B,
                            int Hq, int Hkv, int D, int T, double softmax_scale, double *out,
@@ -659,7 +662,7 @@ void oracle_decode_sampled(int kind, uint32_t seed_lo, uint32_t seed_hi, const u
             int c = 0;
             for (int j = 0; j < D; ++j) {
                 if (mask[row * MW + j / 32] >> (j % 32) & 1u)
-                    ktilde[j] = bf16_bits_to_f64(kept_bf16[row * T + c++]);
+                    ktilde[j] = kept_value(kept_bf16, codes, scale, row, T, c++);
                 else if (a[j] != 0.0f)
                     ktilde[j] = sampled_saliency(kind, (double)mu_all32[row], (double)sigma32[row], seed_lo,
                                                  seed_hi, (uint32_t)(n0 + t), (uint32_t)h, j) / (double)a[j];

@@ -655,6 +655,32 @@ def test_sampled_decode_is_plain_attention_over_the_exported_rebuilt_keys(kind):
 
 
 @pytest.mark.parametrize("kind", [oracle.GAUSSIAN, oracle.EXPONENTIAL])
+def test_sampled_decode_over_int8_kept_entries(kind):
+    """The int8 storage variant under a sampled recovery function: kept entries are code * scale (the codes and
+    scales of the degenerate path, computed after selection), pruned entries are the very samples of the bf16
+    run (the statistics are those of the saliencies before quantisation), and the output is plain attention
+    over those rebuilt keys."""
+    w, t, a32, pr, mu, sigma = _sampled_setup(43)
+    pq = oracle.quant_int8(pr)
+    out, kt = oracle.decode_sampled(kind, 77, t.q, pq, mu, sigma, t.v, t.layout, t.cu, want_ktilde=True)
+    _, kt_bf16 = oracle.decode_sampled(kind, 77, t.q, pr, mu, sigma, t.v, t.layout, t.cu, want_ktilde=True)
+    bits = np.unpackbits(pr.mask.view(np.uint8), axis=-1, bitorder="little").astype(bool)
+    deq = pq.codes.astype(np.float64) * pq.scale.astype(np.float64)[..., None]      # [total,Hkv,T], channel order
+    assert np.array_equal(kt[bits], deq.reshape(-1))
+    assert np.array_equal(kt[~bits], kt_bf16[~bits])
+    assert np.abs(kt[bits] - kt_bf16[bits]).max() <= 0.5 * pq.scale.max() * (1 + 1e-6)   # half a quantisation step
+    qf, vf = fb(t.q).astype(np.float64), fb(t.v).transpose(1, 0, 2).astype(np.float64)
+    G = w.n_q_heads // w.n_kv_heads
+    for b in range(w.batch):
+        n0, n1 = int(t.cu[b]), int(t.cu[b + 1])
+        for g in range(w.n_q_heads):
+            s = kt[n0:n1, g // G, :] @ qf[b, g] / math.sqrt(w.head_dim)
+            p = np.exp(s - s.max())
+            p /= p.sum()
+            assert np.allclose(out[b, g], p @ vf[n0:n1, g // G, :], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("kind", [oracle.GAUSSIAN, oracle.EXPONENTIAL])
 def test_sampled_entries_have_the_moments_of_their_distribution(kind):
     """Rebuilt pruned entries times a are the sampled saliencies: Gaussian N(mu, sigma^2), Exponential with
     mean mu (hence standard deviation mu), per row; checked through standardised samples over many rows."""
