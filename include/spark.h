@@ -81,7 +81,7 @@ typedef struct spark_desc {
                                  the *_values entry points only; 0 where values stay dense */
     int32_t stats;            /* 1: spark_prune also stores, per (token, KV head), the mean and the standard
                                  deviation of the saliency over all channels (8 bytes more per row; needed by
-                                 spark_decode_attn_sampled; bf16 storage only); 0: not stored */
+                                 spark_decode_attn_sampled); 0: not stored */
     int32_t tail_capacity;    /* rows per sequence in the appended-token buffers of spark_decode_attn_tail;
                                  0 elsewhere.  Enters the decode workspace size: keep it the same for the
                                  workspace query, its init and the calls. */
@@ -205,7 +205,7 @@ spark_status spark_check_packed(const spark_desc *desc, const void *packed, int3
  * so a call with the same seed repeats, and a caller that wants fresh samples per step changes the seed.
  * A Gaussian sample may be negative (it is not clamped).
  *
- *   packed    written by spark_prune with desc->stats = 1 (bf16 storage)
+ *   packed    written by spark_prune with desc->stats = 1 (bf16 or int8 storage of the kept entries)
  *   recovery  spark_recovery
  *   seed      64 bits: seed_lo = low word, seed_hi = high word
  * Other arguments as spark_decode_attn.  This variant draws 128 - keep variates per (token, KV head) and is

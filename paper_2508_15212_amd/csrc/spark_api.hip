@@ -32,7 +32,6 @@ bool desc_ok(const spark_desc *d, spark_status *why)
     if (!(G == 1 || G == 2 || G == 4 || G == 8 || G == 16)) return false;
     if (d->pack_dtype != SPARK_PACK_BF16 && d->pack_dtype != SPARK_PACK_INT8) return false;
     if (d->out_dtype != SPARK_OUT_BF16 && d->out_dtype != SPARK_OUT_F32) return false;
-    if (d->stats && d->pack_dtype != SPARK_PACK_BF16) return false;
     *why = SPARK_OK;
     return true;
 }

@@ -690,8 +690,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             auto unif = [&](uint32_t c) {   // ((x >> 9) + 0.5) / 2^23: exact in float32
                 return ((float)(mix(base + c * kGold) >> 9) + 0.5f) * (1.0f / 8388608.0f);
             };
-            const float mu_a = __uint_as_float(r[5]);
-            const float sg = __uint_as_float(*reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, 6)));
+            // (the statistics follow mu, and the scale where the kept entries are int8 codes)
+            const float mu_a = INT8 ? __uint_as_float(*reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, 6)))
+                                    : __uint_as_float(r[5]);
+            const float sg = __uint_as_float(*reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, INT8 ? 7 : 6)));
             constexpr float kLn2 = 0.69314718055994530942f;
 #pragma unroll
             for (int wd = 0; wd < 4; ++wd) {
@@ -1033,8 +1035,8 @@ hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
     // rows that carry the all-channel statistics are longer: only the any-length instantiations read them
     const int T = P.L.stats ? -1 : P.L.T;
     if (P.L.topp) return launch_one<G, 0, 0, 0, 0, 1>(P, nblocks, st);
-    if (P.rec == 1) return launch_one<G, 0, 0, 0, 1>(P, nblocks, st);
-    if (P.rec == 2) return launch_one<G, 0, 0, 0, 2>(P, nblocks, st);
+    if (P.rec == 1) return P.L.int8 ? launch_one<G, 0, 1, 0, 1>(P, nblocks, st) : launch_one<G, 0, 0, 0, 1>(P, nblocks, st);
+    if (P.rec == 2) return P.L.int8 ? launch_one<G, 0, 1, 0, 2>(P, nblocks, st) : launch_one<G, 0, 0, 0, 2>(P, nblocks, st);
     if (P.packed_v) {
         if (P.L.int8) return T == 26 ? launch_pv<G, 26, 1>(P, nblocks, st) : launch_pv<G, 0, 1>(P, nblocks, st);
         if (T == 26) return launch_pv<G, 26>(P, nblocks, st);

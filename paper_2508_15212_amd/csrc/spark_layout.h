@@ -8,6 +8,7 @@
 //   int8 storage : [ m0 m1 m2 m3 | mu | scale | c0 ... c(nv-1) | pad ]   nv = ceil(T/4)
 //   value cache  : [ m0 m1 m2 m3 | v0 v1 ... v(nv-1) | pad ]        (pruned entries are dropped: no statistic)
 //   bf16 + stats : [ m0 m1 m2 m3 | mu | mu_all | sigma_all | v0 ... v(nv-1) | pad ]   (for the sampled recovery functions)
+//   int8 + stats : [ m0 m1 m2 m3 | mu | scale | mu_all | sigma_all | c0 ... c(nv-1) | pad ]
 //   top-p rows   : [ m0 m1 m2 m3 | mu | count ]        the kept entries live in a value stream, see below
 //
 // m0..m3 is the 128-bit channel mask (bit j%32 of word j/32 = channel j kept), mu the
@@ -80,7 +81,7 @@ static inline SPARK_HD SparkLayout spark_make_layout(int T, int int8, int batch,
     L.values = 0;
     L.stats = stats;
     L.nv = int8 ? (T + 3) / 4 : (T + 1) / 2;
-    L.val0 = int8 ? 6 : (stats ? 7 : 5);
+    L.val0 = 5 + (int8 ? 1 : 0) + (stats ? 2 : 0);
     int ndw = L.val0 + L.nv;
     L.ndw = (ndw + 1) & ~1;
     L.nq = L.ndw / 4;

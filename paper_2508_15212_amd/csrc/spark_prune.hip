@@ -269,19 +269,19 @@ __device__ __forceinline__ float fold_pair(float A, float B, bool hi)
 // One tile by one wavefront.  FULL: wavefront number wt (over tiles, then heads) of those that take the tiles which
 // hold all 64 tokens (the first total_tokens / 64 of every head); otherwise wt = the KV head whose partly filled
 // last tile this wavefront takes.  Two instantiations, so that the hot one carries no bounds logic.
-// MODE: 0 = bf16 kept entries, 1 = int8 codes + scale, 2 = bf16 plus the all-channel mean and standard
-// deviation of the row's saliencies (App. "Caching Pruned Channel Statistics", for the sampled recovery).
+// MODE: bit 0 = int8 codes + scale instead of bf16 kept entries; bit 1 = the rows also carry the all-channel mean
+// and standard deviation of the row's saliencies (App. "Caching Pruned Channel Statistics", for the sampled recovery).
 // VALUES: the rows are value-cache rows (App. "Pruning Value Cache Channels"): the score of a channel is
 // |v| itself, there is no channel weight, no sequence bookkeeping and no statistic of the pruned set.
 #ifndef SPARK_PRUNE_MIN_WAVES
-#define SPARK_PRUNE_MIN_WAVES (MODE == 2 ? 6 : 7)
+#define SPARK_PRUNE_MIN_WAVES (MODE >= 2 ? 6 : 7)
 #endif
 template <int MODE, bool FULL, bool VALUES>
 __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64_t k_tok_stride, int64_t k_head_stride,
                                            const int32_t *__restrict__ cu, uint8_t *__restrict__ packed,
                                            const SparkLayout &L, const int rows_per_flush, const int wave, const int64_t wt)
 {
-    constexpr bool INT8 = (MODE == 1), STATS = (MODE == 2);
+    constexpr bool INT8 = (MODE & 1) != 0, STATS = (MODE & 2) != 0;
     extern __shared__ __align__(16) uint8_t smem[];
     const int lane = threadIdx.x & 63;
     const int64_t full_tiles = L.total_tokens / SPARK_TILE_TOKENS;
@@ -650,12 +650,12 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
             row[2] = valid ? (spread16(e_hi) | (spread16(o_hi) << 1)) : low_bits(T - 64);
             row[3] = valid ? (spread16(e_hi >> 16) | (spread16(o_hi >> 16) << 1)) : low_bits(T - 96);
             if (!VALUES) row[4] = __float_as_uint(mu);
-            if (STATS) {
-                row[5] = valid ? muall : 0u;
-                row[6] = valid ? __float_as_uint(sqrtf(sqreg * (1.0f / (float)SPARK_D))) : 0u;
+            if (STATS && valid) {
+                row[INT8 ? 6 : 5] = muall;
+                row[INT8 ? 7 : 6] = __float_as_uint(sqrtf(sqreg * (1.0f / (float)SPARK_D)));
             }
             if (!valid) {
-                for (int d = VALUES ? 4 : (STATS ? 7 : 5); d < sw; ++d) row[d] = 0u;
+                for (int d = VALUES ? 4 : 5; d < sw; ++d) row[d] = 0u;
             } else {
                 const int vend = L.val0 + (T + 1) / 2;               // one past the last staged bf16 word
                 if (T & 1) row[vend - 1] &= 0xFFFFu;                 // unused upper half of the last word
@@ -795,8 +795,8 @@ __global__ void spark_unpack_kernel(const uint8_t *__restrict__ packed, SparkLay
         for (int m = 0; m < 4; ++m) mask_out[idx * 4 + m] = word(m);
     if (mu_out && !L.values) mu_out[idx] = __uint_as_float(word(4));
     if (L.stats) {
-        if (mu_all_out) mu_all_out[idx] = __uint_as_float(word(5));
-        if (sigma_out) sigma_out[idx] = __uint_as_float(word(6));
+        if (mu_all_out) mu_all_out[idx] = __uint_as_float(word(L.int8 ? 6 : 5));
+        if (sigma_out) sigma_out[idx] = __uint_as_float(word(L.int8 ? 7 : 6));
     }
     if (L.int8) {
         if (scale_out) scale_out[idx] = __uint_as_float(word(5));
@@ -836,14 +836,21 @@ hipError_t launch_tiles(const uint16_t *x, int64_t tok_stride, int64_t head_stri
                            packed, L, spark_prune_rows_per_flush(L), tail_blocks);
         return hipGetLastError();
     };
+    const int mode = VALUES ? 0 : (L.int8 ? 1 : 0) + (L.stats ? 2 : 0);
     if (tail_blocks == 0) {
-        if (VALUES || (!L.int8 && !L.stats)) return launch(&spark_prune_kernel<0, VALUES, false>);
-        if (L.int8) return launch(&spark_prune_kernel<1, false, false>);
-        return launch(&spark_prune_kernel<2, false, false>);
+        switch (mode) {
+            case 0: return launch(&spark_prune_kernel<0, VALUES, false>);
+            case 1: return launch(&spark_prune_kernel<1, false, false>);
+            case 2: return launch(&spark_prune_kernel<2, false, false>);
+            default: return launch(&spark_prune_kernel<3, false, false>);
+        }
     }
-    if (VALUES || (!L.int8 && !L.stats)) return launch(&spark_prune_kernel<0, VALUES, true>);
-    if (L.int8) return launch(&spark_prune_kernel<1, false, true>);
-    return launch(&spark_prune_kernel<2, false, true>);
+    switch (mode) {
+        case 0: return launch(&spark_prune_kernel<0, VALUES, true>);
+        case 1: return launch(&spark_prune_kernel<1, false, true>);
+        case 2: return launch(&spark_prune_kernel<2, false, true>);
+        default: return launch(&spark_prune_kernel<3, false, true>);
+    }
 }
 
 }  // namespace

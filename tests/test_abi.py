@@ -152,7 +152,8 @@ def test_statistics_rows_and_sampled_decode_arguments():
     rows = 8 * 32768 * 8
     ds = _desc(stats=1)
     assert spark.packed_bytes(ds) == 256 + 2 * 8 * 8 * 128 * 4 + rows * 80      # 72 + mean + standard deviation
-    assert spark.packed_bytes(_desc(stats=1, pack_dtype=spark.PACK_INT8)) == 0  # bf16 storage only
+    # int8 storage: mask 16 + mu 4 + scale 4 + mean and standard deviation 8 + 7 code words 28 = 60 -> 64-byte rows
+    assert spark.packed_bytes(_desc(stats=1, pack_dtype=spark.PACK_INT8)) == 256 + 2 * 8 * 8 * 128 * 4 + rows * 64
     assert spark.packed_bytes(_desc(stats=2)) == 0
     ws = spark.decode_workspace_bytes(ds)
     u64 = ctypes.c_uint64(1)

@@ -25,8 +25,6 @@ def _one_case(rng, idx, int8=False):
     Tv = int(rng.choice([0, 0, 26, 38, 64, 90]))
     cap = int(rng.choice([0, 0, 3, 70, 300]))
     stats = int(rng.choice([0, 0, 1]))            # rows that also carry the all-channel mean / standard deviation
-    if int8:
-        stats = 0                                 # (statistics rows are bf16 storage only)
     rec = int(rng.choice([0, 1, 2])) if (stats and not Tv and not cap) else 0
     w = wl.small(name=f"sweep{idx}", batch=batch, n_q_heads=G * hkv, n_kv_heads=hkv, keep=T, seqlens=lens,
                  seed=1000 + idx)

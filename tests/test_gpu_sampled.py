@@ -95,3 +95,49 @@ def test_sampled_decode_many_splits_and_ragged_tiles():
     spark.decode_attn_sampled(desc, dq, packed, dv, dcu, out, spark.new_decode_workspace(desc),
                               spark.RECOVER_GAUSSIAN, 11)
     assert np.abs(out.cpu().numpy() - ref).max() <= MAX_ABS
+
+
+@pytest.mark.parametrize("kind", [spark.RECOVER_GAUSSIAN, spark.RECOVER_EXPONENTIAL])
+@pytest.mark.parametrize("G,Hkv,T", [(4, 2, 26), (8, 1, 64), (1, 2, 37)])
+def test_int8_storage_with_statistics_rows(kind, G, Hkv, T):
+    """int8 codes and a statistics-carrying row together: codes, scales, masks bit-exact, the statistics those of
+    the saliencies before quantisation, sampled and degenerate decode against the oracle over code * scale."""
+    w = wl.small(name=f"i8stats{kind}_{G}_{T}", batch=3, n_q_heads=G * Hkv, n_kv_heads=Hkv, keep=T,
+                 seqlens=(300, 0, 131), seed=660 + G + T)
+    t = wl.generate(w)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pq = oracle.quant_int8(oracle.prune(t.k, t.layout, a32, t.cu, T))
+    mu, sigma = oracle.row_stats(t.k, t.layout, a32, t.cu)
+    desc = make_desc(w, "HND")
+    desc.stats = 1
+    desc.pack_dtype = spark.PACK_INT8
+    dk, dv, dq = to_dev(t.k), to_dev(t.v), to_dev(t.q)
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.empty(max(spark.packed_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    spark.prune(desc, dk, to_dev(t.qwin), dcu, packed)
+    assert spark.check_packed(desc, packed) == 0
+    mask = torch.empty((w.total, Hkv, 4), dtype=torch.int32, device="cuda")
+    codes = torch.empty((w.total, Hkv, T), dtype=torch.int8, device="cuda")
+    mup = torch.empty((w.total, Hkv), dtype=torch.float32, device="cuda")
+    scale, mua, sg = torch.empty_like(mup), torch.empty_like(mup), torch.empty_like(mup)
+    spark.unpack(desc, packed, mask, codes, mup, scale, None)
+    spark.unpack_stats(desc, packed, mua, sg)
+    torch.cuda.synchronize()
+    assert np.array_equal(mask.cpu().numpy().view(np.uint32), pq.mask)
+    assert np.array_equal(codes.cpu().numpy(), pq.codes)
+    assert np.array_equal(scale.cpu().numpy(), pq.scale)
+    assert np.allclose(mup.cpu().numpy(), pq.mu32, rtol=1e-5, atol=1e-30)
+    assert np.allclose(mua.cpu().numpy(), mu, rtol=1e-5, atol=1e-30)
+    assert np.allclose(sg.cpu().numpy(), sigma, rtol=1e-5, atol=1e-6 * np.abs(mu).max())
+    ws = spark.new_decode_workspace(desc)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    seed = 0xABCDEF0123456789 + T
+    spark.decode_attn_sampled(desc, dq, packed, dv, dcu, out, ws, kind, seed)
+    ref = oracle.decode_sampled(kind, seed, t.q, pq, mu, sigma, t.v, t.layout, t.cu)
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref)
+    print(f"{w.name}: max|err|={err.max():.3e} mean|err|={err.mean():.3e}")
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS and np.all(out.cpu().numpy()[1] == 0)
+    # the same cache under the degenerate recovery function
+    spark.decode_attn(desc, dq, packed, dv, dcu, out, ws)
+    ref0 = oracle.decode_literal(t.q, pq, t.v, t.layout, t.cu)
+    assert np.abs(out.cpu().numpy().astype(np.float64) - ref0).max() <= MAX_ABS
