@@ -106,11 +106,23 @@ __device__ __forceinline__ float wave_max(float x)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
+// Sum over the 64 lanes, returned wave-uniform.  Data-parallel-primitive moves (shifts by 1, 2, 4, 8 inside each
+// row of 16 lanes, then two row broadcasts) leave the total in lane 63; no LDS round trips.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add_step(float x)
+{
+    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xF, false));
+}
+
 __device__ __forceinline__ float wave_sum(float x)
 {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-    return x;
+    x = dpp_add_step<0x111, 0xF>(x);   // row_shr 1
+    x = dpp_add_step<0x112, 0xF>(x);   // row_shr 2
+    x = dpp_add_step<0x114, 0xF>(x);   // row_shr 4
+    x = dpp_add_step<0x118, 0xF>(x);   // row_shr 8
+    x = dpp_add_step<0x142, 0xA>(x);   // row_bcast 15 -> rows 1, 3
+    x = dpp_add_step<0x143, 0xC>(x);   // row_bcast 31 -> rows 2, 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
 // device-scope (all XCDs) relaxed store / load of one float
@@ -620,10 +632,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                 const uint32_t before = (uint32_t)wave_inclusive_sum_i32((int)words) - words;
                 const uint32_t *vsrc = reinterpret_cast<const uint32_t *>(P.packed + L.off_vals) + (int64_t)h * L.vals_head_words +
                                        reinterpret_cast<const uint32_t *>(P.packed + L.off_dir)[(int64_t)h * (L.n_tiles + 1) + tile] + before;
-                int tmax = (int)cnt;
-#pragma unroll
-                for (int o = 32; o >= 1; o >>= 1) { const int y = __shfl_xor(tmax, o); tmax = tmax > y ? tmax : y; }
-                tmax = __builtin_amdgcn_readfirstlane(tmax);
+                const int tmax = (int)wave_max((float)cnt);     // (counts are at most 128: exact in float32)
                 // The row's words are fetched 16 at a time (32 entries, four 16-byte loads in flight per lane: one
                 // memory round trip per 32 entries instead of one per word); a load whose first word lies past the
                 // lane's row is masked off, one that straddles the row's end reads at most three words of the next

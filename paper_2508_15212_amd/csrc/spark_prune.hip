@@ -265,6 +265,29 @@ __device__ __forceinline__ float fold_pair(float A, float B, bool hi)
     const float stay = hi ? B : A, go = hi ? A : B;
     return stay + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(go), CTRL, 0xF, 0xF, true));
 }
+// The same step across the halves of the wavefront and across neighbouring rows of 16 lanes, where this chip's
+// lane-swap instructions do the selecting for free (two instructions a step instead of three):
+// fold_halves gives A[l] + A[l + 32] in lanes 0..31 and B[l - 32] + B[l] in lanes 32..63,
+// fold_rows   gives A[l] + A[l ^ 16] in rows 0 and 2 and B[l ^ 16] + B[l] in rows 1 and 3.
+__device__ __forceinline__ float fold_halves(float A, float B)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(A), __float_as_uint(B), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float fold_rows(float A, float B)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(A), __float_as_uint(B), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// Four levels of these steps (halves, rows, row rotate by 4, row rotate by 8) and a sum over the lanes of every quad
+// fold 16 tokens x 64 lanes into one register: token t of the sixteen (bits t0..t3) ends up in the four lanes
+// 32 t0 + 16 t1 + 4 t2 + 8 t3 + {0, 1, 2, 3}.
+__device__ __forceinline__ float quad_sum(float x)
+{
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    return x;
+}
 
 // One tile by one wavefront.  FULL: wavefront number wt (over tiles, then heads) of those that take the tiles which
 // hold all 64 tokens (the first total_tokens / 64 of every head); otherwise wt = the KV head whose partly filled
@@ -360,9 +383,10 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
     // lane t collects, for token t, the ballots of kept even channels (em) and kept odd channels (om)
     uint64_t em = 0, om = 0;
     uint64_t tok_bit = 1;                                   // one-hot: the lane of the row being searched
-    float mureg = 0.0f;                                     // lane t: sum of pruned saliencies
+    float mureg = 0.0f;                                     // sums of pruned saliencies: token t in lane
+                                                            // 32 t0 + 16 t1 + 4 t2 + 8 t3 + (t >> 4)
     uint32_t muall = 0;                                     // lane t: mean saliency over all channels (bits)
-    float sqreg = 0.0f;                                     // lane t: sum of squared deviations from it
+    float sqreg = 0.0f;                                     // sums of squared deviations from it, same places
 
     // Rows are fetched a block ahead: while one block of PF rows is searched the next is in flight,
     // in two register sets that swap roles.
@@ -605,27 +629,20 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
     };
 
     // the PF rows held in x (tokens tb .. tb+PF-1); returns their pruned-saliency partials folded into one
-    // register (token tb + u in the lanes with l & 7 == u)
+    // register: row u (bits u0 u1 u2) in the lanes with l5 = u0, l4 = u1, l2 = u2
+    auto fold8 = [&](const float (&p)[PF]) __attribute__((always_inline)) -> float {
+        const float f01 = fold_halves(p[0], p[1]), f23 = fold_halves(p[2], p[3]);
+        const float f45 = fold_halves(p[4], p[5]), f67 = fold_halves(p[6], p[7]);
+        return fold_pair<0x124>(fold_rows(f01, f23), fold_rows(f45, f67), lane & 4);     // row_ror 4
+    };
     auto do_block = [&](const uint32_t (&x)[PF], int tb) __attribute__((always_inline)) -> float2 {
         float ps[PF], qs[PF];
 #pragma unroll
         for (int u0 = 0; u0 < PF; u0 += kBatch) do_batch(x, u0, tb, ps, qs);
         if constexpr (VALUES) return make_float2(0.0f, 0.0f);
         float q07 = 0.0f;
-        if constexpr (STATS) {
-            const float g01 = fold_pair<0xB1>(qs[0], qs[1], lane & 1);
-            const float g23 = fold_pair<0xB1>(qs[2], qs[3], lane & 1);
-            const float g45 = fold_pair<0xB1>(qs[4], qs[5], lane & 1);
-            const float g67 = fold_pair<0xB1>(qs[6], qs[7], lane & 1);
-            q07 = fold_pair<0x124>(fold_pair<0x4E>(g01, g23, lane & 2), fold_pair<0x4E>(g45, g67, lane & 2), lane & 4);
-        }
-        const float f01 = fold_pair<0xB1>(ps[0], ps[1], lane & 1);     // quad_perm [1,0,3,2]
-        const float f23 = fold_pair<0xB1>(ps[2], ps[3], lane & 1);
-        const float f45 = fold_pair<0xB1>(ps[4], ps[5], lane & 1);
-        const float f67 = fold_pair<0xB1>(ps[6], ps[7], lane & 1);
-        const float f03 = fold_pair<0x4E>(f01, f23, lane & 2);         // quad_perm [2,3,0,1]
-        const float f47 = fold_pair<0x4E>(f45, f67, lane & 2);
-        return make_float2(fold_pair<0x124>(f03, f47, lane & 4), q07);   // row_ror 4
+        if constexpr (STATS) q07 = fold8(qs);
+        return make_float2(fold8(ps), q07);
     };
 
     // ---- rows t0 .. t0 + rows_per_flush - 1 leave the staging area, lane = token (the other lanes idle)
@@ -636,10 +653,14 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
         // of the row loop and kept in registers across it)
         int ln = lane;
         asm volatile("" : "+v"(ln));
+        // lane = token fetches its row's sums from the lane the reduction left them in
+        const int src_lane = 32 * (ln & 1) + 16 * ((ln >> 1) & 1) + 4 * ((ln >> 2) & 1) + 8 * ((ln >> 3) & 1) + (ln >> 4);
+        const float mu_sum = VALUES ? 0.0f : __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane * 4, __float_as_int(mureg)));
+        const float sq_sum = STATS ? __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane * 4, __float_as_int(sqreg))) : 0.0f;
         if (ln >= t0 && ln < t0 + rows_per_flush) {
             const bool valid = ln < nvalid;
             uint32_t *row = stage + (size_t)(ln - t0) * sw;
-            const float mu = (!VALUES && valid && T < SPARK_D) ? (mureg / (float)(SPARK_D - T)) : 0.0f;
+            const float mu = (!VALUES && valid && T < SPARK_D) ? (mu_sum / (float)(SPARK_D - T)) : 0.0f;
             // channel-ordered mask: bit 2l of the row = even ballot bit l, bit 2l+1 = odd ballot bit l.
             // Rows past the last token carry a well-formed mask (channels 0..T-1) and zero values, so a
             // reader that walks exactly T bits never runs off the mask.
@@ -652,7 +673,7 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
             if (!VALUES) row[4] = __float_as_uint(mu);
             if (STATS && valid) {
                 row[INT8 ? 6 : 5] = muall;
-                row[INT8 ? 7 : 6] = __float_as_uint(sqrtf(sqreg * (1.0f / (float)SPARK_D)));
+                row[INT8 ? 7 : 6] = __float_as_uint(sqrtf(sq_sum * (1.0f / (float)SPARK_D)));
             }
             if (!valid) {
                 for (int d = VALUES ? 4 : 5; d < sw; ++d) row[d] = 0u;
@@ -732,15 +753,12 @@ __device__ __forceinline__ void prune_tile(const uint16_t *__restrict__ k, int64
         const float2 fb = do_block(xb, tb + PF);
         if constexpr (!VALUES) {
             // pruned-saliency sums of these 16 tokens: pair the two blocks, finish across the four rows
-            float s = fold_pair<0x128>(fa.x, fb.x, lane & 8);              // row_ror 8
-            s += __shfl_xor(s, 16);
-            s += __shfl_xor(s, 32);
-            if ((lane >> 4) == (tb >> 4)) mureg = s;
+            // (the sixteen sums go to the lanes whose two low bits are the group's number, see quad_sum above)
+            const float s = quad_sum(fold_pair<0x128>(fa.x, fb.x, lane & 8));              // row_ror 8
+            if ((lane & 3) == (tb >> 4)) mureg = s;
             if constexpr (STATS) {
-                float s2 = fold_pair<0x128>(fa.y, fb.y, lane & 8);
-                s2 += __shfl_xor(s2, 16);
-                s2 += __shfl_xor(s2, 32);
-                if ((lane >> 4) == (tb >> 4)) sqreg = s2;
+                const float s2 = quad_sum(fold_pair<0x128>(fa.y, fb.y, lane & 8));
+                if ((lane & 3) == (tb >> 4)) sqreg = s2;
             }
         }
         if (((tb + 2 * PF) & (rows_per_flush - 1)) == 0) {
