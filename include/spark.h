@@ -75,7 +75,11 @@ typedef struct spark_desc {
     float   softmax_scale;    /* 0 => 1/sqrt(head_dim) */
     int32_t n_splits;         /* decode: > 0 cuts every sequence into this many blocks per KV head; 0 => the
                                  library cuts sequences in proportion to their length (ragged batches:
-                                 long sequences get more blocks).  Must be the same for the workspace
+                                 long sequences get more blocks), and batches of 32 to 256 short sequences
+                                 are dealt out tile by tile to independent wavefronts (the balanced cut);
+                                 -1 asks for the balanced cut whenever it exists (batch <= 256, at most 8
+                                 query heads per KV head; spark_decode_attn and spark_decode_attn_tail; the
+                                 other entry points cut by length).  Must be the same for the workspace
                                  query, its init and the calls. */
     int32_t keep_v;           /* T_v in [1, D]: channels kept per (token, KV head) of the VALUE cache, used by
                                  the *_values entry points only; 0 where values stay dense */
@@ -345,8 +349,9 @@ spark_status spark_unpack_topp(const spark_desc *desc, const void *packed, uint3
  * as spark_decode_attn, without the workspace: split partials and arrival counters live in an array of
  * SPARK_STATIC_WORKSPACE_BYTES inside the library's device image (one copy per GPU, held until the process
  * ends).  The call allocates nothing, frees nothing and prepares the array itself (no init call).
- *   - SPARK_ERR_WORKSPACE_TOO_SMALL if spark_decode_workspace(desc) exceeds SPARK_STATIC_WORKSPACE_BYTES
- *     (all five benchmark shapes fit; the largest needs 2.7 MB);
+ *   - SPARK_ERR_WORKSPACE_TOO_SMALL if the partial states do not fit SPARK_STATIC_WORKSPACE_BYTES (all five
+ *     benchmark shapes fit; the largest needs 2.7 MB; where the balanced cut of a ragged batch would not fit
+ *     but the cut by length does, the call uses the cut by length);
  *   - the first call on a GPU looks the array's address up (hipGetSymbolAddress): make it outside a capture;
  *   - every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (two streams) race.
  */

@@ -22,7 +22,7 @@ bool desc_ok(const spark_desc *d, spark_status *why)
     if (d->batch > (1 << 18)) return false;
     if (d->keep < 1 || d->keep > d->head_dim) return false;
     if (d->n_q_heads % d->n_kv_heads) return false;
-    if (d->n_splits < 0 || d->n_splits > 4096) return false;
+    if (d->n_splits < -1 || d->n_splits > 4096) return false;
     if (d->keep_v < 0 || d->keep_v > d->head_dim) return false;
     if (d->tail_capacity < 0 || d->tail_capacity > (1 << 20)) return false;
     if (d->stats != 0 && d->stats != 1) return false;
@@ -64,7 +64,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 // still see at least 4 tiles (one per wavefront).  Sequences are cut into chunks of chunk_tiles tiles, so long
 // sequences of a ragged batch get more blocks than short ones; n_splits > 0 (or a batch too large for the
 // in-kernel numbering of the chunks) asks for the same number of chunks for every sequence instead.
-spark::DecodePlan plan_of(const spark_desc *d)
+spark::DecodePlan plan_of(const spark_desc *d, bool allow_balanced = true)
 {
     spark::DecodePlan p;
     p.tail_slots = d->tail_capacity > 0 ? (d->tail_capacity + 255) / 256 : 1;
@@ -88,6 +88,23 @@ spark::DecodePlan plan_of(const spark_desc *d)
         p.nchunk_max = d->batch * p.fixed_splits;
     else   // a sequence of len tokens spans at most len / 64 + 2 tiles, and rounding up costs at most one chunk
         p.nchunk_max = (int)((tiles + 2 * (int64_t)d->batch) / chunk + d->batch + 1);
+    // Many sequences, each too short to be cut: one block per (sequence, KV head) would make the launch last as
+    // long as its longest sequence.  Then (or on request, n_splits = -1) the (sequence, tile) items of a KV head
+    // are dealt out evenly to as many wavefronts as are resident at once, 2048 over all heads.  The mode holds
+    // the batch's sequence table in registers (at most 256 sequences) and numbers items in 32 bits.
+    p.warm_waves = 0;
+    p.chunk_ids = p.nchunk_max;
+    const int64_t pairs = (int64_t)d->batch * d->n_kv_heads;
+    const bool wanted = d->n_splits == -1 || (d->n_splits == 0 && d->batch >= 32 && pairs >= 256);
+    if (allow_balanced && wanted && d->batch <= 256 && d->n_q_heads / d->n_kv_heads <= 8) {
+        const int per_head = 512 / d->n_kv_heads > 0 ? 512 / d->n_kv_heads : 1;     // blocks of four wavefronts
+        const int64_t nw = 4 * (int64_t)per_head;
+        if ((tiles + 2 * (int64_t)d->batch + 1) * nw < ((int64_t)1 << 32)) {
+            p.warm_waves = (int)nw;
+            const int ids = (int)nw + 2 * d->batch;
+            if (p.chunk_ids < ids) p.chunk_ids = ids;
+        }
+    }
     return p;
 }
 
@@ -103,10 +120,10 @@ int pick_splits(const spark_desc *d)
 
 // partial slots in the workspace: one per (chunk, q head), then the appended rows' (one per 256 rows of
 // capacity, at least one, per (batch, q head), so a workspace serves calls with and without appended rows)
-size_t partial_slots(const spark_desc *d)
+size_t partial_slots(const spark_desc *d, bool allow_balanced = true)
 {
-    const spark::DecodePlan p = plan_of(d);
-    return (size_t)p.nchunk_max * d->n_q_heads + (size_t)d->batch * d->n_q_heads * p.tail_slots;
+    const spark::DecodePlan p = plan_of(d, allow_balanced);
+    return (size_t)p.chunk_ids * d->n_q_heads + (size_t)d->batch * d->n_q_heads * p.tail_slots;
 }
 
 // The arrival counters sit at the START of the workspace, so their position depends on batch and n_kv_heads
@@ -234,7 +251,7 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
                            const void *packed_v, const int32_t *cu_seqlens, void *out, void *workspace,
                            size_t workspace_bytes, void *hip_stream, const void *tail_k = nullptr,
                            const void *tail_v = nullptr, const int32_t *tail_len = nullptr, int rec = 0,
-                           uint64_t seed = 0, bool topp = false)
+                           uint64_t seed = 0, bool topp = false, bool allow_balanced = true)
 {
     spark_status why;
     if (!desc_ok(desc, &why)) return why;
@@ -253,12 +270,12 @@ spark_status decode_common(const spark_desc *desc, const void *q_bf16, const voi
         if (!tail_v || !tail_len || desc->tail_capacity < 1) return SPARK_ERR_INVALID_ARG;
         if (!aligned(tail_k, 16) || !aligned(tail_v, 16) || !aligned(tail_len, 4)) return SPARK_ERR_INVALID_ARG;
     }
-    if (workspace_bytes < spark_decode_workspace(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
+    const size_t slots = partial_slots(desc, allow_balanced);
+    if (workspace_bytes < slots * (SPARK_D + 2) * sizeof(float) + counter_bytes(desc)) return SPARK_ERR_WORKSPACE_TOO_SMALL;
     const SparkLayout L = topp ? topp_layout_of(desc) : layout_of(desc);
     SparkLayout Lv = L;
     if (packed_v) Lv = values_layout_of(desc);
-    const spark::DecodePlan plan = plan_of(desc);
-    const size_t slots = partial_slots(desc);
+    const spark::DecodePlan plan = plan_of(desc, allow_balanced);
     uint32_t *counters = static_cast<uint32_t *>(workspace);
     float *part_acc = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + counter_bytes(desc));
     float *part_ml = part_acc + slots * SPARK_D;
@@ -451,7 +468,14 @@ spark_status spark_decode_attn_static(const spark_desc *desc, const void *q_bf16
     spark_status why;
     if (!desc_ok(desc, &why)) return why;
     if (!v_bf16) return SPARK_ERR_INVALID_ARG;
-    const size_t need = spark_decode_workspace(desc);
+    // the balanced cut of a ragged batch needs more partial slots than the chunked one: where only the chunked
+    // one fits the array, that one is used
+    bool balanced = true;
+    size_t need = spark_decode_workspace(desc);
+    if (need > (size_t)SPARK_STATIC_WORKSPACE_BYTES) {
+        balanced = false;
+        need = partial_slots(desc, false) * (SPARK_D + 2) * sizeof(float) + counter_bytes(desc);
+    }
     if (need > (size_t)SPARK_STATIC_WORKSPACE_BYTES) return SPARK_ERR_WORKSPACE_TOO_SMALL;
     void *ws = scratch_address();
     if (!ws) return SPARK_ERR_HIP;
@@ -462,7 +486,7 @@ spark_status spark_decode_attn_static(const spark_desc *desc, const void *q_bf16
                                     static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return SPARK_ERR_HIP;
     return decode_common(desc, q_bf16, packed, v_bf16, nullptr, cu_seqlens, out, ws, SPARK_STATIC_WORKSPACE_BYTES,
-                         hip_stream);
+                         hip_stream, nullptr, nullptr, nullptr, 0, 0, false, balanced);
 }
 
 }  // extern "C"

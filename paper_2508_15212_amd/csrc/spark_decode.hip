@@ -55,9 +55,11 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.fixed_splits = plan.fixed_splits;
     P.chunk_tiles = plan.chunk_tiles;
     P.nchunk_max = plan.nchunk_max;
+    // balanced mode: dense values, degenerate recovery, rows of one length, query groups up to 8 (else chunks)
+    P.warm_waves = (!packed_v && rec == 0 && !L.topp && Hq / L.n_kv_heads <= 8) ? plan.warm_waves : 0;
     P.tail_slots = plan.tail_slots;
     P.ntail = tail_k ? plan.tail_slots : 0;
-    P.tail_base = (int64_t)plan.nchunk_max * Hq;
+    P.tail_base = (int64_t)plan.chunk_ids * Hq;
     P.tail_k = tail_k;
     P.tail_v = tail_v;
     P.tail_len = tail_len;
@@ -68,7 +70,7 @@ hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const ui
     P.scale_log2 = softmax_scale * 1.44269504088896340736f;
     P.L = L;
     const int G = P.Hq / P.Hkv;
-    const int nblocks = P.Hkv * (P.nchunk_max + L.batch * P.ntail);
+    const int nblocks = P.Hkv * ((P.warm_waves > 0 ? P.warm_waves / kDecodeWaves : P.nchunk_max) + L.batch * P.ntail);
     P.trace = (g_timeline != nullptr && (size_t)nblocks <= g_timeline_blocks) ? g_timeline : nullptr;
     switch (G) {
         case 1: return launch_g<1>(P, nblocks, st);

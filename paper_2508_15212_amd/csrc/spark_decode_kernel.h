@@ -61,9 +61,17 @@ struct DecodeParams {
     // Slot of (global chunk c, q head) = c * Hq + head; the appended rows' slots follow at tail_base:
     // ((b * Hq + head) * tail_slots + part).
     int fixed_splits, chunk_tiles, nchunk_max;
+    // Balanced mode (warm_waves > 0; ragged batches of many short sequences): the (sequence, tile) items of a KV
+    // head, sequences back to back, are dealt out in equal contiguous ranges to warm_waves wavefronts, each of
+    // which works on its own and leaves one partial per sequence it touches.  Wavefront w covers items
+    // [w * I / warm_waves, (w + 1) * I / warm_waves) of the I items; the partial of (wavefront w, sequence b) has
+    // chunk id w + b (both grow along the item list, so the ids of one sequence are consecutive and no two
+    // pairs share one); a sequence without tokens has the single id warm_waves + batch + b: warm_waves + 2 * batch
+    // ids in all.
+    int warm_waves;
     int ntail;               // blocks per (batch, KV head) for the appended rows, 256 rows each (0: none)
     int tail_slots;          // slots reserved per (batch, q head) for them (>= max(1, ntail))
-    int64_t tail_base;       // = nchunk_max * Hq
+    int64_t tail_base;       // first of them: the number of chunk ids the workspace provides for, times Hq
     const uint16_t *tail_k, *tail_v;   // appended never-pruned rows [B, tail_cap, Hkv, 128] bf16, or NULL
     const int32_t *tail_len;           // [B]
     int tail_cap;
@@ -191,6 +199,97 @@ __device__ __forceinline__ SeqChunks locate_chunks(const DecodeParams &P, int B,
     return r;
 }
 
+// ---------------------------------------------------------------- balanced mode: the batch as a list of items
+
+// The batch's sequences in registers, lane = sequence 64 k + lane (the mode takes at most 256 sequences): token
+// range and the number of items (tiles spanned; none for a sequence without tokens) up to and including the
+// sequence.  Every lane of a wavefront builds the same table.
+struct WarmSeqs {
+    int s0[4], s1[4], inc[4];
+    int total;
+};
+struct WarmSeq { int b, s0, s1, n, first_item; };
+struct PairInfo { int b, first, nsplit; };   // sequence, chunk id of its first partial, number of its partials
+
+__device__ __forceinline__ WarmSeqs warm_load(const DecodeParams &P, int B, int lane)
+{
+    WarmSeqs W;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int bb = 64 * k + lane;
+        W.s0[k] = W.s1[k] = 0;
+        if (bb < B) { W.s0[k] = P.cu[bb]; W.s1[k] = P.cu[bb + 1]; }
+    }
+    int base = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int n = (W.s1[k] > W.s0[k]) ? ((W.s1[k] - 1) / SPARK_TILE_TOKENS - W.s0[k] / SPARK_TILE_TOKENS + 1) : 0;
+        W.inc[k] = base + wave_inclusive_sum_i32(n);
+        base = __builtin_amdgcn_readlane(W.inc[k], 63);
+    }
+    W.total = base;
+    return W;
+}
+
+// entry of sequence b (wave-uniform b)
+__device__ __forceinline__ WarmSeq warm_get(const WarmSeqs &W, int b)
+{
+    const int k = b >> 6, l = b & 63;
+    // (values, not references to the arrays: the table stays in registers)
+    auto pick = [k, l](int a0, int a1, int a2, int a3) {
+        int v = a0;
+        v = (k == 1) ? a1 : v;
+        v = (k == 2) ? a2 : v;
+        v = (k == 3) ? a3 : v;
+        return __builtin_amdgcn_readlane(v, l);
+    };
+    WarmSeq q;
+    q.b = b;
+    q.s0 = pick(W.s0[0], W.s0[1], W.s0[2], W.s0[3]);
+    q.s1 = pick(W.s1[0], W.s1[1], W.s1[2], W.s1[3]);
+    q.n = (q.s1 > q.s0) ? ((q.s1 - 1) / SPARK_TILE_TOKENS - q.s0 / SPARK_TILE_TOKENS + 1) : 0;
+    q.first_item = pick(W.inc[0], W.inc[1], W.inc[2], W.inc[3]) - q.n;
+    return q;
+}
+
+// the sequence that holds item `item` (0 <= item < W.total)
+__device__ __forceinline__ WarmSeq warm_find(const WarmSeqs &W, int item)
+{
+    int b = 0;
+    bool found = false;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint64_t hit = __ballot(W.inc[k] > item);
+        if (!found && hit != 0ull) { b = 64 * k + __builtin_ctzll(hit); found = true; }
+    }
+    return warm_get(W, b);
+}
+
+// wavefront w of nw covers items [w * total / nw, (w + 1) * total / nw): the one that covers `item`
+__device__ __forceinline__ int warm_wave_of(int item, int nw, int total)
+{
+    return (int)((((uint32_t)item + 1u) * (uint32_t)nw - 1u) / (uint32_t)total);
+}
+
+// Partials of sequence q: one per wavefront that covers some of its items.  `nwe` is the number of wavefronts that
+// take part, min(warm_waves, total): with fewer items than wavefronts each of the first `total` takes one.
+__device__ __forceinline__ PairInfo warm_pair(const DecodeParams &P, const WarmSeq &q, int B, int total)
+{
+    PairInfo pi;
+    pi.b = q.b;
+    if (q.n > 0) {
+        const int nwe = P.warm_waves < total ? P.warm_waves : total;
+        const int wf = warm_wave_of(q.first_item, nwe, total);
+        const int wl = warm_wave_of(q.first_item + q.n - 1, nwe, total);
+        pi.first = wf + q.b;
+        pi.nsplit = wl - wf + 1;
+    } else {
+        pi.first = P.warm_waves + B + q.b;
+        pi.nsplit = 1;
+    }
+    return pi;
+}
+
 // ---------------------------------------------------------------- appended (never pruned) rows
 
 // [Sec. "Preliminaries": each decode step concatenates the new token's key and value to the cache; pruning
@@ -310,6 +409,7 @@ constexpr int decode_min_blocks(int, int) { return 2; }
 // The cache is read once per step: the streaming loads carry the non-temporal hint so they do not
 // displace each other in the L2 / memory-side cache (measured: 129 us -> 118 us on the 32K workload).
 #define NT_LOAD(p) __builtin_nontemporal_load(p)
+
 // Timeline of a launch (a measurement aid, off unless a buffer has been given through spark_decode_timeline):
 // thread 0 of every block files the 100 MHz wall clock at five points - word 0 entry, 1 start of streaming,
 // 2 end of streaming (wavefront 0), 3 partial stored, 4 exit - and, with word 5, its tile count, 6 the
@@ -326,10 +426,15 @@ __device__ __forceinline__ void stamp(const DecodeParams &P, int word, unsigned 
 // VAR: rows keep a per-row number of channels (the top-p variant, Sec. "Adaptive Variants of SparK"): the row's
 // count sits in its sixth word and the kept entries in the head's value stream, located through the tile
 // directory and a wave prefix sum of the lower tokens' lengths.
-template <int G, int TCT, int INT8, int TVC, int REC = 0, int VAR = 0>
+// WARM: balanced mode (see DecodeParams::warm_waves): the four wavefronts of a block work independently, each with
+// its own query table, on a contiguous range of (sequence, tile) items; nothing in a block waits for another
+// wavefront, and a sequence boundary inside a range costs one partial store and one table rebuild while the
+// next tile is already in flight.
+template <int G, int TCT, int INT8, int TVC, int REC = 0, int VAR = 0, int WARM = 0>
 __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void spark_decode_kernel(DecodeParams P)
 {
     static_assert(!VAR || (TCT == 0 && INT8 == 0 && TVC == 0 && REC == 0), "variable-length rows: any-length bf16 path only");
+    static_assert(!WARM || (TVC == 0 && REC == 0 && VAR == 0 && G <= 8), "balanced mode: dense values, degenerate recovery");
     constexpr bool PV = (TVC != 0);             // packed value cache
     constexpr int NVW = PV ? (TVC > 0 ? (((4 + (TVC + 1) / 2) + 1) & ~1) : 4) : 1;   // value-row words in registers
     // LDS row stride (words) of a parked value row.  A row kept whole in registers (NVW words) is parked word by
@@ -346,7 +451,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     constexpr int NDW_CT = (VAL0 + NV_CT + 1) & ~1;
     constexpr int NQ_CT = NDW_CT / 4;
 
-    __shared__ __align__(16) float qtab[SPARK_D * GP];
+    __shared__ __align__(16) float qtab[(WARM ? kDecodeWaves : 1) * SPARK_D * GP];   // (balanced mode: one per wavefront)
     __shared__ float Rsh[16];
     __shared__ __align__(16) uint16_t Pbuf[kDecodeWaves][2][G][64];
     // per wavefront: the accumulators at the end; with packed values, before that, the parked value rows
@@ -374,43 +479,111 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     }
     const SparkLayout &L = P.L;
     const int T = TCT ? TCT : L.T;
-    // blocks [0, nchunk_max * Hkv) are (global chunk, KV head) pairs; when rows have been appended after
-    // prefill, B * Hkv * ntail more blocks follow, each taking 256 of a (batch, KV head)'s appended rows
-    const int nmain = P.nchunk_max * P.Hkv;
+    float *const qt = qtab + (WARM ? wave * SPARK_D * GP : 0);
+    // blocks [0, nmain) stream the cache: (global chunk, KV head) pairs, or in the balanced mode (group of four
+    // wavefronts, KV head); when rows have been appended after prefill, B * Hkv * ntail more blocks follow, each
+    // taking 256 of a (batch, KV head)'s appended rows
+    const int nmain = (WARM ? P.warm_waves / kDecodeWaves : P.nchunk_max) * P.Hkv;
     const bool is_tail = (int)blockIdx.x >= nmain;      // block-uniform
     const int tb = (int)blockIdx.x - nmain;
     const int gid = is_tail ? -1 : (int)(blockIdx.x / P.Hkv);
     const int h = is_tail ? (tb / P.ntail) % P.Hkv : (int)(blockIdx.x % P.Hkv);
-    const SeqChunks sc = locate_chunks(P, L.batch, gid, is_tail ? (tb / P.ntail) / P.Hkv : -1, lane);
-    if (sc.n == 0) return;                               // past the last chunk: the whole block leaves
-    const int b = sc.b;
-    const int bh = b * P.Hkv + h;
-    const int split = is_tail ? 0 : gid - sc.first;     // this block's chunk within its sequence
-    const int nsplit = sc.n;                             // chunks of this sequence
-    const int nmerge = nsplit + P.ntail;                 // partial states the last block folds
-    // partial slot of (q head index within the batch element's heads, i-th partial of this (batch, KV head))
-    auto slot_of = [&](int qh, int i) -> int64_t {
-        return (i < nsplit) ? (int64_t)(sc.first + i) * P.Hq + qh
-                            : P.tail_base + ((int64_t)b * P.Hq + qh) * P.tail_slots + (i - nsplit);
+    WarmSeqs W;
+    PairInfo pi = {0, 0, 0};
+    int s0 = 0, s1 = 0;                                  // token range of the sequence being streamed
+    int split = 0;                                       // this block's (wavefront's) partial within its sequence
+    if constexpr (WARM) {
+        W = warm_load(P, L.batch, lane);
+        if (is_tail) pi = warm_pair(P, warm_get(W, (tb / P.ntail) / P.Hkv), L.batch, W.total);
+    } else {
+        const SeqChunks sc = locate_chunks(P, L.batch, gid, is_tail ? (tb / P.ntail) / P.Hkv : -1, lane);
+        if (sc.n == 0) return;                           // past the last chunk: the whole block leaves
+        pi.b = sc.b;
+        pi.first = sc.first;
+        pi.nsplit = sc.n;                                // chunks of this sequence
+        split = is_tail ? 0 : gid - sc.first;            // this block's chunk within its sequence
+        s0 = sc.s0;
+        s1 = sc.s1;
+    }
+    // partial slot of (q head index within the batch element's heads, i-th partial of a (batch, KV head))
+    auto slot_of = [&](const PairInfo &pr, int qh, int i) -> int64_t {
+        return (i < pr.nsplit) ? (int64_t)(pr.first + i) * P.Hq + qh
+                               : P.tail_base + ((int64_t)pr.b * P.Hq + qh) * P.tail_slots + (i - pr.nsplit);
     };
+    // Folds the nmerge partial states of pair pr for query head h * G + g and writes the output (one wavefront;
+    // lane l takes the output channels 2l, 2l+1).  Up to 64 partial states are folded per round with the
+    // running-maximum rule: lane i fetches the (m, l) pair of partial i - one 8-byte load per lane, the pair's
+    // factor exp2(m_i - M) is then handed out by readlane - while every lane fetches its accumulator pair of
+    // all the partials (64 independent 8-byte loads in flight; the accumulators of the main loop are dead
+    // there, so the registers are there).  All loads are device-scope.  A pair with up to 64 partials is
+    // merged in one memory round trip.
+    auto merge_head = [&](const PairInfo &pr, int nmerge, int g) {
+        constexpr int RN = 64;                   // partials per round
+        const int c2 = lane;
+        const int qh = h * G + g;
+        const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + 2 * c2);
+        const uint64_t *pm = reinterpret_cast<const uint64_t *>(P.part_ml);
+        float M = -INFINITY, Lsum = 0.0f, A0 = 0.0f, A1 = 0.0f;
+        for (int i0 = 0; i0 < nmerge; i0 += RN) {
+            const int n = (nmerge - i0 < RN) ? nmerge - i0 : RN;
+            float mi = -INFINITY, li = 0.0f;
+            if (lane < n) {
+                const uint64_t ml = __hip_atomic_load(pm + slot_of(pr, qh, i0 + lane), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                mi = __uint_as_float((uint32_t)ml);
+                li = __uint_as_float((uint32_t)(ml >> 32));
+            }
+            uint64_t av[RN];
+#pragma unroll
+            for (int k0 = 0; k0 < RN; k0 += 8) {
+                if (k0 < n) {                                      // (wave-uniform: whole groups of eight are skipped)
+#pragma unroll
+                    for (int k = k0; k < k0 + 8; ++k) {
+                        const int i = i0 + ((k < n) ? k : n - 1);  // (past the batch: some valid slot, its factor is 0)
+                        av[k] = __hip_atomic_load(pa + slot_of(pr, qh, i) * (SPARK_D / 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                } else {
+#pragma unroll
+                    for (int k = k0; k < k0 + 8; ++k) av[k] = 0ull;
+                }
+            }
+            const float Mn = fmaxf(M, wave_max(mi));
+            const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
+            const float fo = fast_exp2(M - Ms);               // M = -inf -> 0
+            M = Mn;
+            const float fi = fast_exp2(mi - Ms);              // lane i: factor of partial i0 + i (0 past the batch)
+            Lsum = fmaf(Lsum, fo, wave_sum(li * fi));
+            A0 *= fo;
+            A1 *= fo;
+#pragma unroll
+            for (int k0 = 0; k0 < RN; k0 += 8) {
+                if (k0 < n) {
+#pragma unroll
+                    for (int k = k0; k < k0 + 8; ++k) {
+                        const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fi), k));
+                        A0 = fmaf(__uint_as_float((uint32_t)av[k]), f, A0);
+                        A1 = fmaf(__uint_as_float((uint32_t)(av[k] >> 32)), f, A1);
+                    }
+                }
+            }
+        }
+        const int64_t bq = (int64_t)pr.b * P.Hq + qh;
+        const float o0 = (Lsum > 0.0f) ? (A0 / Lsum) : 0.0f, o1 = (Lsum > 0.0f) ? (A1 / Lsum) : 0.0f;
+        if (P.out_f32) {
+            reinterpret_cast<float2 *>(P.out)[bq * (SPARK_D / 2) + c2] = make_float2(o0, o1);
+        } else {
+            const uint32_t packed2 = (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o0) |
+                                     ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o1) << 16);
+            reinterpret_cast<uint32_t *>(P.out)[bq * (SPARK_D / 2) + c2] = packed2;
+        }
+    };
+    const int b = pi.b;
+    const int nsplit = pi.nsplit;
+    const int nmerge = nsplit + P.ntail;                 // partial states the last arrival folds
     if (is_tail) {
         static_assert(sizeof(qtab) >= G * SPARK_D * 4 && sizeof(Pbuf) >= kDecodeWaves * G * 64 * 4, "LDS reuse");
         tail_partial<G>(P, b, h, tb % P.ntail, qtab, reinterpret_cast<float *>(&Pbuf[0][0][0][0]), red_m, red_l,
                         reinterpret_cast<float *>(&wbuf[0][0]));
     } else {
-    const int s0 = sc.s0, s1 = sc.s1;
-
-    // ---- tiles of this split
-    int t_begin = 0, t_end = 0;
-    if (s1 > s0) {
-        const int tf = s0 / SPARK_TILE_TOKENS, tl = (s1 - 1) / SPARK_TILE_TOKENS;
-        const int ntile = tl - tf + 1;
-        const int chunk = (ntile + nsplit - 1) / nsplit;
-        t_begin = tf + split * chunk;
-        t_end = t_begin + chunk;
-        if (t_end > tl + 1) t_end = tl + 1;
-    }
-
     float m[G], l[G], R[G];
     f32x4 acc[8];
 #pragma unroll
@@ -485,15 +658,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     uint32_t rn[NR];
     uint4 vr[2][8];
     uint32_t vrow[NVW];
-    // Tiles are visited in rotated order, a different rotation per block.  The order does not
-    // matter to the running softmax, and it keeps the blocks (whose V chunks start at large
-    // power-of-two distances) from sweeping the memory channels in lockstep.
-    const int nts = t_end - t_begin;
-    const int rot = nts > 0 ? (int)((blockIdx.x * 37u) % (uint32_t)nts) : 0;
-    auto tile_of = [&](int k) { int li = k + rot; li = (li >= nts) ? li - nts : li; return t_begin + li; };
-    int kidx = wave;
-    int tile = tile_of(kidx);
-    if (kidx < nts) {
+    auto prefetch = [&](int tile) {
         load_row(tile, rn);
         if constexpr (PV) {
             load_vrow(tile, vrow);
@@ -501,70 +666,12 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             load_v(tile, 0, vr[0]);
             load_v(tile, 1, vr[1]);
         }
-    }
-    // (the first tile's loads are already in flight while the table is built)
-    if constexpr (PV) {
-        // Selector table, entry b = mask byte of a group of 8 channels.  The group's kept entries are the
-        // first popcount(b) of a window of 8 candidates = 16 bytes Q0..Q3; output word o holds channels
-        // 2o, 2o+1.  A byte-permute picks from two words (selector 0-3: second operand, 4-7: first, 0x0C:
-        // zero): words 0, 1 need candidates 0..3 only -> one permute of (Q1, Q0); words 2, 3 may reach
-        // into Q2, Q3 -> the OR of a permute of (Q1, Q0) and one of (Q3, Q2).
-        const uint32_t bmask = (uint32_t)tid;
-        uint32_t sel[6];
-#pragma unroll
-        for (int k = 0; k < 6; ++k) sel[k] = 0x0C0C0C0Cu;
-        int rnk = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const bool on = (bmask >> e) & 1u;
-            const int o = e >> 1, sh = (e & 1) * 16;      // output word, bit position of its half
-            const int src = 2 * rnk;                       // candidate's first byte in the window
-            const uint32_t two = (uint32_t)((src & 7) | (((src & 7) + 1) << 8)) << sh;
-            const uint32_t keep = ~(0xFFFFu << sh);
-            if (o < 2) {
-                if (on) sel[o] = (sel[o] & keep) | two;
-            } else {
-                if (on && src < 8) sel[2 * o - 2] = (sel[2 * o - 2] & keep) | two;
-                if (on && src >= 8) sel[2 * o - 1] = (sel[2 * o - 1] & keep) | two;
-            }
-            rnk += on ? 1 : 0;
-        }
-        u32x4 lo4 = {sel[0], sel[1], sel[2], sel[3]};
-        *reinterpret_cast<u32x4 *>(&vlut[tid * 4]) = lo4;
-        vlutb[tid * 2] = sel[4];
-        vlutb[tid * 2 + 1] = sel[5];
-    }
-    // ---- per-step query prep: table {q_g[j] * scale * log2e, 1/a[j]} and R_g
-    if (tid < SPARK_D) {
-        const int j = tid;
-        const float inva = reinterpret_cast<const float *>(P.packed + L.off_inva)[((int64_t)b * P.Hkv + h) * SPARK_D + j];
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-            qtab[j * GP + g] = bf16lo(P.q[((int64_t)b * P.Hq + h * G + g) * SPARK_D + j]) * P.scale_log2;
-        qtab[j * GP + G] = inva;
-#pragma unroll
-        for (int g = G + 1; g < GP; ++g) qtab[j * GP + g] = 0.0f;
-    }
-    __syncthreads();
-    for (int g = wave; g < G; g += kDecodeWaves) {
-        float r = qtab[lane * GP + g] * qtab[lane * GP + G] +
-                  qtab[(lane + 64) * GP + g] * qtab[(lane + 64) * GP + G];
-        r = wave_sum(r);
-        if (lane == 0) Rsh[g] = r;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int g = 0; g < G; ++g) R[g] = Rsh[g];
-
-
-    if (P.trace != nullptr) { stamp(P, 1, wall_clock64()); stamp(P, 5, (unsigned long long)nts); }
-    for (; kidx < nts; kidx += kDecodeWaves) {
-        tile = tile_of(kidx);
+    };
+    // One tile of sequence [s0, s1) whose rows have been requested by prefetch(): scores, online softmax, P V.
+    auto process = [&](int tile) {
         const uint8_t *tp = tiles + (int64_t)tile * L.tile_bytes;
         const int n_lane = tile * SPARK_TILE_TOKENS + lane;
         const bool valid = (n_lane >= s0) && (n_lane < s1);
-        const bool more = kidx + kDecodeWaves < nts;            // wave-uniform
-        const int tnext = tile_of(more ? kidx + kDecodeWaves : kidx);
 
         uint32_t (&r)[NR] = rn;
         // ---- scores, lane = token
@@ -594,7 +701,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                 return (i & 1) ? bf16hi(word) : bf16lo(word);
             };
             auto entry = [&](int i, uint32_t word) {
-                const float *e = &qtab[next_channel(i) * GP];
+                const float *e = &qt[next_channel(i) * GP];
                 const float d = fmaf(-mu, e[G], kept_value(i, word));
 #pragma unroll
                 for (int g = 0; g < G; ++g) s[g] = fmaf(e[g], d, s[g]);
@@ -614,7 +721,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                     for (int u = 0; u < BQ; ++u)
                         if (i0 + u < TCT) {
 #pragma unroll
-                            for (int g = 0; g <= G; ++g) ev[u][g] = qtab[off[u] + g];
+                            for (int g = 0; g <= G; ++g) ev[u][g] = qt[off[u] + g];
                         }
 #pragma unroll
                     for (int u = 0; u < BQ; ++u)
@@ -669,7 +776,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
 #pragma unroll
                         for (int k = 0; k < 8; ++k)
 #pragma unroll
-                            for (int g = 0; g <= G; ++g) ev[k][g] = qtab[off[k] + g];
+                            for (int g = 0; g <= G; ++g) ev[k][g] = qt[off[k] + g];
 #pragma unroll
                         for (int k = 0; k < 8; ++k) {
                             const bool on = (uint32_t)(i0 + 8 * u + k) < cnt;   // lanes whose row is shorter idle through the rest
@@ -720,7 +827,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                         w0 = -mu_a * kLn2 * __builtin_amdgcn_logf(u1);
                         w1 = -mu_a * kLn2 * __builtin_amdgcn_logf(u2);
                     }
-                    const float *e0 = &qtab[j * GP], *e1 = &qtab[(j + 1) * GP];
+                    const float *e0 = &qt[j * GP], *e1 = &qt[(j + 1) * GP];
                     const float t0 = (mw & 1u) ? 0.0f : e0[G] * w0;
                     const float t1 = (mw & 2u) ? 0.0f : e1[G] * w1;
                     mw >>= 2;
@@ -870,15 +977,324 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             }
         }
         wave_lds_sync();   // P buffer is rewritten by the next tile
-        if (more) {   // request the next tile; its latency is covered by the other resident wavefronts
-            load_row(tnext, rn);
-            if constexpr (PV) {
-                load_vrow(tnext, vrow);
-            } else {
-                load_v(tnext, 0, vr[0]);
-                load_v(tnext, 1, vr[1]);
+    };
+    if constexpr (WARM) {
+        // ---- balanced mode: this wavefront's contiguous range of the head's (sequence, tile) items
+        const int B = L.batch, NW = P.warm_waves, total = W.total;
+        const int wid = (int)(blockIdx.x / P.Hkv) * kDecodeWaves + wave;       // wavefront number within the KV head
+        const int nwe = NW < total ? NW : total;                               // wavefronts that get items
+        int item = 0, item_end = 0;
+        if (wid < nwe) {
+            item = (int)(((uint32_t)wid * (uint32_t)total) / (uint32_t)nwe);
+            item_end = (int)((((uint32_t)wid + 1u) * (uint32_t)total) / (uint32_t)nwe);
+        }
+        float *const red = reinterpret_cast<float *>(wbuf[wave]);              // [G][128] staging of the accumulators
+
+        // query table {q_g[j] * scale * log2e, 1/a[j]} and R_g of a sequence, built by this wavefront alone.  The
+        // inputs are requested before the sequence's first tile (loads return in order), the table is written
+        // once the previous sequence's state has been stored.
+        constexpr bool HOIST = G < 8;        // (eight query heads: the registers to hold them across the store are not there)
+        float inva_r[2];
+        uint16_t q_r[2][G];
+        auto request_query = [&](int sb) {
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const int j = lane + 64 * jj;
+                inva_r[jj] = reinterpret_cast<const float *>(P.packed + L.off_inva)[((int64_t)sb * P.Hkv + h) * SPARK_D + j];
+#pragma unroll
+                for (int g = 0; g < G; ++g) q_r[jj][g] = P.q[((int64_t)sb * P.Hq + h * G + g) * SPARK_D + j];
+            }
+        };
+        auto build_query = [&]() {
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const int j = lane + 64 * jj;
+#pragma unroll
+                for (int g = 0; g < G; ++g) qt[j * GP + g] = bf16lo(q_r[jj][g]) * P.scale_log2;
+                qt[j * GP + G] = inva_r[jj];
+#pragma unroll
+                for (int g = G + 1; g < GP; ++g) qt[j * GP + g] = 0.0f;
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                R[g] = wave_sum(qt[lane * GP + g] * qt[lane * GP + G] + qt[(lane + 64) * GP + g] * qt[(lane + 64) * GP + G]);
+        };
+        auto reset_state = [&]() {
+#pragma unroll
+            for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.0f; }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+        };
+        // A stored partial is counted in only after its stores have been acknowledged.  The wait is put off to
+        // a point where nothing else of this wavefront is in flight (just before the next tile is requested, or
+        // at the end), so it costs nothing; whoever counts last merges the pair.
+        PairInfo pend = {0, 0, 0};
+        int pend_n = 0;                      // partial states of the pending pair (0: nothing pending)
+        // Folds the nm partial states of pair pr for all G query heads at once: 64 / G lanes per head, each with
+        // 2 G output channels, every lane fetching the (m, l) pairs of its head (the lanes of a head read the same
+        // words) and its channels of every partial - all loads of a round are independent, so a pair with up to
+        // RN partials costs one memory round trip however many heads it has.
+        auto merge_pair = [&](const PairInfo &pr, int nm) {
+            constexpr int LPH = 64 / G, CPL = 2 * G, RN = (32 / G < 16) ? 32 / G : 16;
+            const int g = lane / LPH, c = lane % LPH;
+            const int qh = h * G + g;
+            const uint64_t *pm = reinterpret_cast<const uint64_t *>(P.part_ml);
+            float M = -INFINITY, Lsum = 0.0f, A[CPL];
+#pragma unroll
+            for (int e = 0; e < CPL; ++e) A[e] = 0.0f;
+            for (int i0 = 0; i0 < nm; i0 += RN) {
+                const int n = (nm - i0 < RN) ? nm - i0 : RN;
+                uint64_t ml[RN], av[RN][G];
+#pragma unroll
+                for (int k = 0; k < RN; ++k) {
+                    if (k < n) {                               // (wave-uniform)
+                        const int64_t slot = slot_of(pr, qh, i0 + k);
+                        ml[k] = __hip_atomic_load(pm + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + slot * SPARK_D + c * CPL);
+#pragma unroll
+                        for (int v = 0; v < G; ++v) av[k][v] = __hip_atomic_load(pa + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    } else {
+                        ml[k] = (uint64_t)__float_as_uint(-INFINITY);      // (m = -inf, l = 0: factor 0)
+#pragma unroll
+                        for (int v = 0; v < G; ++v) av[k][v] = 0ull;
+                    }
+                }
+                float Mn = M;
+#pragma unroll
+                for (int k = 0; k < RN; ++k) Mn = fmaxf(Mn, __uint_as_float((uint32_t)ml[k]));
+                const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
+                const float fo = fast_exp2(M - Ms);            // M = -inf -> 0
+                M = Mn;
+                Lsum *= fo;
+#pragma unroll
+                for (int e = 0; e < CPL; ++e) A[e] *= fo;
+#pragma unroll
+                for (int k = 0; k < RN; ++k) {
+                    const float f = fast_exp2(__uint_as_float((uint32_t)ml[k]) - Ms);
+                    Lsum = fmaf(__uint_as_float((uint32_t)(ml[k] >> 32)), f, Lsum);
+#pragma unroll
+                    for (int v = 0; v < G; ++v) {
+                        A[2 * v] = fmaf(__uint_as_float((uint32_t)av[k][v]), f, A[2 * v]);
+                        A[2 * v + 1] = fmaf(__uint_as_float((uint32_t)(av[k][v] >> 32)), f, A[2 * v + 1]);
+                    }
+                }
+            }
+            const int64_t o2 = (((int64_t)pr.b * P.Hq + qh) * SPARK_D + c * CPL) / 2;      // in pairs of channels
+#pragma unroll
+            for (int v = 0; v < G; ++v) {
+                const float o0 = (Lsum > 0.0f) ? (A[2 * v] / Lsum) : 0.0f, o1 = (Lsum > 0.0f) ? (A[2 * v + 1] / Lsum) : 0.0f;
+                if (P.out_f32) {
+                    reinterpret_cast<float2 *>(P.out)[o2 + v] = make_float2(o0, o1);
+                } else {
+                    reinterpret_cast<uint32_t *>(P.out)[o2 + v] = (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o0) |
+                                                                  ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o1) << 16);
+                }
+            }
+        };
+        auto flush = [&]() {
+            if (pend_n == 0) return;         // (wave-uniform)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);   // this wavefront's stores have been acknowledged
+            uint32_t old = 0u;
+            if (lane == 0) old = atomicInc(&P.counters[pend.b * P.Hkv + h], (uint32_t)(pend_n - 1));
+            old = (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (old == (uint32_t)(pend_n - 1)) {
+                merge_pair(pend, pend_n);
+                if (P.trace != nullptr) stamp(P, 7, 1ull);
+            }
+            pend_n = 0;
+        };
+        // this wavefront's state of pair pr: the output itself when nobody else contributes, else its partial
+        auto finalize = [&](const PairInfo &pr, int my) {
+            flush();                         // (one pair can be pending at a time)
+            const int nm = pr.nsplit + P.ntail;
+            float lt[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) lt[g] = wave_sum(l[g]);
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int g = 4 * tg + rr;
+                if (g < G) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) red[g * SPARK_D + 8 * cn + e] = acc[e][rr];
+                }
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float2 a2 = *reinterpret_cast<const float2 *>(&red[g * SPARK_D + 2 * lane]);
+                const int qh = h * G + g;
+                if (nm == 1) {
+                    const float o0 = (lt[g] > 0.0f) ? (a2.x / lt[g]) : 0.0f, o1 = (lt[g] > 0.0f) ? (a2.y / lt[g]) : 0.0f;
+                    const int64_t oi = ((int64_t)pr.b * P.Hq + qh) * (SPARK_D / 2) + lane;
+                    if (P.out_f32) {
+                        reinterpret_cast<float2 *>(P.out)[oi] = make_float2(o0, o1);
+                    } else {
+                        reinterpret_cast<uint32_t *>(P.out)[oi] = (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o0) |
+                                                                  ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o1) << 16);
+                    }
+                } else {
+                    const int64_t slot = slot_of(pr, qh, my);
+                    const uint64_t two = (uint64_t)__float_as_uint(a2.x) | ((uint64_t)__float_as_uint(a2.y) << 32);
+                    __hip_atomic_store(reinterpret_cast<uint64_t *>(P.part_acc + slot * SPARK_D) + lane, two, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                    if (lane == 0) {
+                        const uint64_t ml = (uint64_t)__float_as_uint(m[g]) | ((uint64_t)__float_as_uint(lt[g]) << 32);
+                        __hip_atomic_store(reinterpret_cast<uint64_t *>(P.part_ml) + slot, ml, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            }
+            wave_lds_sync();   // the staging area is reused
+            if (nm > 1) { pend = pr; pend_n = nm; }
+        };
+
+        if (P.trace != nullptr) stamp(P, 5, (unsigned long long)(item_end - item));
+        if (item < item_end) {
+            WarmSeq cur = warm_find(W, item);
+            PairInfo pr = warm_pair(P, cur, B, total);
+            int my = wid - (pr.first - cur.b);                 // this wavefront's partial within the pair
+            s0 = cur.s0;
+            s1 = cur.s1;
+            int tile = s0 / SPARK_TILE_TOKENS + (item - cur.first_item);
+            if (HOIST) request_query(cur.b);
+            prefetch(tile);
+            if (!HOIST) request_query(cur.b);
+            build_query();
+            reset_state();
+            if (P.trace != nullptr) stamp(P, 1, wall_clock64());
+            for (;;) {
+                ++item;
+                const bool more = item < item_end;
+                const bool newseq = more && (item == cur.first_item + cur.n);   // (wave-uniform)
+                WarmSeq nxt = cur;
+                if (newseq) nxt = warm_find(W, item);
+                const int tnext = newseq ? nxt.s0 / SPARK_TILE_TOKENS : tile + 1;
+                process(tile);
+                if (!more) break;
+                s0 = nxt.s0;
+                s1 = nxt.s1;
+                tile = tnext;
+                flush();                     // (nothing of this wavefront is in flight here, and no tile is held)
+                if (HOIST && newseq) request_query(nxt.b);
+                prefetch(tile);              // in flight while the finished sequence is stored and the table rebuilt
+                if (newseq) {
+                    finalize(pr, my);
+                    cur = nxt;
+                    pr = warm_pair(P, cur, B, total);
+                    my = wid - (pr.first - cur.b);
+                    if (!HOIST) request_query(cur.b);
+                    build_query();
+                    reset_state();
+                }
+            }
+            if (P.trace != nullptr) stamp(P, 2, wall_clock64());
+            finalize(pr, my);
+            if (P.trace != nullptr) stamp(P, 3, wall_clock64());
+            flush();
+        }
+        // sequences without tokens have no item: wavefront b mod NW writes their zeros (or their empty partial)
+        for (int sb = wid; sb < B; sb += NW) {
+            const WarmSeq q = warm_get(W, sb);
+            if (q.n == 0) {
+                reset_state();
+                finalize(warm_pair(P, q, B, total), 0);
+                flush();
             }
         }
+        if (P.trace != nullptr) stamp(P, 4, wall_clock64());
+        return;
+    }
+    // ---- tiles of this split
+    int t_begin = 0, t_end = 0;
+    if (s1 > s0) {
+        const int tf = s0 / SPARK_TILE_TOKENS, tl = (s1 - 1) / SPARK_TILE_TOKENS;
+        const int ntile = tl - tf + 1;
+        const int chunk = (ntile + nsplit - 1) / nsplit;
+        t_begin = tf + split * chunk;
+        t_end = t_begin + chunk;
+        if (t_end > tl + 1) t_end = tl + 1;
+    }
+
+    // Tiles are visited in rotated order, a different rotation per block.  The order does not
+    // matter to the running softmax, and it keeps the blocks (whose V chunks start at large
+    // power-of-two distances) from sweeping the memory channels in lockstep.
+    const int nts = t_end - t_begin;
+    const int rot = nts > 0 ? (int)((blockIdx.x * 37u) % (uint32_t)nts) : 0;
+    auto tile_of = [&](int k) { int li = k + rot; li = (li >= nts) ? li - nts : li; return t_begin + li; };
+    int kidx = wave;
+    int tile = tile_of(kidx);
+    // The query and 1/a are requested before the first tile: loads return in order, so the table can be built
+    // while the tile is still on its way.
+    float inva_r = 0.0f;
+    uint16_t q_r[G];
+    if (tid < SPARK_D) {
+        inva_r = reinterpret_cast<const float *>(P.packed + L.off_inva)[((int64_t)b * P.Hkv + h) * SPARK_D + tid];
+#pragma unroll
+        for (int g = 0; g < G; ++g) q_r[g] = P.q[((int64_t)b * P.Hq + h * G + g) * SPARK_D + tid];
+    }
+    if (kidx < nts) prefetch(tile);
+    if constexpr (PV) {
+        // Selector table, entry b = mask byte of a group of 8 channels.  The group's kept entries are the
+        // first popcount(b) of a window of 8 candidates = 16 bytes Q0..Q3; output word o holds channels
+        // 2o, 2o+1.  A byte-permute picks from two words (selector 0-3: second operand, 4-7: first, 0x0C:
+        // zero): words 0, 1 need candidates 0..3 only -> one permute of (Q1, Q0); words 2, 3 may reach
+        // into Q2, Q3 -> the OR of a permute of (Q1, Q0) and one of (Q3, Q2).
+        const uint32_t bmask = (uint32_t)tid;
+        uint32_t sel[6];
+#pragma unroll
+        for (int k = 0; k < 6; ++k) sel[k] = 0x0C0C0C0Cu;
+        int rnk = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool on = (bmask >> e) & 1u;
+            const int o = e >> 1, sh = (e & 1) * 16;      // output word, bit position of its half
+            const int src = 2 * rnk;                       // candidate's first byte in the window
+            const uint32_t two = (uint32_t)((src & 7) | (((src & 7) + 1) << 8)) << sh;
+            const uint32_t keep = ~(0xFFFFu << sh);
+            if (o < 2) {
+                if (on) sel[o] = (sel[o] & keep) | two;
+            } else {
+                if (on && src < 8) sel[2 * o - 2] = (sel[2 * o - 2] & keep) | two;
+                if (on && src >= 8) sel[2 * o - 1] = (sel[2 * o - 1] & keep) | two;
+            }
+            rnk += on ? 1 : 0;
+        }
+        u32x4 lo4 = {sel[0], sel[1], sel[2], sel[3]};
+        *reinterpret_cast<u32x4 *>(&vlut[tid * 4]) = lo4;
+        vlutb[tid * 2] = sel[4];
+        vlutb[tid * 2 + 1] = sel[5];
+    }
+    // ---- per-step query prep: table {q_g[j] * scale * log2e, 1/a[j]} and R_g
+    if (tid < SPARK_D) {
+        const int j = tid;
+#pragma unroll
+        for (int g = 0; g < G; ++g) qt[j * GP + g] = bf16lo(q_r[g]) * P.scale_log2;
+        qt[j * GP + G] = inva_r;
+#pragma unroll
+        for (int g = G + 1; g < GP; ++g) qt[j * GP + g] = 0.0f;
+    }
+    __syncthreads();
+    for (int g = wave; g < G; g += kDecodeWaves) {
+        float r = qt[lane * GP + g] * qt[lane * GP + G] +
+                  qt[(lane + 64) * GP + g] * qt[(lane + 64) * GP + G];
+        r = wave_sum(r);
+        if (lane == 0) Rsh[g] = r;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < G; ++g) R[g] = Rsh[g];
+
+
+    if (P.trace != nullptr) { stamp(P, 1, wall_clock64()); stamp(P, 5, (unsigned long long)nts); }
+    for (; kidx < nts; kidx += kDecodeWaves) {
+        tile = tile_of(kidx);
+        const bool more = kidx + kDecodeWaves < nts;            // wave-uniform
+        const int tnext = tile_of(more ? kidx + kDecodeWaves : kidx);
+        process(tile);
+        if (more) prefetch(tnext);   // request the next tile; its latency is covered by the other resident wavefronts
     }
 
     if (P.trace != nullptr) stamp(P, 2, wall_clock64());
@@ -923,7 +1339,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             else
                 reinterpret_cast<uint16_t *>(P.out)[oi] = __builtin_bit_cast(uint16_t, (__bf16)o);
         } else {
-            const int64_t slot = slot_of(h * G + g, split);
+            const int64_t slot = slot_of(pi, h * G + g, split);
             st_agent(&P.part_acc[slot * SPARK_D + ch], A);
             if (ch == 0) { st_agent(&P.part_ml[slot * 2], M); st_agent(&P.part_ml[slot * 2 + 1], Lsum); }
         }
@@ -941,87 +1357,34 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);   // this thread's stores have been acknowledged
     __syncthreads();
     if (tid == 0) {
-        const uint32_t old = atomicInc(&P.counters[bh], (uint32_t)(nmerge - 1));
+        const uint32_t old = atomicInc(&P.counters[b * P.Hkv + h], (uint32_t)(nmerge - 1));
         last_flag = (old == (uint32_t)(nmerge - 1));
     }
     __syncthreads();
     if (P.trace != nullptr) stamp(P, 4, wall_clock64());
     if (!last_flag) return;
-    // A wavefront takes one query head per pass, its lane l the output channels 2l, 2l+1.  Up to 64 partial states
-    // are folded per round with the running-maximum rule: lane i fetches the (m, l) pair of partial i - one 8-byte
-    // load per lane, the pair's factor exp2(m_i - M) is then handed out by readlane - while every lane fetches
-    // its accumulator pair of all the partials (64 independent 8-byte loads in flight; the accumulators of the
-    // main loop are dead here, so the registers are there).  All loads are device-scope.  A (batch, KV head)
-    // pair with up to 64 partials is merged in one memory round trip.
-    constexpr int NTH = kDecodeWaves * 64;
-    for (int e0 = wave * 64; e0 < G * (SPARK_D / 2); e0 += NTH) {
-        const int g = e0 / (SPARK_D / 2), c2 = lane;      // (g is wave-uniform)
-        const int qh = h * G + g;
-        const uint64_t *pa = reinterpret_cast<const uint64_t *>(P.part_acc + 2 * c2);
-        const uint64_t *pm = reinterpret_cast<const uint64_t *>(P.part_ml);
-        float M = -INFINITY, Lsum = 0.0f, A0 = 0.0f, A1 = 0.0f;
-        for (int i0 = 0; i0 < nmerge; i0 += 64) {
-            const int n = (nmerge - i0 < 64) ? nmerge - i0 : 64;
-            float mi = -INFINITY, li = 0.0f;
-            if (lane < n) {
-                const uint64_t ml = __hip_atomic_load(pm + slot_of(qh, i0 + lane), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                mi = __uint_as_float((uint32_t)ml);
-                li = __uint_as_float((uint32_t)(ml >> 32));
-            }
-            uint64_t av[64];
-#pragma unroll
-            for (int k0 = 0; k0 < 64; k0 += 8) {
-                if (k0 < n) {                                      // (wave-uniform: whole groups of eight are skipped)
-#pragma unroll
-                    for (int k = k0; k < k0 + 8; ++k) {
-                        const int i = i0 + ((k < n) ? k : n - 1);  // (past the batch: some valid slot, its factor is 0)
-                        av[k] = __hip_atomic_load(pa + slot_of(qh, i) * (SPARK_D / 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
-                } else {
-#pragma unroll
-                    for (int k = k0; k < k0 + 8; ++k) av[k] = 0ull;
-                }
-            }
-            const float Mn = fmaxf(M, wave_max(mi));
-            const float Ms = (Mn == -INFINITY) ? 0.0f : Mn;
-            const float fo = fast_exp2(M - Ms);               // M = -inf -> 0
-            M = Mn;
-            const float fi = fast_exp2(mi - Ms);              // lane i: factor of partial i0 + i (0 past the batch)
-            Lsum = fmaf(Lsum, fo, wave_sum(li * fi));
-            A0 *= fo;
-            A1 *= fo;
-#pragma unroll
-            for (int k0 = 0; k0 < 64; k0 += 8) {
-                if (k0 < n) {
-#pragma unroll
-                    for (int k = k0; k < k0 + 8; ++k) {
-                        const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fi), k));
-                        A0 = fmaf(__uint_as_float((uint32_t)av[k]), f, A0);
-                        A1 = fmaf(__uint_as_float((uint32_t)(av[k] >> 32)), f, A1);
-                    }
-                }
-            }
-        }
-        const int64_t bq = (int64_t)b * P.Hq + qh;
-        const float o0 = (Lsum > 0.0f) ? (A0 / Lsum) : 0.0f, o1 = (Lsum > 0.0f) ? (A1 / Lsum) : 0.0f;
-        if (P.out_f32) {
-            reinterpret_cast<float2 *>(P.out)[bq * (SPARK_D / 2) + c2] = make_float2(o0, o1);
-        } else {
-            const uint32_t packed2 = (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o0) |
-                                     ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)o1) << 16);
-            reinterpret_cast<uint32_t *>(P.out)[bq * (SPARK_D / 2) + c2] = packed2;
-        }
-    }
+    // a wavefront takes one query head per pass
+    for (int g = wave; g < G; g += kDecodeWaves) merge_head(pi, nmerge, g);
     if (P.trace != nullptr) { stamp(P, 4, wall_clock64()); stamp(P, 7, 1ull); }
 }
 
 // ---------------------------------------------------------------- host-side launch
 
-template <int G, int TCT, int INT8, int TVC, int REC = 0, int VAR = 0>
+template <int G, int TCT, int INT8, int TVC, int REC = 0, int VAR = 0, int WARM = 0>
 static hipError_t launch_one(const DecodeParams &P, int nblocks, hipStream_t st)
 {
-    hipLaunchKernelGGL((spark_decode_kernel<G, TCT, INT8, TVC, REC, VAR>), dim3(nblocks), dim3(kDecodeWaves * 64), 0, st, P);
+    hipLaunchKernelGGL((spark_decode_kernel<G, TCT, INT8, TVC, REC, VAR, WARM>), dim3(nblocks), dim3(kDecodeWaves * 64), 0, st, P);
     return hipGetLastError();
+}
+
+// dense values, degenerate recovery, fixed row length: the chunked or the balanced decomposition
+template <int G, int TCT, int INT8>
+static hipError_t launch_plain(const DecodeParams &P, int nblocks, hipStream_t st)
+{
+    if constexpr (G <= 8) {
+        if (P.warm_waves > 0) return launch_one<G, TCT, INT8, 0, 0, 0, 1>(P, nblocks, st);
+    }
+    return launch_one<G, TCT, INT8, 0>(P, nblocks, st);
 }
 
 // packed values: row lengths 64 / 38 / 26 with the row in registers, anything else generic
@@ -1053,14 +1416,14 @@ hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
         return launch_pv<G, 0>(P, nblocks, st);
     }
     if (P.L.int8) {
-        if (T == 26) return launch_one<G, 26, 1, 0>(P, nblocks, st);
-        return launch_one<G, 0, 1, 0>(P, nblocks, st);
+        if (T == 26) return launch_plain<G, 26, 1>(P, nblocks, st);
+        return launch_plain<G, 0, 1>(P, nblocks, st);
     }
-    if (T == 26) return launch_one<G, 26, 0, 0>(P, nblocks, st);
-    if (T == 25) return launch_one<G, 25, 0, 0>(P, nblocks, st);
-    if (T == 38) return launch_one<G, 38, 0, 0>(P, nblocks, st);
-    if (T == 64) return launch_one<G, 64, 0, 0>(P, nblocks, st);
-    return launch_one<G, 0, 0, 0>(P, nblocks, st);
+    if (T == 26) return launch_plain<G, 26, 0>(P, nblocks, st);
+    if (T == 25) return launch_plain<G, 25, 0>(P, nblocks, st);
+    if (T == 38) return launch_plain<G, 38, 0>(P, nblocks, st);
+    if (T == 64) return launch_plain<G, 64, 0>(P, nblocks, st);
+    return launch_plain<G, 0, 0>(P, nblocks, st);
 }
 
 }  // namespace spark

@@ -21,6 +21,10 @@ struct DecodePlan {
     int chunk_tiles;    // else: a sequence spanning ntile tiles gets max(1, ceil(ntile / chunk_tiles)) chunks
     int nchunk_max;     // upper bound on the number of chunks in the batch (grid = nchunk_max * Hkv + tail blocks)
     int tail_slots;     // partial slots reserved per (batch, q head) for appended rows
+    int warm_waves;     // > 0: the balanced mode may be used, with this many wavefronts per KV head; the launch
+                        // falls back to the chunked cut for the kernel variants that have no balanced form
+    int chunk_ids;      // chunk ids the workspace has partial slots for: >= nchunk_max, and >= the balanced
+                        // mode's warm_waves + 2 * batch; the appended rows' slots follow at chunk_ids * Hq
 };
 
 // measurement aid: later decode launches of this process file eight 64-bit words per block into `device_words`
@@ -40,7 +44,7 @@ hipError_t launch_unpack(const uint8_t *packed, const SparkLayout &L, uint32_t *
 
 // q [B,Hq,128] bf16; the caller splits the workspace into part_acc / part_ml / counters.
 // Values are either dense (v, strides; packed_v = NULL) or a packed value cache (packed_v, Lv; v = NULL).
-// Partial slots: plan.nchunk_max * Hq, then batch * Hq * plan.tail_slots; tail_k != NULL adds the appended rows
+// Partial slots: plan.chunk_ids * Hq, then batch * Hq * plan.tail_slots; tail_k != NULL adds the appended rows
 // [B, tail_cap, Hkv, 128].
 hipError_t launch_decode_attn(const uint16_t *q, const uint8_t *packed, const uint16_t *v, int64_t v_tok_stride,
                               int64_t v_head_stride, const uint8_t *packed_v, const SparkLayout *Lv,

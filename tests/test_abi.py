@@ -61,6 +61,30 @@ def test_size_queries_follow_the_layout():
     assert spark.packed_bytes(_desc(batch=1, total_tokens=65)) == 256 + 2 * 8 * 128 * 4 + 2 * 64 * 8 * 72
 
 
+def test_balanced_cut_sizes_its_partial_slots_on_the_host():
+    """n_splits = -1 asks for the balanced cut: 4 * (512 / KV heads) wavefronts per KV head, chunk ids
+    wavefronts + 2 * batch.  Batches of 32 to 256 sequences with 256 or more (batch, KV head) pairs get it
+    unasked; more than 256 sequences, or 16 query heads per KV head, never do."""
+    slot = 130 * 4
+    small = _desc(batch=4, total_tokens=4 * 1000)
+    forced = _desc(batch=4, total_tokens=4 * 1000, n_splits=-1)
+    assert spark.decode_workspace_bytes(forced) == ((256 + 2 * 4) * 32 + 4 * 32) * slot + 256
+    assert spark.decode_workspace_bytes(forced) > spark.decode_workspace_bytes(small)
+    ragged = _desc(batch=64, total_tokens=64 * 1300)
+    assert spark.decode_workspace_bytes(ragged) == ((256 + 2 * 64) * 32 + 64 * 32) * slot + 64 * 8 * 4
+    assert spark.decode_workspace_bytes(_desc(batch=64, total_tokens=64 * 1300, n_splits=-1)) == \
+        spark.decode_workspace_bytes(ragged)
+    # a fixed split count switches it off; so do 16 query heads per KV head and more than 256 sequences
+    assert spark.decode_workspace_bytes(_desc(batch=64, total_tokens=64 * 1300, n_splits=1)) == \
+        (64 * 32 + 64 * 32) * slot + 64 * 8 * 4
+    wide = dict(n_q_heads=128, n_kv_heads=8, batch=4, total_tokens=4 * 1000)
+    assert spark.decode_workspace_bytes(_desc(n_splits=-1, **wide)) == spark.decode_workspace_bytes(_desc(**wide))
+    many = dict(batch=300, total_tokens=300 * 100)
+    assert spark.decode_workspace_bytes(_desc(n_splits=-1, **many)) == spark.decode_workspace_bytes(_desc(**many))
+    assert spark.decode_workspace_bytes(_desc(n_splits=-2)) == 0
+    assert spark.decode_workspace_bytes(_desc(n_splits=4097)) == 0
+
+
 def test_bad_descriptions_are_rejected_on_the_host():
     lib = spark.load()
     assert spark.packed_bytes(_desc(head_dim=64)) == 0

@@ -1,0 +1,111 @@
+"""GPU parity for the balanced cut of decode: the (sequence, tile) items of a KV head dealt out in equal
+contiguous ranges to independent wavefronts, one partial per (wavefront, sequence), merged by whoever counts in
+last.  The library picks it for batches of 32 to 256 short sequences; `n_splits = -1` asks for it on any batch,
+which is how the small cases here reach it.  Same oracle and tolerance as plain decode."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_2508_15212_amd as spark
+from tests.gpu_util import make_desc, to_dev
+from tests.test_gpu_parity import _run
+from tests.test_gpu_tail import _tail_case
+
+pytestmark = pytest.mark.gpu
+
+
+def test_ragged_with_empty_and_single_token_sequences():
+    res, _, _ = _run(wl.small(name="bal_edges", batch=6, seqlens=(0, 1, 63, 64, 65, 0), keep=26, seed=60), n_splits=-1)
+    assert np.all(res["out_f32"][0] == 0) and np.all(res["out_f32"][5] == 0)
+
+
+@pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 2), (4, 2), (8, 2), (16, 1)])
+def test_group_sizes(G, Hkv):
+    # (16 query heads per KV head have no balanced form: the request falls back to the cut by length)
+    _run(wl.small(name=f"bal_gqa{G}", n_q_heads=G * Hkv, n_kv_heads=Hkv, keep=26, seqlens=(257, 64, 190), batch=3,
+                  seed=600 + G), n_splits=-1)
+
+
+@pytest.mark.parametrize("T", [1, 25, 26, 27, 38, 64, 128])
+def test_keep_values(T):
+    _run(wl.small(name=f"bal_keep{T}", keep=T, seqlens=(130, 321), seed=620 + T), n_splits=-1)
+
+
+def test_int8_storage():
+    _run(wl.small(name="bal_int8", keep=26, seqlens=(300, 141), seed=640), int8=True, n_splits=-1)
+    _run(wl.small(name="bal_int8_t25", keep=25, seqlens=(100, 70, 0, 33), batch=4, seed=641), int8=True, n_splits=-1)
+
+
+def test_token_major_layout():
+    _run(wl.small(name="bal_nhd", seqlens=(333, 129), seed=645), layout="NHD", n_splits=-1)
+
+
+def test_one_long_sequence_among_short_ones_gets_many_partials():
+    """Fewer items than wavefronts: every item is a wavefront's whole range, the long sequence ends up with 141
+    partials (nine merge rounds of sixteen), the empty one with the single spare partial id."""
+    _run(wl.small(name="bal_skewed", batch=7, n_q_heads=8, n_kv_heads=2, keep=26,
+                  seqlens=(9000, 64, 0, 700, 1, 130, 2500), seed=650), n_splits=-1)
+
+
+def test_ranges_that_span_several_sequences():
+    """Many KV heads leave 64 wavefronts per head: with some 200 items a head, a wavefront's range holds three or
+    four tiles and crosses sequence boundaries (store a partial, rebuild the table, go on), including runs of
+    empty sequences and sequences that share a tile with their neighbours."""
+    rng = np.random.default_rng(660)
+    lens = [int(x) for x in rng.integers(0, 600, size=40)]
+    lens[3] = lens[4] = lens[5] = 0
+    lens[10], lens[11], lens[12] = 5, 1, 7
+    w = wl.small(name="bal_spans", batch=40, n_q_heads=32, n_kv_heads=32, keep=26, seqlens=tuple(lens), seed=660)
+    _run(w)          # 40 * 32 pairs: the library chooses the balanced cut by itself
+    _run(w, n_splits=-1, want_unpack=True)
+
+
+def test_batch_of_empty_sequences_gives_zero_output():
+    w = wl.small(name="bal_allempty", batch=2, n_q_heads=4, n_kv_heads=2, keep=26, seqlens=(0, 0), seed=1)
+    t = wl.generate(w)
+    desc = make_desc(w, n_splits=-1)
+    desc.k_head_stride = desc.v_head_stride = w.head_dim        # (zero tokens: any valid stride)
+    dq = to_dev(t.q)
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.zeros(max(spark.packed_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    k1 = torch.zeros(256, dtype=torch.int16, device="cuda")          # valid pointers; no row is ever read
+    spark.prune(desc, k1, to_dev(t.qwin), dcu, packed)
+    out = torch.full((w.batch, w.n_q_heads, w.head_dim), 7.0, dtype=torch.float32, device="cuda")
+    spark.decode_attn(desc, dq, packed, k1, dcu, out, spark.new_decode_workspace(desc))
+    torch.cuda.synchronize()
+    assert np.all(out.cpu().numpy() == 0)
+
+
+def test_appended_rows_are_counted_in_with_the_wavefronts_partials():
+    w = wl.small(name="bal_tail", batch=6, seqlens=(0, 1, 63, 300, 65, 0), keep=26, seed=670)
+    got, _ = _tail_case(w, cap=300, tail_len=(5, 0, 300, 1, 0, 0), seed=670, n_splits=-1)
+    assert np.all(got[5] == 0)
+
+
+def test_repeated_calls_on_one_workspace_leave_the_counters_clear():
+    """The arrival counters wrap to zero at the last arrival, also when wavefronts (not blocks) count in: the
+    same workspace serves the balanced and the length-proportional cut in turn, bit for bit each time."""
+    w = wl.small(name="bal_repeat", batch=5, n_q_heads=8, n_kv_heads=2, keep=26, seqlens=(700, 64, 0, 1300, 190), seed=680)
+    t = wl.generate(w)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    ref = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
+    d_bal, d_len = make_desc(w, n_splits=-1), make_desc(w)
+    dk, dv, dqw, dq = to_dev(t.k), to_dev(t.v), to_dev(t.qwin), to_dev(t.q)
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.empty(max(spark.packed_bytes(d_bal), 256), dtype=torch.uint8, device="cuda")
+    spark.prune(d_bal, dk, dqw, dcu, packed)
+    assert spark.decode_workspace_bytes(d_bal) >= spark.decode_workspace_bytes(d_len)
+    ws = spark.new_decode_workspace(d_bal)
+    first = {}
+    for it in range(6):
+        d = d_bal if it % 2 == 0 else d_len
+        out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+        spark.decode_attn(d, dq, packed, dv, dcu, out, ws)
+        got = out.cpu().numpy()
+        assert np.abs(got - ref).max() <= 1e-2
+        if it % 2 not in first:
+            first[it % 2] = got
+        assert np.array_equal(got, first[it % 2])
