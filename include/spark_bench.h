@@ -27,7 +27,9 @@ spark_status spark_probe_read(const void *src, size_t bytes, void *sink, int32_t
  * fits (64 bytes per block) lets thread 0 of each block file eight 64-bit words into `device_buffer`:
  *   0 wall clock (100 MHz) at entry          1 at the start of streaming      2 at its end (wavefront 0)
  *   3 when its partial state is stored       4 at exit (after the merge, if it merged)
- *   5 tiles it streamed                      6 XCC id << 32 | HW_ID           7 1 if it merged its pair
+ *   5 tiles it streamed                      6 XCC id << 32 | HW_ID           7 1 if it merged a pair
+ * (in the balanced cut of a ragged batch the wavefronts of a block work on their own: the words are wavefront
+ * 0's, and word 5 is 1 << 32 | its tiles).
  * The caller owns the buffer, clears it, reads it back after synchronising, and calls again with NULL to
  * switch the aid off (the buffer must stay valid until then).  Process-wide and not thread safe; the
  * method's results do not depend on it.  SPARK_ERR_INVALID_ARG for a misaligned buffer or bytes < 64.

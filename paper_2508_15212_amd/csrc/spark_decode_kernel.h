@@ -412,8 +412,9 @@ constexpr int decode_min_blocks(int, int) { return 2; }
 
 // Timeline of a launch (a measurement aid, off unless a buffer has been given through spark_decode_timeline):
 // thread 0 of every block files the 100 MHz wall clock at five points - word 0 entry, 1 start of streaming,
-// 2 end of streaming (wavefront 0), 3 partial stored, 4 exit - and, with word 5, its tile count, 6 the
-// hardware ids (XCC id << 32 | HW_ID), 7 whether it merged its (batch, KV head) pair.
+// 2 end of streaming (wavefront 0), 3 partial stored, 4 exit - and, with word 5, its tile count (in the balanced
+// mode: 1 << 32 | tiles of wavefront 0), 6 the hardware ids (XCC id << 32 | HW_ID), 7 whether it merged a
+// (batch, KV head) pair.
 __device__ __forceinline__ void stamp(const DecodeParams &P, int word, unsigned long long value)
 {
     if (P.trace != nullptr && threadIdx.x == 0) P.trace[(size_t)blockIdx.x * 8 + word] = value;
@@ -1028,7 +1029,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         };
         // A stored partial is counted in only after its stores have been acknowledged.  The wait is put off to
         // a point where nothing else of this wavefront is in flight (just before the next tile is requested, or
-        // at the end), so it costs nothing; whoever counts last merges the pair.
+        // at the end), so it costs nothing; whoever counts last merges the pair.  (Looking at the count's answer
+        // one tile later still, to save its round trip as well, was measured 30 % slower: a load result that is
+        // live around the loop makes the compiler wait for all memory at the top of every iteration.)
         PairInfo pend = {0, 0, 0};
         int pend_n = 0;                      // partial states of the pending pair (0: nothing pending)
         // Folds the nm partial states of pair pr for all G query heads at once: 64 / G lanes per head, each with
@@ -1151,7 +1154,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             if (nm > 1) { pend = pr; pend_n = nm; }
         };
 
-        if (P.trace != nullptr) stamp(P, 5, (unsigned long long)(item_end - item));
+        if (P.trace != nullptr) stamp(P, 5, (1ull << 32) | (unsigned long long)(item_end - item));   // (bit 32: balanced mode)
         if (item < item_end) {
             WarmSeq cur = warm_find(W, item);
             PairInfo pr = warm_pair(P, cur, B, total);

@@ -11,11 +11,13 @@
 //
 // Kernels
 //   spark_topp_select_kernel  one wavefront per tile of 64 tokens; per token a radix selection ON SUMS: the float32
-//                             bit pattern of the smallest kept saliency is fixed six bits at a time, each level
+//                             bit pattern of the smallest kept saliency is fixed level by level, each level
 //                             adding the q of the still undecided keys to 64 LDS bins by their next digit; a wave
 //                             prefix sum over the bins (highest digit first) and one ballot give the digit at
-//                             which the running sum reaches `need`; the levels end as soon as one key alone
-//                             starts with the bits fixed so far.  Writes the rows' fixed part (mask, mean
+//                             which the running sum reaches `need`.  The first level takes eleven bits (exponent
+//                             and three mantissa bits) over a window of eight octaves below the row's largest
+//                             key, the others six bits each; the levels end as soon as one key alone starts
+//                             with the bits fixed so far.  Writes the rows' fixed part (mask, mean
 //                             saliency of the pruned channels, count) and the tile's length in the value stream.
 //   spark_topp_scan_kernel    exclusive prefix sum of the tile lengths of every KV head: the directory.
 //   spark_topp_pack_kernel    one wavefront per row: reads the dense key row with one coalesced load; every lane
@@ -117,7 +119,8 @@ __global__ __launch_bounds__(kWaves * 64) void spark_topp_select_kernel(
         const float w1 = __fmul_rn(a01.y, fabsf(__uint_as_float(xx & 0xFFFF0000u)));
         const uint32_t k0 = __float_as_uint(w0), k1 = __float_as_uint(w1);
         // integer saliencies in units of the last place of the row's largest
-        int emax = (int)(wave_max_u32(k0 > k1 ? k0 : k1) >> 23);
+        const uint32_t kmax = wave_max_u32(k0 > k1 ? k0 : k1);
+        int emax = (int)(kmax >> 23);
         emax = emax < 1 ? 1 : emax;
         const uint32_t q0 = quantise(k0, emax), q1 = quantise(k1, emax);
         const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_sum(q0 + q1), 63);
@@ -159,7 +162,41 @@ __global__ __launch_bounds__(kWaves * 64) void spark_topp_select_kernel(
                             : (uint32_t)__builtin_amdgcn_readlane((int)k1, __builtin_ctzll(in1 | (1ull << 63)));
                 return true;
             };
-            if (!level(25, 6) && !level(19, 6) && !level(13, 6) && !level(7, 6) && !level(1, 6)) level(0, 1);
+            // First level: the exponent and three mantissa bits at once (eight bins an octave), over the eight
+            // octaves below the row's largest key.  All of a row's keys share their top bits, so a level on the
+            // top six bits alone would drop nearly every key into one or two bins (and serialise the adds);
+            // here they spread over some forty.  Keys further down go to the spare words; if the kept sum is
+            // not reached inside the window (a row whose mass sits in keys 256 times smaller than its largest),
+            // the row falls back to plain six-bit levels from the top.
+            bool done;
+            {
+                const uint32_t dmax = kmax >> 20;
+                const uint32_t spare = 64u + (uint32_t)lane;
+                const uint32_t i0 = dmax - (k0 >> 20), i1 = dmax - (k1 >> 20);
+                hist[lane] = 0u;
+                prune_lds_sync();
+                atomicAdd(&hist[i0 < 64u ? i0 : spare], q0);
+                atomicAdd(&hist[i1 < 64u ? i1 : spare], q1);
+                prune_lds_sync();
+                const uint32_t c = wave_inclusive_sum(hist[lane]);
+                prune_lds_sync();
+                const uint64_t reached = __ballot(c >= need);
+                if (reached != 0ull) {
+                    const int l2 = __builtin_ctzll(reached);
+                    if (l2 > 0) above = (uint32_t)__builtin_amdgcn_readlane((int)c, l2 - 1);
+                    theta = (dmax - (uint32_t)l2) << 20;
+                    const uint64_t in0 = __ballot((k0 >> 20) == (theta >> 20)), in1 = __ballot((k1 >> 20) == (theta >> 20));
+                    done = (__popcll(in0) + __popcll(in1) == 1);
+                    if (done)
+                        theta = in0 ? (uint32_t)__builtin_amdgcn_readlane((int)k0, __builtin_ctzll(in0))
+                                    : (uint32_t)__builtin_amdgcn_readlane((int)k1, __builtin_ctzll(in1 | (1ull << 63)));
+                    else
+                        done = level(14, 6) || level(8, 6) || level(2, 6) || level(0, 2);
+                } else {
+                    done = level(25, 6) || level(19, 6) || level(13, 6) || level(7, 6) || level(1, 6) || level(0, 1);
+                }
+            }
+            (void)done;
             // `above` is now the sum over the keys > theta; the keys == theta (each worth q_theta) fill the rest,
             // lowest channels first
             const bool eq0 = (k0 == theta), eq1 = (k1 == theta);

@@ -66,25 +66,33 @@ def main() -> int:
     tr = tr[(tr[:, 0] != 0) & (tr[:, 4] != 0)]    # (blocks past the last chunk of a ragged batch leave at once)
     us = lambda ticks: np.asarray(ticks, np.float64) / 100.0
     t00 = tr[:, 0].min()
-    nts = tr[:, 5]
-    rounds = np.maximum(1, (nts + 3) // 4)
+    balanced = bool((tr[:, 5] >> 32).any())       # (the balanced cut: words are wavefront 0's, tiles its own)
+    nts = tr[:, 5] & 0xFFFFFFFF
+    tr = tr[nts > 0] if balanced else tr           # (wavefronts without a tile only look after empty sequences)
+    nts = tr[:, 5] & 0xFFFFFFFF
+    rounds = np.maximum(1, nts if balanced else (nts + 3) // 4)
     per_round = us(tr[:, 2] - tr[:, 1]) / rounds
     pct = lambda x, ps: "  /  ".join("%.1f" % v for v in np.percentile(x, ps))
     xcc = (tr[:, 6] >> 32) & 0xF
     merged = tr[:, 7] == 1
-    print(f"## {w.name}, T = {w.keep}: {len(tr)} working blocks of {launched} launched, "
-          f"{spark.decode_splits(d)} chunk(s) per average sequence\n")
+    print(f"## {w.name}, T = {w.keep}: {len(tr)} working blocks of {launched} launched, " +
+          ("balanced cut (figures are those of each block's first wavefront)\n" if balanced else
+           f"{spark.decode_splits(d)} chunk(s) per average sequence\n"))
     print("| quantity | value |\n|---|---|")
     print(f"| kernel span (first entry to last exit) | {us(tr[:, 4].max() - t00):.1f} us |")
-    print(f"| tiles per block, min / mean / max | {nts.min()} / {nts.mean():.1f} / {nts.max()} |")
+    print(f"| tiles per {'wavefront' if balanced else 'block'}, min / mean / max | {nts.min()} / {nts.mean():.1f} / {nts.max()} |")
     print(f"| entry -> start of streaming, p10 / p50 / p90 (us) | {pct(us(tr[:, 1] - tr[:, 0]), [10, 50, 90])} |")
     print(f"| one round of tiles per wavefront, p10 / p50 / p90 (us) | {pct(per_round, [10, 50, 90])} |")
     print(f"| end of streaming after the first entry, p10 / p50 / p90 / max (us) | {pct(us(tr[:, 2] - t00), [10, 50, 90, 100])} |")
-    print(f"| end of streaming -> partial stored (wait for the block's slowest wavefront, reduce), p50 / p90 (us) | {pct(us(tr[:, 3] - tr[:, 2]), [50, 90])} |")
-    if merged.any():
-        print(f"| partial stored -> merged output written, blocks that merged ({int(merged.sum())}), mean (us) | {us(tr[:, 4] - tr[:, 3])[merged].mean():.1f} |")
+    if balanced:
+        print(f"| end of streaming -> exit, wavefronts that merged no pair / merged one, mean (us) | "
+              f"{us(tr[:, 4] - tr[:, 2])[~merged].mean():.1f} / {us(tr[:, 4] - tr[:, 2])[merged].mean() if merged.any() else 0.0:.1f} |")
+    else:
+        print(f"| end of streaming -> partial stored (wait for the block's slowest wavefront, reduce), p50 / p90 (us) | {pct(us(tr[:, 3] - tr[:, 2]), [50, 90])} |")
+        if merged.any():
+            print(f"| partial stored -> merged output written, blocks that merged ({int(merged.sum())}), mean (us) | {us(tr[:, 4] - tr[:, 3])[merged].mean():.1f} |")
     print("| round time by XCC id, mean (us) | " + ", ".join(f"{x}: {per_round[xcc == x].mean():.2f}" for x in sorted(set(xcc.tolist()))) + " |")
-    groups = [(0, 8), (8, 16), (16, 24), (24, 40), (40, 1 << 30)]
+    groups = [(0, 4), (4, 5), (5, 6), (6, 8)] if balanced else [(0, 8), (8, 16), (16, 24), (24, 40), (40, 1 << 30)]
     for lo, hi in groups:
         m = (nts > lo) & (nts <= hi)
         if m.any() and not m.all():

@@ -99,9 +99,15 @@ def test_special_rows():
     k[0, 8] = 0.0                                  # ... and of half a unit (rounded down to nothing)
     k[0, 8, 40] = 1.0
     k[0, 8, [3, 77, 101]] = 2.0 ** -24
+    # one large key over a plateau of small ones that holds the cut: ten octaves down (far outside the window of
+    # the selection's first level), in the window's last bin, and in the first bin outside it
+    for row, small in ((9, 2.0 ** -10), (10, 1.125 * 2.0 ** -8), (11, 2.0 ** -8)):
+        k[0, row] = small
+        k[0, row, 5] = 1.0
     t.k = wl.f32_to_bf16_bits(k)
     t.qwin = wl.f32_to_bf16_bits(np.ones(t.qwin.shape, np.float32))      # a = 1 everywhere
     pr = _run(w, t)
+    assert 100 < pr.count[9, 0] < 128 and 100 < pr.count[10, 0] < 128 and 100 < pr.count[11, 0] < 128
     assert pr.count[0, 0] == 1 and pr.count[1, 0] == 127 and pr.count[2, 0] == 1 and pr.count[3, 0] == 1
     pr = _run(w, t, p_bp=10000)
     assert pr.count[7, 0] == 4 and pr.count[8, 0] == 1
