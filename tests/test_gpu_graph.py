@@ -12,10 +12,13 @@ from tests.gpu_util import make_desc, to_dev
 pytestmark = pytest.mark.gpu
 
 
-def test_prune_and_decode_replay_from_a_captured_graph():
+@pytest.mark.parametrize("n_splits", [0, -1])
+def test_prune_and_decode_replay_from_a_captured_graph(n_splits):
+    """n_splits = -1: the balanced cut, whose wavefronts count in one by one (its merge takes the partials in
+    slot order whatever the order of arrival, so replays are bit-identical too)."""
     w = wl.small(name="graph", batch=3, n_q_heads=8, n_kv_heads=2, keep=26, seqlens=(700, 64, 190), seed=500)
     t = wl.generate(w)
-    desc = make_desc(w)
+    desc = make_desc(w, n_splits=n_splits)
     dk, dv, dqw, dq = to_dev(t.k), to_dev(t.v), to_dev(t.qwin), to_dev(t.q)
     dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
     packed = torch.empty(spark.packed_bytes(desc), dtype=torch.uint8, device="cuda")

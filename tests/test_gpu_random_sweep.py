@@ -21,7 +21,7 @@ def _one_case(rng, idx, int8=False):
     lens = tuple(int(x) for x in rng.choice([0, 1, 5, 63, 64, 65, 127, 130, 300, 777], size=batch))
     T = int(rng.choice([1, 13, 25, 26, 38, 64, 100, 128]))
     layout = str(rng.choice(["HND", "NHD"]))
-    n_splits = int(rng.choice([0, 0, 1, 2, 5]))
+    n_splits = int(rng.choice([0, 0, 1, 2, 5, -1, -1]))      # (-1: the balanced cut where the entry point has one)
     Tv = int(rng.choice([0, 0, 26, 38, 64, 90]))
     cap = int(rng.choice([0, 0, 3, 70, 300]))
     stats = int(rng.choice([0, 0, 1]))            # rows that also carry the all-channel mean / standard deviation
