@@ -687,7 +687,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
             int jb = 0;
             float scale_row = 1.0f;
             if (INT8) scale_row = __uint_as_float(r[5]);
-            uint32_t vw = 0;
             // next kept channel of this lane's row (ascending); exactly T bits are set
             auto next_channel = [&](int i) {
                 const bool sw = (i == clo);          // first entry of channels 64..127
@@ -788,11 +787,68 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                     }
                 }
             } else {
-                for (int i = 0; i < T; ++i) {
-                    const int per = INT8 ? 4 : 2;
-                    if (i % per == 0)
-                        vw = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, L.val0 + i / per));
-                    entry(i, vw);
+                // Any row length: the row's value words [w_lo, w_hi) are fetched in the 16-byte sections they are
+                // stored in, four sections in flight per lane (coalesced 1 KB requests; one load per word cost
+                // 1.5 x the time of a row-length instantiation).  A section that holds value words only is taken
+                // like the fixed-length path takes its entries - eight channel numbers off the mask, eight table
+                // gathers in flight, eight multiply-adds; the first section (the row's fixed words come first) and
+                // the last one go entry by entry.  Every lane has the same T, so all of this is wave-uniform.
+                constexpr int per = INT8 ? 4 : 2;              // entries per word
+                constexpr int NLD = 4;
+                const int w_lo = L.val0, w_hi = L.val0 + (T + per - 1) / per;
+                for (int qd0 = w_lo >> 2; 4 * qd0 < w_hi; qd0 += NLD) {
+                    u32x4 wv[NLD];
+#pragma unroll
+                    for (int u = 0; u < NLD; ++u) {
+                        const int qd = qd0 + u;
+                        wv[u] = u32x4{0u, 0u, 0u, 0u};
+                        if (4 * qd < w_hi) {
+                            if (qd < L.nq) {
+                                wv[u] = NT_LOAD(reinterpret_cast<const u32x4 *>(tp + qd * 1024 + lane * 16));
+                            } else {                           // the 2-word section at the end of the row
+                                const uint2 x = *reinterpret_cast<const uint2 *>(tp + L.nq * 1024 + lane * 8);
+                                wv[u].x = x.x;
+                                wv[u].y = x.y;
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < NLD; ++u) {
+                        const int wq = 4 * (qd0 + u);          // first word of this section
+                        if (wq >= w_hi) break;
+                        const uint32_t w4[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
+                        const int i_first = (wq - w_lo) * per; // entry its first word starts with
+                        if (wq >= w_lo && i_first + 4 * per <= T) {
+#pragma unroll
+                            for (int grp = 0; grp < per / 2; ++grp) {
+                                const int i0 = i_first + 8 * grp;
+                                int off[8];
+#pragma unroll
+                                for (int k = 0; k < 8; ++k) off[k] = next_channel(i0 + k) * GP;
+                                float ev[8][G + 1];
+#pragma unroll
+                                for (int k = 0; k < 8; ++k)
+#pragma unroll
+                                    for (int g = 0; g <= G; ++g) ev[k][g] = qt[off[k] + g];
+#pragma unroll
+                                for (int k = 0; k < 8; ++k) {
+                                    const float d = fmaf(-mu, ev[k][G], kept_value(i0 + k, w4[(8 * grp + k) / per]));
+#pragma unroll
+                                    for (int g = 0; g < G; ++g) s[g] = fmaf(ev[k][g], d, s[g]);
+                                }
+                            }
+                        } else {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                const int w = wq + c;
+                                if (w < w_lo || w >= w_hi) continue;
+                                for (int e = 0; e < per; ++e) {
+                                    const int i = (w - w_lo) * per + e;
+                                    if (i < T) entry(i, w4[c]);
+                                }
+                            }
+                        }
+                    }
                 }
             }
         }
