@@ -602,6 +602,29 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     const uint8_t *vtiles = PV ? P.packed_v + Lv.off_tiles + (int64_t)h * Lv.n_tiles * Lv.tile_bytes : nullptr;
     const int rsv = (TVC > 0) ? RSV : 8 * ((Lv.ndw + 3) / 8) + 4;   // parked-row stride in words
 
+    // Rows of any length: value words [w_lo, w_hi) of the row, fetched in the 16-byte sections they are stored
+    // in, NLD sections (a batch) per request.  The first batch is requested with the row's fixed words.
+    constexpr int NLD = 4;
+    constexpr int per_word = INT8 ? 4 : 2;          // entries per value word
+    const int w_lo = L.val0, w_hi = L.val0 + (T + per_word - 1) / per_word;
+    auto load_batch = [&](int tile, int qd0, u32x4 (&wv)[NLD]) {
+        const uint8_t *tp = tiles + (int64_t)tile * L.tile_bytes;
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int qd = qd0 + u;
+            wv[u] = u32x4{0u, 0u, 0u, 0u};
+            if (4 * qd < w_hi) {
+                if (qd < L.nq) {
+                    wv[u] = NT_LOAD(reinterpret_cast<const u32x4 *>(tp + qd * 1024 + lane * 16));
+                } else {                           // the 2-word section at the end of the row
+                    const uint2 x = *reinterpret_cast<const uint2 *>(tp + L.nq * 1024 + lane * 8);
+                    wv[u].x = x.x;
+                    wv[u].y = x.y;
+                }
+            }
+        }
+    };
+    u32x4 wfirst[(TCT || VAR) ? 1 : NLD];            // (any length, fixed per cache: the first batch of the tile in flight)
     constexpr int NR = TCT ? NDW_CT : 6;    // row words held in registers
     auto load_row = [&](int tile, uint32_t (&r)[NR]) {
         const uint8_t *tp = tiles + (int64_t)tile * L.tile_bytes;
@@ -619,6 +642,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
 #pragma unroll
             for (int d = 0; d < 6; ++d)
                 r[d] = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, d));
+            if constexpr (!TCT && !VAR) load_batch(tile, w_lo >> 2, wfirst);
         }
     };
     // half a tile of V: lane (tg, cn) takes 16 bytes (channels 8cn..8cn+7) of rows 4i + tg, so that
@@ -787,31 +811,15 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                     }
                 }
             } else {
-                // Any row length: the row's value words [w_lo, w_hi) are fetched in the 16-byte sections they are
-                // stored in, four sections in flight per lane (coalesced 1 KB requests; one load per word cost
-                // 1.5 x the time of a row-length instantiation).  A section that holds value words only is taken
-                // like the fixed-length path takes its entries - eight channel numbers off the mask, eight table
-                // gathers in flight, eight multiply-adds; the first section (the row's fixed words come first) and
-                // the last one go entry by entry.  Every lane has the same T, so all of this is wave-uniform.
-                constexpr int per = INT8 ? 4 : 2;              // entries per word
-                constexpr int NLD = 4;
-                const int w_lo = L.val0, w_hi = L.val0 + (T + per - 1) / per;
-                for (int qd0 = w_lo >> 2; 4 * qd0 < w_hi; qd0 += NLD) {
-                    u32x4 wv[NLD];
-#pragma unroll
-                    for (int u = 0; u < NLD; ++u) {
-                        const int qd = qd0 + u;
-                        wv[u] = u32x4{0u, 0u, 0u, 0u};
-                        if (4 * qd < w_hi) {
-                            if (qd < L.nq) {
-                                wv[u] = NT_LOAD(reinterpret_cast<const u32x4 *>(tp + qd * 1024 + lane * 16));
-                            } else {                           // the 2-word section at the end of the row
-                                const uint2 x = *reinterpret_cast<const uint2 *>(tp + L.nq * 1024 + lane * 8);
-                                wv[u].x = x.x;
-                                wv[u].y = x.y;
-                            }
-                        }
-                    }
+                // Any row length: the row's value words come in batches of four 16-byte sections (coalesced 1 KB
+                // requests; one load per word cost 1.5 x the time of a row-length instantiation).  The first batch
+                // was requested with the row's fixed words; each further one is requested before the batch in
+                // hand is worked on.  A section that holds value words only is taken like the fixed-length path
+                // takes its entries - eight channel numbers off the mask, eight table gathers in flight, eight
+                // multiply-adds; the first section (the row's fixed words come first) and the last one go entry
+                // by entry.  Every lane has the same T, so all of this is wave-uniform.
+                constexpr int per = per_word;
+                auto do_batch = [&](int qd0, const u32x4 (&wv)[NLD]) {
 #pragma unroll
                     for (int u = 0; u < NLD; ++u) {
                         const int wq = 4 * (qd0 + u);          // first word of this section
@@ -849,6 +857,19 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                             }
                         }
                     }
+                };
+                u32x4 wcur[NLD], wnxt[NLD];
+#pragma unroll
+                for (int u = 0; u < NLD; ++u) wcur[u] = wfirst[u];
+                for (int qd0 = w_lo >> 2;;) {
+                    const int qd1 = qd0 + NLD;
+                    const bool further = 4 * qd1 < w_hi;       // (wave-uniform)
+                    if (further) load_batch(tile, qd1, wnxt);
+                    do_batch(qd0, wcur);
+                    if (!further) break;
+#pragma unroll
+                    for (int u = 0; u < NLD; ++u) wcur[u] = wnxt[u];
+                    qd0 = qd1;
                 }
             }
         }
