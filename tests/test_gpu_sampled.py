@@ -58,6 +58,11 @@ def test_row_statistics_and_selection_with_stats_rows(T):
     spark.decode_attn(desc, dq, packed, dv, dcu, out, spark.new_decode_workspace(desc))
     ref = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
     assert np.abs(out.cpu().numpy() - ref).max() <= MAX_ABS
+    # ... also with the balanced cut (wavefronts on their own ranges of tiles)
+    desc.n_splits = -1
+    out2 = torch.empty_like(out)
+    spark.decode_attn(desc, dq, packed, dv, dcu, out2, spark.new_decode_workspace(desc))
+    assert np.abs(out2.cpu().numpy() - ref).max() <= MAX_ABS
 
 
 @pytest.mark.parametrize("kind", [spark.RECOVER_GAUSSIAN, spark.RECOVER_EXPONENTIAL])
