@@ -25,6 +25,10 @@
 // (zeros elsewhere).  The cost does not depend on how many entries a row keeps.
 // Split partials (m, l, unnormalised output) go to the workspace; the block that arrives last at
 // its (batch, KV head) counter merges them and writes the output, so one launch does the step.
+// Batches of many short sequences take another decomposition (the balanced mode, see DecodeParams::warm_waves):
+// the tiles of a KV head, sequences back to back, are dealt out in equal contiguous ranges to wavefronts that
+// work independently of their block - own query table, one partial per sequence touched, the wavefront that
+// counts in last merges the pair - so the launch does not last as long as its longest sequence.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>

@@ -109,3 +109,40 @@ def test_repeated_calls_on_one_workspace_leave_the_counters_clear():
         if it % 2 not in first:
             first[it % 2] = got
         assert np.array_equal(got, first[it % 2])
+
+
+def test_both_cuts_agree_on_larger_random_batches():
+    """Sizes the oracle would take minutes for: twelve seeded ragged batches of 32 to 200 sequences (empty ones
+    included), head counts and row lengths varied; the balanced cut (the library's own choice here, or asked
+    for) against one block per sequence on the same cache.  The two differ in summation order only."""
+    rng = np.random.default_rng(7001)
+    for case in range(12):
+        B = int(rng.integers(32, 200))
+        hkv = int(rng.choice([1, 2, 4, 8, 32]))
+        G = int(rng.choice([1, 2, 4, 8]))
+        T = int(rng.choice([26, 64, 38, 25, int(rng.integers(1, 128))]))
+        int8 = bool(rng.integers(0, 2)) and T in (26, 25, 51)
+        top = int(rng.choice([300, 1500, 4000]))
+        lens = [int(x) for x in np.exp(rng.uniform(np.log(8), np.log(top), size=B))]
+        for i in rng.integers(0, B, size=3):
+            lens[int(i)] = 0
+        w = wl.small(name=f"bal_rand{case}", batch=B, n_q_heads=G * hkv, n_kv_heads=hkv, keep=T, seqlens=tuple(lens),
+                     seed=7100 + case)
+        t = wl.generate(w)
+        pack = spark.PACK_INT8 if int8 else spark.PACK_BF16
+        d_bal, d_one = make_desc(w, pack=pack, n_splits=-1), make_desc(w, pack=pack, n_splits=1)
+        dk, dv, dqw, dq = to_dev(t.k), to_dev(t.v), to_dev(t.qwin), to_dev(t.q)
+        dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+        packed = torch.empty(max(spark.packed_bytes(d_bal), 256), dtype=torch.uint8, device="cuda")
+        spark.prune(d_bal, dk, dqw, dcu, packed)
+        outs = []
+        for d in (d_bal, d_one):
+            out = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+            spark.decode_attn(d, dq, packed, dv, dcu, out, spark.new_decode_workspace(d))
+            outs.append(out.cpu().numpy())
+        diff = np.abs(outs[0] - outs[1]).max()
+        print(f"case {case}: B={B} Hkv={hkv} G={G} T={T} int8={int8} tokens={sum(lens)} max|diff|={diff:.2e}", flush=True)
+        assert np.all(np.isfinite(outs[0])) and diff <= 2e-4
+        for i, n in enumerate(lens):
+            if n == 0:
+                assert np.all(outs[0][i] == 0)
