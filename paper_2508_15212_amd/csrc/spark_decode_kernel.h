@@ -1501,6 +1501,8 @@ hipError_t launch_g(const DecodeParams &P, int nblocks, hipStream_t st)
     }
     if (P.L.int8) {
         if (T == 26) return launch_plain<G, 26, 1>(P, nblocks, st);
+        if (T == 38) return launch_plain<G, 38, 1>(P, nblocks, st);
+        if (T == 64) return launch_plain<G, 64, 1>(P, nblocks, st);
         return launch_plain<G, 0, 1>(P, nblocks, st);
     }
     if (T == 26) return launch_plain<G, 26, 0>(P, nblocks, st);

@@ -36,6 +36,7 @@ def test_keep_values(T):
 def test_int8_storage():
     _run(wl.small(name="bal_int8", keep=26, seqlens=(300, 141), seed=640), int8=True, n_splits=-1)
     _run(wl.small(name="bal_int8_t25", keep=25, seqlens=(100, 70, 0, 33), batch=4, seed=641), int8=True, n_splits=-1)
+    _run(wl.small(name="bal_int8_t64", keep=64, seqlens=(300, 141, 77), batch=3, seed=642), int8=True, n_splits=-1)
 
 
 def test_token_major_layout():

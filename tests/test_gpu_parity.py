@@ -130,6 +130,10 @@ def test_constructed_ties_and_zero_rows():
 def test_int8_storage_variant():
     _run(wl.small(name="int8", keep=26, seqlens=(300, 141), seed=90), int8=True)
     _run(wl.small(name="int8_t25", keep=25, seqlens=(100, 70), seed=91), int8=True)
+    # (row lengths with an instantiation of their own, and one without)
+    _run(wl.small(name="int8_t38", keep=38, seqlens=(200, 131), seed=92), int8=True)
+    _run(wl.small(name="int8_t64", keep=64, seqlens=(257, 64, 190), batch=3, n_q_heads=16, n_kv_heads=2, seed=93), int8=True)
+    _run(wl.small(name="int8_t51", keep=51, seqlens=(150, 90), seed=94), int8=True)
 
 
 def test_peaked_softmax_keeps_tolerance():
