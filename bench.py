@@ -119,6 +119,7 @@ def main() -> int:
     desc.k_token_stride = desc.v_token_stride = D
     desc.k_head_stride = desc.v_head_stride = total * D
     desc.n_splits = args.splits
+    desc.max_seqlen = int(np.max(np.diff(np.asarray(t.cu, np.int64))))     # (a serving engine knows its batch)
     desc.keep_v = args.keep_v
     Tv = args.keep_v
     ntail = args.tail

@@ -42,6 +42,7 @@ class SparkDesc(ctypes.Structure):
         ("v_token_stride", ctypes.c_int64), ("v_head_stride", ctypes.c_int64),
         ("softmax_scale", ctypes.c_float), ("n_splits", ctypes.c_int32),
         ("keep_v", ctypes.c_int32), ("stats", ctypes.c_int32), ("tail_capacity", ctypes.c_int32),
+        ("max_seqlen", ctypes.c_int32),
     ]
 
 

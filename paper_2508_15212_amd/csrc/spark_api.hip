@@ -23,6 +23,7 @@ bool desc_ok(const spark_desc *d, spark_status *why)
     if (d->keep < 1 || d->keep > d->head_dim) return false;
     if (d->n_q_heads % d->n_kv_heads) return false;
     if (d->n_splits < -1 || d->n_splits > 4096) return false;
+    if (d->max_seqlen < 0) return false;
     if (d->keep_v < 0 || d->keep_v > d->head_dim) return false;
     if (d->tail_capacity < 0 || d->tail_capacity > (1 << 20)) return false;
     if (d->stats != 0 && d->stats != 1) return false;
@@ -95,7 +96,9 @@ spark::DecodePlan plan_of(const spark_desc *d, bool allow_balanced = true)
     p.warm_waves = 0;
     p.chunk_ids = p.nchunk_max;
     const int64_t pairs = (int64_t)d->batch * d->n_kv_heads;
-    const bool wanted = d->n_splits == -1 || (d->n_splits == 0 && d->batch >= 32 && pairs >= 256);
+    // (a batch that its caller knows to be near-uniform is balanced with one block per sequence already)
+    const bool even = d->max_seqlen > 0 && (int64_t)d->max_seqlen * d->batch * 8 <= d->total_tokens * 9;
+    const bool wanted = d->n_splits == -1 || (d->n_splits == 0 && d->batch >= 32 && pairs >= 256 && !even);
     if (allow_balanced && wanted && d->batch <= 256 && d->n_q_heads / d->n_kv_heads <= 8) {
         const int per_head = 512 / d->n_kv_heads > 0 ? 512 / d->n_kv_heads : 1;     // blocks of four wavefronts
         const int64_t nw = 4 * (int64_t)per_head;

@@ -484,7 +484,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     }
     const SparkLayout &L = P.L;
     const int T = TCT ? TCT : L.T;
-    float *const qt = qtab + (WARM ? wave * SPARK_D * GP : 0);
     // blocks [0, nmain) stream the cache: (global chunk, KV head) pairs, or in the balanced mode (group of four
     // wavefronts, KV head); when rows have been appended after prefill, B * Hkv * ntail more blocks follow, each
     // taking 256 of a (batch, KV head)'s appended rows
@@ -497,6 +496,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
     PairInfo pi = {0, 0, 0};
     int s0 = 0, s1 = 0;                                  // token range of the sequence being streamed
     int split = 0;                                       // this block's (wavefront's) partial within its sequence
+    float *const qt = qtab + (WARM ? wave * SPARK_D * GP : 0);
     if constexpr (WARM) {
         W = warm_load(P, L.batch, lane);
         if (is_tail) pi = warm_pair(P, warm_get(W, (tb / P.ntail) / P.Hkv), L.batch, W.total);
@@ -608,7 +608,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
 
     // Rows of any length: value words [w_lo, w_hi) of the row, fetched in the 16-byte sections they are stored
     // in, NLD sections (a batch) per request.  The first batch is requested with the row's fixed words.
-    constexpr int NLD = 4;
+    constexpr int NLD = 2;
     constexpr int per_word = INT8 ? 4 : 2;          // entries per value word
     const int w_lo = L.val0, w_hi = L.val0 + (T + per_word - 1) / per_word;
     auto load_batch = [&](int tile, int qd0, u32x4 (&wv)[NLD]) {
@@ -646,7 +646,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
 #pragma unroll
             for (int d = 0; d < 6; ++d)
                 r[d] = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, d));
-            if constexpr (!TCT && !VAR) load_batch(tile, w_lo >> 2, wfirst);
+            if constexpr (!TCT && !VAR && G <= 8) load_batch(tile, w_lo >> 2, wfirst);
         }
     };
     // half a tile of V: lane (tg, cn) takes 16 bytes (channels 8cn..8cn+7) of rows 4i + tg, so that
@@ -814,8 +814,17 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                         }
                     }
                 }
+            } else if constexpr (G > 8) {
+                // Any row length, sixteen query heads: the registers leave no room for batches of sections; one
+                // load per value word, one table gather at a time.
+                uint32_t vw = 0;
+                for (int i = 0; i < T; ++i) {
+                    if (i % per_word == 0)
+                        vw = *reinterpret_cast<const uint32_t *>(tp + spark_tile_word_offset(L, lane, L.val0 + i / per_word));
+                    entry(i, vw);
+                }
             } else {
-                // Any row length: the row's value words come in batches of four 16-byte sections (coalesced 1 KB
+                // Any row length: the row's value words come in batches of two 16-byte sections (coalesced 1 KB
                 // requests; one load per word cost 1.5 x the time of a row-length instantiation).  The first batch
                 // was requested with the row's fixed words; each further one is requested before the batch in
                 // hand is worked on.  A section that holds value words only is taken like the fixed-length path
@@ -823,6 +832,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                 // multiply-adds; the first section (the row's fixed words come first) and the last one go entry
                 // by entry.  Every lane has the same T, so all of this is wave-uniform.
                 constexpr int per = per_word;
+                // table gathers in flight, bounded by registers (as in the fixed-length path)
+                constexpr int GS = (G <= 4) ? ((WARM && INT8) ? 4 : 8) : 4;
                 auto do_batch = [&](int qd0, const u32x4 (&wv)[NLD]) {
 #pragma unroll
                     for (int u = 0; u < NLD; ++u) {
@@ -832,19 +843,19 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                         const int i_first = (wq - w_lo) * per; // entry its first word starts with
                         if (wq >= w_lo && i_first + 4 * per <= T) {
 #pragma unroll
-                            for (int grp = 0; grp < per / 2; ++grp) {
-                                const int i0 = i_first + 8 * grp;
-                                int off[8];
+                            for (int grp = 0; grp < 4 * per / GS; ++grp) {
+                                const int i0 = i_first + GS * grp;
+                                int off[GS];
 #pragma unroll
-                                for (int k = 0; k < 8; ++k) off[k] = next_channel(i0 + k) * GP;
-                                float ev[8][G + 1];
+                                for (int k = 0; k < GS; ++k) off[k] = next_channel(i0 + k) * GP;
+                                float ev[GS][G + 1];
 #pragma unroll
-                                for (int k = 0; k < 8; ++k)
+                                for (int k = 0; k < GS; ++k)
 #pragma unroll
                                     for (int g = 0; g <= G; ++g) ev[k][g] = qt[off[k] + g];
 #pragma unroll
-                                for (int k = 0; k < 8; ++k) {
-                                    const float d = fmaf(-mu, ev[k][G], kept_value(i0 + k, w4[(8 * grp + k) / per]));
+                                for (int k = 0; k < GS; ++k) {
+                                    const float d = fmaf(-mu, ev[k][G], kept_value(i0 + k, w4[(GS * grp + k) / per]));
 #pragma unroll
                                     for (int g = 0; g < G; ++g) s[g] = fmaf(ev[k][g], d, s[g]);
                                 }
@@ -862,18 +873,29 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                         }
                     }
                 };
-                u32x4 wcur[NLD], wnxt[NLD];
+                u32x4 wcur[NLD];
 #pragma unroll
                 for (int u = 0; u < NLD; ++u) wcur[u] = wfirst[u];
-                for (int qd0 = w_lo >> 2;;) {
-                    const int qd1 = qd0 + NLD;
-                    const bool further = 4 * qd1 < w_hi;       // (wave-uniform)
-                    if (further) load_batch(tile, qd1, wnxt);
-                    do_batch(qd0, wcur);
-                    if (!further) break;
+                if constexpr (G <= 4) {
+                    u32x4 wnxt[NLD];
+                    for (int qd0 = w_lo >> 2;;) {
+                        const int qd1 = qd0 + NLD;
+                        const bool further = 4 * qd1 < w_hi;       // (wave-uniform)
+                        if (further) load_batch(tile, qd1, wnxt);
+                        do_batch(qd0, wcur);
+                        if (!further) break;
 #pragma unroll
-                    for (int u = 0; u < NLD; ++u) wcur[u] = wnxt[u];
-                    qd0 = qd1;
+                        for (int u = 0; u < NLD; ++u) wcur[u] = wnxt[u];
+                        qd0 = qd1;
+                    }
+                } else {
+                    // (eight query heads: no registers for a second batch; it is requested when the first is done)
+                    for (int qd0 = w_lo >> 2;;) {
+                        do_batch(qd0, wcur);
+                        qd0 += NLD;
+                        if (4 * qd0 >= w_hi) break;
+                        load_batch(tile, qd0, wcur);
+                    }
                 }
             }
         }
@@ -1075,7 +1097,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
         // query table {q_g[j] * scale * log2e, 1/a[j]} and R_g of a sequence, built by this wavefront alone.  The
         // inputs are requested before the sequence's first tile (loads return in order), the table is written
         // once the previous sequence's state has been stored.
-        constexpr bool HOIST = G < 8;        // (eight query heads: the registers to hold them across the store are not there)
+        constexpr bool HOIST = G < 8 && TCT != 0;   // (eight query heads, or the any-length loop's buffers: the registers
+                                                    //  to hold the query across the store are not there)
         float inva_r[2];
         uint16_t q_r[2][G];
         auto request_query = [&](int sb) {

@@ -81,6 +81,13 @@ def test_balanced_cut_sizes_its_partial_slots_on_the_host():
     assert spark.decode_workspace_bytes(_desc(n_splits=-1, **wide)) == spark.decode_workspace_bytes(_desc(**wide))
     many = dict(batch=300, total_tokens=300 * 100)
     assert spark.decode_workspace_bytes(_desc(n_splits=-1, **many)) == spark.decode_workspace_bytes(_desc(**many))
+    # the caller's hint: a longest sequence within 9/8 of the average keeps one block per sequence
+    # (chunks of 2 * ceil(1300 tiles * 8 heads / 512) = 42 tiles: at most (1300 + 128) // 42 + 64 + 1 = 99 of them)
+    by_length = (99 * 32 + 64 * 32) * slot + 64 * 8 * 4
+    assert spark.decode_workspace_bytes(_desc(batch=64, total_tokens=64 * 1300, max_seqlen=1400)) == by_length
+    assert spark.decode_workspace_bytes(_desc(batch=64, total_tokens=64 * 1300, max_seqlen=1463)) > by_length
+    assert spark.decode_workspace_bytes(_desc(batch=64, total_tokens=64 * 1300, max_seqlen=1400, n_splits=-1)) > by_length
+    assert spark.decode_workspace_bytes(_desc(max_seqlen=-1)) == 0
     assert spark.decode_workspace_bytes(_desc(n_splits=-2)) == 0
     assert spark.decode_workspace_bytes(_desc(n_splits=4097)) == 0
 

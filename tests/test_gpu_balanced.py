@@ -147,3 +147,31 @@ def test_both_cuts_agree_on_larger_random_batches():
         for i, n in enumerate(lens):
             if n == 0:
                 assert np.all(outs[0][i] == 0)
+
+
+def test_longest_sequence_hint_keeps_one_block_per_sequence_on_even_batches():
+    """desc.max_seqlen within 9/8 of the average: the batch is balanced as it is and the library does not deal it
+    out to wavefronts - same cut, so bit for bit the same result, as n_splits = 1; a hint that says "ragged", or
+    none, leaves the balanced cut on."""
+    rng = np.random.default_rng(690)
+    lens = tuple(int(x) for x in rng.integers(380, 420, size=40))
+    w = wl.small(name="bal_hint", batch=40, n_q_heads=32, n_kv_heads=8, keep=26, seqlens=lens, seed=690)
+    t = wl.generate(w)
+    _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
+    pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)
+    ref = oracle.decode_literal(t.q, pr, t.v, t.layout, t.cu)
+    dk, dv, dqw, dq = to_dev(t.k), to_dev(t.v), to_dev(t.qwin), to_dev(t.q)
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    outs = {}
+    for tag, ns, hint in (("one", 1, 0), ("even", 0, max(lens)), ("ragged", 0, 4 * max(lens)), ("none", 0, 0)):
+        d = make_desc(w, n_splits=ns)
+        d.max_seqlen = hint
+        packed = torch.empty(max(spark.packed_bytes(d), 256), dtype=torch.uint8, device="cuda")
+        spark.prune(d, dk, dqw, dcu, packed)
+        out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+        spark.decode_attn(d, dq, packed, dv, dcu, out, spark.new_decode_workspace(d))
+        outs[tag] = out.cpu().numpy()
+        assert np.abs(outs[tag] - ref).max() <= 1e-2
+    assert np.array_equal(outs["even"], outs["one"])
+    assert np.array_equal(outs["ragged"], outs["none"])
+    assert not np.array_equal(outs["none"], outs["one"])        # (another summation order)
