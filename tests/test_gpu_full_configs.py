@@ -203,6 +203,42 @@ def test_config2_decode_replayed_500_times_on_one_workspace():
     assert np.abs(first[0].cpu().numpy().astype(np.float64) - ref).max() <= 1e-2
 
 
+def test_config4_balanced_decode_replayed_400_times_on_one_workspace():
+    """The same soak for the balanced cut of the ragged batch, where wavefronts (2048 of them) count in one by one
+    and any of them may be the one that merges a pair: 400 launches on one workspace, rotating query sets, every
+    output bit for bit equal to the first output of its query set (the merge folds the partials in slot order,
+    whatever the order of arrival)."""
+    import torch
+    from tests.gpu_util import make_desc, to_dev
+    w, t = _tensors(4)
+    desc = make_desc(w, out_dtype=spark.OUT_F32)
+    dcu = torch.from_numpy(np.asarray(t.cu, np.int32)).cuda()
+    packed = torch.empty(spark.packed_bytes(desc), dtype=torch.uint8, device="cuda")
+    spark.prune(desc, to_dev(t.k), to_dev(t.qwin), dcu, packed)
+    dv = to_dev(t.v)
+    rng = np.random.default_rng(11)
+    qs = [to_dev(t.q)] + [to_dev(wl.f32_to_bf16_bits(rng.standard_normal(t.q.shape).astype(np.float32))) for _ in range(3)]
+    # (the library's own choice for this batch: more partial slots than one block per sequence would need)
+    assert spark.decode_workspace_bytes(desc) > spark.decode_workspace_bytes(make_desc(w, out_dtype=spark.OUT_F32, n_splits=1))
+    ws = spark.new_decode_workspace(desc)
+    first = [None] * len(qs)
+    outs = [torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda") for _ in range(8)]
+    for i in range(400):
+        j = i % len(qs)
+        o = outs[i % len(outs)]
+        spark.decode_attn(desc, qs[j], packed, dv, dcu, o, ws)
+        if first[j] is None:
+            first[j] = o.clone()
+        elif i % 8 == 7 or i == 399:
+            for back in range(min(8, i + 1)):
+                ii = i - back
+                assert torch.equal(outs[ii % len(outs)], first[ii % len(qs)]), f"replay {ii} differs from its first run"
+    torch.cuda.synchronize()
+    ref = oracle.decode_literal(t.q, oracle.prune(t.k, t.layout, oracle.window_stat(t.qwin, w.n_kv_heads)[2], t.cu, w.keep),
+                                t.v, t.layout, t.cu)
+    assert np.abs(first[0].cpu().numpy().astype(np.float64) - ref).max() <= 1e-2
+
+
 def test_config5_int8_keys_with_pruned_values_keep64():
     """The Qwen-shaped workload with int8 key entries and the value cache pruned to 64 channels per row."""
     import torch
