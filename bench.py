@@ -287,7 +287,7 @@ def main() -> int:
             "pack": "int8" if args.int8 else "bf16", "keep_v": Tv if Tv else None, "tail_rows_per_sequence": ntail if ntail else None,
             "recovery": args.recovery, "top_p_basis_points": topp if topp else None,
             "mean_kept_per_row": mean_kept,
-            "splits": spark.decode_splits(desc),
+            "splits": spark.decode_splits(desc),       # (0: the balanced cut, tiles dealt out to wavefronts)
             "input_copies_rotated": ncopy, "seed": w.seed, "step": ("spark_prune + spark_prune_values + spark_decode_attn_values" if Tv
                                                               else "spark_prune_topp + spark_decode_attn_topp" if topp
                                                               else "spark_prune + spark_decode_attn_tail" if ntail

@@ -118,7 +118,8 @@ size_t spark_decode_workspace(const spark_desc *desc);
 spark_status spark_decode_workspace_init(const spark_desc *desc, void *workspace,
                                          size_t workspace_bytes, void *hip_stream);
 
-/* Number of blocks per KV head spark_decode_attn uses for a sequence of average length. */
+/* Number of blocks per KV head spark_decode_attn uses for a sequence of average length; 0 where
+ * spark_decode_attn and spark_decode_attn_tail take the balanced cut instead (see n_splits). */
 int32_t spark_decode_splits(const spark_desc *desc);
 
 /*

@@ -111,10 +111,11 @@ spark::DecodePlan plan_of(const spark_desc *d, bool allow_balanced = true)
     return p;
 }
 
-// chunks an average-length sequence is cut into (what spark_decode_splits reports)
+// chunks an average-length sequence is cut into; 0 for the balanced cut (what spark_decode_splits reports)
 int pick_splits(const spark_desc *d)
 {
     const spark::DecodePlan p = plan_of(d);
+    if (p.warm_waves > 0) return 0;
     if (p.fixed_splits > 0) return p.fixed_splits;
     const int64_t avg_tiles = (d->total_tokens / d->batch + SPARK_TILE_TOKENS - 1) / SPARK_TILE_TOKENS;
     const int64_t n = (avg_tiles + p.chunk_tiles - 1) / p.chunk_tiles;

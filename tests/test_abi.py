@@ -70,6 +70,7 @@ def test_balanced_cut_sizes_its_partial_slots_on_the_host():
     forced = _desc(batch=4, total_tokens=4 * 1000, n_splits=-1)
     assert spark.decode_workspace_bytes(forced) == ((256 + 2 * 4) * 32 + 4 * 32) * slot + 256
     assert spark.decode_workspace_bytes(forced) > spark.decode_workspace_bytes(small)
+    assert spark.decode_splits(forced) == 0 and spark.decode_splits(small) >= 1     # (0: the balanced cut)
     ragged = _desc(batch=64, total_tokens=64 * 1300)
     assert spark.decode_workspace_bytes(ragged) == ((256 + 2 * 64) * 32 + 64 * 32) * slot + 64 * 8 * 4
     assert spark.decode_workspace_bytes(_desc(batch=64, total_tokens=64 * 1300, n_splits=-1)) == \
