@@ -114,6 +114,18 @@ def test_special_rows():
     _run(w, t, p_bp=9999)
 
 
+def test_keys_concentrated_in_a_minority_of_channels():
+    """The benchmark's recipe for this variant: 60 % of each head's key channels quiet, so that 99 % of a row's
+    saliency sits in some fifty channels (the cut then falls between the loud and the quiet channels, seven
+    octaves apart: near the end of the selection's first-level window)."""
+    w = wl.small(name="toppquiet", batch=3, n_q_heads=16, n_kv_heads=4, seqlens=(700, 129, 300), seed=325)
+    w.quiet_fraction, w.quiet_scale = 0.6, 0.008
+    pr = _run(w, wl.generate(w))
+    assert 35 < pr.count.mean() < 70
+    _run(w, wl.generate(w), p_bp=9990)
+    _run(w, wl.generate(w), p_bp=9000)
+
+
 def test_config2_size():
     """The 32K benchmark shape (2.1 M rows): every count, mask and kept entry checked, decode checked."""
     w = wl.config(2)
