@@ -14,8 +14,8 @@
 //                             bit pattern of the smallest kept saliency is fixed level by level, each level
 //                             adding the q of the still undecided keys to 64 LDS bins by their next digit; a wave
 //                             prefix sum over the bins (highest digit first) and one ballot give the digit at
-//                             which the running sum reaches `need`.  The first level takes eleven bits (exponent
-//                             and three mantissa bits) over a window of eight octaves below the row's largest
+//                             which the running sum reaches `need`.  The first level takes ten bits (exponent
+//                             and two mantissa bits) over a window of sixteen octaves below the row's largest
 //                             key, the others six bits each; the levels end as soon as one key alone starts
 //                             with the bits fixed so far.  Writes the rows' fixed part (mask, mean
 //                             saliency of the pruned channels, count) and the tile's length in the value stream.
@@ -162,17 +162,19 @@ __global__ __launch_bounds__(kWaves * 64) void spark_topp_select_kernel(
                             : (uint32_t)__builtin_amdgcn_readlane((int)k1, __builtin_ctzll(in1 | (1ull << 63)));
                 return true;
             };
-            // First level: the exponent and three mantissa bits at once (eight bins an octave), over the eight
+            // First level: the exponent and two mantissa bits at once (four bins an octave), over the sixteen
             // octaves below the row's largest key.  All of a row's keys share their top bits, so a level on the
             // top six bits alone would drop nearly every key into one or two bins (and serialise the adds);
-            // here they spread over some forty.  Keys further down go to the spare words; if the kept sum is
-            // not reached inside the window (a row whose mass sits in keys 256 times smaller than its largest),
-            // the row falls back to plain six-bit levels from the top.
+            // here they spread over some forty.  The window is that long because the cut of a row whose loud
+            // channels hold nearly all of its saliency lies among the quiet ones, seven to ten octaves below
+            // the largest (an outlier) key.  Keys further down go to the spare words; if the kept sum is not
+            // reached inside the window, the row falls back to plain six-bit levels from the top.
             bool done;
             {
-                const uint32_t dmax = kmax >> 20;
+                constexpr int kSh = 21;
+                const uint32_t dmax = kmax >> kSh;
                 const uint32_t spare = 64u + (uint32_t)lane;
-                const uint32_t i0 = dmax - (k0 >> 20), i1 = dmax - (k1 >> 20);
+                const uint32_t i0 = dmax - (k0 >> kSh), i1 = dmax - (k1 >> kSh);
                 hist[lane] = 0u;
                 prune_lds_sync();
                 atomicAdd(&hist[i0 < 64u ? i0 : spare], q0);
@@ -184,14 +186,14 @@ __global__ __launch_bounds__(kWaves * 64) void spark_topp_select_kernel(
                 if (reached != 0ull) {
                     const int l2 = __builtin_ctzll(reached);
                     if (l2 > 0) above = (uint32_t)__builtin_amdgcn_readlane((int)c, l2 - 1);
-                    theta = (dmax - (uint32_t)l2) << 20;
-                    const uint64_t in0 = __ballot((k0 >> 20) == (theta >> 20)), in1 = __ballot((k1 >> 20) == (theta >> 20));
+                    theta = (dmax - (uint32_t)l2) << kSh;
+                    const uint64_t in0 = __ballot((k0 >> kSh) == (theta >> kSh)), in1 = __ballot((k1 >> kSh) == (theta >> kSh));
                     done = (__popcll(in0) + __popcll(in1) == 1);
                     if (done)
                         theta = in0 ? (uint32_t)__builtin_amdgcn_readlane((int)k0, __builtin_ctzll(in0))
                                     : (uint32_t)__builtin_amdgcn_readlane((int)k1, __builtin_ctzll(in1 | (1ull << 63)));
                     else
-                        done = level(14, 6) || level(8, 6) || level(2, 6) || level(0, 2);
+                        done = level(15, 6) || level(9, 6) || level(3, 6) || level(0, 3);
                 } else {
                     done = level(25, 6) || level(19, 6) || level(13, 6) || level(7, 6) || level(1, 6) || level(0, 1);
                 }

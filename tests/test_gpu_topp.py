@@ -104,6 +104,11 @@ def test_special_rows():
     for row, small in ((9, 2.0 ** -10), (10, 1.125 * 2.0 ** -8), (11, 2.0 ** -8)):
         k[0, row] = small
         k[0, row, 5] = 1.0
+    # ... and sixteen octaves down, where that window (four bins an octave) ends: its last bin and the first
+    # outside it; the plateau holds the cut at p = 99.99 % and 100 %
+    for row, small in ((12, 1.25 * 2.0 ** -16), (13, 2.0 ** -16), (14, 2.0 ** -20)):
+        k[0, row] = small
+        k[0, row, 77] = -1.0
     t.k = wl.f32_to_bf16_bits(k)
     t.qwin = wl.f32_to_bf16_bits(np.ones(t.qwin.shape, np.float32))      # a = 1 everywhere
     pr = _run(w, t)
@@ -111,7 +116,8 @@ def test_special_rows():
     assert pr.count[0, 0] == 1 and pr.count[1, 0] == 127 and pr.count[2, 0] == 1 and pr.count[3, 0] == 1
     pr = _run(w, t, p_bp=10000)
     assert pr.count[7, 0] == 4 and pr.count[8, 0] == 1
-    _run(w, t, p_bp=9999)
+    pr = _run(w, t, p_bp=9999)
+    assert 100 < pr.count[12, 0] < 128 and 100 < pr.count[13, 0] < 128 and pr.count[14, 0] < 128
 
 
 def test_keys_concentrated_in_a_minority_of_channels():
