@@ -1298,7 +1298,53 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                 }
             }
             if (P.trace != nullptr) stamp(P, 2, wall_clock64());
-            finalize(pr, my);
+            // A pair whose partials are exactly this block's four wavefronts' last ones (batches of equal
+            // sequences: every sequence is one block's share) needs no partials in memory: the four states are
+            // folded through LDS and the output written, as the cut by length does with one block per sequence.
+            // All four wavefronts see the same condition, and each meets the barrier once, at its end.
+            const int wf = pr.first - cur.b;
+            const bool block_pair = pr.nsplit == kDecodeWaves && (wf % kDecodeWaves) == 0 && P.ntail == 0 &&
+                                    (int)((((uint32_t)wf + (uint32_t)kDecodeWaves) * (uint32_t)total) / (uint32_t)nwe) ==
+                                        cur.first_item + cur.n;
+            if (block_pair) {
+                flush();
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const float lt = wave_sum(l[g]);
+                    if (lane == 0) { red_m[wave][g] = m[g]; red_l[wave][g] = lt; }
+                }
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int g = 4 * tg + rr;
+                    if (g < G) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) red[g * SPARK_D + 8 * cn + e] = acc[e][rr];
+                    }
+                }
+                __syncthreads();
+                for (int idx = tid; idx < G * SPARK_D; idx += kDecodeWaves * 64) {
+                    const int g = idx / SPARK_D, ch = idx % SPARK_D;
+                    float M = -INFINITY;
+#pragma unroll
+                    for (int w2 = 0; w2 < kDecodeWaves; ++w2) M = fmaxf(M, red_m[w2][g]);
+                    const float Ms = (M == -INFINITY) ? 0.0f : M;
+                    float Lsum = 0.0f, A = 0.0f;
+#pragma unroll
+                    for (int w2 = 0; w2 < kDecodeWaves; ++w2) {
+                        const float f = fast_exp2(red_m[w2][g] - Ms);
+                        Lsum = fmaf(red_l[w2][g], f, Lsum);
+                        A = fmaf(reinterpret_cast<const float *>(wbuf[w2])[g * SPARK_D + ch], f, A);
+                    }
+                    const float o = (Lsum > 0.0f) ? (A / Lsum) : 0.0f;
+                    const int64_t oi = ((int64_t)cur.b * P.Hq + h * G + g) * SPARK_D + ch;
+                    if (P.out_f32)
+                        reinterpret_cast<float *>(P.out)[oi] = o;
+                    else
+                        reinterpret_cast<uint16_t *>(P.out)[oi] = __builtin_bit_cast(uint16_t, (__bf16)o);
+                }
+            } else {
+                finalize(pr, my);
+            }
             if (P.trace != nullptr) stamp(P, 3, wall_clock64());
             flush();
         }

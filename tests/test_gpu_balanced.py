@@ -175,3 +175,14 @@ def test_longest_sequence_hint_keeps_one_block_per_sequence_on_even_batches():
     assert np.array_equal(outs["even"], outs["one"])
     assert np.array_equal(outs["ragged"], outs["none"])
     assert not np.array_equal(outs["none"], outs["one"])        # (another summation order)
+
+
+def test_sequences_that_are_exactly_one_blocks_share():
+    """64 equal sequences x 8 KV heads, 256 wavefronts per head: every sequence is the share of one block's four
+    wavefronts, whose states are folded through LDS and written out without partials in memory; then the same
+    with one sequence cut short, so that most pairs still align with blocks and the ones after it do not."""
+    w = wl.small(name="bal_aligned", batch=64, n_q_heads=32, n_kv_heads=8, keep=26, seqlens=(512,) * 64, seed=700)
+    _run(w)
+    lens = [512] * 64
+    lens[20] = 130
+    _run(wl.small(name="bal_misaligned", batch=64, n_q_heads=32, n_kv_heads=8, keep=64, seqlens=tuple(lens), seed=701))
