@@ -1342,6 +1342,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, decode_min_blocks(G, TCT)) void 
                     else
                         reinterpret_cast<uint16_t *>(P.out)[oi] = __builtin_bit_cast(uint16_t, (__bf16)o);
                 }
+                __syncthreads();             // (a wavefront that looks after an empty sequence next reuses its staging area)
             } else {
                 finalize(pr, my);
             }

@@ -183,6 +183,11 @@ def test_sequences_that_are_exactly_one_blocks_share():
     with one sequence cut short, so that most pairs still align with blocks and the ones after it do not."""
     w = wl.small(name="bal_aligned", batch=64, n_q_heads=32, n_kv_heads=8, keep=26, seqlens=(512,) * 64, seed=700)
     _run(w)
+    # sequences without tokens are looked after by the wavefront of their number: here wavefronts of blocks whose
+    # pair is folded through LDS (sequences 0 .. 4 still align with blocks 0 .. 4; wavefronts 5, 6, 7 sit in block 1)
+    lens = [512] * 64
+    lens[5] = lens[6] = lens[7] = 0
+    _run(wl.small(name="bal_aligned_empty", batch=64, n_q_heads=32, n_kv_heads=8, keep=26, seqlens=tuple(lens), seed=702))
     lens = [512] * 64
     lens[20] = 130
     _run(wl.small(name="bal_misaligned", batch=64, n_q_heads=32, n_kv_heads=8, keep=64, seqlens=tuple(lens), seed=701))
