@@ -76,8 +76,8 @@ typedef struct spark_desc {
     int32_t n_splits;         /* decode: > 0 cuts every sequence into this many blocks per KV head; 0 => the
                                  library cuts sequences in proportion to their length (ragged batches:
                                  long sequences get more blocks), and batches of 32 to 256 short sequences
-                                 are dealt out tile by tile to independent wavefronts (the balanced cut;
-                                 see max_seqlen);
+                                 (with at least two 64-token tiles per resident wavefront) are dealt out
+                                 tile by tile to independent wavefronts (the balanced cut; see max_seqlen);
                                  -1 asks for the balanced cut whenever it exists (batch <= 256, at most 8
                                  query heads per KV head; spark_decode_attn and spark_decode_attn_tail; the
                                  other entry points cut by length).  Must be the same for the workspace

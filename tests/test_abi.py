@@ -63,8 +63,8 @@ def test_size_queries_follow_the_layout():
 
 def test_balanced_cut_sizes_its_partial_slots_on_the_host():
     """n_splits = -1 asks for the balanced cut: 4 * (512 / KV heads) wavefronts per KV head, chunk ids
-    wavefronts + 2 * batch.  Batches of 32 to 256 sequences with 256 or more (batch, KV head) pairs get it
-    unasked; more than 256 sequences, or 16 query heads per KV head, never do."""
+    wavefronts + 2 * batch.  Batches of 32 to 256 sequences with 256 or more (batch, KV head) pairs and two
+    tiles or more per wavefront get it unasked; more than 256 sequences, or 16 query heads per KV head, never do."""
     slot = 130 * 4
     small = _desc(batch=4, total_tokens=4 * 1000)
     forced = _desc(batch=4, total_tokens=4 * 1000, n_splits=-1)
@@ -88,6 +88,9 @@ def test_balanced_cut_sizes_its_partial_slots_on_the_host():
     assert spark.decode_workspace_bytes(_desc(batch=64, total_tokens=64 * 1300, max_seqlen=1400)) == by_length
     assert spark.decode_workspace_bytes(_desc(batch=64, total_tokens=64 * 1300, max_seqlen=1463)) > by_length
     assert spark.decode_workspace_bytes(_desc(batch=64, total_tokens=64 * 1300, max_seqlen=1400, n_splits=-1)) > by_length
+    # ... and a batch with less than two tiles per wavefront (here 400 tiles for 256 wavefronts) is left alone
+    assert spark.decode_splits(_desc(batch=64, total_tokens=64 * 400)) >= 1
+    assert spark.decode_splits(_desc(batch=64, total_tokens=64 * 400, n_splits=-1)) == 0
     assert spark.decode_workspace_bytes(_desc(max_seqlen=-1)) == 0
     assert spark.decode_workspace_bytes(_desc(n_splits=-2)) == 0
     assert spark.decode_workspace_bytes(_desc(n_splits=4097)) == 0

@@ -154,8 +154,8 @@ def test_longest_sequence_hint_keeps_one_block_per_sequence_on_even_batches():
     out to wavefronts - same cut, so bit for bit the same result, as n_splits = 1; a hint that says "ragged", or
     none, leaves the balanced cut on."""
     rng = np.random.default_rng(690)
-    lens = tuple(int(x) for x in rng.integers(380, 420, size=40))
-    w = wl.small(name="bal_hint", batch=40, n_q_heads=32, n_kv_heads=8, keep=26, seqlens=lens, seed=690)
+    lens = tuple(int(x) for x in rng.integers(780, 820, size=48))         # (600 tiles: two per wavefront and more)
+    w = wl.small(name="bal_hint", batch=48, n_q_heads=32, n_kv_heads=8, keep=26, seqlens=lens, seed=690)
     t = wl.generate(w)
     _, _, a32 = oracle.window_stat(t.qwin, w.n_kv_heads)
     pr = oracle.prune(t.k, t.layout, a32, t.cu, w.keep)

@@ -41,7 +41,7 @@ def test_static_scratch_uses_the_cut_by_length_where_the_balanced_cut_does_not_f
     """64 short sequences x 8 KV heads: spark_decode_attn takes the balanced cut, whose partial slots exceed the
     array; the cut by length fits, and the static entry point uses that one (same result up to summation order)."""
     rng = np.random.default_rng(83)
-    lens = tuple(int(x) for x in rng.integers(40, 400, size=64))
+    lens = tuple(int(x) for x in rng.integers(300, 1000, size=64))        # (enough tiles for the balanced cut)
     w = wl.small(name="static_ragged", batch=64, n_q_heads=32, n_kv_heads=8, keep=26, seqlens=lens, seed=83)
     t = wl.generate(w)
     res = run_gpu_case(w, t, want_unpack=False, want_bf16=False)
