@@ -61,6 +61,26 @@ def measured_traffic(workload: str, pack: str):
     return None, None
 
 
+def device_state(torch) -> dict:
+    """Name, size and clocks of the GPU the run used (the clocks as rocm-smi reports them after the run, if it can
+    be asked; a reading that fails is left out rather than guessed)."""
+    import subprocess
+    p = torch.cuda.get_device_properties(0)
+    dev = {"name": p.name, "compute_units": p.multi_processor_count, "memory_GiB": round(p.total_memory / 2 ** 30, 1),
+           "max_engine_clock_MHz": round(getattr(p, "clock_rate", 0) / 1e3) or None,
+           "max_memory_clock_MHz": round(getattr(p, "memory_clock_rate", 0) / 1e3) or None, "rocm_smi": None}
+    try:
+        out = subprocess.run(["rocm-smi", "-d", "0", "--showclocks", "--showperflevel", "--showpower", "--json"],
+                             capture_output=True, text=True, timeout=15)
+        if out.returncode == 0 and out.stdout.strip().startswith("{"):
+            card = next(iter(json.loads(out.stdout).values()))
+            dev["rocm_smi"] = {k: v for k, v in card.items()
+                               if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "performance level", "power"))}
+    except Exception:
+        pass
+    return {k: v for k, v in dev.items() if v is not None}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -372,6 +392,7 @@ def main() -> int:
                             "near_tie_rows_gap_lt_1e-6": pr.near_ties(), "rows": int(rows),
                             "decode_max_abs_err": float(err.max()), "decode_mean_abs_err": float(err.mean())}
 
+    result["device"] = device_state(torch)
     print(json.dumps(result))
     return 0
 
